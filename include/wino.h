@@ -1,0 +1,147 @@
+/*
+ * libwino — Winograd-algorithm 2-D convolution (3x3 filter, stride 1, zero pad 1,
+ * dilation 1, groups 1) for AMD Instinct MI355X (gfx950).
+ *
+ * The operator is the 2-D convolution that the paper's Section "Techniques"
+ * replaces by a Winograd path with three steps: (i) preprocess of the filter and
+ * of the activation, (ii) element-wise multiplication of the preprocessed
+ * tensors (summed over input channels, i.e. alpha^2 batched matrix products),
+ * (iii) postprocess of the intermediate result.  Tensor orders follow the header
+ * of the paper's Table 1 (filter [KW,KH,IC,OC], activation [IW,IH,IC,N], fastest
+ * dimension first): w[K][C][3][3], x[N][C][H][W], y[N][K][H][W].
+ *
+ *     y[n,k,i,j] = bias[k] + sum_{c,r,s} xhat[n,c,i+r-1,j+s-1] * w[k,c,r,s]
+ *     xhat = x inside the image, 0 outside            (cross-correlation, no flip)
+ *
+ * Notation: m = output tile edge (2 or 4), alpha = m+2, th = ceil(H/m),
+ * tw = ceil(W/m), T = N*th*tw tiles, tile index t = (n*th+ti)*tw+tj,
+ * xi*alpha+nu in [0, alpha^2) = position inside the transformed tile.
+ *
+ * General conventions
+ *  - Every pointer named x, w, w_t->data, bias, y, U, V, M or workspace is DEVICE
+ *    memory owned by the caller; the library keeps nothing after a call returns
+ *    (wino_conv2d borrows its workspace from the stream-ordered allocator and
+ *    returns it on the same stream).  wino_filter is a HOST struct.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *    default stream).  No call synchronises with the host.
+ *  - Arguments are validated on the host before anything is launched; errors come
+ *    back as a wino_status and nothing is enqueued.  No exceptions, no abort.
+ *  - Device pointers must be 16-byte aligned.  x and y must not overlap.
+ *  - bias is always fp32 [K] and may be NULL.  Accumulation is always fp32.
+ *  - Results are deterministic run to run (no atomics).
+ *  - fp16 range: the F4 activation transform can grow values by up to 100x, so
+ *    |x| must stay below ~650 on the fp16 F4 path (F2: 4x, ~16000).
+ */
+#ifndef WINO_H
+#define WINO_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum wino_status {
+    WINO_OK = 0,
+    WINO_ERR_NULL = 1,       /* a required pointer is NULL                         */
+    WINO_ERR_DIM = 2,        /* a dimension is < 1, mismatches w_t, or overflows   */
+    WINO_ERR_DTYPE = 3,      /* dtype enum out of range or unsupported here        */
+    WINO_ERR_VARIANT = 4,    /* variant enum out of range or unsupported here      */
+    WINO_ERR_ALIGN = 5,      /* a device pointer is not 16-byte aligned            */
+    WINO_ERR_WORKSPACE = 6,  /* workspace NULL or smaller than wino_workspace_bytes*/
+    WINO_ERR_ALIAS = 7,      /* x and y byte ranges overlap                        */
+    WINO_ERR_HIP = 8,        /* a HIP call (launch, allocation) failed             */
+    WINO_ERR_LAYOUT = 9      /* layout enum out of range or unsupported here       */
+} wino_status;
+
+/* Storage type of x, w, y and of the transformed tensors U and V. */
+typedef enum wino_dtype { WINO_F32 = 0, WINO_F16 = 1 } wino_dtype;
+
+/*
+ * WINO_F2 / WINO_F4: Winograd F(2x2,3x3) / F(4x4,3x3), three kernels (activation
+ * transform, batched MFMA GEMM, output transform).  WINO_DIRECT: plain direct
+ * correlation, for checking.  WINO_AUTO: the library picks F2 or F4 per shape.
+ */
+typedef enum wino_variant { WINO_AUTO = 0, WINO_DIRECT = 1, WINO_F2 = 2, WINO_F4 = 4 } wino_variant;
+
+typedef enum wino_layout { WINO_NCHW = 0 } wino_layout;
+
+/* Host-side descriptor of a transformed filter.  `data` is the caller's device
+ * buffer; the blob holds no pointers and can be copied or saved by the caller. */
+typedef struct wino_filter {
+    void *data;      /* device, U[alpha^2][K][Cp] in `dtype`, Cp = C rounded up to 8 */
+    int K, C;
+    int dtype;       /* wino_dtype   */
+    int variant;     /* wino_variant, resolved: WINO_F2 or WINO_F4 */
+} wino_filter;
+
+int wino_version(void);                         /* major*10000 + minor*100 + patch */
+const char *wino_status_string(int status);     /* static string, never NULL       */
+
+/* WINO_AUTO -> WINO_F2 or WINO_F4 for this shape; other values returned as they
+ * are; -1 on bad arguments. */
+int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int variant);
+
+/* Sizes (elements, not bytes) of the transformed tensors for a resolved variant:
+ * *Cp = C rounded up to a multiple of 8 (zero-filled), *T = N*ceil(H/m)*ceil(W/m).
+ * Returns WINO_OK or an error; outputs may be NULL. */
+int wino_transformed_dims(int N, int C, int H, int W, int K, int variant, int *alpha, int *Cp, int *T);
+
+/* Bytes of the device buffer that holds U.  0 on bad arguments / AUTO / DIRECT. */
+size_t wino_filter_bytes(int K, int C, int dtype, int variant);
+
+/* Bytes of scratch (V then M, each 256-byte aligned) that wino_conv2d_ex needs for
+ * a resolved Winograd variant; 0 for WINO_DIRECT and on bad arguments. */
+size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int dtype, int variant);
+
+/*
+ * Step (i), filter:  U[xi,nu,k,c] = (G g[k,c] G^T)[xi,nu], computed in fp32 and
+ * rounded once to `dtype`.  Done once per weight tensor.
+ *   w         device, [K][C][3][3] in `dtype`
+ *   w_t_data  device, at least wino_filter_bytes(K,C,dtype,variant) bytes
+ *   variant   WINO_F2 or WINO_F4 (AUTO is rejected: the shape is not known here)
+ *   out       host, filled on success
+ */
+int wino_filter_transform(const void *w, void *w_t_data, int K, int C, int dtype, int variant,
+                          wino_filter *out, void *stream);
+
+/*
+ * The whole path (steps (i) activation, (ii), (iii) + bias) with the variant held
+ * in w_t.  x[N][C][H][W] and y[N][K][H][W] in w_t->dtype; y is fully overwritten.
+ * Borrows wino_workspace_bytes() of scratch from hipMallocAsync on `stream` and
+ * returns it with hipFreeAsync on `stream`.
+ */
+int wino_conv2d(const void *x, const wino_filter *w_t, const float *bias, void *y,
+                int N, int C, int H, int W, int K, void *stream);
+
+/* Same, scratch supplied by the caller; allocates nothing. */
+int wino_conv2d_ex(const void *x, const wino_filter *w_t, const float *bias, void *y,
+                   int N, int C, int H, int W, int K, int layout,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The three stages on their own (the same kernels wino_conv2d_ex chains), for
+ * stage-by-stage checks and per-kernel measurement.  Layouts, `e` = dtype:
+ *   V[alpha^2][T][Cp]  e     step (i), activation: V[xi,nu,t,c] = (B^T d[c,t] B)[xi,nu],
+ *                            d = alpha x alpha window of xhat at rows m*ti-1.., cols m*tj-1..;
+ *                            entries with c >= C are written as zero
+ *   U[alpha^2][K][Cp]  e     as produced by wino_filter_transform
+ *   M[alpha^2][K][T]   fp32  step (ii): M[xi,nu,k,t] = sum_c U[xi,nu,k,c] * V[xi,nu,t,c]
+ *   y[N][K][H][W]      e     step (iii): y tile = A^T M[.,.,k,t] A (+ bias[k]), cropped to HxW
+ */
+int wino_input_transform(const void *x, void *V, int N, int C, int H, int W,
+                         int dtype, int variant, int layout, void *stream);
+int wino_batched_gemm(const void *U, const void *V, float *M, int K, int C, int T,
+                      int dtype, int variant, void *stream);
+int wino_output_transform(const float *M, const float *bias, void *y, int N, int K, int H, int W,
+                          int dtype, int variant, int layout, void *stream);
+
+/* Direct correlation on the GPU from the untransformed filter (fp32 accumulate),
+ * one thread per output; a checking fallback, not a fast path. */
+int wino_direct_conv2d(const void *x, const void *w, const float *bias, void *y,
+                       int N, int C, int H, int W, int K, int dtype, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WINO_H */

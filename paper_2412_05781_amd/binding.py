@@ -1,0 +1,236 @@
+"""ctypes binding of libwino.so — argument marshalling only.
+
+Function names and argument order mirror ``include/wino.h``.  Tensors are torch
+tensors on the GPU (torch is used for device memory and streams only); every
+step of the path runs inside the library's HIP kernels.  There is no fallback:
+if the library is missing, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libwino.so")
+
+WINO_OK = 0
+WINO_ERR_NULL, WINO_ERR_DIM, WINO_ERR_DTYPE, WINO_ERR_VARIANT = 1, 2, 3, 4
+WINO_ERR_ALIGN, WINO_ERR_WORKSPACE, WINO_ERR_ALIAS, WINO_ERR_HIP, WINO_ERR_LAYOUT = 5, 6, 7, 8, 9
+WINO_F32, WINO_F16 = 0, 1
+WINO_AUTO, WINO_DIRECT, WINO_F2, WINO_F4 = 0, 1, 2, 4
+WINO_NCHW = 0
+
+DTYPE_OF = {torch.float32: WINO_F32, torch.float16: WINO_F16}
+TORCH_OF = {WINO_F32: torch.float32, WINO_F16: torch.float16}
+
+EXPORTS = [
+    "wino_version", "wino_status_string", "wino_resolve_variant", "wino_transformed_dims",
+    "wino_filter_bytes", "wino_workspace_bytes", "wino_filter_transform", "wino_conv2d",
+    "wino_conv2d_ex", "wino_input_transform", "wino_batched_gemm", "wino_output_transform",
+    "wino_direct_conv2d",
+]
+
+
+class wino_filter(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("K", ctypes.c_int), ("C", ctypes.c_int),
+                ("dtype", ctypes.c_int), ("variant", ctypes.c_int)]
+
+
+class WinoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Open libwino.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2412_05781_amd.build` "
+                               "(or __graft_entry__.build()); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        i, vp, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+        ip = ctypes.POINTER(ctypes.c_int)
+        fp = ctypes.POINTER(wino_filter)
+        L.wino_version.restype = i; L.wino_version.argtypes = []
+        L.wino_status_string.restype = ctypes.c_char_p; L.wino_status_string.argtypes = [i]
+        L.wino_resolve_variant.restype = i; L.wino_resolve_variant.argtypes = [i] * 7
+        L.wino_transformed_dims.restype = i; L.wino_transformed_dims.argtypes = [i] * 6 + [ip, ip, ip]
+        L.wino_filter_bytes.restype = sz; L.wino_filter_bytes.argtypes = [i] * 4
+        L.wino_workspace_bytes.restype = sz; L.wino_workspace_bytes.argtypes = [i] * 7
+        L.wino_filter_transform.restype = i
+        L.wino_filter_transform.argtypes = [vp, vp, i, i, i, i, fp, vp]
+        L.wino_conv2d.restype = i
+        L.wino_conv2d.argtypes = [vp, fp, vp, vp, i, i, i, i, i, vp]
+        L.wino_conv2d_ex.restype = i
+        L.wino_conv2d_ex.argtypes = [vp, fp, vp, vp, i, i, i, i, i, i, vp, sz, vp]
+        L.wino_input_transform.restype = i
+        L.wino_input_transform.argtypes = [vp, vp, i, i, i, i, i, i, i, vp]
+        L.wino_batched_gemm.restype = i
+        L.wino_batched_gemm.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        L.wino_output_transform.restype = i
+        L.wino_output_transform.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.wino_direct_conv2d.restype = i
+        L.wino_direct_conv2d.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+        _lib = L
+    return _lib
+
+
+# ---- helpers -------------------------------------------------------------------------------
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream: Optional[torch.cuda.Stream]):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev(t: torch.Tensor, name: str):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous GPU tensor")
+
+
+def _check(status: int, where: str):
+    if status != WINO_OK:
+        raise WinoError(status, where)
+
+
+# ---- same names as the C ABI ------------------------------------------------------------------
+def wino_version() -> int:
+    return lib().wino_version()
+
+
+def status_string(status: int) -> str:
+    return lib().wino_status_string(int(status)).decode()
+
+
+wino_status_string = status_string
+
+
+def wino_resolve_variant(N, C, H, W, K, dtype, variant) -> int:
+    return lib().wino_resolve_variant(N, C, H, W, K, dtype, variant)
+
+
+def wino_transformed_dims(N, C, H, W, K, variant):
+    a, cp, t = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib().wino_transformed_dims(N, C, H, W, K, variant, ctypes.byref(a), ctypes.byref(cp), ctypes.byref(t)),
+           "wino_transformed_dims")
+    return a.value, cp.value, t.value
+
+
+def wino_filter_bytes(K, C, dtype, variant) -> int:
+    return lib().wino_filter_bytes(K, C, dtype, variant)
+
+
+def wino_workspace_bytes(N, C, H, W, K, dtype, variant) -> int:
+    return lib().wino_workspace_bytes(N, C, H, W, K, dtype, variant)
+
+
+class Filter:
+    """A transformed filter: the device buffer (kept alive here) plus the host descriptor."""
+
+    def __init__(self, buf: torch.Tensor, desc: wino_filter):
+        self.buf, self.desc = buf, desc
+
+    @property
+    def variant(self):
+        return self.desc.variant
+
+
+def wino_filter_transform(w: torch.Tensor, variant: int, stream=None) -> Filter:
+    """w[K,C,3,3] (GPU) -> Filter holding U[alpha^2][K][Cp]."""
+    _dev(w, "w")
+    K, C = int(w.shape[0]), int(w.shape[1])
+    if tuple(w.shape) != (K, C, 3, 3):
+        raise ValueError("w must be [K,C,3,3]")
+    dt = DTYPE_OF[w.dtype]
+    nbytes = wino_filter_bytes(K, C, dt, variant)
+    if nbytes == 0:
+        raise WinoError(WINO_ERR_VARIANT, "wino_filter_bytes")
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    desc = wino_filter()
+    _check(lib().wino_filter_transform(_ptr(w), _ptr(buf), K, C, dt, variant, ctypes.byref(desc), _stream(stream)),
+           "wino_filter_transform")
+    return Filter(buf, desc)
+
+
+def wino_conv2d(x: torch.Tensor, w_t: Filter, bias: Optional[torch.Tensor], y: torch.Tensor, stream=None) -> torch.Tensor:
+    _dev(x, "x"); _dev(y, "y")
+    N, C, H, W = map(int, x.shape)
+    K = int(y.shape[1])
+    _check(lib().wino_conv2d(_ptr(x), ctypes.byref(w_t.desc), _ptr(bias), _ptr(y), N, C, H, W, K, _stream(stream)),
+           "wino_conv2d")
+    return y
+
+
+def wino_conv2d_ex(x, w_t: Filter, bias, y, workspace: torch.Tensor, layout: int = WINO_NCHW, stream=None):
+    _dev(x, "x"); _dev(y, "y"); _dev(workspace, "workspace")
+    N, C, H, W = map(int, x.shape)
+    K = int(y.shape[1])
+    _check(lib().wino_conv2d_ex(_ptr(x), ctypes.byref(w_t.desc), _ptr(bias), _ptr(y), N, C, H, W, K, layout,
+                                _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "wino_conv2d_ex")
+    return y
+
+
+def wino_input_transform(x: torch.Tensor, variant: int, layout: int = WINO_NCHW, stream=None) -> torch.Tensor:
+    """x[N,C,H,W] -> V[alpha^2, T, Cp] (same dtype)."""
+    _dev(x, "x")
+    N, C, H, W = map(int, x.shape)
+    alpha, Cp, T = wino_transformed_dims(N, C, H, W, 1, variant)
+    V = torch.empty((alpha * alpha, T, Cp), dtype=x.dtype, device=x.device)
+    _check(lib().wino_input_transform(_ptr(x), _ptr(V), N, C, H, W, DTYPE_OF[x.dtype], variant, layout, _stream(stream)),
+           "wino_input_transform")
+    return V
+
+
+def wino_batched_gemm(U: torch.Tensor, V: torch.Tensor, K: int, C: int, T: int, variant: int, stream=None) -> torch.Tensor:
+    """U[alpha^2,K,Cp], V[alpha^2,T,Cp] -> M[alpha^2,K,T] fp32."""
+    _dev(U, "U"); _dev(V, "V")
+    a2 = (variant + 2) ** 2
+    M = torch.empty((a2, K, T), dtype=torch.float32, device=U.device)
+    _check(lib().wino_batched_gemm(_ptr(U), _ptr(V), _ptr(M), K, C, T, DTYPE_OF[U.dtype], variant, _stream(stream)),
+           "wino_batched_gemm")
+    return M
+
+
+def wino_output_transform(M: torch.Tensor, bias, N: int, K: int, H: int, W: int, dtype: torch.dtype,
+                          variant: int, layout: int = WINO_NCHW, stream=None) -> torch.Tensor:
+    _dev(M, "M")
+    y = torch.empty((N, K, H, W), dtype=dtype, device=M.device)
+    _check(lib().wino_output_transform(_ptr(M), _ptr(bias), _ptr(y), N, K, H, W, DTYPE_OF[dtype], variant, layout,
+                                       _stream(stream)), "wino_output_transform")
+    return y
+
+
+def wino_direct_conv2d(x: torch.Tensor, w: torch.Tensor, bias, y: torch.Tensor, stream=None) -> torch.Tensor:
+    _dev(x, "x"); _dev(w, "w"); _dev(y, "y")
+    N, C, H, W = map(int, x.shape)
+    K = int(w.shape[0])
+    _check(lib().wino_direct_conv2d(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), N, C, H, W, K, DTYPE_OF[x.dtype], _stream(stream)),
+           "wino_direct_conv2d")
+    return y
+
+
+# ---- convenience (allocation only) ------------------------------------------------------------
+def conv2d(x: torch.Tensor, w: torch.Tensor, bias=None, variant: int = WINO_AUTO) -> torch.Tensor:
+    """Transform the filter, allocate workspace and output, run the chosen variant."""
+    N, C, H, W = map(int, x.shape)
+    K = int(w.shape[0])
+    y = torch.empty((N, K, H, W), dtype=x.dtype, device=x.device)
+    v = wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant)
+    if v < 0:
+        raise WinoError(WINO_ERR_DIM, "wino_resolve_variant")
+    if v == WINO_DIRECT:
+        return wino_direct_conv2d(x, w, bias, y)
+    w_t = wino_filter_transform(w, v)
+    ws = torch.empty(wino_workspace_bytes(N, C, H, W, K, DTYPE_OF[x.dtype], v), dtype=torch.uint8, device=x.device)
+    return wino_conv2d_ex(x, w_t, bias, y, ws)

@@ -1,0 +1,106 @@
+// Step (i), activation side (Section "Techniques"): V = B^T d B for every
+// overlapping alpha x alpha window d of the zero-padded image, per channel.
+//
+// x is NCHW (W contiguous) but the GEMM stage wants the reduction index c
+// contiguous, V[alpha^2][T][Cp].  A workgroup therefore stages a patch of
+// CB channels x alpha rows x (m*TJ+2) columns in LDS with loads that run along
+// W, then each lane takes one channel of one tile, transforms it in fp32 and
+// stores with lanes running along c.  Out-of-image taps and channels >= C are
+// staged as zeros, so V's padded reduction columns are exact zeros.
+// Bound by HBM/L2 traffic: reads x once (plus the 2-row/2-column halo), writes V.
+#include "wino_internal.h"
+#include "wino_transforms.h"
+
+namespace wino {
+
+template <int M, typename E, int CB, int TJ>
+__global__ void __launch_bounds__(256)
+input_transform_nchw_kernel(const E* __restrict__ x, E* __restrict__ V,
+                            int N, int C, int H, int W, int th, int tw, int T, int Cp, int strips_per_row) {
+    constexpr int A = M + 2;
+    constexpr int PW = M * TJ + 2;                       // patch width (elements)
+    // channel stride: odd number of 32-bit words so lanes (= channels) hit distinct banks
+    constexpr int RAW = A * PW;
+    constexpr int EPW = 4 / (int)sizeof(E);              // elements per 32-bit word
+    constexpr int WORDS = (RAW + EPW - 1) / EPW;
+    constexpr int CS = ((WORDS % 2 == 0) ? WORDS + 1 : WORDS) * EPW;
+    __shared__ E patch[CB * CS];
+
+    const int tid = threadIdx.x;
+    int sidx = blockIdx.x;
+    const int js = sidx % strips_per_row; sidx /= strips_per_row;
+    const int ti = sidx % th;
+    const int n = sidx / th;
+    const int tj0 = js * TJ;
+    const int c0 = blockIdx.y * CB;
+    const int row0 = M * ti - 1;
+    const int col0 = M * tj0 - 1;
+
+    // ---- stage the patch: consecutive lanes walk along W -------------------------------
+    for (int e = tid; e < CB * RAW; e += 256) {
+        const int cc = e / RAW;
+        const int rem = e - cc * RAW;
+        const int a = rem / PW;
+        const int b = rem - a * PW;
+        const int r = row0 + a, q = col0 + b, c = c0 + cc;
+        E v = from_f32<E>(0.f);
+        if (c < C && r >= 0 && r < H && q >= 0 && q < W)
+            v = x[(((size_t)n * C + c) * H + r) * W + q];
+        patch[cc * CS + rem] = v;
+    }
+    __syncthreads();
+
+    // ---- transform: lane = channel, one tile per wave per iteration ----------------------
+    const int cc = tid % CB;
+    const int c = c0 + cc;
+    constexpr int TILES_PER_ITER = 256 / CB;
+    const size_t plane = (size_t)T * Cp;
+    for (int tl = tid / CB; tl < TJ; tl += TILES_PER_ITER) {
+        const int tj = tj0 + tl;
+        if (tj >= tw || c >= Cp) continue;
+        const E* p = patch + cc * CS + M * tl;
+        float d[A][A];
+#pragma unroll
+        for (int a = 0; a < A; ++a)
+#pragma unroll
+            for (int b = 0; b < A; ++b) d[a][b] = to_f32<E>(p[a * PW + b]);
+        // columns: tmp[:, b] = B^T d[:, b]
+        float tmp[A][A];
+#pragma unroll
+        for (int b = 0; b < A; ++b) {
+            float in[A], out[A];
+#pragma unroll
+            for (int a = 0; a < A; ++a) in[a] = d[a][b];
+            bt_1d<M>(in, out);
+#pragma unroll
+            for (int a = 0; a < A; ++a) tmp[a][b] = out[a];
+        }
+        const size_t t = ((size_t)n * th + ti) * tw + tj;
+        E* dst = V + t * Cp + c;
+#pragma unroll
+        for (int xi = 0; xi < A; ++xi) {
+            float out[A];
+            bt_1d<M>(tmp[xi], out);                      // rows: (B^T d) B = (B^T (B^T d)^T)^T
+#pragma unroll
+            for (int nu = 0; nu < A; ++nu) dst[(size_t)(xi * A + nu) * plane] = from_f32<E>(out[nu]);
+        }
+    }
+}
+
+template <int M, typename E>
+static hipError_t launch_it(const void* x, void* V, const Geom& g, hipStream_t s) {
+    constexpr int CB = 64;
+    constexpr int TJ = (M == 4) ? 8 : 16;
+    const int strips = (g.tw + TJ - 1) / TJ;
+    dim3 block(256), grid((unsigned)(g.N * g.th * strips), (unsigned)((g.Cp + CB - 1) / CB));
+    hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ>), grid, block, 0, s,
+                       (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips);
+    return hipGetLastError();
+}
+
+hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, hipStream_t s) {
+    if (g.m == 2) return f16 ? launch_it<2, __half>(x, V, g, s) : launch_it<2, float>(x, V, g, s);
+    return f16 ? launch_it<4, __half>(x, V, g, s) : launch_it<4, float>(x, V, g, s);
+}
+
+}  // namespace wino

@@ -1,0 +1,97 @@
+// Step (iii) (Section "Techniques"): y tile = A^T M A per (k, tile), plus bias,
+// cropped to the image, rounded once to the storage type.
+// One lane per (k, t), t fastest, so the alpha^2 reads of M[alpha^2][K][T] are
+// contiguous across lanes and the m-wide row stores of neighbouring tiles abut.
+// Bound by HBM/L2 traffic: reads alpha^2 fp32 per m^2 outputs.
+#include "wino_internal.h"
+#include "wino_transforms.h"
+
+namespace wino {
+
+template <typename E, int M> struct RowVec;
+template <> struct RowVec<float, 2> { using type = float2; };
+template <> struct RowVec<float, 4> { using type = float4; };
+template <> struct RowVec<__half, 2> { using type = __half2; };
+template <> struct RowVec<__half, 4> { struct alignas(8) type { __half2 lo, hi; }; };
+
+template <typename E, int M>
+__device__ __forceinline__ void store_row(E* p, const float* v) {
+    typename RowVec<E, M>::type r;
+    if constexpr (sizeof(E) == 4) {
+        if constexpr (M == 2) { r.x = v[0]; r.y = v[1]; }
+        else { r.x = v[0]; r.y = v[1]; r.z = v[2]; r.w = v[3]; }
+    } else {
+        if constexpr (M == 2) { r = __floats2half2_rn(v[0], v[1]); }
+        else { r.lo = __floats2half2_rn(v[0], v[1]); r.hi = __floats2half2_rn(v[2], v[3]); }
+    }
+    *reinterpret_cast<typename RowVec<E, M>::type*>(p) = r;
+}
+
+template <int M, typename E>
+__global__ void __launch_bounds__(256)
+output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
+                             int N, int K, int H, int W, int th, int tw, int T, int vec_ok) {
+    constexpr int A = M + 2;
+    const size_t KT = (size_t)K * T;
+    const size_t f = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (f >= KT) return;
+    const int k = (int)(f / T);
+    int t = (int)(f - (size_t)k * T);
+    const int tj = t % tw; t /= tw;
+    const int ti = t % th;
+    const int n = t / th;
+
+    float v[A][A];
+#pragma unroll
+    for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+        for (int nu = 0; nu < A; ++nu) v[xi][nu] = Mt[(size_t)(xi * A + nu) * KT + f];
+
+    // columns: tmp[:, nu] = A^T v[:, nu]
+    float tmp[M][A];
+#pragma unroll
+    for (int nu = 0; nu < A; ++nu) {
+        float in[A], out[M];
+#pragma unroll
+        for (int xi = 0; xi < A; ++xi) in[xi] = v[xi][nu];
+        at_1d<M>(in, out);
+#pragma unroll
+        for (int a = 0; a < M; ++a) tmp[a][nu] = out[a];
+    }
+    const float b = bias ? bias[k] : 0.f;
+    const int i0 = M * ti, j0 = M * tj;
+    E* yp = y + (((size_t)n * K + k) * H + i0) * W + j0;
+#pragma unroll
+    for (int a = 0; a < M; ++a) {
+        float out[M];
+        at_1d<M>(tmp[a], out);
+#pragma unroll
+        for (int q = 0; q < M; ++q) out[q] += b;
+        if (i0 + a < H) {
+            if (vec_ok) {
+                store_row<E, M>(yp + (size_t)a * W, out);
+            } else {
+#pragma unroll
+                for (int q = 0; q < M; ++q)
+                    if (j0 + q < W) yp[(size_t)a * W + q] = from_f32<E>(out[q]);
+            }
+        }
+    }
+}
+
+template <int M, typename E>
+static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const Geom& g, hipStream_t s) {
+    const size_t KT = (size_t)g.K * g.T;
+    dim3 block(256), grid((unsigned)((KT + 255) / 256));
+    const int vec_ok = (g.W % M == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0);
+    hipLaunchKernelGGL((output_transform_nchw_kernel<M, E>), grid, block, 0, s,
+                       Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, vec_ok);
+    return hipGetLastError();
+}
+
+hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, hipStream_t s) {
+    if (g.m == 2) return f16 ? launch_ot<2, __half>(M, bias, y, g, s) : launch_ot<2, float>(M, bias, y, g, s);
+    return f16 ? launch_ot<4, __half>(M, bias, y, g, s) : launch_ot<4, float>(M, bias, y, g, s);
+}
+
+}  // namespace wino

@@ -1,0 +1,235 @@
+// C-ABI boundary of libwino: argument validation on the host, variant choice,
+// workspace carving, and the chain of launches for the three Winograd steps
+// (Section "Techniques").  Nothing here computes; every step runs in a kernel.
+#include "../../include/wino.h"
+#include "wino_internal.h"
+
+#include <limits.h>
+
+using namespace wino;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool dtype_ok(int d) { return d == WINO_F32 || d == WINO_F16; }
+inline size_t esize(int d) { return d == WINO_F16 ? 2 : 4; }
+inline bool wino_variant_ok(int v) { return v == WINO_F2 || v == WINO_F4; }
+
+// products that must fit: element counts as size_t and tile counts as int
+bool dims_ok(int N, int C, int H, int W, int K, int m) {
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1) return false;
+    if (C > (1 << 22) || K > (1 << 22)) return false;      // grid.y of the transform kernels carries C/64
+    const unsigned long long lim = 1ULL << 40;    // elements; far above 288 GB of fp16 already
+    const unsigned long long th = (unsigned long long)(H + m - 1) / m, tw = (unsigned long long)(W + m - 1) / m;
+    const unsigned long long T = (unsigned long long)N * th * tw;
+    if (T > (unsigned long long)INT_MAX / 2) return false;
+    const unsigned long long a2 = (unsigned long long)(m + 2) * (m + 2);
+    const unsigned long long Cp = (unsigned long long)(C + 7) / 8 * 8;
+    if ((unsigned long long)N * C * H > lim / W) return false;
+    if ((unsigned long long)N * K * H > lim / W) return false;
+    if (a2 * T > lim / Cp) return false;
+    if (a2 * T > lim / (unsigned long long)K) return false;
+    if (a2 * (unsigned long long)K > lim / Cp) return false;
+    if ((unsigned long long)K * T > (unsigned long long)INT_MAX * 128ULL) return false;
+    return true;
+}
+
+struct Workspace { size_t v_bytes, m_bytes, total; };
+Workspace workspace_layout(const Geom& g, int dtype) {
+    Workspace ws;
+    const size_t a2 = (size_t)g.alpha * g.alpha;
+    ws.v_bytes = align_up(a2 * (size_t)g.T * g.Cp * esize(dtype));
+    ws.m_bytes = align_up(a2 * (size_t)g.K * g.T * sizeof(float));
+    ws.total = ws.v_bytes + ws.m_bytes;
+    return ws;
+}
+
+int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y, const Geom& g,
+              void* workspace, hipStream_t s) {
+    const bool f16 = w_t->dtype == WINO_F16;
+    const Workspace ws = workspace_layout(g, w_t->dtype);
+    void* V = workspace;
+    float* M = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + ws.v_bytes);
+    if (launch_input_transform(x, V, g, f16, s) != hipSuccess) return WINO_ERR_HIP;
+    if (launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, g.alpha * g.alpha, f16, s) != hipSuccess) return WINO_ERR_HIP;
+    if (launch_output_transform(M, bias, y, g, f16, s) != hipSuccess) return WINO_ERR_HIP;
+    return WINO_OK;
+}
+
+int check_conv_args(const void* x, const wino_filter* w_t, const float* bias, const void* y,
+                    int N, int C, int H, int W, int K) {
+    if (!x || !w_t || !y || !w_t->data) return WINO_ERR_NULL;
+    if (!dtype_ok(w_t->dtype)) return WINO_ERR_DTYPE;
+    if (!wino_variant_ok(w_t->variant)) return WINO_ERR_VARIANT;
+    if (!dims_ok(N, C, H, W, K, w_t->variant)) return WINO_ERR_DIM;
+    if (w_t->K != K || w_t->C != C) return WINO_ERR_DIM;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(w_t->data) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)))
+        return WINO_ERR_ALIGN;
+    const size_t es = esize(w_t->dtype);
+    const uintptr_t xb = reinterpret_cast<uintptr_t>(x), xe = xb + (size_t)N * C * H * W * es;
+    const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + (size_t)N * K * H * W * es;
+    if (xb < ye && yb < xe) return WINO_ERR_ALIAS;
+    return WINO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int wino_version(void) { return 100; }   // 0.1.0
+
+const char* wino_status_string(int status) {
+    switch (status) {
+        case WINO_OK: return "ok";
+        case WINO_ERR_NULL: return "required pointer is NULL";
+        case WINO_ERR_DIM: return "bad dimension (non-positive, mismatching the transformed filter, or too large)";
+        case WINO_ERR_DTYPE: return "unsupported dtype";
+        case WINO_ERR_VARIANT: return "unsupported variant";
+        case WINO_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case WINO_ERR_WORKSPACE: return "workspace missing or too small";
+        case WINO_ERR_ALIAS: return "x and y overlap";
+        case WINO_ERR_HIP: return "HIP call failed";
+        case WINO_ERR_LAYOUT: return "unsupported layout";
+        default: return "unknown status";
+    }
+}
+
+int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int variant) {
+    if (!dtype_ok(dtype)) return -1;
+    if (variant == WINO_DIRECT || variant == WINO_F2 || variant == WINO_F4) {
+        return dims_ok(N, C, H, W, K, variant == WINO_F2 ? 2 : 4) ? variant : -1;
+    }
+    if (variant != WINO_AUTO) return -1;
+    if (!dims_ok(N, C, H, W, K, 2) || !dims_ok(N, C, H, W, K, 4)) return -1;
+    // Traffic model of the three-kernel chain (bytes moved once each): x + 2V + U + 2M + y.
+    // F4 moves fewer activation bytes but a 2.25x larger U, which dominates for tiny images.
+    double bytes[2];
+    for (int i = 0; i < 2; ++i) {
+        const Geom g = make_geom(N, C, H, W, K, i == 0 ? 2 : 4);
+        const double a2 = (double)g.alpha * g.alpha, e = (double)esize(dtype);
+        bytes[i] = (double)N * C * H * W * e + 2.0 * a2 * g.T * g.Cp * e + a2 * (double)K * g.Cp * e +
+                   2.0 * a2 * (double)K * g.T * 4.0 + (double)N * K * H * W * e;
+    }
+    const int pick = bytes[0] < bytes[1] ? WINO_F2 : WINO_F4;
+    return pick;
+}
+
+int wino_transformed_dims(int N, int C, int H, int W, int K, int variant, int* alpha, int* Cp, int* T) {
+    if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
+    if (!dims_ok(N, C, H, W, K, variant)) return WINO_ERR_DIM;
+    const Geom g = make_geom(N, C, H, W, K, variant);
+    if (alpha) *alpha = g.alpha;
+    if (Cp) *Cp = g.Cp;
+    if (T) *T = g.T;
+    return WINO_OK;
+}
+
+size_t wino_filter_bytes(int K, int C, int dtype, int variant) {
+    if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !dims_ok(1, C, 1, 1, K, variant)) return 0;
+    const size_t a = variant + 2;
+    return a * a * (size_t)K * (size_t)round_up(C, 8) * esize(dtype);
+}
+
+size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int dtype, int variant) {
+    if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !dims_ok(N, C, H, W, K, variant)) return 0;
+    return workspace_layout(make_geom(N, C, H, W, K, variant), dtype).total;
+}
+
+int wino_filter_transform(const void* w, void* w_t_data, int K, int C, int dtype, int variant,
+                          wino_filter* out, void* stream) {
+    if (!w || !w_t_data || !out) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
+    if (!dims_ok(1, C, 1, 1, K, variant) || K > 65535) return WINO_ERR_DIM;   // grid.y carries k
+    if (!aligned16(w) || !aligned16(w_t_data)) return WINO_ERR_ALIGN;
+    if (launch_filter_transform(w, w_t_data, K, C, round_up(C, 8), variant, dtype == WINO_F16,
+                                static_cast<hipStream_t>(stream)) != hipSuccess)
+        return WINO_ERR_HIP;
+    out->data = w_t_data; out->K = K; out->C = C; out->dtype = dtype; out->variant = variant;
+    return WINO_OK;
+}
+
+int wino_conv2d_ex(const void* x, const wino_filter* w_t, const float* bias, void* y,
+                   int N, int C, int H, int W, int K, int layout,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_conv_args(x, w_t, bias, y, N, C, H, W, K);
+    if (rc != WINO_OK) return rc;
+    if (layout != WINO_NCHW) return WINO_ERR_LAYOUT;
+    const Geom g = make_geom(N, C, H, W, K, w_t->variant);
+    const Workspace ws = workspace_layout(g, w_t->dtype);
+    if (!workspace || workspace_bytes < ws.total) return WINO_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return WINO_ERR_ALIGN;
+    return run_chain(x, w_t, bias, y, g, workspace, static_cast<hipStream_t>(stream));
+}
+
+int wino_conv2d(const void* x, const wino_filter* w_t, const float* bias, void* y,
+                int N, int C, int H, int W, int K, void* stream) {
+    const int rc = check_conv_args(x, w_t, bias, y, N, C, H, W, K);
+    if (rc != WINO_OK) return rc;
+    const Geom g = make_geom(N, C, H, W, K, w_t->variant);
+    const Workspace ws = workspace_layout(g, w_t->dtype);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    void* workspace = nullptr;
+    if (hipMallocAsync(&workspace, ws.total, s) != hipSuccess || !workspace) return WINO_ERR_HIP;
+    const int rc2 = run_chain(x, w_t, bias, y, g, workspace, s);
+    if (hipFreeAsync(workspace, s) != hipSuccess) return WINO_ERR_HIP;
+    return rc2;
+}
+
+int wino_input_transform(const void* x, void* V, int N, int C, int H, int W,
+                         int dtype, int variant, int layout, void* stream) {
+    if (!x || !V) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
+    if (layout != WINO_NCHW) return WINO_ERR_LAYOUT;
+    if (!dims_ok(N, C, H, W, 1, variant)) return WINO_ERR_DIM;
+    if (!aligned16(x) || !aligned16(V)) return WINO_ERR_ALIGN;
+    const Geom g = make_geom(N, C, H, W, 1, variant);
+    return launch_input_transform(x, V, g, dtype == WINO_F16, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? WINO_OK : WINO_ERR_HIP;
+}
+
+int wino_batched_gemm(const void* U, const void* V, float* M, int K, int C, int T,
+                      int dtype, int variant, void* stream) {
+    if (!U || !V || !M) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
+    if (K < 1 || C < 1 || T < 1 || T > INT_MAX / 2 || !dims_ok(1, C, 1, 1, K, variant)) return WINO_ERR_DIM;
+    const unsigned long long a2 = (unsigned long long)(variant + 2) * (variant + 2);
+    if (a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)round_up(C, 8) ||
+        a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)K) return WINO_ERR_DIM;
+    if (!aligned16(U) || !aligned16(V) || !aligned16(M)) return WINO_ERR_ALIGN;
+    return launch_batched_gemm(U, V, M, K, round_up(C, 8), T, (int)a2, dtype == WINO_F16,
+                               static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+}
+
+int wino_output_transform(const float* M, const float* bias, void* y, int N, int K, int H, int W,
+                          int dtype, int variant, int layout, void* stream) {
+    if (!M || !y) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
+    if (layout != WINO_NCHW) return WINO_ERR_LAYOUT;
+    if (!dims_ok(N, 1, H, W, K, variant)) return WINO_ERR_DIM;
+    if (!aligned16(M) || !aligned16(y)) return WINO_ERR_ALIGN;
+    const Geom g = make_geom(N, 1, H, W, K, variant);
+    return launch_output_transform(M, bias, y, g, dtype == WINO_F16, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? WINO_OK : WINO_ERR_HIP;
+}
+
+int wino_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
+                       int N, int C, int H, int W, int K, int dtype, void* stream) {
+    if (!x || !w || !y) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (!dims_ok(N, C, H, W, K, 2)) return WINO_ERR_DIM;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return WINO_ERR_ALIGN;
+    const size_t es = esize(dtype);
+    const uintptr_t xb = reinterpret_cast<uintptr_t>(x), xe = xb + (size_t)N * C * H * W * es;
+    const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + (size_t)N * K * H * W * es;
+    if (xb < ye && yb < xe) return WINO_ERR_ALIAS;
+    return launch_direct_conv2d(x, w, bias, y, N, C, H, W, K, dtype == WINO_F16,
+                                static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+}
+
+}  // extern "C"

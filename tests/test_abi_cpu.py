@@ -1,0 +1,112 @@
+"""Host-side checks of the C-ABI boundary that need no GPU: the library loads, exports every
+symbol the header declares, answers size queries, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2412_05781_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2412_05781_amd.build import build_libwino
+        build_libwino()
+    return B.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "wino.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(wino_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_library_agree(L):
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS), (names, B.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_status_strings(L):
+    assert B.wino_version() >= 100
+    seen = {B.status_string(s) for s in range(0, 10)}
+    assert len(seen) == 10 and "ok" in seen
+    assert B.status_string(12345) == "unknown status"
+
+
+def test_sizes(L):
+    # U[alpha^2][K][Cp]
+    assert B.wino_filter_bytes(320, 320, B.WINO_F16, B.WINO_F4) == 36 * 320 * 320 * 2
+    assert B.wino_filter_bytes(320, 4, B.WINO_F32, B.WINO_F2) == 16 * 320 * 8 * 4      # C padded to 8
+    assert B.wino_filter_bytes(320, 320, B.WINO_F16, B.WINO_AUTO) == 0
+    assert B.wino_filter_bytes(0, 320, B.WINO_F16, B.WINO_F2) == 0
+    assert B.wino_filter_bytes(8, 8, 7, B.WINO_F2) == 0
+    assert B.wino_transformed_dims(2, 320, 64, 64, 320, B.WINO_F4) == (6, 320, 512)
+    assert B.wino_transformed_dims(2, 320, 64, 64, 320, B.WINO_F2) == (4, 320, 2048)
+    assert B.wino_transformed_dims(1, 5, 7, 9, 3, B.WINO_F4) == (6, 8, 2 * 3)
+    ws = B.wino_workspace_bytes(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_F4)
+    assert ws == 36 * 512 * 320 * 2 + 36 * 320 * 512 * 4
+    assert B.wino_workspace_bytes(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_DIRECT) == 0
+    assert B.wino_workspace_bytes(2, 320, 64, -1, 320, B.WINO_F16, B.WINO_F4) == 0
+
+
+def test_resolve_variant(L):
+    assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_F2) == B.WINO_F2
+    assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
+    # 8x8 images with wide channels: the transformed filter dominates the traffic, F2's is 2.25x smaller
+    assert B.wino_resolve_variant(2, 1280, 8, 8, 1280, B.WINO_F16, B.WINO_AUTO) == B.WINO_F2
+    assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, 3) == -1
+    assert B.wino_resolve_variant(2, 320, 64, 64, 320, 9, B.WINO_AUTO) == -1
+    assert B.wino_resolve_variant(0, 320, 64, 64, 320, B.WINO_F16, B.WINO_AUTO) == -1
+
+
+def test_argument_validation_happens_before_any_launch(L):
+    vp = ctypes.c_void_p
+    desc = B.wino_filter()
+    good = vp(0x1000)
+    # filter transform
+    assert L.wino_filter_transform(None, good, 8, 8, B.WINO_F16, B.WINO_F4, ctypes.byref(desc), None) == B.WINO_ERR_NULL
+    assert L.wino_filter_transform(good, good, 8, 8, B.WINO_F16, B.WINO_F4, None, None) == B.WINO_ERR_NULL
+    assert L.wino_filter_transform(good, good, 8, 8, 5, B.WINO_F4, ctypes.byref(desc), None) == B.WINO_ERR_DTYPE
+    assert L.wino_filter_transform(good, good, 8, 8, B.WINO_F16, B.WINO_AUTO, ctypes.byref(desc), None) == B.WINO_ERR_VARIANT
+    assert L.wino_filter_transform(good, good, 0, 8, B.WINO_F16, B.WINO_F4, ctypes.byref(desc), None) == B.WINO_ERR_DIM
+    assert L.wino_filter_transform(vp(0x1004), good, 8, 8, B.WINO_F16, B.WINO_F4, ctypes.byref(desc), None) == B.WINO_ERR_ALIGN
+    # conv
+    desc.data, desc.K, desc.C, desc.dtype, desc.variant = 0x2000, 8, 8, B.WINO_F16, B.WINO_F4
+    args = dict(N=1, C=8, H=4, W=4, K=8)
+    call = lambda x, y, d=desc, ws=vp(0x100000), wsb=1 << 30, layout=0, **kw: L.wino_conv2d_ex(
+        x, ctypes.byref(d), None, y, kw.get("N", 1), kw.get("C", 8), kw.get("H", 4), kw.get("W", 4), kw.get("K", 8),
+        layout, ws, wsb, None)
+    assert call(None, vp(0x9000)) == B.WINO_ERR_NULL
+    assert call(vp(0x8000), None) == B.WINO_ERR_NULL
+    assert call(vp(0x8000), vp(0x9000), H=0) == B.WINO_ERR_DIM
+    assert call(vp(0x8000), vp(0x9000), C=16) == B.WINO_ERR_DIM           # mismatches the transformed filter
+    assert call(vp(0x8008), vp(0x9000)) == B.WINO_ERR_ALIGN
+    assert call(vp(0x8000), vp(0x8010)) == B.WINO_ERR_ALIAS               # 1*8*4*4*2 = 256 bytes each
+    assert call(vp(0x8000), vp(0x9000), wsb=16) == B.WINO_ERR_WORKSPACE
+    assert call(vp(0x8000), vp(0x9000), ws=None) == B.WINO_ERR_WORKSPACE
+    assert call(vp(0x8000), vp(0x9000), layout=3) == B.WINO_ERR_LAYOUT
+    bad = B.wino_filter(); bad.data, bad.K, bad.C, bad.dtype, bad.variant = 0x2000, 8, 8, B.WINO_F16, B.WINO_AUTO
+    assert call(vp(0x8000), vp(0x9000), d=bad) == B.WINO_ERR_VARIANT
+    assert L.wino_conv2d(None, ctypes.byref(desc), None, vp(0x9000), 1, 8, 4, 4, 8, None) == B.WINO_ERR_NULL
+    # stages and direct fallback
+    assert L.wino_input_transform(None, good, 1, 8, 4, 4, B.WINO_F16, B.WINO_F4, 0, None) == B.WINO_ERR_NULL
+    assert L.wino_input_transform(good, good, 1, 8, 4, 4, B.WINO_F16, B.WINO_DIRECT, 0, None) == B.WINO_ERR_VARIANT
+    assert L.wino_batched_gemm(good, good, None, 8, 8, 4, B.WINO_F16, B.WINO_F4, None) == B.WINO_ERR_NULL
+    assert L.wino_batched_gemm(good, good, good, 8, 8, 0, B.WINO_F16, B.WINO_F4, None) == B.WINO_ERR_DIM
+    assert L.wino_output_transform(good, None, None, 1, 8, 4, 4, B.WINO_F16, B.WINO_F4, 0, None) == B.WINO_ERR_NULL
+    assert L.wino_output_transform(good, None, good, 1, 8, 4, 4, 2, B.WINO_F4, 0, None) == B.WINO_ERR_DTYPE
+    assert L.wino_direct_conv2d(good, None, None, good, 1, 8, 4, 4, 8, B.WINO_F16, None) == B.WINO_ERR_NULL
+    assert L.wino_direct_conv2d(vp(0x8000), good, None, vp(0x8000), 1, 8, 4, 4, 8, B.WINO_F16, None) == B.WINO_ERR_ALIAS
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        B.lib()

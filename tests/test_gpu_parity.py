@@ -1,0 +1,150 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Tolerances (relative L2 over the whole output tensor): 1e-5 for fp32 storage, 5e-3 for fp16
+storage with fp32 accumulation.  Stage checks compare each kernel with the matching step of
+the fp64 Winograd reference (Section "Techniques", steps (i)-(iii))."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import winograd_ref as wr
+from paper_2412_05781_amd import binding as B
+from paper_2412_05781_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "f16": 5e-3}
+DEV = "cuda:0"
+
+
+def _run(x, w, b, variant):
+    xd, wd = x.to(DEV), w.to(DEV)
+    bd = None if b is None else b.to(DEV)
+    y = B.conv2d(xd, wd, bd, variant)
+    torch.cuda.synchronize()
+    return y.float().cpu().numpy().astype(np.float64)
+
+
+def _np(t):
+    return t.float().numpy().astype(np.float64)
+
+
+SMALL = [
+    # N, C, K, H, W  — odd sizes, ragged tiles, channel counts off the MFMA tile
+    (1, 1, 1, 1, 1), (1, 4, 3, 2, 3), (2, 5, 7, 5, 7), (3, 8, 16, 9, 13), (1, 33, 65, 17, 30),
+    (2, 64, 130, 33, 9), (1, 100, 40, 12, 40), (2, 136, 200, 16, 16), (1, 72, 129, 70, 6),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4, B.WINO_DIRECT])
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_shapes_full_tensor(shape, variant, dtype):
+    N, C, K, H, W = shape
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=1000 + sum(shape))
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    y = _run(x, w, b, variant)
+    assert y.shape == ref.shape
+    err = oracle.rel_l2(y, ref)
+    assert err <= TOL[dtype], (shape, variant, dtype, err)
+
+
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+def test_no_bias_and_zero_input(variant):
+    x, w, b = synth.make_inputs(2, 16, 24, 10, 11, "f32", seed=5)
+    ref = oracle.conv2d_direct(_np(x), _np(w), None)
+    assert oracle.rel_l2(_run(x, w, None, variant), ref) <= 1e-5
+    # all-zero input: the output is exactly the bias
+    y0 = _run(torch.zeros_like(x), w, b, variant)
+    assert np.array_equal(y0, np.broadcast_to(_np(b).reshape(1, -1, 1, 1), y0.shape))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+def test_stage_by_stage(variant, dtype):
+    m = variant
+    N, C, K, H, W = 2, 40, 72, 13, 18
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=77)
+    xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
+    alpha, Cp, T = B.wino_transformed_dims(N, C, H, W, K, variant)
+    a2 = alpha * alpha
+    eps = 2.0 ** -11 if dtype == "f16" else 2.0 ** -24
+
+    # step (i), filter
+    filt = B.wino_filter_transform(wd, variant)
+    U = filt.buf.view(x.dtype).view(a2, K, Cp)
+    U_ref = wr.filter_transform(_np(w), m).reshape(a2, K, C)
+    Uh = U.float().cpu().numpy().astype(np.float64)
+    assert np.all(Uh[:, :, C:] == 0)
+    assert np.abs(Uh[:, :, :C] - U_ref).max() <= 4 * eps * np.abs(U_ref).max()
+
+    # step (i), activation
+    V = B.wino_input_transform(xd, variant)
+    V_ref = wr.input_transform(_np(x), m).reshape(a2, C, T).transpose(0, 2, 1)
+    Vh = V.float().cpu().numpy().astype(np.float64)
+    assert Vh.shape == (a2, T, Cp) and np.all(Vh[:, :, C:] == 0)
+    assert np.abs(Vh[:, :, :C] - V_ref).max() <= 4 * eps * np.abs(V_ref).max()
+
+    # step (ii): compare with the fp64 product of the *stored* U and V
+    M = B.wino_batched_gemm(U, V, K, C, T, variant)
+    M_ref = np.einsum("bkc,btc->bkt", Uh, Vh)
+    Mh = M.cpu().numpy().astype(np.float64)
+    assert oracle.rel_l2(Mh, M_ref) <= 1e-6
+
+    # step (iii): compare with A^T M A of the stored M
+    y = B.wino_output_transform(M, bd, N, K, H, W, x.dtype, variant)
+    y_ref = wr.output_transform(Mh.reshape(alpha, alpha, K, T), _np(b), N, H, W, m)
+    torch.cuda.synchronize()
+    assert oracle.rel_l2(y.float().cpu().numpy(), y_ref) <= (1e-6 if dtype == "f32" else 6e-4)
+
+
+@pytest.mark.parametrize("name", ["A_conv_in", "B_resblock"])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+def test_baseline_configs_full_tensor(name, variant):
+    layer = synth.LAYERS[name]
+    x, w, b = synth.make_layer_inputs(layer)
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    err = oracle.rel_l2(_run(x, w, b, variant), ref)
+    print(f"{name} F{variant}: relL2 {err:.3e}")
+    assert err <= TOL[layer.dtype]
+
+
+SWEEP = [l.name for l in synth.ALL_LAYERS if l.name not in ("A_conv_in", "B_resblock")
+         and l.N * l.K * l.H * l.W * l.C <= 2 * 1280 * 1280 * 32 * 32]
+
+
+@pytest.mark.parametrize("name", SWEEP)
+def test_layer_sweep_sampled_outputs(name):
+    """Full-size layers in the launch configuration the bench times (AUTO variant): a seeded
+    sample of outputs against the oracle's one-by-one sum, error measured over the sample."""
+    layer = synth.LAYERS[name]
+    x, w, b = synth.make_layer_inputs(layer)
+    y = _run(x, w, b, B.WINO_AUTO)
+    rng = np.random.default_rng(layer.index)
+    idx = rng.integers(0, y.size, size=4096)
+    ref = oracle.conv2d_direct_at(_np(x), _np(w), _np(b), idx)
+    err = np.linalg.norm(y.ravel()[idx] - ref) / np.linalg.norm(ref)
+    print(f"{name}: sampled relL2 {err:.3e}")
+    assert err <= TOL[layer.dtype]
+    assert np.isfinite(y).all()
+
+
+def test_run_to_run_determinism():
+    x, w, b = synth.make_inputs(2, 96, 80, 20, 20, "f16", seed=3)
+    xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
+    y1 = B.conv2d(xd, wd, bd, B.WINO_F4).clone()
+    y2 = B.conv2d(xd, wd, bd, B.WINO_F4)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+
+
+def test_stream_ordered_entry_point_matches_explicit_workspace():
+    x, w, b = synth.make_inputs(1, 32, 48, 12, 12, "f16", seed=4)
+    xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
+    w_t = B.wino_filter_transform(wd, B.WINO_F4)
+    y1 = torch.empty((1, 48, 12, 12), dtype=torch.float16, device=DEV)
+    B.wino_conv2d(xd, w_t, bd, y1)
+    y2 = B.conv2d(xd, wd, bd, B.WINO_F4)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
