@@ -103,6 +103,18 @@ def _check(status: int, where: str):
         raise WinoError(status, where)
 
 
+def _conv_shapes(x, w_t, bias, y):
+    """Host-side shape/dtype agreement (the C side cannot see tensor extents)."""
+    N, C, H, W = map(int, x.shape)
+    K = int(w_t.desc.K)
+    dt = TORCH_OF[w_t.desc.dtype]
+    if tuple(y.shape) != (N, K, H, W) or x.dtype != dt or y.dtype != dt:
+        raise ValueError(f"expected y[{N},{K},{H},{W}] and dtype {dt} for x and y")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != K or not bias.is_cuda):
+        raise ValueError("bias must be a GPU fp32 tensor of K elements")
+    return N, C, H, W, K
+
+
 # ---- same names as the C ABI ------------------------------------------------------------------
 def wino_version() -> int:
     return lib().wino_version()
@@ -164,8 +176,7 @@ def wino_filter_transform(w: torch.Tensor, variant: int, stream=None) -> Filter:
 
 def wino_conv2d(x: torch.Tensor, w_t: Filter, bias: Optional[torch.Tensor], y: torch.Tensor, stream=None) -> torch.Tensor:
     _dev(x, "x"); _dev(y, "y")
-    N, C, H, W = map(int, x.shape)
-    K = int(y.shape[1])
+    N, C, H, W, K = _conv_shapes(x, w_t, bias, y)
     _check(lib().wino_conv2d(_ptr(x), ctypes.byref(w_t.desc), _ptr(bias), _ptr(y), N, C, H, W, K, _stream(stream)),
            "wino_conv2d")
     return y
@@ -173,39 +184,50 @@ def wino_conv2d(x: torch.Tensor, w_t: Filter, bias: Optional[torch.Tensor], y: t
 
 def wino_conv2d_ex(x, w_t: Filter, bias, y, workspace: torch.Tensor, layout: int = WINO_NCHW, stream=None):
     _dev(x, "x"); _dev(y, "y"); _dev(workspace, "workspace")
-    N, C, H, W = map(int, x.shape)
-    K = int(y.shape[1])
+    N, C, H, W, K = _conv_shapes(x, w_t, bias, y)
     _check(lib().wino_conv2d_ex(_ptr(x), ctypes.byref(w_t.desc), _ptr(bias), _ptr(y), N, C, H, W, K, layout,
                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "wino_conv2d_ex")
     return y
 
 
-def wino_input_transform(x: torch.Tensor, variant: int, layout: int = WINO_NCHW, stream=None) -> torch.Tensor:
+def wino_input_transform(x: torch.Tensor, variant: int, layout: int = WINO_NCHW, stream=None, out=None) -> torch.Tensor:
     """x[N,C,H,W] -> V[alpha^2, T, Cp] (same dtype)."""
     _dev(x, "x")
     N, C, H, W = map(int, x.shape)
     alpha, Cp, T = wino_transformed_dims(N, C, H, W, 1, variant)
-    V = torch.empty((alpha * alpha, T, Cp), dtype=x.dtype, device=x.device)
+    V = out if out is not None else torch.empty((alpha * alpha, T, Cp), dtype=x.dtype, device=x.device)
+    if V.numel() < alpha * alpha * T * Cp or V.dtype != x.dtype:
+        raise ValueError("V buffer too small or of the wrong dtype")
     _check(lib().wino_input_transform(_ptr(x), _ptr(V), N, C, H, W, DTYPE_OF[x.dtype], variant, layout, _stream(stream)),
            "wino_input_transform")
     return V
 
 
-def wino_batched_gemm(U: torch.Tensor, V: torch.Tensor, K: int, C: int, T: int, variant: int, stream=None) -> torch.Tensor:
+def wino_batched_gemm(U: torch.Tensor, V: torch.Tensor, K: int, C: int, T: int, variant: int, stream=None, out=None) -> torch.Tensor:
     """U[alpha^2,K,Cp], V[alpha^2,T,Cp] -> M[alpha^2,K,T] fp32."""
     _dev(U, "U"); _dev(V, "V")
     a2 = (variant + 2) ** 2
-    M = torch.empty((a2, K, T), dtype=torch.float32, device=U.device)
+    Cp = (C + 7) // 8 * 8
+    if U.numel() < a2 * K * Cp or V.numel() < a2 * T * Cp or U.dtype != V.dtype:
+        raise ValueError("U or V buffer too small for these dimensions")
+    M = out if out is not None else torch.empty((a2, K, T), dtype=torch.float32, device=U.device)
+    if M.numel() < a2 * K * T or M.dtype != torch.float32:
+        raise ValueError("M buffer too small or not fp32")
     _check(lib().wino_batched_gemm(_ptr(U), _ptr(V), _ptr(M), K, C, T, DTYPE_OF[U.dtype], variant, _stream(stream)),
            "wino_batched_gemm")
     return M
 
 
 def wino_output_transform(M: torch.Tensor, bias, N: int, K: int, H: int, W: int, dtype: torch.dtype,
-                          variant: int, layout: int = WINO_NCHW, stream=None) -> torch.Tensor:
+                          variant: int, layout: int = WINO_NCHW, stream=None, out=None) -> torch.Tensor:
     _dev(M, "M")
-    y = torch.empty((N, K, H, W), dtype=dtype, device=M.device)
+    m = variant
+    if M.numel() < (m + 2) ** 2 * K * N * (-(-H // m)) * (-(-W // m)) or M.dtype != torch.float32:
+        raise ValueError("M buffer too small or not fp32")
+    y = out if out is not None else torch.empty((N, K, H, W), dtype=dtype, device=M.device)
+    if y.numel() < N * K * H * W or y.dtype != dtype:
+        raise ValueError("y buffer too small or of the wrong dtype")
     _check(lib().wino_output_transform(_ptr(M), _ptr(bias), _ptr(y), N, K, H, W, DTYPE_OF[dtype], variant, layout,
                                        _stream(stream)), "wino_output_transform")
     return y
@@ -215,6 +237,10 @@ def wino_direct_conv2d(x: torch.Tensor, w: torch.Tensor, bias, y: torch.Tensor, 
     _dev(x, "x"); _dev(w, "w"); _dev(y, "y")
     N, C, H, W = map(int, x.shape)
     K = int(w.shape[0])
+    if tuple(w.shape) != (K, C, 3, 3) or tuple(y.shape) != (N, K, H, W) or w.dtype != x.dtype or y.dtype != x.dtype:
+        raise ValueError("direct conv: need w[K,C,3,3], y[N,K,H,W], one dtype")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != K or not bias.is_cuda):
+        raise ValueError("bias must be a GPU fp32 tensor of K elements")
     _check(lib().wino_direct_conv2d(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), N, C, H, W, K, DTYPE_OF[x.dtype], _stream(stream)),
            "wino_direct_conv2d")
     return y
