@@ -87,14 +87,107 @@ input_transform_nchw_kernel(const E* __restrict__ x, E* __restrict__ V,
     }
 }
 
+// Fast path for rows that are whole 16-byte chunks (W*sizeof(E) a multiple of 16): the patch is
+// fetched as 16-byte chunks, all loads of a lane issued before the first LDS write, so one global
+// round trip covers the whole patch.  Patch columns run from m*tj0 - EPC to m*(tj0+TJ) + EPC
+// (EPC = elements per chunk); a chunk is either wholly inside the image or wholly outside (zero).
+template <int M, typename E, int CB, int TJ>
+__global__ void __launch_bounds__(256)
+input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
+                                int N, int C, int H, int W, int th, int tw, int T, int Cp, int strips_per_row) {
+    constexpr int A = M + 2;
+    constexpr int EPC = 16 / (int)sizeof(E);
+    static_assert((M * TJ) % EPC == 0, "strip width must be whole chunks");
+    constexpr int NCH = (M * TJ) / EPC + 2;              // chunks per patch row
+    constexpr int ROWW = NCH * 4;                        // 32-bit words per patch row
+    constexpr int CSW = (A * ROWW) | 1;                  // words per channel, odd: lanes = channels hit distinct banks
+    constexpr int TOTAL = CB * A * NCH;                  // chunks per patch
+    constexpr int NL = (TOTAL + 255) / 256;
+    __shared__ uint32_t patch[CB * CSW];
+
+    const int tid = threadIdx.x;
+    int sidx = blockIdx.x;
+    const int js = sidx % strips_per_row; sidx /= strips_per_row;
+    const int ti = sidx % th;
+    const int n = sidx / th;
+    const int tj0 = js * TJ;
+    const int c0 = blockIdx.y * CB;
+    const int row0 = M * ti - 1;
+    const int col0 = M * tj0 - EPC;
+
+    uint4 reg[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int q = tid + i * 256;
+        const int cc = q / (A * NCH);
+        const int rem = q - cc * (A * NCH);
+        const int a = rem / NCH, ch = rem - a * NCH;
+        const int r = row0 + a, col = col0 + ch * EPC, c = c0 + cc;
+        reg[i] = make_uint4(0, 0, 0, 0);
+        if (q < TOTAL && c < C && r >= 0 && r < H && col >= 0 && col + EPC <= W)
+            reg[i] = *reinterpret_cast<const uint4*>(x + (((size_t)n * C + c) * H + r) * W + col);
+    }
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int q = tid + i * 256;
+        if (q < TOTAL) {
+            const int cc = q / (A * NCH);
+            const int rem = q - cc * (A * NCH);
+            uint32_t* dst = patch + cc * CSW + rem * 4;
+            dst[0] = reg[i].x; dst[1] = reg[i].y; dst[2] = reg[i].z; dst[3] = reg[i].w;
+        }
+    }
+    __syncthreads();
+
+    const int cc = tid % CB;
+    const int c = c0 + cc;
+    constexpr int TILES_PER_ITER = 256 / CB;
+    const size_t plane = (size_t)T * Cp;
+    const E* pch = reinterpret_cast<const E*>(patch + cc * CSW);
+    for (int tl = tid / CB; tl < TJ; tl += TILES_PER_ITER) {
+        const int tj = tj0 + tl;
+        if (tj >= tw || c >= Cp) continue;
+        const E* p = pch + (EPC - 1) + M * tl;
+        float d[A][A];
+#pragma unroll
+        for (int a = 0; a < A; ++a)
+#pragma unroll
+            for (int b = 0; b < A; ++b) d[a][b] = to_f32<E>(p[a * (NCH * EPC) + b]);
+        float tmp[A][A];
+#pragma unroll
+        for (int b = 0; b < A; ++b) {
+            float in[A], out[A];
+#pragma unroll
+            for (int a = 0; a < A; ++a) in[a] = d[a][b];
+            bt_1d<M>(in, out);
+#pragma unroll
+            for (int a = 0; a < A; ++a) tmp[a][b] = out[a];
+        }
+        const size_t t = ((size_t)n * th + ti) * tw + tj;
+        E* dst = V + t * Cp + c;
+#pragma unroll
+        for (int xi = 0; xi < A; ++xi) {
+            float out[A];
+            bt_1d<M>(tmp[xi], out);
+#pragma unroll
+            for (int nu = 0; nu < A; ++nu) dst[(size_t)(xi * A + nu) * plane] = from_f32<E>(out[nu]);
+        }
+    }
+}
+
 template <int M, typename E>
 static hipError_t launch_it(const void* x, void* V, const Geom& g, hipStream_t s) {
     constexpr int CB = 64;
     constexpr int TJ = (M == 4) ? 8 : 16;
     const int strips = (g.tw + TJ - 1) / TJ;
     dim3 block(256), grid((unsigned)(g.N * g.th * strips), (unsigned)((g.Cp + CB - 1) / CB));
-    hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ>), grid, block, 0, s,
-                       (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips);
+    const bool rows_are_chunks = ((size_t)g.W * sizeof(E)) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+    if (rows_are_chunks)
+        hipLaunchKernelGGL((input_transform_nchw_vec_kernel<M, E, CB, TJ>), grid, block, 0, s,
+                           (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips);
+    else
+        hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ>), grid, block, 0, s,
+                           (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips);
     return hipGetLastError();
 }
 

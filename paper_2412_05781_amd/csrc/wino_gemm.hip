@@ -5,23 +5,25 @@
 // the MFMA units with fp32 accumulation.
 //
 // Both operands are row-major with the reduction index contiguous, so a lane's
-// MFMA fragment is one 16-byte load.  A workgroup owns a BM x BN block of one
-// batch; 4 waves in a 2x2 grid, each wave (BM/2)x(BN/2) as 32x32 MFMA tiles.
-// Stages of 128 bytes per row (64 fp16 / 32 fp32 reduction elements) go global
-// -> registers -> LDS (rows padded by 16 bytes: conflict-free 128-bit reads),
-// double-buffered so the next stage's global loads fly during the MFMAs.
-// Rows beyond K / T and reduction chunks beyond Cp are staged as zeros.
+// MFMA fragment is one 16-byte LDS read.  A workgroup (4 waves, 2x2) owns a
+// BM x BN block of one batch; each wave (BM/2)x(BN/2) as 32x32 MFMA tiles.
+// The reduction is cut into stages of RB bytes per row.  Stages travel
+// global -> LDS directly (global_load_lds, 16 bytes per lane, no staging
+// registers) through a ring of NST slots, so NST-1 stages are in flight while
+// one is being multiplied; one barrier per stage.  LDS rows are unpadded (the
+// DMA writes lanes linearly); bank conflicts are avoided by an XOR swizzle of
+// the 16-byte chunk index, applied on the global-address side when loading and
+// on the LDS-address side when reading fragments.
+// Rows beyond K / T are clamped to the last valid row (their products are never
+// stored); a ragged last reduction stage (Cp not a multiple of the stage) goes
+// through registers with zero fill instead.
 #include "wino_internal.h"
+#include <stdlib.h>
 
 namespace wino {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
-
-constexpr int kRowBytes = 128;                 // reduction bytes per row per stage
-constexpr int kPitch = kRowBytes + 16;         // LDS row pitch
-constexpr int kChunksPerRow = kRowBytes / 16;  // 8
 
 template <typename E> struct Mma;
 template <> struct Mma<__half> {
@@ -40,19 +42,49 @@ template <> struct Mma<float> {
     }
 };
 
-template <typename E, int BM, int BN>
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// One wave-wide global -> LDS transfer: lane l's 16 bytes at `src` land at lds_dst + 16*l
+// (lds_dst wave-uniform).  Written as inline assembly on purpose: the compiler then does not
+// track the transfer and does not drain every outstanding one before each barrier and LDS read;
+// the kernel waits with explicit vmcnt values instead (see the reduction loop).
+typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+__device__ __forceinline__ void dma_load_1k(const void* src, unsigned char* lds_dst) {
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t*)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(m0v), "v"(src) : "memory");   // nothing else in these kernels reads m0
+}
+
+// L2 prefetch: a 4-byte-per-lane transfer into a dump area of LDS that nobody reads.  It has
+// no register destination, so nothing has to stay reserved until the data returns.
+__device__ __forceinline__ void dma_touch(const void* src, unsigned char* lds_dump) {
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t*)lds_dump);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+                 :: "s"(m0v), "v"(src) : "memory");
+}
+
+template <typename E, int BM, int BN, int RB, int NST, int PFD>
 __global__ void __launch_bounds__(256)
 wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __restrict__ Mo,
                  int K, int Cp, int T, int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd) {
-    constexpr int BKE = kRowBytes / (int)sizeof(E);       // reduction elements per stage
-    constexpr int EPC = 16 / (int)sizeof(E);              // elements per 16-byte chunk
-    constexpr int WTM = BM / 2, WTN = BN / 2;             // wave tile
-    constexpr int FM = WTM / 32, FN = WTN / 32;           // 32x32 MFMA tiles per wave
-    constexpr int A_CHUNKS = BM * kChunksPerRow / 256;    // 16-byte chunks per thread per stage
-    constexpr int B_CHUNKS = BN * kChunksPerRow / 256;
-    static_assert(BM % 64 == 0 && BN % 64 == 0, "wave tile must be a multiple of 32");
+    constexpr int CPR = RB / 16;                          // 16-byte chunks per row per stage
+    constexpr int BKE = RB / (int)sizeof(E);              // reduction elements per stage
+    constexpr int EPC = 16 / (int)sizeof(E);              // elements per chunk
+    constexpr int ROWS = BM + BN;
+    constexpr int RPL = 1024 / RB;                        // rows covered by one wave-wide load
+    constexpr int LPW = ROWS / RPL / 4;                   // wave-wide loads per wave per stage
+    constexpr int SWZ_SHIFT = (RB == 128) ? 1 : 2;        // rows per 256-byte bank wrap = 256/RB
+    constexpr int WTM = BM / 2, WTN = BN / 2;
+    constexpr int FM = WTM / 32, FN = WTN / 32;
+    constexpr int STAGE_BYTES = ROWS * RB;
+    static_assert(RB == 128 || RB == 64, "stage row bytes");
+    static_assert(BM % 64 == 0 && BN % 64 == 0 && ROWS % (RPL * 4) == 0, "tile shape");
+    static_assert(NST >= 2 && NST <= 4, "ring depth");
+    static_assert(LPW * (NST - 1) < 64, "vmcnt range");
 
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][(BM + BN) * kPitch];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     // XCD-aware mapping: hardware deals workgroups round-robin to the 8 XCDs, so give
     // each XCD a contiguous range of logical blocks (same batch -> same L2).
@@ -70,38 +102,59 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     const E* Ub = U + (size_t)batch * K * Cp;
     const E* Vb = V + (size_t)batch * T * Cp;
 
-    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
-    auto load_stage = [&](int kt) {
-        const int kbase = kt * BKE;
+    // per-lane source rows of this lane's LPW loads (fixed over the reduction loop)
+    const int lrow = lane / CPR, lchunk = lane % CPR;
+    const E* src[LPW];
+    int src_chunk[LPW];
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            const int q = tid + i * 256;
-            const int r = q / kChunksPerRow, ch = q % kChunksPerRow;
-            const int gr = row_k0 + r, gk = kbase + ch * EPC;
-            ra[i] = (gr < K && gk < Cp) ? *reinterpret_cast<const uint4*>(Ub + (size_t)gr * Cp + gk)
-                                        : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < LPW; ++i) {
+        const int row = (wave + 4 * i) * RPL + lrow;       // row inside the stage, A rows first
+        const int chunk = lchunk ^ ((row >> SWZ_SHIFT) & (CPR - 1));
+        src_chunk[i] = chunk;
+        if (row < BM) {
+            int g = row_k0 + row; g = g < K ? g : K - 1;
+            src[i] = Ub + (size_t)g * Cp + chunk * EPC;
+        } else {
+            int g = row_t0 + (row - BM); g = g < T ? g : T - 1;
+            src[i] = Vb + (size_t)g * Cp + chunk * EPC;
         }
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            const int q = tid + i * 256;
-            const int r = q / kChunksPerRow, ch = q % kChunksPerRow;
-            const int gr = row_t0 + r, gk = kbase + ch * EPC;
-            rb[i] = (gr < T && gk < Cp) ? *reinterpret_cast<const uint4*>(Vb + (size_t)gr * Cp + gk)
-                                        : make_uint4(0, 0, 0, 0);
-        }
+    }
+
+    const int nk = (Cp + BKE - 1) / BKE;
+    const bool ragged = (Cp % BKE) != 0;
+
+    // Every workgroup of an XCD walks the reduction in step, so each stage would be a fresh L2
+    // miss for all of them.  One lane per operand row therefore touches the 128-byte line PFD
+    // stages ahead of the ring, which turns the ring's own loads into L2 hits.
+    static_assert(ROWS <= 256, "one prefetch lane per row");
+    unsigned char* dump = lds + NST * STAGE_BYTES + wave * 256;
+    const unsigned char* pf_row;
+    {
+        const int row = tid < ROWS ? tid : ROWS - 1;
+        if (row < BM) { int g = row_k0 + row; g = g < K ? g : K - 1; pf_row = reinterpret_cast<const unsigned char*>(Ub + (size_t)g * Cp); }
+        else { int g = row_t0 + (row - BM); g = g < T ? g : T - 1; pf_row = reinterpret_cast<const unsigned char*>(Vb + (size_t)g * Cp); }
+    }
+    const int row_bytes = Cp * (int)sizeof(E);
+    const int pf_blocks = (row_bytes + 127) / 128;            // 128-byte lines per operand row
+    auto touch_block = [&](int b) {                           // exactly one transfer per wave per call
+        b = b < pf_blocks ? b : pf_blocks - 1;
+        dma_touch(pf_row + (size_t)b * 128, dump);
     };
-    auto store_stage = [&](int buf) {
-        unsigned char* la = lds[buf];
-        unsigned char* lb = lds[buf] + BM * kPitch;
+
+    auto issue_stage = [&](int kt) {
+        unsigned char* slot = lds + (kt % NST) * STAGE_BYTES;
+        if (ragged && kt == nk - 1) {
+            // last, partial stage: through registers, chunks beyond Cp become zeros
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            const int q = tid + i * 256;
-            *reinterpret_cast<uint4*>(la + (q / kChunksPerRow) * kPitch + (q % kChunksPerRow) * 16) = ra[i];
-        }
+            for (int i = 0; i < LPW; ++i) {
+                const int gk = kt * BKE + src_chunk[i] * EPC;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (gk < Cp) v = *reinterpret_cast<const uint4*>(src[i] + kt * BKE);
+                *reinterpret_cast<uint4*>(slot + (wave + 4 * i) * 1024 + lane * 16) = v;
+            }
+        } else {
 #pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            const int q = tid + i * 256;
-            *reinterpret_cast<uint4*>(lb + (q / kChunksPerRow) * kPitch + (q % kChunksPerRow) * 16) = rb[i];
+            for (int i = 0; i < LPW; ++i) dma_load_1k(src[i] + kt * BKE, slot + (wave + 4 * i) * 1024);
         }
     };
 
@@ -113,31 +166,55 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nk = (Cp + BKE - 1) / BKE;
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
+    // prologue: touch the lines of the first NST-1+PFD stages, then start the ring
+    {
+        const int ahead = PFD > 0 ? ((NST - 1 + PFD) * RB + 127) / 128 : 0;
+        for (int b = 0; b < ahead && b < pf_blocks; ++b) touch_block(b);
+    }
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < nk) issue_stage(s);
 
     const int frag_row = lane & 31, frag_half = lane >> 5;
     for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_stage(kt + 1);
-        const unsigned char* la = lds[buf] + (wm * WTM + frag_row) * kPitch + frag_half * 16;
-        const unsigned char* lb = lds[buf] + BM * kPitch + (wn * WTN + frag_row) * kPitch + frag_half * 16;
+        // Stage kt must have landed.  Transfers complete in issue order, so it is enough to allow
+        // as many outstanding as were issued after it: in steady state NST-2 stages of the ring
+        // plus one touch per iteration since; during ramp-up fewer touches (waiting for more is
+        // safe), and once the ring stops refilling simply everything.
+        if (kt + NST - 1 >= nk) wait_vmcnt<0>();
+        else if (kt < NST - 1) wait_vmcnt<(NST - 2) * LPW>();
+        else wait_vmcnt<(NST - 2) * LPW + (PFD > 0 ? NST - 1 : 0)>();
+        __syncthreads();            // stage kt visible to all waves; everyone is done with stage kt-1
+        if (kt + NST - 1 < nk) {
+            issue_stage(kt + NST - 1);                        // refills the slot stage kt-1 used
+            if (PFD > 0) touch_block(((kt + NST - 1 + PFD) * RB) / 128);
+        }
+
+        const unsigned char* slot = lds + (kt % NST) * STAGE_BYTES;
 #pragma unroll
-        for (int ks = 0; ks < kChunksPerRow / 2; ++ks) {
+        for (int ks = 0; ks < CPR / 2; ++ks) {
             uint4 fa[FM], fb[FN];
 #pragma unroll
-            for (int i = 0; i < FM; ++i) fa[i] = *reinterpret_cast<const uint4*>(la + i * 32 * kPitch + ks * 32);
+            for (int i = 0; i < FM; ++i) {
+                const int row = wm * WTM + i * 32 + frag_row;
+                const int chunk = (2 * ks + frag_half) ^ ((row >> SWZ_SHIFT) & (CPR - 1));
+                fa[i] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
+            }
 #pragma unroll
-            for (int j = 0; j < FN; ++j) fb[j] = *reinterpret_cast<const uint4*>(lb + j * 32 * kPitch + ks * 32);
+            for (int j = 0; j < FN; ++j) {
+                const int row = BM + wn * WTN + j * 32 + frag_row;
+                const int chunk = (2 * ks + frag_half) ^ ((row >> SWZ_SHIFT) & (CPR - 1));
+                fb[j] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
+            }
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
+#if defined(WINO_PROBE_NOMMA)
+                for (int j = 0; j < FN; ++j) { acc[i][j][0] += __uint_as_float(fa[i].x ^ fb[j].y); }
+#else
                 for (int j = 0; j < FN; ++j) Mma<E>::run(fa[i], fb[j], acc[i][j]);
+#endif
         }
-        if (kt + 1 < nk) store_stage(buf ^ 1);
-        __syncthreads();
     }
 
     // 32x32 accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
@@ -150,31 +227,72 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int k = row_k0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+#if defined(WINO_PROBE_NOSTORE)
+                if (k < K && t < T && acc[i][j][r] == 123456.789f) Mb[(size_t)k * T + t] = acc[i][j][r];
+#else
                 if (k < K && t < T) Mb[(size_t)k * T + t] = acc[i][j][r];
+#endif
             }
         }
 }
 
-template <typename E, int BM, int BN>
+template <typename E, int BM, int BN, int RB, int NST, int PFD = 0>
 static hipError_t launch_gemm_cfg(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, hipStream_t s) {
     const int tiles_m = (K + BM - 1) / BM, tiles_n = (T + BN - 1) / BN;
     const long long total = (long long)tiles_m * tiles_n * nbatch;
     if (total > 0x3fffffffLL) return hipErrorInvalidValue;
     const int per_xcd = (int)((total + 7) / 8);
+    constexpr int lds_bytes = (BM + BN) * RB * NST + 1024;    // ring + prefetch dump area
+    static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+    auto kern = wino_gemm_kernel<E, BM, BN, RB, NST, PFD>;
+    static bool attr_set = false;                 // per instantiation; raising the limit is idempotent
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     dim3 block(256), grid((unsigned)(per_xcd * 8));
-    hipLaunchKernelGGL((wino_gemm_kernel<E, BM, BN>), grid, block, 0, s, (const E*)U, (const E*)V, M,
+    hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, (const E*)U, (const E*)V, M,
                        K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd);
     return hipGetLastError();
 }
 
-hipError_t launch_batched_gemm(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, bool f16, hipStream_t s) {
-    // narrow T (small images): 64-wide column blocks waste fewer MFMA columns
-    if (f16) {
-        if (T <= 64) return launch_gemm_cfg<__half, 128, 64>(U, V, M, K, Cp, T, nbatch, s);
-        return launch_gemm_cfg<__half, 128, 128>(U, V, M, K, Cp, T, nbatch, s);
+// Block shapes on offer.  Every ring fits in 64 KB so two workgroups share a CU.
+struct BlockShape { int bm, bn; double eff; };
+static const BlockShape kMenu[4] = {{128, 128, 1.00}, {128, 64, 0.85}, {64, 128, 0.85}, {64, 64, 0.70}};
+
+// Pick the shape with the least padded MFMA work per unit of (operand reuse x machine fill).
+// WINO_GEMM_SHAPE=0..3 (read once) pins a menu entry, for tuning runs.
+static int pick_shape(int K, int T, int nbatch) {
+    static const int forced = [] {
+        const char* e = getenv("WINO_GEMM_SHAPE");
+        return (e && e[0] >= '0' && e[0] <= '3' && e[1] == 0) ? e[0] - '0' : -1;
+    }();
+    if (forced >= 0) return forced;
+    int best = 0; double best_score = 1e300;
+    for (int i = 0; i < 4; ++i) {
+        const double tm = (K + kMenu[i].bm - 1) / kMenu[i].bm, tn = (T + kMenu[i].bn - 1) / kMenu[i].bn;
+        const double blocks = tm * tn * nbatch;
+        const double padded = tm * kMenu[i].bm * tn * kMenu[i].bn;
+        const double fill = blocks >= 256.0 ? 1.0 : blocks / 256.0;
+        const double score = padded / (kMenu[i].eff * fill);
+        if (score < best_score) { best_score = score; best = i; }
     }
-    if (T <= 64) return launch_gemm_cfg<float, 128, 64>(U, V, M, K, Cp, T, nbatch, s);
-    return launch_gemm_cfg<float, 128, 128>(U, V, M, K, Cp, T, nbatch, s);
+    return best;
+}
+
+template <typename E>
+static hipError_t launch_gemm_t(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, hipStream_t s) {
+    switch (pick_shape(K, T, nbatch)) {
+        case 0: return launch_gemm_cfg<E, 128, 128, 64, 4>(U, V, M, K, Cp, T, nbatch, s);
+        case 1: return launch_gemm_cfg<E, 128, 64, 64, 4>(U, V, M, K, Cp, T, nbatch, s);
+        case 2: return launch_gemm_cfg<E, 64, 128, 64, 4>(U, V, M, K, Cp, T, nbatch, s);
+        default: return launch_gemm_cfg<E, 64, 64, 128, 4>(U, V, M, K, Cp, T, nbatch, s);
+    }
+}
+
+hipError_t launch_batched_gemm(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, bool f16, hipStream_t s) {
+    return f16 ? launch_gemm_t<__half>(U, V, M, K, Cp, T, nbatch, s) : launch_gemm_t<float>(U, V, M, K, Cp, T, nbatch, s);
 }
 
 }  // namespace wino
