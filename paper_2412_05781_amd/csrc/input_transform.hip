@@ -10,6 +10,7 @@
 // Bound by HBM/L2 traffic: reads x once (plus the 2-row/2-column halo), writes V.
 #include "wino_internal.h"
 #include "wino_transforms.h"
+#include <stdlib.h>
 
 namespace wino {
 
@@ -175,10 +176,8 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
     }
 }
 
-template <int M, typename E>
-static hipError_t launch_it(const void* x, void* V, const Geom& g, hipStream_t s) {
-    constexpr int CB = 64;
-    constexpr int TJ = (M == 4) ? 8 : 16;
+template <int M, typename E, int CB, int TJ>
+static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, hipStream_t s) {
     const int strips = (g.tw + TJ - 1) / TJ;
     dim3 block(256), grid((unsigned)(g.N * g.th * strips), (unsigned)((g.Cp + CB - 1) / CB));
     const bool rows_are_chunks = ((size_t)g.W * sizeof(E)) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
@@ -189,6 +188,20 @@ static hipError_t launch_it(const void* x, void* V, const Geom& g, hipStream_t s
         hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ>), grid, block, 0, s,
                            (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips);
     return hipGetLastError();
+}
+
+template <int M, typename E>
+static hipError_t launch_it(const void* x, void* V, const Geom& g, hipStream_t s) {
+    constexpr int Q = 8 / M;      // TJ multiples that keep strips whole 16-byte chunks for fp16
+    static const int cfg = [] { const char* e = getenv("WINO_IT_CFG"); return e ? atoi(e) : 0; }();
+    switch (cfg) {
+        case 1: return launch_it_cfg<M, E, 64, 2 * Q>(x, V, g, s);
+        case 2: return launch_it_cfg<M, E, 32, 4 * Q>(x, V, g, s);
+        case 3: return launch_it_cfg<M, E, 32, 2 * Q>(x, V, g, s);
+        case 4: return launch_it_cfg<M, E, 64, 1 * Q>(x, V, g, s);
+        case 5: return launch_it_cfg<M, E, 32, 1 * Q>(x, V, g, s);
+        default: return launch_it_cfg<M, E, 64, 4 * Q>(x, V, g, s);
+    }
 }
 
 hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, hipStream_t s) {

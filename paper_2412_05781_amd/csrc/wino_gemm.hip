@@ -91,9 +91,14 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     const int bid = blockIdx.x;
     const int logical = (bid % 8) * blocks_per_xcd + bid / 8;
     if (logical >= total_blocks) return;                  // uniform per workgroup, before any barrier
-    const int tn = logical % tiles_n;
-    const int tm = (logical / tiles_n) % tiles_m;
+    // Inside a batch the shorter tile dimension runs fastest: the workgroups resident together
+    // then sweep ALL blocks of the smaller operand (which stays in L2) against a few blocks of
+    // the larger one, which is streamed from memory once.
     const int batch = logical / (tiles_n * tiles_m);
+    const int in_batch = logical - batch * (tiles_n * tiles_m);
+    int tm, tn;
+    if (tiles_m <= tiles_n) { tm = in_batch % tiles_m; tn = in_batch / tiles_m; }
+    else { tn = in_batch % tiles_n; tm = in_batch / tiles_n; }
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -126,7 +131,7 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     // Every workgroup of an XCD walks the reduction in step, so each stage would be a fresh L2
     // miss for all of them.  One lane per operand row therefore touches the 128-byte line PFD
     // stages ahead of the ring, which turns the ring's own loads into L2 hits.
-    static_assert(ROWS <= 256, "one prefetch lane per row");
+    static_assert(PFD == 0 || ROWS <= 256, "one prefetch lane per row");
     unsigned char* dump = lds + NST * STAGE_BYTES + wave * 256;
     const unsigned char* pf_row;
     {
@@ -190,31 +195,30 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
             if (PFD > 0) touch_block(((kt + NST - 1 + PFD) * RB) / 128);
         }
 
+        // all fragment reads of the stage first, then the MFMAs, so LDS latency is paid once
         const unsigned char* slot = lds + (kt % NST) * STAGE_BYTES;
+        uint4 fa[CPR / 2][FM], fb[CPR / 2][FN];
 #pragma unroll
         for (int ks = 0; ks < CPR / 2; ++ks) {
-            uint4 fa[FM], fb[FN];
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
                 const int row = wm * WTM + i * 32 + frag_row;
                 const int chunk = (2 * ks + frag_half) ^ ((row >> SWZ_SHIFT) & (CPR - 1));
-                fa[i] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
+                fa[ks][i] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
             }
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
                 const int row = BM + wn * WTN + j * 32 + frag_row;
                 const int chunk = (2 * ks + frag_half) ^ ((row >> SWZ_SHIFT) & (CPR - 1));
-                fb[j] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
+                fb[ks][j] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
             }
+        }
+#pragma unroll
+        for (int ks = 0; ks < CPR / 2; ++ks)
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
-#if defined(WINO_PROBE_NOMMA)
-                for (int j = 0; j < FN; ++j) { acc[i][j][0] += __uint_as_float(fa[i].x ^ fb[j].y); }
-#else
-                for (int j = 0; j < FN; ++j) Mma<E>::run(fa[i], fb[j], acc[i][j]);
-#endif
-        }
+                for (int j = 0; j < FN; ++j) Mma<E>::run(fa[ks][i], fb[ks][j], acc[i][j]);
     }
 
     // 32x32 accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
@@ -257,7 +261,9 @@ static hipError_t launch_gemm_cfg(const void* U, const void* V, float* M, int K,
     return hipGetLastError();
 }
 
-// Block shapes on offer.  Every ring fits in 64 KB so two workgroups share a CU.
+// Block shapes on offer.  Every ring fits in 64 KB so at least two workgroups share a CU
+// (measured: occupancy buys more than ring depth, because per-CU L2 bandwidth grows with the
+// number of waves that have loads in flight).
 struct BlockShape { int bm, bn; double eff; };
 static const BlockShape kMenu[4] = {{128, 128, 1.00}, {128, 64, 0.85}, {64, 128, 0.85}, {64, 64, 0.70}};
 
@@ -274,7 +280,7 @@ static int pick_shape(int K, int T, int nbatch) {
         const double tm = (K + kMenu[i].bm - 1) / kMenu[i].bm, tn = (T + kMenu[i].bn - 1) / kMenu[i].bn;
         const double blocks = tm * tn * nbatch;
         const double padded = tm * kMenu[i].bm * tn * kMenu[i].bn;
-        const double fill = blocks >= 256.0 ? 1.0 : blocks / 256.0;
+        const double fill = blocks >= 512.0 ? 1.0 : blocks / 512.0;     // two resident workgroups per CU
         const double score = padded / (kMenu[i].eff * fill);
         if (score < best_score) { best_score = score; best = i; }
     }
@@ -283,10 +289,26 @@ static int pick_shape(int K, int T, int nbatch) {
 
 template <typename E>
 static hipError_t launch_gemm_t(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, hipStream_t s) {
+    static const int exp_cfg = [] { const char* e = getenv("WINO_GEMM_CFG"); return e ? atoi(e) : -1; }();
+    switch (exp_cfg) {      // tuning-only configurations
+        case 10: return launch_gemm_cfg<E, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
+        case 11: return launch_gemm_cfg<E, 128, 128, 128, 3>(U, V, M, K, Cp, T, nbatch, s);
+        case 12: return launch_gemm_cfg<E, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
+        case 13: return launch_gemm_cfg<E, 64, 128, 128, 3>(U, V, M, K, Cp, T, nbatch, s);
+        case 14: return launch_gemm_cfg<E, 64, 128, 128, 4>(U, V, M, K, Cp, T, nbatch, s);
+        case 15: return launch_gemm_cfg<E, 128, 128, 128, 4>(U, V, M, K, Cp, T, nbatch, s);
+        case 16: return launch_gemm_cfg<E, 128, 128, 64, 3>(U, V, M, K, Cp, T, nbatch, s);
+        case 17: return launch_gemm_cfg<E, 256, 128, 64, 2>(U, V, M, K, Cp, T, nbatch, s);
+        case 18: return launch_gemm_cfg<E, 128, 256, 64, 2>(U, V, M, K, Cp, T, nbatch, s);
+        case 19: return launch_gemm_cfg<E, 256, 128, 64, 3>(U, V, M, K, Cp, T, nbatch, s);
+        case 20: return launch_gemm_cfg<E, 256, 256, 64, 2>(U, V, M, K, Cp, T, nbatch, s);
+        case 21: return launch_gemm_cfg<E, 128, 256, 64, 3>(U, V, M, K, Cp, T, nbatch, s);
+        default: break;
+    }
     switch (pick_shape(K, T, nbatch)) {
-        case 0: return launch_gemm_cfg<E, 128, 128, 64, 4>(U, V, M, K, Cp, T, nbatch, s);
-        case 1: return launch_gemm_cfg<E, 128, 64, 64, 4>(U, V, M, K, Cp, T, nbatch, s);
-        case 2: return launch_gemm_cfg<E, 64, 128, 64, 4>(U, V, M, K, Cp, T, nbatch, s);
+        case 0: return launch_gemm_cfg<E, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
+        case 1: return launch_gemm_cfg<E, 128, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
+        case 2: return launch_gemm_cfg<E, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
         default: return launch_gemm_cfg<E, 64, 64, 128, 4>(U, V, M, K, Cp, T, nbatch, s);
     }
 }
