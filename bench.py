@@ -27,6 +27,10 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"f16": 2500.0, "f32": 157.3}     # dense MFMA, published
 PEAK_HBM_GBS = 8000.0
 MALL_BYTES = 256 << 20
+# HBM bytes per GEMM launch from rocprofv3 --pmc (FETCH_SIZE x 1.99 + WRITE_SIZE, both KiB per
+# dispatch; the factors come from a plain copy kernel of known size in the same runs), see
+# profiles/B_resblock_f4_pmc_traffic.txt.  Only for workloads that were profiled.
+MEASURED_TRAFFIC = {("B_resblock", 4): int((10135.0 * 1.99 + 23040.0) * 1024)}
 
 
 def parse():
@@ -116,18 +120,32 @@ def main():
     U0 = sets[0][1].buf.view(xd.dtype)
     Vbuf = torch.empty((a2, T, Cp), dtype=xd.dtype, device=dev)
     Mbuf = torch.empty((a2, K, T), dtype=torch.float32, device=dev)
-    reps = max(20, min(args.steps, 200))
+    reps = 2 * nsets                                # every buffer set twice per replay
 
     def time_kernel(fn):
-        for i in range(5):
-            fn(i)
-        torch.cuda.synchronize()
-        a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for i in range(reps):
-            fn(i)
-        z.record(); torch.cuda.synchronize()
-        return a.elapsed_time(z) / reps * 1e-3      # seconds per launch
+        """Average GPU duration of one launch: `reps` launches captured in a HIP graph on a side
+        stream (so the host's launch cost is out of the picture), replayed between two HIP events
+        recorded on that same stream."""
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            for i in range(3):
+                fn(i)
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                for i in range(reps):
+                    fn(i)
+            g.replay()
+            side.synchronize()
+            best = float("inf")
+            for _ in range(5):
+                a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(side)
+                g.replay()
+                z.record(side)
+                side.synchronize()
+                best = min(best, a.elapsed_time(z))
+        return best / reps * 1e-3                   # seconds per launch
 
     t_in = time_kernel(lambda i: B.wino_input_transform(sets[i % nsets][0], variant, out=Vbuf))
     t_gemm = time_kernel(lambda i: B.wino_batched_gemm(sets[i % nsets][1].buf.view(xd.dtype), Vbuf, K, C, T, variant, out=Mbuf))
@@ -147,10 +165,19 @@ def main():
         "output_transform": {"us": t_out * 1e6, "bound": "hbm", "achieved": bytes_out / t_out / 1e9,
                              "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": bytes_out / t_out / 1e9 / PEAK_HBM_GBS},
     }
-    # the GEMM stage is the path's one dense contraction and the metric's "% of MFMA peak" leg
-    dom = "batched_gemm"
-    roofline = {k: stages[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
-    roofline.update({"kernel": "wino_gemm_kernel", "traffic": None, "avg_launch_us": stages[dom]["us"]})
+    # The GEMM stage is the path's one dense contraction and the longest kernel.  Its binding roof
+    # is the smaller of the MFMA roof and the HBM roof at its algorithmic intensity.
+    g = stages["batched_gemm"]
+    g["hbm_frac"] = bytes_gemm / t_gemm / 1e9 / PEAK_HBM_GBS
+    t_mfma, t_hbm = flops_gemm / (PEAK_TFLOPS[layer.dtype] * 1e12), bytes_gemm / (PEAK_HBM_GBS * 1e9)
+    if t_hbm >= t_mfma:
+        roofline = {"bound": "hbm", "achieved": bytes_gemm / t_gemm / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": g["hbm_frac"]}
+    else:
+        roofline = {"bound": "mfma", "achieved": g["achieved"], "peak": g["peak"], "unit": "TFLOP/s", "frac": g["frac"]}
+    roofline.update({"kernel": "wino_gemm_kernel", "avg_launch_us": g["us"], "mfma_frac": g["frac"],
+                     "algorithmic_bytes": bytes_gemm, "algorithmic_flops": flops_gemm,
+                     "traffic": MEASURED_TRAFFIC.get((layer.name, variant))})
 
     # ---- parity of what was just timed ---------------------------------------------------------------
     import oracle

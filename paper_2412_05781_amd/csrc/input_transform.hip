@@ -95,7 +95,8 @@ input_transform_nchw_kernel(const E* __restrict__ x, E* __restrict__ V,
 template <int M, typename E, int CB, int TJ>
 __global__ void __launch_bounds__(256)
 input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
-                                int N, int C, int H, int W, int th, int tw, int T, int Cp, int strips_per_row) {
+                                int N, int C, int H, int W, int th, int tw, int T, int Cp, int strips_per_row,
+                                int total_blocks, int blocks_per_xcd) {
     constexpr int A = M + 2;
     constexpr int EPC = 16 / (int)sizeof(E);
     static_assert((M * TJ) % EPC == 0, "strip width must be whole chunks");
@@ -107,12 +108,16 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
     __shared__ uint32_t patch[CB * CSW];
 
     const int tid = threadIdx.x;
-    int sidx = blockIdx.x;
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
+    // (channel chunk, n, tile row, strip) so neighbours that share halo rows share an L2.
+    const int logical = (blockIdx.x % 8) * blocks_per_xcd + blockIdx.x / 8;
+    if (logical >= total_blocks) return;                 // uniform, before the barrier
+    int sidx = logical;
     const int js = sidx % strips_per_row; sidx /= strips_per_row;
-    const int ti = sidx % th;
-    const int n = sidx / th;
+    const int ti = sidx % th; sidx /= th;
+    const int n = sidx % N;
+    const int c0 = (sidx / N) * CB;
     const int tj0 = js * TJ;
-    const int c0 = blockIdx.y * CB;
     const int row0 = M * ti - 1;
     const int col0 = M * tj0 - EPC;
 
@@ -125,7 +130,11 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
         const int a = rem / NCH, ch = rem - a * NCH;
         const int r = row0 + a, col = col0 + ch * EPC, c = c0 + cc;
         reg[i] = make_uint4(0, 0, 0, 0);
+#if defined(WINO_PROBE_IT_NOLOAD)
+        if (q < TOTAL && c < C && r >= 0 && r < H && col >= 0 && col + EPC <= W && N == 12345)
+#else
         if (q < TOTAL && c < C && r >= 0 && r < H && col >= 0 && col + EPC <= W)
+#endif
             reg[i] = *reinterpret_cast<const uint4*>(x + (((size_t)n * C + c) * H + r) * W + col);
     }
 #pragma unroll
@@ -171,7 +180,11 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
             float out[A];
             bt_1d<M>(tmp[xi], out);
 #pragma unroll
+#if defined(WINO_PROBE_IT_NOSTORE)
+            for (int nu = 0; nu < A; ++nu) if (out[nu] == 123456.789f) dst[(size_t)(xi * A + nu) * plane] = from_f32<E>(out[nu]);
+#else
             for (int nu = 0; nu < A; ++nu) dst[(size_t)(xi * A + nu) * plane] = from_f32<E>(out[nu]);
+#endif
         }
     }
 }
@@ -181,10 +194,13 @@ static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, hipStream
     const int strips = (g.tw + TJ - 1) / TJ;
     dim3 block(256), grid((unsigned)(g.N * g.th * strips), (unsigned)((g.Cp + CB - 1) / CB));
     const bool rows_are_chunks = ((size_t)g.W * sizeof(E)) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
-    if (rows_are_chunks)
-        hipLaunchKernelGGL((input_transform_nchw_vec_kernel<M, E, CB, TJ>), grid, block, 0, s,
-                           (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips);
-    else
+    if (rows_are_chunks) {
+        const long long total = (long long)grid.x * grid.y;
+        if (total > 0x3fffffffLL) return hipErrorInvalidValue;
+        const int per_xcd = (int)((total + 7) / 8);
+        hipLaunchKernelGGL((input_transform_nchw_vec_kernel<M, E, CB, TJ>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
+                           (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips, (int)total, per_xcd);
+    } else
         hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ>), grid, block, 0, s,
                            (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips);
     return hipGetLastError();
