@@ -121,6 +121,9 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
     const int row0 = M * ti - 1;
     const int col0 = M * tj0 - EPC;
 
+    // 32-bit lane offsets against wave-uniform 64-bit bases keep the address arithmetic off the
+    // vector ALU (the transform itself is only ~200 operations per tile and channel).
+    const unsigned char* xb = reinterpret_cast<const unsigned char*>(x + ((size_t)n * C + c0) * H * W);
     uint4 reg[NL];
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
@@ -130,12 +133,13 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
         const int a = rem / NCH, ch = rem - a * NCH;
         const int r = row0 + a, col = col0 + ch * EPC, c = c0 + cc;
         reg[i] = make_uint4(0, 0, 0, 0);
+        const unsigned off = (unsigned)(((cc * H + r) * W + col) * (int)sizeof(E));   // < CB*H*W*sizeof(E), checked on the host
 #if defined(WINO_PROBE_IT_NOLOAD)
         if (q < TOTAL && c < C && r >= 0 && r < H && col >= 0 && col + EPC <= W && N == 12345)
 #else
         if (q < TOTAL && c < C && r >= 0 && r < H && col >= 0 && col + EPC <= W)
 #endif
-            reg[i] = *reinterpret_cast<const uint4*>(x + (((size_t)n * C + c) * H + r) * W + col);
+            reg[i] = *reinterpret_cast<const uint4*>(xb + off);
     }
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
@@ -149,14 +153,15 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
     }
     __syncthreads();
 
-    const int cc = tid % CB;
+    // one tile per wave per iteration (lane = channel), so the tile index is wave-uniform
+    static_assert(CB == 64, "lane = channel");
+    const int cc = tid & 63;
     const int c = c0 + cc;
-    constexpr int TILES_PER_ITER = 256 / CB;
     const size_t plane = (size_t)T * Cp;
     const E* pch = reinterpret_cast<const E*>(patch + cc * CSW);
-    for (int tl = tid / CB; tl < TJ; tl += TILES_PER_ITER) {
+    for (int tl = __builtin_amdgcn_readfirstlane(tid >> 6); tl < TJ; tl += 4) {
         const int tj = tj0 + tl;
-        if (tj >= tw || c >= Cp) continue;
+        if (tj >= tw) break;                              // wave-uniform
         const E* p = pch + (EPC - 1) + M * tl;
         float d[A][A];
 #pragma unroll
@@ -173,18 +178,22 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
 #pragma unroll
             for (int a = 0; a < A; ++a) tmp[a][b] = out[a];
         }
-        const size_t t = ((size_t)n * th + ti) * tw + tj;
-        E* dst = V + t * Cp + c;
+        const size_t t = ((size_t)n * th + ti) * tw + tj;  // wave-uniform
+        E* rowp = V + t * Cp;                              // wave-uniform base; lane offset is just c
+        const unsigned coff = (unsigned)c * (unsigned)sizeof(E);
+        if (c < Cp) {
 #pragma unroll
-        for (int xi = 0; xi < A; ++xi) {
-            float out[A];
-            bt_1d<M>(tmp[xi], out);
+            for (int xi = 0; xi < A; ++xi) {
+                float out[A];
+                bt_1d<M>(tmp[xi], out);
 #pragma unroll
+                for (int nu = 0; nu < A; ++nu) {
 #if defined(WINO_PROBE_IT_NOSTORE)
-            for (int nu = 0; nu < A; ++nu) if (out[nu] == 123456.789f) dst[(size_t)(xi * A + nu) * plane] = from_f32<E>(out[nu]);
-#else
-            for (int nu = 0; nu < A; ++nu) dst[(size_t)(xi * A + nu) * plane] = from_f32<E>(out[nu]);
+                    if (out[nu] == 123456.789f)
 #endif
+                    *reinterpret_cast<E*>(reinterpret_cast<unsigned char*>(rowp + (size_t)(xi * A + nu) * plane) + coff) = from_f32<E>(out[nu]);
+                }
+            }
         }
     }
 }
@@ -193,7 +202,9 @@ template <int M, typename E, int CB, int TJ>
 static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, hipStream_t s) {
     const int strips = (g.tw + TJ - 1) / TJ;
     dim3 block(256), grid((unsigned)(g.N * g.th * strips), (unsigned)((g.Cp + CB - 1) / CB));
-    const bool rows_are_chunks = ((size_t)g.W * sizeof(E)) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+    // fast path: rows are whole 16-byte chunks and a 64-channel slab of x spans < 2 GB (32-bit lane offsets)
+    const bool rows_are_chunks = ((size_t)g.W * sizeof(E)) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0 &&
+                                 (size_t)CB * g.H * g.W * sizeof(E) < ((size_t)1 << 31);
     if (rows_are_chunks) {
         const long long total = (long long)grid.x * grid.y;
         if (total > 0x3fffffffLL) return hipErrorInvalidValue;
@@ -210,13 +221,11 @@ template <int M, typename E>
 static hipError_t launch_it(const void* x, void* V, const Geom& g, hipStream_t s) {
     constexpr int Q = 8 / M;      // TJ multiples that keep strips whole 16-byte chunks for fp16
     static const int cfg = [] { const char* e = getenv("WINO_IT_CFG"); return e ? atoi(e) : 0; }();
-    switch (cfg) {
-        case 1: return launch_it_cfg<M, E, 64, 2 * Q>(x, V, g, s);
-        case 2: return launch_it_cfg<M, E, 32, 4 * Q>(x, V, g, s);
-        case 3: return launch_it_cfg<M, E, 32, 2 * Q>(x, V, g, s);
-        case 4: return launch_it_cfg<M, E, 64, 1 * Q>(x, V, g, s);
-        case 5: return launch_it_cfg<M, E, 32, 1 * Q>(x, V, g, s);
-        default: return launch_it_cfg<M, E, 64, 4 * Q>(x, V, g, s);
+    switch (cfg) {                // tuning knob: tiles per strip (measured best: one tile per wave)
+        case 1: return launch_it_cfg<M, E, 64, 4 * Q>(x, V, g, s);
+        case 2: return launch_it_cfg<M, E, 64, 1 * Q>(x, V, g, s);
+        case 3: return launch_it_cfg<M, E, 64, 8 * Q>(x, V, g, s);
+        default: return launch_it_cfg<M, E, 64, 2 * Q>(x, V, g, s);
     }
 }
 

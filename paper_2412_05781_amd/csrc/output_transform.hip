@@ -5,6 +5,7 @@
 // Bound by HBM/L2 traffic: reads alpha^2 fp32 per m^2 outputs.
 #include "wino_internal.h"
 #include "wino_transforms.h"
+#include <stdlib.h>
 
 namespace wino {
 
@@ -27,66 +28,93 @@ __device__ __forceinline__ void store_row(E* p, const float* v) {
     *reinterpret_cast<typename RowVec<E, M>::type*>(p) = r;
 }
 
-template <int M, typename E>
+template <int TPT> struct FVec;
+template <> struct FVec<1> { using type = float; };
+template <> struct FVec<2> { using type = float2; };
+template <> struct FVec<4> { using type = float4; };
+
+// One lane handles TPT consecutive tiles of one output channel (TPT divides T), so each of the
+// alpha^2 reads is a TPT*4-byte vector and a wave reads TPT*256 contiguous bytes per plane.
+template <int M, typename E, int TPT>
 __global__ void __launch_bounds__(256)
 output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
                              int N, int K, int H, int W, int th, int tw, int T, int vec_ok) {
     constexpr int A = M + 2;
     const size_t KT = (size_t)K * T;
-    const size_t f = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (f >= KT) return;
-    const int k = (int)(f / T);
-    int t = (int)(f - (size_t)k * T);
-    const int tj = t % tw; t /= tw;
-    const int ti = t % th;
-    const int n = t / th;
+    const int Tq = T / TPT;
+    const size_t fq = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (fq >= (size_t)K * Tq) return;
+    const int k = (int)(fq / Tq);
+    const int t0 = (int)(fq - (size_t)k * Tq) * TPT;
+    const size_t f = (size_t)k * T + t0;
 
-    float v[A][A];
+    float v[A * A][TPT];
 #pragma unroll
-    for (int xi = 0; xi < A; ++xi)
+    for (int p = 0; p < A * A; ++p) {
+        const typename FVec<TPT>::type q = *reinterpret_cast<const typename FVec<TPT>::type*>(Mt + (size_t)p * KT + f);
+        const float* qf = reinterpret_cast<const float*>(&q);
 #pragma unroll
-        for (int nu = 0; nu < A; ++nu) v[xi][nu] = Mt[(size_t)(xi * A + nu) * KT + f];
-
-    // columns: tmp[:, nu] = A^T v[:, nu]
-    float tmp[M][A];
-#pragma unroll
-    for (int nu = 0; nu < A; ++nu) {
-        float in[A], out[M];
-#pragma unroll
-        for (int xi = 0; xi < A; ++xi) in[xi] = v[xi][nu];
-        at_1d<M>(in, out);
-#pragma unroll
-        for (int a = 0; a < M; ++a) tmp[a][nu] = out[a];
+        for (int u = 0; u < TPT; ++u) v[p][u] = qf[u];
     }
     const float b = bias ? bias[k] : 0.f;
-    const int i0 = M * ti, j0 = M * tj;
-    E* yp = y + (((size_t)n * K + k) * H + i0) * W + j0;
 #pragma unroll
-    for (int a = 0; a < M; ++a) {
-        float out[M];
-        at_1d<M>(tmp[a], out);
+    for (int u = 0; u < TPT; ++u) {
+        int t = t0 + u;
+        const int tj = t % tw; t /= tw;
+        const int ti = t % th;
+        const int n = t / th;
+        // columns: tmp[:, nu] = A^T v[:, nu]
+        float tmp[M][A];
 #pragma unroll
-        for (int q = 0; q < M; ++q) out[q] += b;
-        if (i0 + a < H) {
-            if (vec_ok) {
-                store_row<E, M>(yp + (size_t)a * W, out);
-            } else {
+        for (int nu = 0; nu < A; ++nu) {
+            float in[A], out[M];
 #pragma unroll
-                for (int q = 0; q < M; ++q)
-                    if (j0 + q < W) yp[(size_t)a * W + q] = from_f32<E>(out[q]);
+            for (int xi = 0; xi < A; ++xi) in[xi] = v[xi * A + nu][u];
+            at_1d<M>(in, out);
+#pragma unroll
+            for (int a = 0; a < M; ++a) tmp[a][nu] = out[a];
+        }
+        const int i0 = M * ti, j0 = M * tj;
+        E* yp = y + (((size_t)n * K + k) * H + i0) * W + j0;
+#pragma unroll
+        for (int a = 0; a < M; ++a) {
+            float out[M];
+            at_1d<M>(tmp[a], out);
+#pragma unroll
+            for (int q = 0; q < M; ++q) out[q] += b;
+            if (i0 + a < H) {
+                if (vec_ok) {
+                    store_row<E, M>(yp + (size_t)a * W, out);
+                } else {
+#pragma unroll
+                    for (int q = 0; q < M; ++q)
+                        if (j0 + q < W) yp[(size_t)a * W + q] = from_f32<E>(out[q]);
+                }
             }
         }
     }
 }
 
-template <int M, typename E>
-static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const Geom& g, hipStream_t s) {
-    const size_t KT = (size_t)g.K * g.T;
-    dim3 block(256), grid((unsigned)((KT + 255) / 256));
+template <int M, typename E, int TPT>
+static hipError_t launch_ot_cfg(const float* Mt, const float* bias, void* y, const Geom& g, hipStream_t s) {
+    const size_t items = (size_t)g.K * (g.T / TPT);
+    dim3 block(256), grid((unsigned)((items + 255) / 256));
     const int vec_ok = (g.W % M == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0);
-    hipLaunchKernelGGL((output_transform_nchw_kernel<M, E>), grid, block, 0, s,
+    hipLaunchKernelGGL((output_transform_nchw_kernel<M, E, TPT>), grid, block, 0, s,
                        Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, vec_ok);
     return hipGetLastError();
+}
+
+template <int M, typename E>
+static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const Geom& g, hipStream_t s) {
+    static const int cfg = [] { const char* e = getenv("WINO_OT_TPT"); return e ? atoi(e) : 0; }();   // tuning knob
+    // measured: two tiles per lane pays once the launch is large (F4, >= 1M lane-items); small
+    // launches want the extra parallelism of one tile per lane
+    int tpt = cfg ? cfg : ((M == 4 && (size_t)g.K * g.T >= ((size_t)1 << 20)) ? 2 : 1);
+    const bool aligned = (reinterpret_cast<uintptr_t>(Mt) & 15u) == 0;
+    if (tpt == 4 && g.T % 4 == 0 && aligned) return launch_ot_cfg<M, E, 4>(Mt, bias, y, g, s);
+    if (tpt >= 2 && g.T % 2 == 0 && aligned) return launch_ot_cfg<M, E, 2>(Mt, bias, y, g, s);
+    return launch_ot_cfg<M, E, 1>(Mt, bias, y, g, s);
 }
 
 hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, hipStream_t s) {

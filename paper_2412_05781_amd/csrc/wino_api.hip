@@ -103,16 +103,13 @@ int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int varia
     }
     if (variant != WINO_AUTO) return -1;
     if (!dims_ok(N, C, H, W, K, 2) || !dims_ok(N, C, H, W, K, 4)) return -1;
-    // Traffic model of the three-kernel chain (bytes moved once each): x + 2V + U + 2M + y.
-    // F4 moves fewer activation bytes but a 2.25x larger U, which dominates for tiny images.
-    double bytes[2];
-    for (int i = 0; i < 2; ++i) {
-        const Geom g = make_geom(N, C, H, W, K, i == 0 ? 2 : 4);
-        const double a2 = (double)g.alpha * g.alpha, e = (double)esize(dtype);
-        bytes[i] = (double)N * C * H * W * e + 2.0 * a2 * g.T * g.Cp * e + a2 * (double)K * g.Cp * e +
-                   2.0 * a2 * (double)K * g.T * 4.0 + (double)N * K * H * W * e;
-    }
-    const int pick = bytes[0] < bytes[1] ? WINO_F2 : WINO_F4;
+    // Measured over the SD-shaped layers: F(4x4) moves fewer activation bytes and wins whenever
+    // there are enough tiles to fill the GEMM's column blocks; with very few tiles (8x8 and 16x16
+    // images) the 2.25x larger transformed filter and the empty MFMA columns make F(2x2) faster.
+    const Geom g4 = make_geom(N, C, H, W, K, 4);
+    int pick = g4.T >= 64 ? WINO_F4 : WINO_F2;
+    // fp32 storage promises 1e-5: F(4x4) rounding grows with the reduction length, keep a margin
+    if (dtype == WINO_F32 && C > 640) pick = WINO_F2;
     return pick;
 }
 
