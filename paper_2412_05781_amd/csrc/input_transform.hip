@@ -103,8 +103,6 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
     constexpr int NCH = (M * TJ) / EPC + 2;              // chunks per patch row
     constexpr int ROWW = NCH * 4;                        // 32-bit words per patch row
     constexpr int CSW = (A * ROWW) | 1;                  // words per channel, odd: lanes = channels hit distinct banks
-    constexpr int TOTAL = CB * A * NCH;                  // chunks per patch
-    constexpr int NL = (TOTAL + 255) / 256;
     __shared__ uint32_t patch[CB * CSW];
 
     const int tid = threadIdx.x;
@@ -124,31 +122,40 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
     // 32-bit lane offsets against wave-uniform 64-bit bases keep the address arithmetic off the
     // vector ALU (the transform itself is only ~200 operations per tile and channel).
     const unsigned char* xb = reinterpret_cast<const unsigned char*>(x + ((size_t)n * C + c0) * H * W);
-    uint4 reg[NL];
+    // a lane owns one (channel, chunk column) and walks the alpha patch rows: one add per load
+    constexpr int ITEMS = CB * NCH;
+    constexpr int PASSES = (ITEMS + 255) / 256;
+    uint4 reg[PASSES][A];
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-        const int q = tid + i * 256;
-        const int cc = q / (A * NCH);
-        const int rem = q - cc * (A * NCH);
-        const int a = rem / NCH, ch = rem - a * NCH;
-        const int r = row0 + a, col = col0 + ch * EPC, c = c0 + cc;
-        reg[i] = make_uint4(0, 0, 0, 0);
-        const unsigned off = (unsigned)(((cc * H + r) * W + col) * (int)sizeof(E));   // < CB*H*W*sizeof(E), checked on the host
+    for (int ps = 0; ps < PASSES; ++ps) {
+        const int item = tid + ps * 256;
+        const int cc = item / NCH, ch = item - cc * NCH;
+        const int col = col0 + ch * EPC;
+        const bool ok = item < ITEMS && (c0 + cc) < C && col >= 0 && col + EPC <= W;
+        const unsigned off0 = (unsigned)(((cc * H + row0) * W + col) * (int)sizeof(E));   // may wrap for row0 = -1; only used when the row is valid
+#pragma unroll
+        for (int a = 0; a < A; ++a) {
+            const int r = row0 + a;
+            reg[ps][a] = make_uint4(0, 0, 0, 0);
 #if defined(WINO_PROBE_IT_NOLOAD)
-        if (q < TOTAL && c < C && r >= 0 && r < H && col >= 0 && col + EPC <= W && N == 12345)
+            if (ok && r >= 0 && r < H && N == 12345)
 #else
-        if (q < TOTAL && c < C && r >= 0 && r < H && col >= 0 && col + EPC <= W)
+            if (ok && r >= 0 && r < H)
 #endif
-            reg[i] = *reinterpret_cast<const uint4*>(xb + off);
+                reg[ps][a] = *reinterpret_cast<const uint4*>(xb + (off0 + (unsigned)(a * W * (int)sizeof(E))));
+        }
     }
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-        const int q = tid + i * 256;
-        if (q < TOTAL) {
-            const int cc = q / (A * NCH);
-            const int rem = q - cc * (A * NCH);
-            uint32_t* dst = patch + cc * CSW + rem * 4;
-            dst[0] = reg[i].x; dst[1] = reg[i].y; dst[2] = reg[i].z; dst[3] = reg[i].w;
+    for (int ps = 0; ps < PASSES; ++ps) {
+        const int item = tid + ps * 256;
+        if (item < ITEMS) {
+            const int cc = item / NCH, ch = item - cc * NCH;
+            uint32_t* dst = patch + cc * CSW + ch * 4;
+#pragma unroll
+            for (int a = 0; a < A; ++a) {
+                dst[a * ROWW + 0] = reg[ps][a].x; dst[a * ROWW + 1] = reg[ps][a].y;
+                dst[a * ROWW + 2] = reg[ps][a].z; dst[a * ROWW + 3] = reg[ps][a].w;
+            }
         }
     }
     __syncthreads();
@@ -182,6 +189,8 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
         E* rowp = V + t * Cp;                              // wave-uniform base; lane offset is just c
         const unsigned coff = (unsigned)c * (unsigned)sizeof(E);
         if (c < Cp) {
+            unsigned char* pp = reinterpret_cast<unsigned char*>(rowp);     // walks the alpha^2 planes
+            const size_t plane_bytes = plane * sizeof(E);
 #pragma unroll
             for (int xi = 0; xi < A; ++xi) {
                 float out[A];
@@ -191,7 +200,8 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
 #if defined(WINO_PROBE_IT_NOSTORE)
                     if (out[nu] == 123456.789f)
 #endif
-                    *reinterpret_cast<E*>(reinterpret_cast<unsigned char*>(rowp + (size_t)(xi * A + nu) * plane) + coff) = from_f32<E>(out[nu]);
+                    *reinterpret_cast<E*>(pp + coff) = from_f32<E>(out[nu]);
+                    pp += plane_bytes;
                 }
             }
         }
