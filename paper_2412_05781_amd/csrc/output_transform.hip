@@ -108,9 +108,8 @@ static hipError_t launch_ot_cfg(const float* Mt, const float* bias, void* y, con
 template <int M, typename E>
 static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const Geom& g, hipStream_t s) {
     static const int cfg = [] { const char* e = getenv("WINO_OT_TPT"); return e ? atoi(e) : 0; }();   // tuning knob
-    // measured: two tiles per lane pays once the launch is large (F4, >= 1M lane-items); small
-    // launches want the extra parallelism of one tile per lane
-    int tpt = cfg ? cfg : ((M == 4 && (size_t)g.K * g.T >= ((size_t)1 << 20)) ? 2 : 1);
+    // measured over the layer sweep: one tile per lane is never worse in the chained path
+    int tpt = cfg ? cfg : 1;
     const bool aligned = (reinterpret_cast<uintptr_t>(Mt) & 15u) == 0;
     if (tpt == 4 && g.T % 4 == 0 && aligned) return launch_ot_cfg<M, E, 4>(Mt, bias, y, g, s);
     if (tpt >= 2 && g.T % 2 == 0 && aligned) return launch_ot_cfg<M, E, 2>(Mt, bias, y, g, s);
