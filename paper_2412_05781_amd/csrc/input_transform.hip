@@ -137,11 +137,7 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
         for (int a = 0; a < A; ++a) {
             const int r = row0 + a;
             reg[ps][a] = make_uint4(0, 0, 0, 0);
-#if defined(WINO_PROBE_IT_NOLOAD)
-            if (ok && r >= 0 && r < H && N == 12345)
-#else
             if (ok && r >= 0 && r < H)
-#endif
                 reg[ps][a] = *reinterpret_cast<const uint4*>(xb + (off0 + (unsigned)(a * W * (int)sizeof(E))));
         }
     }
@@ -197,9 +193,6 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
                 bt_1d<M>(tmp[xi], out);
 #pragma unroll
                 for (int nu = 0; nu < A; ++nu) {
-#if defined(WINO_PROBE_IT_NOSTORE)
-                    if (out[nu] == 123456.789f)
-#endif
                     *reinterpret_cast<E*>(pp + coff) = from_f32<E>(out[nu]);
                     pp += plane_bytes;
                 }

@@ -5,15 +5,14 @@
 // the MFMA units with fp32 accumulation.
 //
 // Both operands are row-major with the reduction index contiguous, so a lane's
-// MFMA fragment is one 16-byte LDS read.  A workgroup (4 waves, 2x2) owns a
-// BM x BN block of one batch; each wave (BM/2)x(BN/2) as 32x32 MFMA tiles.
+// MFMA fragment is one 16-byte LDS read.  A workgroup (WGM x WGN waves) owns a
+// BM x BN block of one batch; each wave (BM/WGM)x(BN/WGN) as 32x32 MFMA tiles.
 // The reduction is cut into stages of RB bytes per row.  Stages travel
 // global -> LDS directly (global_load_lds, 16 bytes per lane, no staging
-// registers) through a ring of NST slots, so NST-1 stages are in flight while
-// one is being multiplied; one barrier per stage.  LDS rows are unpadded (the
-// DMA writes lanes linearly); bank conflicts are avoided by an XOR swizzle of
-// the 16-byte chunk index, applied on the global-address side when loading and
-// on the LDS-address side when reading fragments.
+// registers) through a ring of NST slots; one barrier per stage.  LDS rows are
+// unpadded (the transfer writes lanes linearly); bank conflicts are avoided by
+// an XOR swizzle of the 16-byte chunk index, applied on the global-address side
+// when loading and on the LDS-address side when reading fragments.
 // Rows beyond K / T are clamped to the last valid row (their products are never
 // stored); a ragged last reduction stage (Cp not a multiple of the stage) goes
 // through registers with zero fill instead.
@@ -57,16 +56,8 @@ __device__ __forceinline__ void dma_load_1k(const void* src, unsigned char* lds_
                  :: "s"(m0v), "v"(src) : "memory");   // nothing else in these kernels reads m0
 }
 
-// L2 prefetch: a 4-byte-per-lane transfer into a dump area of LDS that nobody reads.  It has
-// no register destination, so nothing has to stay reserved until the data returns.
-__device__ __forceinline__ void dma_touch(const void* src, unsigned char* lds_dump) {
-    const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t*)lds_dump);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
-                 :: "s"(m0v), "v"(src) : "memory");
-}
-
-template <typename E, int BM, int BN, int RB, int NST, int PFD>
-__global__ void __launch_bounds__(256)
+template <typename E, int BM, int BN, int RB, int NST, int WGM, int WGN>
+__global__ void __launch_bounds__(WGM * WGN * 64)
 wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __restrict__ Mo,
                  int K, int Cp, int T, int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd) {
     constexpr int CPR = RB / 16;                          // 16-byte chunks per row per stage
@@ -74,13 +65,14 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     constexpr int EPC = 16 / (int)sizeof(E);              // elements per chunk
     constexpr int ROWS = BM + BN;
     constexpr int RPL = 1024 / RB;                        // rows covered by one wave-wide load
-    constexpr int LPW = ROWS / RPL / 4;                   // wave-wide loads per wave per stage
+    constexpr int NW = WGM * WGN;                         // waves per workgroup
+    constexpr int LPW = ROWS / RPL / NW;                  // wave-wide loads per wave per stage
     constexpr int SWZ_SHIFT = (RB == 128) ? 1 : 2;        // rows per 256-byte bank wrap = 256/RB
-    constexpr int WTM = BM / 2, WTN = BN / 2;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int FM = WTM / 32, FN = WTN / 32;
     constexpr int STAGE_BYTES = ROWS * RB;
     static_assert(RB == 128 || RB == 64, "stage row bytes");
-    static_assert(BM % 64 == 0 && BN % 64 == 0 && ROWS % (RPL * 4) == 0, "tile shape");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && ROWS % (RPL * NW) == 0, "tile shape");
     static_assert(NST >= 2 && NST <= 4, "ring depth");
     static_assert(LPW * (NST - 1) < 64, "vmcnt range");
 
@@ -101,7 +93,7 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     else { tn = in_batch % tiles_n; tm = in_batch / tiles_n; }
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int row_k0 = tm * BM, row_t0 = tn * BN;
 
     const E* Ub = U + (size_t)batch * K * Cp;
@@ -113,7 +105,7 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     int src_chunk[LPW];
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
-        const int row = (wave + 4 * i) * RPL + lrow;       // row inside the stage, A rows first
+        const int row = (wave + NW * i) * RPL + lrow;       // row inside the stage, A rows first
         const int chunk = lchunk ^ ((row >> SWZ_SHIFT) & (CPR - 1));
         src_chunk[i] = chunk;
         if (row < BM) {
@@ -128,24 +120,6 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     const int nk = (Cp + BKE - 1) / BKE;
     const bool ragged = (Cp % BKE) != 0;
 
-    // Every workgroup of an XCD walks the reduction in step, so each stage would be a fresh L2
-    // miss for all of them.  One lane per operand row therefore touches the 128-byte line PFD
-    // stages ahead of the ring, which turns the ring's own loads into L2 hits.
-    static_assert(PFD == 0 || ROWS <= 256, "one prefetch lane per row");
-    unsigned char* dump = lds + NST * STAGE_BYTES + wave * 256;
-    const unsigned char* pf_row;
-    {
-        const int row = tid < ROWS ? tid : ROWS - 1;
-        if (row < BM) { int g = row_k0 + row; g = g < K ? g : K - 1; pf_row = reinterpret_cast<const unsigned char*>(Ub + (size_t)g * Cp); }
-        else { int g = row_t0 + (row - BM); g = g < T ? g : T - 1; pf_row = reinterpret_cast<const unsigned char*>(Vb + (size_t)g * Cp); }
-    }
-    const int row_bytes = Cp * (int)sizeof(E);
-    const int pf_blocks = (row_bytes + 127) / 128;            // 128-byte lines per operand row
-    auto touch_block = [&](int b) {                           // exactly one transfer per wave per call
-        b = b < pf_blocks ? b : pf_blocks - 1;
-        dma_touch(pf_row + (size_t)b * 128, dump);
-    };
-
     auto issue_stage = [&](int kt) {
         unsigned char* slot = lds + (kt % NST) * STAGE_BYTES;
         if (ragged && kt == nk - 1) {
@@ -155,11 +129,11 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
                 const int gk = kt * BKE + src_chunk[i] * EPC;
                 uint4 v = make_uint4(0, 0, 0, 0);
                 if (gk < Cp) v = *reinterpret_cast<const uint4*>(src[i] + kt * BKE);
-                *reinterpret_cast<uint4*>(slot + (wave + 4 * i) * 1024 + lane * 16) = v;
+                *reinterpret_cast<uint4*>(slot + (wave + NW * i) * 1024 + lane * 16) = v;
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < LPW; ++i) dma_load_1k(src[i] + kt * BKE, slot + (wave + 4 * i) * 1024);
+            for (int i = 0; i < LPW; ++i) dma_load_1k(src[i] + kt * BKE, slot + (wave + NW * i) * 1024);
         }
     };
 
@@ -171,11 +145,6 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // prologue: touch the lines of the first NST-1+PFD stages, then start the ring
-    {
-        const int ahead = PFD > 0 ? ((NST - 1 + PFD) * RB + 127) / 128 : 0;
-        for (int b = 0; b < ahead && b < pf_blocks; ++b) touch_block(b);
-    }
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
         if (s < nk) issue_stage(s);
@@ -183,17 +152,12 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     const int frag_row = lane & 31, frag_half = lane >> 5;
     for (int kt = 0; kt < nk; ++kt) {
         // Stage kt must have landed.  Transfers complete in issue order, so it is enough to allow
-        // as many outstanding as were issued after it: in steady state NST-2 stages of the ring
-        // plus one touch per iteration since; during ramp-up fewer touches (waiting for more is
-        // safe), and once the ring stops refilling simply everything.
+        // as many outstanding as were issued after it: NST-2 stages in steady state, and once the
+        // ring stops refilling simply everything.
         if (kt + NST - 1 >= nk) wait_vmcnt<0>();
-        else if (kt < NST - 1) wait_vmcnt<(NST - 2) * LPW>();
-        else wait_vmcnt<(NST - 2) * LPW + (PFD > 0 ? NST - 1 : 0)>();
+        else wait_vmcnt<(NST - 2) * LPW>();
         __syncthreads();            // stage kt visible to all waves; everyone is done with stage kt-1
-        if (kt + NST - 1 < nk) {
-            issue_stage(kt + NST - 1);                        // refills the slot stage kt-1 used
-            if (PFD > 0) touch_block(((kt + NST - 1 + PFD) * RB) / 128);
-        }
+        if (kt + NST - 1 < nk) issue_stage(kt + NST - 1);   // refills the slot stage kt-1 used
 
         // all fragment reads of the stage first, then the MFMAs, so LDS latency is paid once
         const unsigned char* slot = lds + (kt % NST) * STAGE_BYTES;
@@ -231,50 +195,47 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int k = row_k0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
-#if defined(WINO_PROBE_NOSTORE)
-                if (k < K && t < T && acc[i][j][r] == 123456.789f) Mb[(size_t)k * T + t] = acc[i][j][r];
-#else
                 if (k < K && t < T) Mb[(size_t)k * T + t] = acc[i][j][r];
-#endif
             }
         }
 }
 
-template <typename E, int BM, int BN, int RB, int NST, int PFD = 0>
+template <typename E, int BM, int BN, int RB, int NST, int WGM = 2, int WGN = 2>
 static hipError_t launch_gemm_cfg(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, hipStream_t s) {
     const int tiles_m = (K + BM - 1) / BM, tiles_n = (T + BN - 1) / BN;
     const long long total = (long long)tiles_m * tiles_n * nbatch;
     if (total > 0x3fffffffLL) return hipErrorInvalidValue;
     const int per_xcd = (int)((total + 7) / 8);
-    constexpr int lds_bytes = (BM + BN) * RB * NST + 1024;    // ring + prefetch dump area
+    constexpr int lds_bytes = (BM + BN) * RB * NST;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
-    auto kern = wino_gemm_kernel<E, BM, BN, RB, NST, PFD>;
+    auto kern = wino_gemm_kernel<E, BM, BN, RB, NST, WGM, WGN>;
     static bool attr_set = false;                 // per instantiation; raising the limit is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 block(256), grid((unsigned)(per_xcd * 8));
+    dim3 block(WGM * WGN * 64), grid((unsigned)(per_xcd * 8));
     hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, (const E*)U, (const E*)V, M,
                        K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd);
     return hipGetLastError();
 }
 
-// Block shapes on offer.  Every ring fits in 64 KB so at least two workgroups share a CU
-// (measured: occupancy buys more than ring depth, because per-CU L2 bandwidth grows with the
-// number of waves that have loads in flight).
+// Block shapes on offer (rows of U x rows of V per workgroup).  Rings are two stages of 128 bytes
+// per row; measured on the SD-shaped layers, occupancy buys more than ring depth.  The 256x256
+// block runs 16 waves (4x4) and halves the L2 traffic per flop; it pays only for very long T.
 struct BlockShape { int bm, bn; double eff; };
-static const BlockShape kMenu[4] = {{128, 128, 1.00}, {128, 64, 0.85}, {64, 128, 0.85}, {64, 64, 0.70}};
+static const BlockShape kMenu[4] = {{128, 128, 1.00}, {128, 64, 0.85}, {64, 128, 0.90}, {64, 64, 0.70}};
 
 // Pick the shape with the least padded MFMA work per unit of (operand reuse x machine fill).
-// WINO_GEMM_SHAPE=0..3 (read once) pins a menu entry, for tuning runs.
+// WINO_GEMM_SHAPE=0..4 (read once) pins an entry, for tuning runs.
 static int pick_shape(int K, int T, int nbatch) {
     static const int forced = [] {
         const char* e = getenv("WINO_GEMM_SHAPE");
-        return (e && e[0] >= '0' && e[0] <= '3' && e[1] == 0) ? e[0] - '0' : -1;
+        return (e && e[0] >= '0' && e[0] <= '4' && e[1] == 0) ? e[0] - '0' : -1;
     }();
     if (forced >= 0) return forced;
+    if (K % 256 == 0 && T >= 4096) return 4;
     int best = 0; double best_score = 1e300;
     for (int i = 0; i < 4; ++i) {
         const double tm = (K + kMenu[i].bm - 1) / kMenu[i].bm, tn = (T + kMenu[i].bn - 1) / kMenu[i].bn;
@@ -289,27 +250,12 @@ static int pick_shape(int K, int T, int nbatch) {
 
 template <typename E>
 static hipError_t launch_gemm_t(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, hipStream_t s) {
-    static const int exp_cfg = [] { const char* e = getenv("WINO_GEMM_CFG"); return e ? atoi(e) : -1; }();
-    switch (exp_cfg) {      // tuning-only configurations
-        case 10: return launch_gemm_cfg<E, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
-        case 11: return launch_gemm_cfg<E, 128, 128, 128, 3>(U, V, M, K, Cp, T, nbatch, s);
-        case 12: return launch_gemm_cfg<E, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
-        case 13: return launch_gemm_cfg<E, 64, 128, 128, 3>(U, V, M, K, Cp, T, nbatch, s);
-        case 14: return launch_gemm_cfg<E, 64, 128, 128, 4>(U, V, M, K, Cp, T, nbatch, s);
-        case 15: return launch_gemm_cfg<E, 128, 128, 128, 4>(U, V, M, K, Cp, T, nbatch, s);
-        case 16: return launch_gemm_cfg<E, 128, 128, 64, 3>(U, V, M, K, Cp, T, nbatch, s);
-        case 17: return launch_gemm_cfg<E, 256, 128, 64, 2>(U, V, M, K, Cp, T, nbatch, s);
-        case 18: return launch_gemm_cfg<E, 128, 256, 64, 2>(U, V, M, K, Cp, T, nbatch, s);
-        case 19: return launch_gemm_cfg<E, 256, 128, 64, 3>(U, V, M, K, Cp, T, nbatch, s);
-        case 20: return launch_gemm_cfg<E, 256, 256, 64, 2>(U, V, M, K, Cp, T, nbatch, s);
-        case 21: return launch_gemm_cfg<E, 128, 256, 64, 3>(U, V, M, K, Cp, T, nbatch, s);
-        default: break;
-    }
     switch (pick_shape(K, T, nbatch)) {
         case 0: return launch_gemm_cfg<E, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
         case 1: return launch_gemm_cfg<E, 128, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
         case 2: return launch_gemm_cfg<E, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
-        default: return launch_gemm_cfg<E, 64, 64, 128, 4>(U, V, M, K, Cp, T, nbatch, s);
+        case 3: return launch_gemm_cfg<E, 64, 64, 128, 4>(U, V, M, K, Cp, T, nbatch, s);
+        default: return launch_gemm_cfg<E, 256, 256, 128, 2, 4, 4>(U, V, M, K, Cp, T, nbatch, s);
     }
 }
 
