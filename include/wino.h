@@ -64,7 +64,8 @@ typedef enum wino_dtype { WINO_F32 = 0, WINO_F16 = 1 } wino_dtype;
  */
 typedef enum wino_variant { WINO_AUTO = 0, WINO_DIRECT = 1, WINO_F2 = 2, WINO_F4 = 4 } wino_variant;
 
-typedef enum wino_layout { WINO_NCHW = 0 } wino_layout;
+/* Layout of x and y only (w is always [K][C][3][3]); NHWC = x[N][H][W][C], y[N][H][W][K]. */
+typedef enum wino_layout { WINO_NCHW = 0, WINO_NHWC = 1 } wino_layout;
 
 /* Host-side descriptor of a transformed filter.  `data` is the caller's device
  * buffer; the blob holds no pointers and can be copied or saved by the caller. */
@@ -107,14 +108,15 @@ int wino_filter_transform(const void *w, void *w_t_data, int K, int C, int dtype
 
 /*
  * The whole path (steps (i) activation, (ii), (iii) + bias) with the variant held
- * in w_t.  x[N][C][H][W] and y[N][K][H][W] in w_t->dtype; y is fully overwritten.
+ * in w_t.  x[N][C][H][W] and y[N][K][H][W] (NCHW) in w_t->dtype; y is fully overwritten.
  * Borrows wino_workspace_bytes() of scratch from hipMallocAsync on `stream` and
  * returns it with hipFreeAsync on `stream`.
  */
 int wino_conv2d(const void *x, const wino_filter *w_t, const float *bias, void *y,
                 int N, int C, int H, int W, int K, void *stream);
 
-/* Same, scratch supplied by the caller; allocates nothing. */
+/* Same, scratch supplied by the caller; allocates nothing.  `layout` is a wino_layout
+ * and applies to both x and y. */
 int wino_conv2d_ex(const void *x, const wino_filter *w_t, const float *bias, void *y,
                    int N, int C, int H, int W, int K, int layout,
                    void *workspace, size_t workspace_bytes, void *stream);

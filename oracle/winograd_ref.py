@@ -136,3 +136,21 @@ def conv2d_winograd(x, w, bias, m: int) -> np.ndarray:
     V = input_transform(x, m)
     M = multiply(U, V)
     return output_transform(M, bias, N, H, W, m)
+
+
+def conv2d_winograd_storage_model(x, w, bias, m: int, store_dtype=np.float16) -> np.ndarray:
+    """Error model of a low-precision Winograd path (not the definition of the result): the
+    same three steps, with U and V rounded once to `store_dtype` as a kernel that keeps them
+    in that type would, the products accumulated exactly (fp64 stands in for fp32), and the
+    output rounded once to `store_dtype`.  Used to predict the relative L2 error a correct
+    fp16-storage implementation must show - far above or far below means a different path ran."""
+    x = np.asarray(x, dtype=np.float64)
+    N, C, H, W = x.shape
+    if np.dtype(store_dtype).itemsize >= 8:
+        q = lambda a: a
+    else:                       # the kernels transform in fp32, then round once to the storage type
+        q = lambda a: a.astype(np.float32).astype(store_dtype).astype(np.float64)
+    U = q(filter_transform(w, m))
+    V = q(input_transform(x, m))
+    M = multiply(U, V)
+    return q(output_transform(M, bias, N, H, W, m))

@@ -21,7 +21,7 @@ WINO_ERR_NULL, WINO_ERR_DIM, WINO_ERR_DTYPE, WINO_ERR_VARIANT = 1, 2, 3, 4
 WINO_ERR_ALIGN, WINO_ERR_WORKSPACE, WINO_ERR_ALIAS, WINO_ERR_HIP, WINO_ERR_LAYOUT = 5, 6, 7, 8, 9
 WINO_F32, WINO_F16 = 0, 1
 WINO_AUTO, WINO_DIRECT, WINO_F2, WINO_F4 = 0, 1, 2, 4
-WINO_NCHW = 0
+WINO_NCHW, WINO_NHWC = 0, 1
 
 DTYPE_OF = {torch.float32: WINO_F32, torch.float16: WINO_F16}
 TORCH_OF = {WINO_F32: torch.float32, WINO_F16: torch.float16}
@@ -103,13 +103,30 @@ def _check(status: int, where: str):
         raise WinoError(status, where)
 
 
-def _conv_shapes(x, w_t, bias, y):
+def _unpack(x, layout):
+    """(N, C, H, W) of an activation tensor stored as NCHW or NHWC."""
+    if x.dim() != 4:
+        raise ValueError("activation tensors are 4-D")
+    if layout == WINO_NHWC:
+        N, H, W, C = map(int, x.shape)
+    elif layout == WINO_NCHW:
+        N, C, H, W = map(int, x.shape)
+    else:
+        raise WinoError(WINO_ERR_LAYOUT, "layout")
+    return N, C, H, W
+
+
+def _act_shape(N, C, H, W, layout):
+    return (N, H, W, C) if layout == WINO_NHWC else (N, C, H, W)
+
+
+def _conv_shapes(x, w_t, bias, y, layout=WINO_NCHW):
     """Host-side shape/dtype agreement (the C side cannot see tensor extents)."""
-    N, C, H, W = map(int, x.shape)
+    N, C, H, W = _unpack(x, layout)
     K = int(w_t.desc.K)
     dt = TORCH_OF[w_t.desc.dtype]
-    if tuple(y.shape) != (N, K, H, W) or x.dtype != dt or y.dtype != dt:
-        raise ValueError(f"expected y[{N},{K},{H},{W}] and dtype {dt} for x and y")
+    if tuple(y.shape) != _act_shape(N, K, H, W, layout) or x.dtype != dt or y.dtype != dt:
+        raise ValueError(f"expected y{_act_shape(N, K, H, W, layout)} and dtype {dt} for x and y")
     if bias is not None and (bias.dtype != torch.float32 or bias.numel() != K or not bias.is_cuda):
         raise ValueError("bias must be a GPU fp32 tensor of K elements")
     return N, C, H, W, K
@@ -184,7 +201,7 @@ def wino_conv2d(x: torch.Tensor, w_t: Filter, bias: Optional[torch.Tensor], y: t
 
 def wino_conv2d_ex(x, w_t: Filter, bias, y, workspace: torch.Tensor, layout: int = WINO_NCHW, stream=None):
     _dev(x, "x"); _dev(y, "y"); _dev(workspace, "workspace")
-    N, C, H, W, K = _conv_shapes(x, w_t, bias, y)
+    N, C, H, W, K = _conv_shapes(x, w_t, bias, y, layout)
     _check(lib().wino_conv2d_ex(_ptr(x), ctypes.byref(w_t.desc), _ptr(bias), _ptr(y), N, C, H, W, K, layout,
                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "wino_conv2d_ex")
@@ -192,9 +209,9 @@ def wino_conv2d_ex(x, w_t: Filter, bias, y, workspace: torch.Tensor, layout: int
 
 
 def wino_input_transform(x: torch.Tensor, variant: int, layout: int = WINO_NCHW, stream=None, out=None) -> torch.Tensor:
-    """x[N,C,H,W] -> V[alpha^2, T, Cp] (same dtype)."""
+    """x[N,C,H,W] (or [N,H,W,C] for NHWC) -> V[alpha^2, T, Cp] (same dtype)."""
     _dev(x, "x")
-    N, C, H, W = map(int, x.shape)
+    N, C, H, W = _unpack(x, layout)
     alpha, Cp, T = wino_transformed_dims(N, C, H, W, 1, variant)
     V = out if out is not None else torch.empty((alpha * alpha, T, Cp), dtype=x.dtype, device=x.device)
     if V.numel() < alpha * alpha * T * Cp or V.dtype != x.dtype:
@@ -225,7 +242,9 @@ def wino_output_transform(M: torch.Tensor, bias, N: int, K: int, H: int, W: int,
     m = variant
     if M.numel() < (m + 2) ** 2 * K * N * (-(-H // m)) * (-(-W // m)) or M.dtype != torch.float32:
         raise ValueError("M buffer too small or not fp32")
-    y = out if out is not None else torch.empty((N, K, H, W), dtype=dtype, device=M.device)
+    y = out if out is not None else torch.empty(_act_shape(N, K, H, W, layout), dtype=dtype, device=M.device)
+    if layout not in (WINO_NCHW, WINO_NHWC):
+        raise WinoError(WINO_ERR_LAYOUT, "layout")
     if y.numel() < N * K * H * W or y.dtype != dtype:
         raise ValueError("y buffer too small or of the wrong dtype")
     _check(lib().wino_output_transform(_ptr(M), _ptr(bias), _ptr(y), N, K, H, W, DTYPE_OF[dtype], variant, layout,
@@ -247,16 +266,18 @@ def wino_direct_conv2d(x: torch.Tensor, w: torch.Tensor, bias, y: torch.Tensor, 
 
 
 # ---- convenience (allocation only) ------------------------------------------------------------
-def conv2d(x: torch.Tensor, w: torch.Tensor, bias=None, variant: int = WINO_AUTO) -> torch.Tensor:
+def conv2d(x: torch.Tensor, w: torch.Tensor, bias=None, variant: int = WINO_AUTO, layout: int = WINO_NCHW) -> torch.Tensor:
     """Transform the filter, allocate workspace and output, run the chosen variant."""
-    N, C, H, W = map(int, x.shape)
+    N, C, H, W = _unpack(x, layout)
     K = int(w.shape[0])
-    y = torch.empty((N, K, H, W), dtype=x.dtype, device=x.device)
+    y = torch.empty(_act_shape(N, K, H, W, layout), dtype=x.dtype, device=x.device)
     v = wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant)
     if v < 0:
         raise WinoError(WINO_ERR_DIM, "wino_resolve_variant")
     if v == WINO_DIRECT:
+        if layout != WINO_NCHW:
+            raise WinoError(WINO_ERR_LAYOUT, "wino_direct_conv2d is NCHW only")
         return wino_direct_conv2d(x, w, bias, y)
     w_t = wino_filter_transform(w, v)
     ws = torch.empty(wino_workspace_bytes(N, C, H, W, K, DTYPE_OF[x.dtype], v), dtype=torch.uint8, device=x.device)
-    return wino_conv2d_ex(x, w_t, bias, y, ws)
+    return wino_conv2d_ex(x, w_t, bias, y, ws, layout)

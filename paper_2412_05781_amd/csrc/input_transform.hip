@@ -201,6 +201,94 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
     }
 }
 
+// NHWC activations (channels contiguous): no transposition is needed, V's rows are channel-
+// contiguous too.  One lane owns CPT adjacent channels of one tile, reads its alpha x alpha window
+// straight from global memory (neighbouring lanes read neighbouring channels, so every load is
+// one contiguous run; the 2.25x / 4x window overlap is served by L1/L2) and stores CPT values
+// per transformed position.  Channels in [C, Cp) are written as zeros.
+template <int M, typename E, int CPT>
+__global__ void __launch_bounds__(256)
+input_transform_nhwc_kernel(const E* __restrict__ x, E* __restrict__ V,
+                            int N, int C, int H, int W, int th, int tw, int T, int Cp) {
+    constexpr int A = M + 2;
+    const int groups = Cp / CPT;                               // Cp is a multiple of 8
+    const size_t item = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= (size_t)T * groups) return;
+    const int gidx = (int)(item % groups);
+    int t = (int)(item / groups);
+    const int c = gidx * CPT;
+    const int tj = t % tw; int q = t / tw;
+    const int ti = q % th;
+    const int n = q / th;
+    const bool live = c < C;                                   // CPT divides C on this path
+    float d[CPT][A][A];
+#pragma unroll
+    for (int a = 0; a < A; ++a) {
+        const int r = M * ti - 1 + a;
+#pragma unroll
+        for (int b = 0; b < A; ++b) {
+            const int col = M * tj - 1 + b;
+            E v[CPT];
+#pragma unroll
+            for (int u = 0; u < CPT; ++u) v[u] = from_f32<E>(0.f);
+            if (live && r >= 0 && r < H && col >= 0 && col < W) {
+                const E* p = x + (((size_t)n * H + r) * W + col) * C + c;
+                if constexpr (CPT == 2) { *reinterpret_cast<uint32_t*>(v) = *reinterpret_cast<const uint32_t*>(p); }
+                else { v[0] = p[0]; }
+            }
+#pragma unroll
+            for (int u = 0; u < CPT; ++u) d[u][a][b] = to_f32<E>(v[u]);
+        }
+    }
+    float o[CPT][A][A];
+#pragma unroll
+    for (int u = 0; u < CPT; ++u) {
+        float tmp[A][A];
+#pragma unroll
+        for (int b = 0; b < A; ++b) {
+            float in[A], out[A];
+#pragma unroll
+            for (int a = 0; a < A; ++a) in[a] = d[u][a][b];
+            bt_1d<M>(in, out);
+#pragma unroll
+            for (int a = 0; a < A; ++a) tmp[a][b] = out[a];
+        }
+#pragma unroll
+        for (int xi = 0; xi < A; ++xi) bt_1d<M>(tmp[xi], o[u][xi]);
+    }
+    const size_t plane = (size_t)T * Cp;
+    E* dst = V + (size_t)t * Cp + c;
+#pragma unroll
+    for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+        for (int nu = 0; nu < A; ++nu) {
+            E v[CPT];
+#pragma unroll
+            for (int u = 0; u < CPT; ++u) v[u] = from_f32<E>(o[u][xi][nu]);
+            E* p = dst + (size_t)(xi * A + nu) * plane;
+            if constexpr (CPT == 2) { *reinterpret_cast<uint32_t*>(p) = *reinterpret_cast<const uint32_t*>(v); }
+            else { p[0] = v[0]; }
+        }
+}
+
+template <int M, typename E>
+static hipError_t launch_it_nhwc(const void* x, void* V, const Geom& g, hipStream_t s) {
+    // two fp16 channels per lane (4-byte accesses) when channel pairs never straddle C
+    const bool pair = sizeof(E) == 2 && g.C % 2 == 0 && (reinterpret_cast<uintptr_t>(x) & 3u) == 0;
+    const int cpt = pair ? 2 : 1;
+    const size_t items = (size_t)g.T * (g.Cp / cpt);
+    const size_t blocks = (items + 255) / 256;
+    if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+    dim3 block(256), grid((unsigned)blocks);
+    if (pair) {
+        if constexpr (sizeof(E) == 2)
+            hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp);
+    } else {
+        hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp);
+    }
+    return hipGetLastError();
+}
+
 template <int M, typename E, int CB, int TJ>
 static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, hipStream_t s) {
     const int strips = (g.tw + TJ - 1) / TJ;
@@ -232,7 +320,11 @@ static hipError_t launch_it(const void* x, void* V, const Geom& g, hipStream_t s
     }
 }
 
-hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, hipStream_t s) {
+hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, bool nhwc, hipStream_t s) {
+    if (nhwc) {
+        if (g.m == 2) return f16 ? launch_it_nhwc<2, __half>(x, V, g, s) : launch_it_nhwc<2, float>(x, V, g, s);
+        return f16 ? launch_it_nhwc<4, __half>(x, V, g, s) : launch_it_nhwc<4, float>(x, V, g, s);
+    }
     if (g.m == 2) return f16 ? launch_it<2, __half>(x, V, g, s) : launch_it<2, float>(x, V, g, s);
     return f16 ? launch_it<4, __half>(x, V, g, s) : launch_it<4, float>(x, V, g, s);
 }

@@ -116,7 +116,83 @@ static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const G
     return launch_ot_cfg<M, E, 1>(Mt, bias, y, g, s);
 }
 
-hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, hipStream_t s) {
+// NHWC output (y[N][H][W][K], channels contiguous).  M is read exactly as in the NCHW kernel
+// (lanes along t), the m x m results are parked in LDS as [tile][a][b][k] and written out with
+// lanes along k, so both sides are contiguous runs.  A workgroup owns KB channels x TB tiles.
+template <int M, typename E, int KB, int TB>
+__global__ void __launch_bounds__(256)
+output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
+                             int N, int K, int H, int W, int th, int tw, int T, int tblocks) {
+    constexpr int A = M + 2;
+    constexpr int KP = KB + (sizeof(E) == 2 ? 2 : 1);          // odd number of 32-bit words per row: no bank conflicts
+    __shared__ E park[TB * M * M * KP];
+    const int tb = blockIdx.x % tblocks, kb = blockIdx.x / tblocks;
+    const int k0 = kb * KB, t0 = tb * TB;
+    const size_t KT = (size_t)K * T;
+    // phase 1: lanes along t (TB consecutive tiles), waves along k
+    for (int it = threadIdx.x; it < KB * TB; it += 256) {
+        const int tl = it % TB, kl = it / TB;
+        const int k = k0 + kl, t = t0 + tl;
+        if (k >= K || t >= T) continue;
+        const size_t f = (size_t)k * T + t;
+        float v[A][A];
+#pragma unroll
+        for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+            for (int nu = 0; nu < A; ++nu) v[xi][nu] = Mt[(size_t)(xi * A + nu) * KT + f];
+        float tmp[M][A];
+#pragma unroll
+        for (int nu = 0; nu < A; ++nu) {
+            float in[A], out[M];
+#pragma unroll
+            for (int xi = 0; xi < A; ++xi) in[xi] = v[xi][nu];
+            at_1d<M>(in, out);
+#pragma unroll
+            for (int a = 0; a < M; ++a) tmp[a][nu] = out[a];
+        }
+        const float b = bias ? bias[k] : 0.f;
+#pragma unroll
+        for (int a = 0; a < M; ++a) {
+            float out[M];
+            at_1d<M>(tmp[a], out);
+#pragma unroll
+            for (int q = 0; q < M; ++q) park[((tl * M + a) * M + q) * KP + kl] = from_f32<E>(out[q] + b);
+        }
+    }
+    __syncthreads();
+    // phase 2: lanes along k
+    for (int it = threadIdx.x; it < TB * M * M * KB; it += 256) {
+        const int kl = it % KB;
+        const int pix = it / KB;                               // (tl, a, q)
+        const int q = pix % M, a = (pix / M) % M, tl = pix / (M * M);
+        const int k = k0 + kl;
+        int t = t0 + tl;
+        if (k >= K || t >= T) continue;
+        const int tj = t % tw; t /= tw;
+        const int ti = t % th;
+        const int n = t / th;
+        const int i = M * ti + a, j = M * tj + q;
+        if (i < H && j < W) y[(((size_t)n * H + i) * W + j) * K + k] = park[pix * KP + kl];
+    }
+}
+
+template <int M, typename E>
+static hipError_t launch_ot_nhwc(const float* Mt, const float* bias, void* y, const Geom& g, hipStream_t s) {
+    constexpr int KB = 64;
+    constexpr int TB = (M == 4) ? 8 : 32;                      // <= 33 KB of LDS either way
+    const int tblocks = (g.T + TB - 1) / TB, kblocks = (g.K + KB - 1) / KB;
+    const long long total = (long long)tblocks * kblocks;
+    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, KB, TB>), dim3((unsigned)total), dim3(256), 0, s,
+                       Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, tblocks);
+    return hipGetLastError();
+}
+
+hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, bool nhwc, hipStream_t s) {
+    if (nhwc) {
+        if (g.m == 2) return f16 ? launch_ot_nhwc<2, __half>(M, bias, y, g, s) : launch_ot_nhwc<2, float>(M, bias, y, g, s);
+        return f16 ? launch_ot_nhwc<4, __half>(M, bias, y, g, s) : launch_ot_nhwc<4, float>(M, bias, y, g, s);
+    }
     if (g.m == 2) return f16 ? launch_ot<2, __half>(M, bias, y, g, s) : launch_ot<2, float>(M, bias, y, g, s);
     return f16 ? launch_ot<4, __half>(M, bias, y, g, s) : launch_ot<4, float>(M, bias, y, g, s);
 }

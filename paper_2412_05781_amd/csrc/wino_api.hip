@@ -47,14 +47,14 @@ Workspace workspace_layout(const Geom& g, int dtype) {
 }
 
 int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y, const Geom& g,
-              void* workspace, hipStream_t s) {
+              void* workspace, bool nhwc, hipStream_t s) {
     const bool f16 = w_t->dtype == WINO_F16;
     const Workspace ws = workspace_layout(g, w_t->dtype);
     void* V = workspace;
     float* M = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + ws.v_bytes);
-    if (launch_input_transform(x, V, g, f16, s) != hipSuccess) return WINO_ERR_HIP;
+    if (launch_input_transform(x, V, g, f16, nhwc, s) != hipSuccess) return WINO_ERR_HIP;
     if (launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, g.alpha * g.alpha, f16, s) != hipSuccess) return WINO_ERR_HIP;
-    if (launch_output_transform(M, bias, y, g, f16, s) != hipSuccess) return WINO_ERR_HIP;
+    if (launch_output_transform(M, bias, y, g, f16, nhwc, s) != hipSuccess) return WINO_ERR_HIP;
     return WINO_OK;
 }
 
@@ -153,12 +153,12 @@ int wino_conv2d_ex(const void* x, const wino_filter* w_t, const float* bias, voi
                    void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_conv_args(x, w_t, bias, y, N, C, H, W, K);
     if (rc != WINO_OK) return rc;
-    if (layout != WINO_NCHW) return WINO_ERR_LAYOUT;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
     const Geom g = make_geom(N, C, H, W, K, w_t->variant);
     const Workspace ws = workspace_layout(g, w_t->dtype);
     if (!workspace || workspace_bytes < ws.total) return WINO_ERR_WORKSPACE;
     if (!aligned16(workspace)) return WINO_ERR_ALIGN;
-    return run_chain(x, w_t, bias, y, g, workspace, static_cast<hipStream_t>(stream));
+    return run_chain(x, w_t, bias, y, g, workspace, layout == WINO_NHWC, static_cast<hipStream_t>(stream));
 }
 
 int wino_conv2d(const void* x, const wino_filter* w_t, const float* bias, void* y,
@@ -170,7 +170,7 @@ int wino_conv2d(const void* x, const wino_filter* w_t, const float* bias, void* 
     hipStream_t s = static_cast<hipStream_t>(stream);
     void* workspace = nullptr;
     if (hipMallocAsync(&workspace, ws.total, s) != hipSuccess || !workspace) return WINO_ERR_HIP;
-    const int rc2 = run_chain(x, w_t, bias, y, g, workspace, s);
+    const int rc2 = run_chain(x, w_t, bias, y, g, workspace, false, s);
     if (hipFreeAsync(workspace, s) != hipSuccess) return WINO_ERR_HIP;
     return rc2;
 }
@@ -180,11 +180,11 @@ int wino_input_transform(const void* x, void* V, int N, int C, int H, int W,
     if (!x || !V) return WINO_ERR_NULL;
     if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
     if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
-    if (layout != WINO_NCHW) return WINO_ERR_LAYOUT;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
     if (!dims_ok(N, C, H, W, 1, variant)) return WINO_ERR_DIM;
     if (!aligned16(x) || !aligned16(V)) return WINO_ERR_ALIGN;
     const Geom g = make_geom(N, C, H, W, 1, variant);
-    return launch_input_transform(x, V, g, dtype == WINO_F16, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_input_transform(x, V, g, dtype == WINO_F16, layout == WINO_NHWC, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
 
@@ -207,11 +207,11 @@ int wino_output_transform(const float* M, const float* bias, void* y, int N, int
     if (!M || !y) return WINO_ERR_NULL;
     if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
     if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
-    if (layout != WINO_NCHW) return WINO_ERR_LAYOUT;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
     if (!dims_ok(N, 1, H, W, K, variant)) return WINO_ERR_DIM;
     if (!aligned16(M) || !aligned16(y)) return WINO_ERR_ALIGN;
     const Geom g = make_geom(N, 1, H, W, K, variant);
-    return launch_output_transform(M, bias, y, g, dtype == WINO_F16, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_output_transform(M, bias, y, g, dtype == WINO_F16, layout == WINO_NHWC, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
 

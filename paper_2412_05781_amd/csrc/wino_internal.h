@@ -39,9 +39,9 @@ template <> __device__ __forceinline__ __half from_f32<__half>(float v) { return
 
 // launchers (each enqueues on `s`, returns the launch status)
 hipError_t launch_filter_transform(const void* w, void* U, int K, int C, int Cp, int m, bool f16, hipStream_t s);
-hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, hipStream_t s);
+hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, bool nhwc, hipStream_t s);
 hipError_t launch_batched_gemm(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, bool f16, hipStream_t s);
-hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, hipStream_t s);
+hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, bool nhwc, hipStream_t s);
 hipError_t launch_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
                                 int N, int C, int H, int W, int K, bool f16, hipStream_t s);
 

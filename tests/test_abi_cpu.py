@@ -91,6 +91,7 @@ def test_argument_validation_happens_before_any_launch(L):
     assert call(vp(0x8000), vp(0x9000), wsb=16) == B.WINO_ERR_WORKSPACE
     assert call(vp(0x8000), vp(0x9000), ws=None) == B.WINO_ERR_WORKSPACE
     assert call(vp(0x8000), vp(0x9000), layout=3) == B.WINO_ERR_LAYOUT
+    assert L.wino_input_transform(good, good, 1, 8, 4, 4, B.WINO_F16, B.WINO_F4, 2, None) == B.WINO_ERR_LAYOUT
     bad = B.wino_filter(); bad.data, bad.K, bad.C, bad.dtype, bad.variant = 0x2000, 8, 8, B.WINO_F16, B.WINO_AUTO
     assert call(vp(0x8000), vp(0x9000), d=bad) == B.WINO_ERR_VARIANT
     assert L.wino_conv2d(None, ctypes.byref(desc), None, vp(0x9000), 1, 8, 4, 4, 8, None) == B.WINO_ERR_NULL

@@ -1,0 +1,38 @@
+"""The rounding-error model of the fp16-storage Winograd path (CPU only).
+
+The paper gives no accuracy figure; the tolerance (relative L2 <= 5e-3 for fp16 storage with fp32
+accumulation) is this build's target.  These tests fix what a CORRECT fp16-storage path must show,
+from the arithmetic alone: F(2x2) rounds to about 5e-4, F(4x4) to about 3e-3 (its transforms
+amplify the rounding of V), both independent of the channel count.  The GPU tests use the same
+bands to detect a path that silently ran something else."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import winograd_ref as wr
+
+# expected relative-L2 band of a correct fp16-storage path, per output tile size
+BANDS = {2: (2.5e-4, 1.0e-3), 4: (1.5e-3, 4.5e-3)}
+
+
+@pytest.mark.parametrize("C", [32, 320])
+@pytest.mark.parametrize("m", [2, 4])
+def test_fp16_storage_error_band(m, C):
+    rng = np.random.default_rng(C + m)
+    N, K, H, W = 1, 16, 16, 16
+    x = rng.standard_normal((N, C, H, W)).astype(np.float16)
+    w = (rng.standard_normal((K, C, 3, 3)) / np.sqrt(9 * C)).astype(np.float16)
+    b = (0.01 * rng.standard_normal(K)).astype(np.float32)
+    ref = oracle.conv2d_direct(x, w, b)
+    y = wr.conv2d_winograd_storage_model(x.astype(np.float64), w.astype(np.float64), b.astype(np.float64), m)
+    err = oracle.rel_l2(y, ref)
+    lo, hi = BANDS[m]
+    assert lo <= err <= hi, (m, C, err)
+    assert err <= 5e-3
+
+
+def test_model_without_rounding_is_exact():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((1, 8, 9, 10)); w = rng.standard_normal((4, 8, 3, 3)); b = rng.standard_normal(4)
+    y = wr.conv2d_winograd_storage_model(x, w, b, 4, store_dtype=np.float64)
+    assert oracle.rel_l2(y, oracle.conv2d_direct(x, w, b)) < 1e-13

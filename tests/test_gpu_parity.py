@@ -99,15 +99,25 @@ def test_stage_by_stage(variant, dtype):
     assert oracle.rel_l2(y.float().cpu().numpy(), y_ref) <= (1e-6 if dtype == "f32" else 6e-4)
 
 
+# what a correct path must show (tests/test_error_model.py derives the fp16 bands on the CPU);
+# the direct fallback rounds only its output, so it sits an order of magnitude lower
+FP16_BAND = {B.WINO_F2: (2.5e-4, 1.0e-3), B.WINO_F4: (1.5e-3, 4.5e-3), B.WINO_DIRECT: (1e-4, 4e-4)}
+
+
 @pytest.mark.parametrize("name", ["A_conv_in", "B_resblock"])
-@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4, B.WINO_DIRECT])
 def test_baseline_configs_full_tensor(name, variant):
     layer = synth.LAYERS[name]
     x, w, b = synth.make_layer_inputs(layer)
     ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
     err = oracle.rel_l2(_run(x, w, b, variant), ref)
-    print(f"{name} F{variant}: relL2 {err:.3e}")
+    print(f"{name} variant {variant}: relL2 {err:.3e}")
     assert err <= TOL[layer.dtype]
+    if layer.dtype == "f16":
+        lo, hi = FP16_BAND[variant]
+        assert lo <= err <= hi, "error outside the band of the requested variant: did another path run?"
+    else:
+        assert 1e-8 <= err, "fp32 result suspiciously exact"
 
 
 SWEEP = [l.name for l in synth.ALL_LAYERS if l.name not in ("A_conv_in", "B_resblock")]
@@ -142,6 +152,49 @@ def test_large_layers_other_variant(name, variant):
     """The variant AUTO does not pick, on the largest workspaces (E4/F2: M alone is 2.1 GB, so byte
     offsets pass 2^31) and the smallest images."""
     _sampled_check(name, variant)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1, 1), (2, 5, 7, 5, 7), (1, 33, 65, 17, 30), (2, 64, 130, 33, 9),
+                                   (1, 100, 40, 12, 40), (2, 136, 200, 16, 16)])
+def test_nhwc_layout(shape, variant, dtype):
+    """Channels-last activations: same operator, x[N,H,W,C] -> y[N,H,W,K]."""
+    N, C, K, H, W = shape
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=2000 + sum(shape))
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    x_nhwc = x.permute(0, 2, 3, 1).contiguous().to(DEV)
+    y = B.conv2d(x_nhwc, w.to(DEV), b.to(DEV), variant, layout=B.WINO_NHWC)
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == (N, H, W, K)
+    y_nchw = y.float().cpu().permute(0, 3, 1, 2).numpy().astype(np.float64)
+    err = oracle.rel_l2(y_nchw, ref)
+    assert err <= TOL[dtype], (shape, variant, dtype, err)
+
+
+def test_nhwc_stages_match_nchw_stages_bitwise():
+    """Both layouts feed the same GEMM: V must be identical, and y identical up to the permutation."""
+    N, C, K, H, W = 2, 48, 40, 14, 19
+    x, w, b = synth.make_inputs(N, C, K, H, W, "f16", seed=9)
+    xd = x.to(DEV)
+    for variant in (B.WINO_F2, B.WINO_F4):
+        V1 = B.wino_input_transform(xd, variant)
+        V2 = B.wino_input_transform(xd.permute(0, 2, 3, 1).contiguous(), variant, layout=B.WINO_NHWC)
+        assert torch.equal(V1, V2)
+        y1 = B.conv2d(xd, w.to(DEV), b.to(DEV), variant)
+        y2 = B.conv2d(xd.permute(0, 2, 3, 1).contiguous(), w.to(DEV), b.to(DEV), variant, layout=B.WINO_NHWC)
+        torch.cuda.synchronize()
+        assert torch.equal(y1, y2.permute(0, 3, 1, 2))
+
+
+def test_nhwc_full_layer():
+    layer = synth.LAYERS["B_resblock"]
+    x, w, b = synth.make_layer_inputs(layer)
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    y = B.conv2d(x.permute(0, 2, 3, 1).contiguous().to(DEV), w.to(DEV), b.to(DEV), B.WINO_AUTO, layout=B.WINO_NHWC)
+    torch.cuda.synchronize()
+    err = oracle.rel_l2(y.float().cpu().permute(0, 3, 1, 2).numpy(), ref)
+    assert err <= TOL["f16"] and FP16_BAND[B.WINO_F4][0] <= err
 
 
 def test_run_to_run_determinism():
