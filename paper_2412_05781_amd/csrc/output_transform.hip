@@ -178,8 +178,10 @@ output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restri
 
 template <int M, typename E>
 static hipError_t launch_ot_nhwc(const float* Mt, const float* bias, void* y, const Geom& g, hipStream_t s) {
-    constexpr int KB = 64;
-    constexpr int TB = (M == 4) ? 8 : 32;                      // <= 33 KB of LDS either way
+    // 32 tiles per block keep the fp32 reads of M in 128-byte runs (they are 4-9x the bytes of
+    // y); 32 channels per block give 64/128-byte runs on the store side.  LDS: 34-68 KB.
+    constexpr int KB = 32;
+    constexpr int TB = (M == 4 && sizeof(E) == 4) ? 16 : ((M == 4) ? 32 : 64);
     const int tblocks = (g.T + TB - 1) / TB, kblocks = (g.K + KB - 1) / KB;
     const long long total = (long long)tblocks * kblocks;
     if (total > 0x7fffffffLL) return hipErrorInvalidValue;

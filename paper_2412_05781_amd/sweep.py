@@ -45,7 +45,7 @@ def graph_time(fn, reps, replays=4):
     return best / reps * 1e-3
 
 
-def run_layer(layer, variant, dev):
+def run_layer(layer, variant, dev, layout=B.WINO_NCHW):
     N, C, K, H, W = layer.N, layer.C, layer.K, layer.H, layer.W
     tdt = synth.TORCH_DTYPE[layer.dtype]
     dt = B.DTYPE_OF[tdt]
@@ -59,16 +59,18 @@ def run_layer(layer, variant, dev):
     nsets = max(2, min(24, -(-(320 << 20) // set_bytes)))
     sets = []
     for _ in range(nsets):
-        sets.append((torch.randn((N, C, H, W), device=dev, generator=g).to(tdt), B.wino_filter_transform(wd, variant),
-                     torch.empty((N, K, H, W), device=dev, dtype=tdt)))
+        xs = (N, H, W, C) if layout == B.WINO_NHWC else (N, C, H, W)
+        ys = (N, H, W, K) if layout == B.WINO_NHWC else (N, K, H, W)
+        sets.append((torch.randn(xs, device=dev, generator=g).to(tdt), B.wino_filter_transform(wd, variant),
+                     torch.empty(ys, device=dev, dtype=tdt)))
     ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, dt, variant), dtype=torch.uint8, device=dev)
     V = torch.empty((a2, T, Cp), dtype=tdt, device=dev)
     M = torch.empty((a2, K, T), dtype=torch.float32, device=dev)
     reps = max(2, min(2 * nsets, 40))
-    t_all = graph_time(lambda i: B.wino_conv2d_ex(sets[i % nsets][0], sets[i % nsets][1], bd, sets[i % nsets][2], ws), reps)
-    t_in = graph_time(lambda i: B.wino_input_transform(sets[i % nsets][0], variant, out=V), reps)
+    t_all = graph_time(lambda i: B.wino_conv2d_ex(sets[i % nsets][0], sets[i % nsets][1], bd, sets[i % nsets][2], ws, layout), reps)
+    t_in = graph_time(lambda i: B.wino_input_transform(sets[i % nsets][0], variant, layout, out=V), reps)
     t_g = graph_time(lambda i: B.wino_batched_gemm(sets[i % nsets][1].buf.view(tdt), V, K, C, T, variant, out=M), reps)
-    t_out = graph_time(lambda i: B.wino_output_transform(M, bd, N, K, H, W, tdt, variant, out=sets[i % nsets][2]), reps)
+    t_out = graph_time(lambda i: B.wino_output_transform(M, bd, N, K, H, W, tdt, variant, layout, out=sets[i % nsets][2]), reps)
     fl = 2 * a2 * K * C * T
     return {
         "layer": layer.name, "variant": f"F{variant}", "dtype": layer.dtype, "us": t_all * 1e6,
@@ -86,6 +88,7 @@ def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--layers", default=",".join(l.name for l in synth.ALL_LAYERS))
     ap.add_argument("--json", default=None)
+    ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"])
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         sys.exit("sweep needs a GPU")
@@ -95,7 +98,7 @@ def main(argv=None):
     for name in args.layers.split(","):
         layer = synth.LAYERS[name]
         for variant in (B.WINO_F2, B.WINO_F4):
-            r = run_layer(layer, variant, dev)
+            r = run_layer(layer, variant, dev, B.WINO_NHWC if args.layout == "nhwc" else B.WINO_NCHW)
             rows.append(r)
             print(f"{r['layer']:18s} {r['variant']:3s} {r['us']:9.2f} {r['direct_equiv_tflops']:8.1f} | {r['us_input']:8.2f} {r['us_gemm']:8.2f} "
                   f"{r['us_output']:8.2f} | {r['gemm_tflops']:8.1f} {r['gemm_pct_mfma_peak']:6.1f} {r['input_GBs']:8.0f} {r['output_GBs']:8.0f}"
