@@ -65,6 +65,12 @@ ALL_LAYERS = _mk([
     ("T1_2560_1280_16",  1, 2560, 1280, 16, "f16"),
     ("T1_320_320_64",    1,  320,  320, 64, "f16"),
     ("T1_640_320_64",    1,  640,  320, 64, "f16"),
+    # the same five shapes with fp32 storage (the paper's F32 model type)
+    ("T1f32_640_640_32",    1,  640,  640, 32, "f32"),
+    ("T1f32_1280_1280_16",  1, 1280, 1280, 16, "f32"),
+    ("T1f32_2560_1280_16",  1, 2560, 1280, 16, "f32"),
+    ("T1f32_320_320_64",    1,  320,  320, 64, "f32"),
+    ("T1f32_640_320_64",    1,  640,  320, 64, "f32"),
 ])
 LAYERS = {l.name: l for l in ALL_LAYERS}
 
