@@ -197,6 +197,46 @@ def test_nhwc_full_layer():
     assert err <= TOL["f16"] and FP16_BAND[B.WINO_F4][0] <= err
 
 
+def test_random_shapes_against_oracle():
+    """Seeded random small problems (all variants, both dtypes, both layouts): ragged tiles in both
+    directions, channel counts off every block size, batch > 1."""
+    rng = np.random.default_rng(20241205)
+    for trial in range(40):
+        N = int(rng.integers(1, 4)); C = int(rng.integers(1, 150)); K = int(rng.integers(1, 150))
+        H = int(rng.integers(1, 40)); W = int(rng.integers(1, 40))
+        dtype = "f16" if trial % 2 else "f32"
+        variant = [B.WINO_F2, B.WINO_F4][(trial // 2) % 2]
+        layout = B.WINO_NHWC if (trial // 4) % 2 else B.WINO_NCHW
+        x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=5000 + trial, with_bias=bool(trial % 3))
+        ref = oracle.conv2d_direct(_np(x), _np(w), None if b is None else _np(b))
+        xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+        y = B.conv2d(xd, w.to(DEV), None if b is None else b.to(DEV), variant, layout=layout)
+        torch.cuda.synchronize()
+        y = y.float().cpu()
+        if layout == B.WINO_NHWC:
+            y = y.permute(0, 3, 1, 2)
+        err = oracle.rel_l2(y.numpy(), ref)
+        assert err <= TOL[dtype], (trial, (N, C, K, H, W), dtype, variant, layout, err)
+
+
+def test_non_default_stream_and_unaligned_pointer():
+    x, w, b = synth.make_inputs(1, 16, 16, 8, 8, "f16", seed=6)
+    xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
+    ref = B.conv2d(xd, wd, bd, B.WINO_F4)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        y = B.conv2d(xd, wd, bd, B.WINO_F4)      # binding passes torch's current stream
+    s.synchronize(); torch.cuda.synchronize()
+    assert torch.equal(y, ref)
+    # a view that starts 2 bytes into a buffer is rejected on the host, nothing is launched
+    big = torch.zeros(xd.numel() + 8, dtype=torch.float16, device=DEV)
+    x_off = big[1:1 + xd.numel()].view(xd.shape)
+    with pytest.raises(B.WinoError) as e:
+        B.conv2d(x_off, wd, bd, B.WINO_F4)
+    assert e.value.status == B.WINO_ERR_ALIGN
+
+
 def test_run_to_run_determinism():
     x, w, b = synth.make_inputs(2, 96, 80, 20, 20, "f16", seed=3)
     xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
