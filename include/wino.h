@@ -138,6 +138,41 @@ int wino_batched_gemm(const void *U, const void *V, float *M, int K, int C, int 
 int wino_output_transform(const float *M, const float *bias, void *y, int N, int K, int H, int W,
                           int dtype, int variant, int layout, void *stream);
 
+/*
+ * The operators on either side of the convolution inside a residual block, fused into the
+ * transforms so that the activation is not rewritten to memory in between (the paper's Section
+ * "Techniques" argues for keeping dependent steps local; it names none of these operators, the
+ * textbook definitions apply):
+ *   on the way in   x' = SiLU(GroupNorm(x)), GroupNorm over gn_groups equal channel groups per image
+ *                   with affine gamma/beta; zero padding applies to x'.  Active iff gn_stats != NULL.
+ *   on the way out  y = conv(x') + bias + addvec[n][k] + residual.  Each part optional.
+ * All pointers are device memory.  residual has the layout, dtype and shape of y and may be y
+ * itself (in-place accumulate) but must not otherwise overlap it.
+ */
+typedef struct wino_fusion {
+    const float *gn_stats;   /* [N][gn_groups][2] = (mean, 1/sqrt(var+eps)), from wino_groupnorm_stats */
+    const float *gn_gamma;   /* fp32 [C] */
+    const float *gn_beta;    /* fp32 [C] */
+    int gn_groups;           /* must divide C */
+    const float *addvec;     /* fp32 [N][K], or NULL */
+    const void *residual;    /* like y, or NULL */
+} wino_fusion;
+
+/* Bytes of the buffer wino_groupnorm_stats writes (statistics first, then its partial sums);
+ * 0 on bad arguments. */
+size_t wino_groupnorm_stats_bytes(int N, int groups);
+
+/* Statistics of x (NCHW or NHWC, `dtype`) for the fused GroupNorm: mean and 1/sqrt(biased
+ * variance + eps) per (image, group), fp32, at the start of `stats` (16-byte aligned, at least
+ * wino_groupnorm_stats_bytes(N, groups)).  Deterministic. */
+int wino_groupnorm_stats(const void *x, float *stats, int N, int C, int H, int W, int groups, float eps,
+                         int dtype, int layout, void *stream);
+
+/* wino_conv2d_ex with the fused operators of `f` (host struct, read during the call). */
+int wino_conv2d_fused(const void *x, const wino_filter *w_t, const float *bias, void *y,
+                      int N, int C, int H, int W, int K, int layout, const wino_fusion *f,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Direct correlation on the GPU from the untransformed filter (fp32 accumulate),
  * one thread per output; a checking fallback, not a fast path. */
 int wino_direct_conv2d(const void *x, const void *w, const float *bias, void *y,

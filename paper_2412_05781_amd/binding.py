@@ -30,13 +30,18 @@ EXPORTS = [
     "wino_version", "wino_status_string", "wino_resolve_variant", "wino_transformed_dims",
     "wino_filter_bytes", "wino_workspace_bytes", "wino_filter_transform", "wino_conv2d",
     "wino_conv2d_ex", "wino_input_transform", "wino_batched_gemm", "wino_output_transform",
-    "wino_direct_conv2d",
+    "wino_direct_conv2d", "wino_groupnorm_stats_bytes", "wino_groupnorm_stats", "wino_conv2d_fused",
 ]
 
 
 class wino_filter(ctypes.Structure):
     _fields_ = [("data", ctypes.c_void_p), ("K", ctypes.c_int), ("C", ctypes.c_int),
                 ("dtype", ctypes.c_int), ("variant", ctypes.c_int)]
+
+
+class wino_fusion(ctypes.Structure):
+    _fields_ = [("gn_stats", ctypes.c_void_p), ("gn_gamma", ctypes.c_void_p), ("gn_beta", ctypes.c_void_p),
+                ("gn_groups", ctypes.c_int), ("addvec", ctypes.c_void_p), ("residual", ctypes.c_void_p)]
 
 
 class WinoError(RuntimeError):
@@ -79,6 +84,11 @@ def lib() -> ctypes.CDLL:
         L.wino_output_transform.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.wino_direct_conv2d.restype = i
         L.wino_direct_conv2d.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp]
+        L.wino_groupnorm_stats_bytes.restype = sz; L.wino_groupnorm_stats_bytes.argtypes = [i, i]
+        L.wino_groupnorm_stats.restype = i
+        L.wino_groupnorm_stats.argtypes = [vp, vp, i, i, i, i, i, ctypes.c_float, i, i, vp]
+        L.wino_conv2d_fused.restype = i
+        L.wino_conv2d_fused.argtypes = [vp, fp, vp, vp, i, i, i, i, i, i, ctypes.POINTER(wino_fusion), vp, sz, vp]
         _lib = L
     return _lib
 
@@ -265,6 +275,59 @@ def wino_direct_conv2d(x: torch.Tensor, w: torch.Tensor, bias, y: torch.Tensor, 
     return y
 
 
+def wino_groupnorm_stats_bytes(N, groups) -> int:
+    return lib().wino_groupnorm_stats_bytes(N, groups)
+
+
+def wino_groupnorm_stats(x: torch.Tensor, groups: int, eps: float = 1e-5, layout: int = WINO_NCHW, stream=None,
+                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """(mean, rstd) per (image, group) for the fused GroupNorm.  Returns the raw byte buffer; its
+    first N*groups*2 floats are the statistics (`stats_view`)."""
+    _dev(x, "x")
+    N, C, H, W = _unpack(x, layout)
+    nbytes = wino_groupnorm_stats_bytes(N, groups)
+    if nbytes == 0 or C % groups:
+        raise WinoError(WINO_ERR_DIM, "wino_groupnorm_stats_bytes")
+    buf = out if out is not None else torch.empty(nbytes, dtype=torch.uint8, device=x.device)
+    if buf.numel() * buf.element_size() < nbytes:
+        raise ValueError("stats buffer too small")
+    _check(lib().wino_groupnorm_stats(_ptr(x), _ptr(buf), N, C, H, W, groups, ctypes.c_float(eps), DTYPE_OF[x.dtype],
+                                      layout, _stream(stream)), "wino_groupnorm_stats")
+    return buf
+
+
+def stats_view(buf: torch.Tensor, N: int, groups: int) -> torch.Tensor:
+    return buf[: N * groups * 8].view(torch.float32).view(N, groups, 2)
+
+
+def wino_conv2d_fused(x, w_t: Filter, bias, y, workspace, layout: int = WINO_NCHW, gn_stats=None, gn_gamma=None,
+                      gn_beta=None, gn_groups: int = 32, addvec=None, residual=None, stream=None):
+    """wino_conv2d_ex with SiLU(GroupNorm(x)) on the way in and + addvec[n,k] + residual on the way out."""
+    _dev(x, "x"); _dev(y, "y"); _dev(workspace, "workspace")
+    N, C, H, W, K = _conv_shapes(x, w_t, bias, y, layout)
+    f = wino_fusion()
+    if gn_stats is not None:
+        for t, n, cnt in ((gn_gamma, "gn_gamma", C), (gn_beta, "gn_beta", C)):
+            if t is None or not t.is_cuda or t.dtype != torch.float32 or t.numel() != cnt or not t.is_contiguous():
+                raise ValueError(f"{n} must be a contiguous GPU fp32 tensor of {cnt} elements")
+        if C % gn_groups or gn_stats.numel() * gn_stats.element_size() < N * gn_groups * 8 or not gn_stats.is_cuda:
+            raise ValueError("gn_stats too small for N x gn_groups, or gn_groups does not divide C")
+        f.gn_stats, f.gn_gamma, f.gn_beta, f.gn_groups = gn_stats.data_ptr(), gn_gamma.data_ptr(), gn_beta.data_ptr(), gn_groups
+    if addvec is not None:
+        if not addvec.is_cuda or addvec.dtype != torch.float32 or tuple(addvec.shape) != (N, K) or not addvec.is_contiguous():
+            raise ValueError("addvec must be a contiguous GPU fp32 tensor [N, K]")
+        f.addvec = addvec.data_ptr()
+    if residual is not None:
+        _dev(residual, "residual")
+        if tuple(residual.shape) != tuple(y.shape) or residual.dtype != y.dtype:
+            raise ValueError("residual must have the shape and dtype of y")
+        f.residual = residual.data_ptr()
+    _check(lib().wino_conv2d_fused(_ptr(x), ctypes.byref(w_t.desc), _ptr(bias), _ptr(y), N, C, H, W, K, layout,
+                                   ctypes.byref(f), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream(stream)), "wino_conv2d_fused")
+    return y
+
+
 # ---- convenience (allocation only) ------------------------------------------------------------
 def conv2d(x: torch.Tensor, w: torch.Tensor, bias=None, variant: int = WINO_AUTO, layout: int = WINO_NCHW) -> torch.Tensor:
     """Transform the filter, allocate workspace and output, run the chosen variant."""
@@ -281,3 +344,18 @@ def conv2d(x: torch.Tensor, w: torch.Tensor, bias=None, variant: int = WINO_AUTO
     w_t = wino_filter_transform(w, v)
     ws = torch.empty(wino_workspace_bytes(N, C, H, W, K, DTYPE_OF[x.dtype], v), dtype=torch.uint8, device=x.device)
     return wino_conv2d_ex(x, w_t, bias, y, ws, layout)
+
+
+def conv2d_fused(x, w, bias=None, variant: int = WINO_AUTO, layout: int = WINO_NCHW, gn_gamma=None, gn_beta=None,
+                 gn_groups: int = 32, eps: float = 1e-5, addvec=None, residual=None) -> torch.Tensor:
+    """Statistics (if GroupNorm is asked for), filter transform, workspace, then the fused call."""
+    N, C, H, W = _unpack(x, layout)
+    K = int(w.shape[0])
+    y = torch.empty(_act_shape(N, K, H, W, layout), dtype=x.dtype, device=x.device)
+    v = wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant)
+    if v not in (WINO_F2, WINO_F4):
+        raise WinoError(WINO_ERR_VARIANT, "conv2d_fused needs a Winograd variant")
+    stats = wino_groupnorm_stats(x, gn_groups, eps, layout) if gn_gamma is not None else None
+    w_t = wino_filter_transform(w, v)
+    ws = torch.empty(wino_workspace_bytes(N, C, H, W, K, DTYPE_OF[x.dtype], v), dtype=torch.uint8, device=x.device)
+    return wino_conv2d_fused(x, w_t, bias, y, ws, layout, stats, gn_gamma, gn_beta, gn_groups, addvec, residual)

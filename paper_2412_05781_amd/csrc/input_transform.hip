@@ -14,10 +14,10 @@
 
 namespace wino {
 
-template <int M, typename E, int CB, int TJ>
+template <int M, typename E, int CB, int TJ, bool PRE>
 __global__ void __launch_bounds__(256)
 input_transform_nchw_kernel(const E* __restrict__ x, E* __restrict__ V,
-                            int N, int C, int H, int W, int th, int tw, int T, int Cp, int strips_per_row) {
+                            int N, int C, int H, int W, int th, int tw, int T, int Cp, int strips_per_row, PreOp pre) {
     constexpr int A = M + 2;
     constexpr int PW = M * TJ + 2;                       // patch width (elements)
     // channel stride: odd number of 32-bit words so lanes (= channels) hit distinct banks
@@ -61,10 +61,18 @@ input_transform_nchw_kernel(const E* __restrict__ x, E* __restrict__ V,
         if (tj >= tw || c >= Cp) continue;
         const E* p = patch + cc * CS + M * tl;
         float d[A][A];
+        PreLane pl = {0.f, 0.f, false};
+        if (PRE) pl = pre_lane(pre, n, c, C);
 #pragma unroll
         for (int a = 0; a < A; ++a)
 #pragma unroll
-            for (int b = 0; b < A; ++b) d[a][b] = to_f32<E>(p[a * PW + b]);
+            for (int b = 0; b < A; ++b) {
+                d[a][b] = to_f32<E>(p[a * PW + b]);
+                if (PRE) {
+                    const int r = M * ti - 1 + a, q = M * tj - 1 + b;
+                    d[a][b] = pre_apply(d[a][b], pl, r >= 0 && r < H && q >= 0 && q < W);
+                }
+            }
         // columns: tmp[:, b] = B^T d[:, b]
         float tmp[A][A];
 #pragma unroll
@@ -92,11 +100,11 @@ input_transform_nchw_kernel(const E* __restrict__ x, E* __restrict__ V,
 // fetched as 16-byte chunks, all loads of a lane issued before the first LDS write, so one global
 // round trip covers the whole patch.  Patch columns run from m*tj0 - EPC to m*(tj0+TJ) + EPC
 // (EPC = elements per chunk); a chunk is either wholly inside the image or wholly outside (zero).
-template <int M, typename E, int CB, int TJ>
+template <int M, typename E, int CB, int TJ, bool PRE>
 __global__ void __launch_bounds__(256)
 input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
                                 int N, int C, int H, int W, int th, int tw, int T, int Cp, int strips_per_row,
-                                int total_blocks, int blocks_per_xcd) {
+                                int total_blocks, int blocks_per_xcd, PreOp pre) {
     constexpr int A = M + 2;
     constexpr int EPC = 16 / (int)sizeof(E);
     static_assert((M * TJ) % EPC == 0, "strip width must be whole chunks");
@@ -167,10 +175,18 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
         if (tj >= tw) break;                              // wave-uniform
         const E* p = pch + (EPC - 1) + M * tl;
         float d[A][A];
+        PreLane pl = {0.f, 0.f, false};
+        if (PRE) pl = pre_lane(pre, n, c, C);
 #pragma unroll
         for (int a = 0; a < A; ++a)
 #pragma unroll
-            for (int b = 0; b < A; ++b) d[a][b] = to_f32<E>(p[a * (NCH * EPC) + b]);
+            for (int b = 0; b < A; ++b) {
+                d[a][b] = to_f32<E>(p[a * (NCH * EPC) + b]);
+                if (PRE) {
+                    const int r = M * ti - 1 + a, q = M * tj - 1 + b;
+                    d[a][b] = pre_apply(d[a][b], pl, r >= 0 && r < H && q >= 0 && q < W);
+                }
+            }
         float tmp[A][A];
 #pragma unroll
         for (int b = 0; b < A; ++b) {
@@ -206,10 +222,10 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
 // straight from global memory (neighbouring lanes read neighbouring channels, so every load is
 // one contiguous run; the 2.25x / 4x window overlap is served by L1/L2) and stores CPT values
 // per transformed position.  Channels in [C, Cp) are written as zeros.
-template <int M, typename E, int CPT>
+template <int M, typename E, int CPT, bool PRE>
 __global__ void __launch_bounds__(256)
 input_transform_nhwc_kernel(const E* __restrict__ x, E* __restrict__ V,
-                            int N, int C, int H, int W, int th, int tw, int T, int Cp) {
+                            int N, int C, int H, int W, int th, int tw, int T, int Cp, PreOp pre) {
     constexpr int A = M + 2;
     const int groups = Cp / CPT;                               // Cp is a multiple of 8
     const size_t item = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -221,6 +237,9 @@ input_transform_nhwc_kernel(const E* __restrict__ x, E* __restrict__ V,
     const int ti = q % th;
     const int n = q / th;
     const bool live = c < C;                                   // CPT divides C on this path
+    PreLane pl[CPT];
+#pragma unroll
+    for (int u = 0; u < CPT; ++u) { pl[u].sc = 0.f; pl[u].sh = 0.f; pl[u].on = false; if (PRE) pl[u] = pre_lane(pre, n, c + u, C); }
     float d[CPT][A][A];
 #pragma unroll
     for (int a = 0; a < A; ++a) {
@@ -237,7 +256,10 @@ input_transform_nhwc_kernel(const E* __restrict__ x, E* __restrict__ V,
                 else { v[0] = p[0]; }
             }
 #pragma unroll
-            for (int u = 0; u < CPT; ++u) d[u][a][b] = to_f32<E>(v[u]);
+            for (int u = 0; u < CPT; ++u) {
+                d[u][a][b] = to_f32<E>(v[u]);
+                if (PRE) d[u][a][b] = pre_apply(d[u][a][b], pl[u], r >= 0 && r < H && col >= 0 && col < W);
+            }
         }
     }
     float o[CPT][A][A];
@@ -272,7 +294,8 @@ input_transform_nhwc_kernel(const E* __restrict__ x, E* __restrict__ V,
 }
 
 template <int M, typename E>
-static hipError_t launch_it_nhwc(const void* x, void* V, const Geom& g, hipStream_t s) {
+static hipError_t launch_it_nhwc(const void* x, void* V, const Geom& g, const PreOp* pre, hipStream_t s) {
+    const PreOp po = pre ? *pre : PreOp();
     // two fp16 channels per lane (4-byte accesses) when channel pairs never straddle C
     const bool pair = sizeof(E) == 2 && g.C % 2 == 0 && (reinterpret_cast<uintptr_t>(x) & 3u) == 0;
     const int cpt = pair ? 2 : 1;
@@ -281,16 +304,20 @@ static hipError_t launch_it_nhwc(const void* x, void* V, const Geom& g, hipStrea
     if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
     dim3 block(256), grid((unsigned)blocks);
     if (pair) {
-        if constexpr (sizeof(E) == 2)
-            hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp);
+        if constexpr (sizeof(E) == 2) {
+            if (pre) hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2, true>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, po);
+            else     hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2, false>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, po);
+        }
     } else {
-        hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp);
+        if (pre) hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1, true>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, po);
+        else     hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1, false>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, po);
     }
     return hipGetLastError();
 }
 
 template <int M, typename E, int CB, int TJ>
-static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, hipStream_t s) {
+static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, const PreOp* pre, hipStream_t s) {
+    const PreOp po = pre ? *pre : PreOp();
     const int strips = (g.tw + TJ - 1) / TJ;
     dim3 block(256), grid((unsigned)(g.N * g.th * strips), (unsigned)((g.Cp + CB - 1) / CB));
     // fast path: rows are whole 16-byte chunks and a 64-channel slab of x spans < 2 GB (32-bit lane offsets)
@@ -300,33 +327,38 @@ static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, hipStream
         const long long total = (long long)grid.x * grid.y;
         if (total > 0x3fffffffLL) return hipErrorInvalidValue;
         const int per_xcd = (int)((total + 7) / 8);
-        hipLaunchKernelGGL((input_transform_nchw_vec_kernel<M, E, CB, TJ>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
-                           (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips, (int)total, per_xcd);
-    } else
-        hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ>), grid, block, 0, s,
-                           (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips);
+        if (pre) hipLaunchKernelGGL((input_transform_nchw_vec_kernel<M, E, CB, TJ, true>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
+                                    (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips, (int)total, per_xcd, po);
+        else     hipLaunchKernelGGL((input_transform_nchw_vec_kernel<M, E, CB, TJ, false>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
+                                    (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips, (int)total, per_xcd, po);
+    } else {
+        if (pre) hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ, true>), grid, block, 0, s,
+                                    (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips, po);
+        else     hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ, false>), grid, block, 0, s,
+                                    (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips, po);
+    }
     return hipGetLastError();
 }
 
 template <int M, typename E>
-static hipError_t launch_it(const void* x, void* V, const Geom& g, hipStream_t s) {
+static hipError_t launch_it(const void* x, void* V, const Geom& g, const PreOp* pre, hipStream_t s) {
     constexpr int Q = 8 / M;      // TJ multiples that keep strips whole 16-byte chunks for fp16
     static const int cfg = [] { const char* e = getenv("WINO_IT_CFG"); return e ? atoi(e) : 0; }();
     switch (cfg) {                // tuning knob: tiles per strip (measured best: one tile per wave)
-        case 1: return launch_it_cfg<M, E, 64, 4 * Q>(x, V, g, s);
-        case 2: return launch_it_cfg<M, E, 64, 1 * Q>(x, V, g, s);
-        case 3: return launch_it_cfg<M, E, 64, 8 * Q>(x, V, g, s);
-        default: return launch_it_cfg<M, E, 64, 2 * Q>(x, V, g, s);
+        case 1: return launch_it_cfg<M, E, 64, 4 * Q>(x, V, g, pre, s);
+        case 2: return launch_it_cfg<M, E, 64, 1 * Q>(x, V, g, pre, s);
+        case 3: return launch_it_cfg<M, E, 64, 8 * Q>(x, V, g, pre, s);
+        default: return launch_it_cfg<M, E, 64, 2 * Q>(x, V, g, pre, s);
     }
 }
 
-hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, bool nhwc, hipStream_t s) {
+hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, bool nhwc, const PreOp* pre, hipStream_t s) {
     if (nhwc) {
-        if (g.m == 2) return f16 ? launch_it_nhwc<2, __half>(x, V, g, s) : launch_it_nhwc<2, float>(x, V, g, s);
-        return f16 ? launch_it_nhwc<4, __half>(x, V, g, s) : launch_it_nhwc<4, float>(x, V, g, s);
+        if (g.m == 2) return f16 ? launch_it_nhwc<2, __half>(x, V, g, pre, s) : launch_it_nhwc<2, float>(x, V, g, pre, s);
+        return f16 ? launch_it_nhwc<4, __half>(x, V, g, pre, s) : launch_it_nhwc<4, float>(x, V, g, pre, s);
     }
-    if (g.m == 2) return f16 ? launch_it<2, __half>(x, V, g, s) : launch_it<2, float>(x, V, g, s);
-    return f16 ? launch_it<4, __half>(x, V, g, s) : launch_it<4, float>(x, V, g, s);
+    if (g.m == 2) return f16 ? launch_it<2, __half>(x, V, g, pre, s) : launch_it<2, float>(x, V, g, pre, s);
+    return f16 ? launch_it<4, __half>(x, V, g, pre, s) : launch_it<4, float>(x, V, g, pre, s);
 }
 
 }  // namespace wino

@@ -28,6 +28,19 @@ __device__ __forceinline__ void store_row(E* p, const float* v) {
     *reinterpret_cast<typename RowVec<E, M>::type*>(p) = r;
 }
 
+// residual row of m elements (same vector type as the store), added in fp32
+template <typename E, int M>
+__device__ __forceinline__ void add_row(const E* p, float* v) {
+    const typename RowVec<E, M>::type r = *reinterpret_cast<const typename RowVec<E, M>::type*>(p);
+    if constexpr (sizeof(E) == 4) {
+        if constexpr (M == 2) { v[0] += r.x; v[1] += r.y; }
+        else { v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w; }
+    } else {
+        if constexpr (M == 2) { const float2 f = __half22float2(r); v[0] += f.x; v[1] += f.y; }
+        else { const float2 f = __half22float2(r.lo), g = __half22float2(r.hi); v[0] += f.x; v[1] += f.y; v[2] += g.x; v[3] += g.y; }
+    }
+}
+
 template <int TPT> struct FVec;
 template <> struct FVec<1> { using type = float; };
 template <> struct FVec<2> { using type = float2; };
@@ -38,7 +51,7 @@ template <> struct FVec<4> { using type = float4; };
 template <int M, typename E, int TPT>
 __global__ void __launch_bounds__(256)
 output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
-                             int N, int K, int H, int W, int th, int tw, int T, int vec_ok) {
+                             int N, int K, int H, int W, int th, int tw, int T, int vec_ok, PostOp post) {
     constexpr int A = M + 2;
     const size_t KT = (size_t)K * T;
     const int Tq = T / TPT;
@@ -75,20 +88,24 @@ output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restri
             for (int a = 0; a < M; ++a) tmp[a][nu] = out[a];
         }
         const int i0 = M * ti, j0 = M * tj;
-        E* yp = y + (((size_t)n * K + k) * H + i0) * W + j0;
+        const size_t yoff = (((size_t)n * K + k) * H + i0) * W + j0;
+        E* yp = y + yoff;
+        const E* rp = post.residual ? static_cast<const E*>(post.residual) + yoff : nullptr;
+        const float bb = b + (post.addvec ? post.addvec[(size_t)n * K + k] : 0.f);
 #pragma unroll
         for (int a = 0; a < M; ++a) {
             float out[M];
             at_1d<M>(tmp[a], out);
 #pragma unroll
-            for (int q = 0; q < M; ++q) out[q] += b;
+            for (int q = 0; q < M; ++q) out[q] += bb;
             if (i0 + a < H) {
                 if (vec_ok) {
+                    if (rp) add_row<E, M>(rp + (size_t)a * W, out);
                     store_row<E, M>(yp + (size_t)a * W, out);
                 } else {
 #pragma unroll
                     for (int q = 0; q < M; ++q)
-                        if (j0 + q < W) yp[(size_t)a * W + q] = from_f32<E>(out[q]);
+                        if (j0 + q < W) yp[(size_t)a * W + q] = from_f32<E>(out[q] + (rp ? to_f32<E>(rp[(size_t)a * W + q]) : 0.f));
                 }
             }
         }
@@ -96,24 +113,25 @@ output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restri
 }
 
 template <int M, typename E, int TPT>
-static hipError_t launch_ot_cfg(const float* Mt, const float* bias, void* y, const Geom& g, hipStream_t s) {
+static hipError_t launch_ot_cfg(const float* Mt, const float* bias, void* y, const Geom& g, const PostOp& post, hipStream_t s) {
     const size_t items = (size_t)g.K * (g.T / TPT);
     dim3 block(256), grid((unsigned)((items + 255) / 256));
-    const int vec_ok = (g.W % M == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0);
+    const int vec_ok = (g.W % M == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0) &&
+                       ((reinterpret_cast<uintptr_t>(post.residual) & 15u) == 0);
     hipLaunchKernelGGL((output_transform_nchw_kernel<M, E, TPT>), grid, block, 0, s,
-                       Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, vec_ok);
+                       Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, vec_ok, post);
     return hipGetLastError();
 }
 
 template <int M, typename E>
-static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const Geom& g, hipStream_t s) {
+static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const Geom& g, const PostOp& post, hipStream_t s) {
     static const int cfg = [] { const char* e = getenv("WINO_OT_TPT"); return e ? atoi(e) : 0; }();   // tuning knob
     // measured over the layer sweep: one tile per lane is never worse in the chained path
     int tpt = cfg ? cfg : 1;
     const bool aligned = (reinterpret_cast<uintptr_t>(Mt) & 15u) == 0;
-    if (tpt == 4 && g.T % 4 == 0 && aligned) return launch_ot_cfg<M, E, 4>(Mt, bias, y, g, s);
-    if (tpt >= 2 && g.T % 2 == 0 && aligned) return launch_ot_cfg<M, E, 2>(Mt, bias, y, g, s);
-    return launch_ot_cfg<M, E, 1>(Mt, bias, y, g, s);
+    if (tpt == 4 && g.T % 4 == 0 && aligned) return launch_ot_cfg<M, E, 4>(Mt, bias, y, g, post, s);
+    if (tpt >= 2 && g.T % 2 == 0 && aligned) return launch_ot_cfg<M, E, 2>(Mt, bias, y, g, post, s);
+    return launch_ot_cfg<M, E, 1>(Mt, bias, y, g, post, s);
 }
 
 // NHWC output (y[N][H][W][K], channels contiguous).  M is read exactly as in the NCHW kernel
@@ -122,7 +140,7 @@ static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const G
 template <int M, typename E, int KB, int TB>
 __global__ void __launch_bounds__(256)
 output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
-                             int N, int K, int H, int W, int th, int tw, int T, int tblocks) {
+                             int N, int K, int H, int W, int th, int tw, int T, int tblocks, PostOp post) {
     constexpr int A = M + 2;
     constexpr int KP = KB + (sizeof(E) == 2 ? 2 : 1);          // odd number of 32-bit words per row: no bank conflicts
     __shared__ E park[TB * M * M * KP];
@@ -150,7 +168,7 @@ output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restri
 #pragma unroll
             for (int a = 0; a < M; ++a) tmp[a][nu] = out[a];
         }
-        const float b = bias ? bias[k] : 0.f;
+        const float b = (bias ? bias[k] : 0.f) + (post.addvec ? post.addvec[(size_t)(t / (th * tw)) * K + k] : 0.f);
 #pragma unroll
         for (int a = 0; a < M; ++a) {
             float out[M];
@@ -172,12 +190,17 @@ output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restri
         const int ti = t % th;
         const int n = t / th;
         const int i = M * ti + a, j = M * tj + q;
-        if (i < H && j < W) y[(((size_t)n * H + i) * W + j) * K + k] = park[pix * KP + kl];
+        if (i < H && j < W) {
+            const size_t o = (((size_t)n * H + i) * W + j) * K + k;
+            // the residual is added after the parked value was rounded to E (one extra rounding)
+            y[o] = post.residual ? from_f32<E>(to_f32<E>(park[pix * KP + kl]) + to_f32<E>(static_cast<const E*>(post.residual)[o]))
+                                 : park[pix * KP + kl];
+        }
     }
 }
 
 template <int M, typename E>
-static hipError_t launch_ot_nhwc(const float* Mt, const float* bias, void* y, const Geom& g, hipStream_t s) {
+static hipError_t launch_ot_nhwc(const float* Mt, const float* bias, void* y, const Geom& g, const PostOp& post, hipStream_t s) {
     // 32 tiles per block keep the fp32 reads of M in 128-byte runs (they are 4-9x the bytes of
     // y); 32 channels per block give 64/128-byte runs on the store side.  LDS: 34-68 KB.
     constexpr int KB = 32;
@@ -186,17 +209,18 @@ static hipError_t launch_ot_nhwc(const float* Mt, const float* bias, void* y, co
     const long long total = (long long)tblocks * kblocks;
     if (total > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, KB, TB>), dim3((unsigned)total), dim3(256), 0, s,
-                       Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, tblocks);
+                       Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, tblocks, post);
     return hipGetLastError();
 }
 
-hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, bool nhwc, hipStream_t s) {
+hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, bool nhwc, const PostOp* postp, hipStream_t s) {
+    const PostOp post = postp ? *postp : PostOp();
     if (nhwc) {
-        if (g.m == 2) return f16 ? launch_ot_nhwc<2, __half>(M, bias, y, g, s) : launch_ot_nhwc<2, float>(M, bias, y, g, s);
-        return f16 ? launch_ot_nhwc<4, __half>(M, bias, y, g, s) : launch_ot_nhwc<4, float>(M, bias, y, g, s);
+        if (g.m == 2) return f16 ? launch_ot_nhwc<2, __half>(M, bias, y, g, post, s) : launch_ot_nhwc<2, float>(M, bias, y, g, post, s);
+        return f16 ? launch_ot_nhwc<4, __half>(M, bias, y, g, post, s) : launch_ot_nhwc<4, float>(M, bias, y, g, post, s);
     }
-    if (g.m == 2) return f16 ? launch_ot<2, __half>(M, bias, y, g, s) : launch_ot<2, float>(M, bias, y, g, s);
-    return f16 ? launch_ot<4, __half>(M, bias, y, g, s) : launch_ot<4, float>(M, bias, y, g, s);
+    if (g.m == 2) return f16 ? launch_ot<2, __half>(M, bias, y, g, post, s) : launch_ot<2, float>(M, bias, y, g, post, s);
+    return f16 ? launch_ot<4, __half>(M, bias, y, g, post, s) : launch_ot<4, float>(M, bias, y, g, post, s);
 }
 
 }  // namespace wino

@@ -47,14 +47,14 @@ Workspace workspace_layout(const Geom& g, int dtype) {
 }
 
 int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y, const Geom& g,
-              void* workspace, bool nhwc, hipStream_t s) {
+              void* workspace, bool nhwc, const PreOp* pre, const PostOp* post, hipStream_t s) {
     const bool f16 = w_t->dtype == WINO_F16;
     const Workspace ws = workspace_layout(g, w_t->dtype);
     void* V = workspace;
     float* M = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + ws.v_bytes);
-    if (launch_input_transform(x, V, g, f16, nhwc, s) != hipSuccess) return WINO_ERR_HIP;
+    if (launch_input_transform(x, V, g, f16, nhwc, pre, s) != hipSuccess) return WINO_ERR_HIP;
     if (launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, g.alpha * g.alpha, f16, s) != hipSuccess) return WINO_ERR_HIP;
-    if (launch_output_transform(M, bias, y, g, f16, nhwc, s) != hipSuccess) return WINO_ERR_HIP;
+    if (launch_output_transform(M, bias, y, g, f16, nhwc, post, s) != hipSuccess) return WINO_ERR_HIP;
     return WINO_OK;
 }
 
@@ -158,7 +158,7 @@ int wino_conv2d_ex(const void* x, const wino_filter* w_t, const float* bias, voi
     const Workspace ws = workspace_layout(g, w_t->dtype);
     if (!workspace || workspace_bytes < ws.total) return WINO_ERR_WORKSPACE;
     if (!aligned16(workspace)) return WINO_ERR_ALIGN;
-    return run_chain(x, w_t, bias, y, g, workspace, layout == WINO_NHWC, static_cast<hipStream_t>(stream));
+    return run_chain(x, w_t, bias, y, g, workspace, layout == WINO_NHWC, nullptr, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int wino_conv2d(const void* x, const wino_filter* w_t, const float* bias, void* y,
@@ -170,9 +170,60 @@ int wino_conv2d(const void* x, const wino_filter* w_t, const float* bias, void* 
     hipStream_t s = static_cast<hipStream_t>(stream);
     void* workspace = nullptr;
     if (hipMallocAsync(&workspace, ws.total, s) != hipSuccess || !workspace) return WINO_ERR_HIP;
-    const int rc2 = run_chain(x, w_t, bias, y, g, workspace, false, s);
+    const int rc2 = run_chain(x, w_t, bias, y, g, workspace, false, nullptr, nullptr, s);
     if (hipFreeAsync(workspace, s) != hipSuccess) return WINO_ERR_HIP;
     return rc2;
+}
+
+size_t wino_groupnorm_stats_bytes(int N, int groups) {
+    if (N < 1 || groups < 1 || (long long)N * groups > (1LL << 24)) return 0;
+    return groupnorm_stats_bytes(N, groups);
+}
+
+int wino_groupnorm_stats(const void* x, float* stats, int N, int C, int H, int W, int groups, float eps,
+                         int dtype, int layout, void* stream) {
+    if (!x || !stats) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    if (!dims_ok(N, C, H, W, 1, 2) || groups < 1 || C % groups != 0 || (long long)N * groups > (1LL << 24) ||
+        (long long)H * W > INT_MAX || !(eps >= 0.f)) return WINO_ERR_DIM;
+    if (!aligned16(x) || !aligned16(stats)) return WINO_ERR_ALIGN;
+    return launch_groupnorm_stats(x, stats, N, C, H, W, groups, eps, dtype == WINO_F16, layout == WINO_NHWC,
+                                  static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+}
+
+int wino_conv2d_fused(const void* x, const wino_filter* w_t, const float* bias, void* y,
+                      int N, int C, int H, int W, int K, int layout, const wino_fusion* f,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_conv_args(x, w_t, bias, y, N, C, H, W, K);
+    if (rc != WINO_OK) return rc;
+    if (!f) return WINO_ERR_NULL;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    PreOp pre; PostOp post;
+    const bool has_pre = f->gn_stats != nullptr;
+    if (has_pre) {
+        if (!f->gn_gamma || !f->gn_beta) return WINO_ERR_NULL;
+        if (f->gn_groups < 1 || C % f->gn_groups != 0) return WINO_ERR_DIM;
+        if ((reinterpret_cast<uintptr_t>(f->gn_stats) | reinterpret_cast<uintptr_t>(f->gn_gamma) |
+             reinterpret_cast<uintptr_t>(f->gn_beta)) & 3u) return WINO_ERR_ALIGN;
+        pre.stats = f->gn_stats; pre.gamma = f->gn_gamma; pre.beta = f->gn_beta;
+        pre.groups = f->gn_groups; pre.cpg = C / f->gn_groups;
+    }
+    if (f->addvec && (reinterpret_cast<uintptr_t>(f->addvec) & 3u)) return WINO_ERR_ALIGN;
+    if (f->residual) {
+        if (!aligned16(f->residual)) return WINO_ERR_ALIGN;
+        const size_t es = esize(w_t->dtype);
+        const uintptr_t rb = reinterpret_cast<uintptr_t>(f->residual), re = rb + (size_t)N * K * H * W * es;
+        const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + (size_t)N * K * H * W * es;
+        if (rb != yb && rb < ye && yb < re) return WINO_ERR_ALIAS;    // identical is fine (each element read, then written, by one lane)
+    }
+    post.addvec = f->addvec; post.residual = f->residual;
+    const Geom g = make_geom(N, C, H, W, K, w_t->variant);
+    const Workspace ws = workspace_layout(g, w_t->dtype);
+    if (!workspace || workspace_bytes < ws.total) return WINO_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return WINO_ERR_ALIGN;
+    return run_chain(x, w_t, bias, y, g, workspace, layout == WINO_NHWC, has_pre ? &pre : nullptr, &post,
+                     static_cast<hipStream_t>(stream));
 }
 
 int wino_input_transform(const void* x, void* V, int N, int C, int H, int W,
@@ -184,7 +235,7 @@ int wino_input_transform(const void* x, void* V, int N, int C, int H, int W,
     if (!dims_ok(N, C, H, W, 1, variant)) return WINO_ERR_DIM;
     if (!aligned16(x) || !aligned16(V)) return WINO_ERR_ALIGN;
     const Geom g = make_geom(N, C, H, W, 1, variant);
-    return launch_input_transform(x, V, g, dtype == WINO_F16, layout == WINO_NHWC, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_input_transform(x, V, g, dtype == WINO_F16, layout == WINO_NHWC, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
 
@@ -211,7 +262,7 @@ int wino_output_transform(const float* M, const float* bias, void* y, int N, int
     if (!dims_ok(N, 1, H, W, K, variant)) return WINO_ERR_DIM;
     if (!aligned16(M) || !aligned16(y)) return WINO_ERR_ALIGN;
     const Geom g = make_geom(N, 1, H, W, K, variant);
-    return launch_output_transform(M, bias, y, g, dtype == WINO_F16, layout == WINO_NHWC, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_output_transform(M, bias, y, g, dtype == WINO_F16, layout == WINO_NHWC, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
 

@@ -37,11 +37,46 @@ template <typename E> __device__ __forceinline__ E from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ __half from_f32<__half>(float v) { return __float2half_rn(v); }
 
+// Optional operators fused around the convolution.  PreOp: x' = SiLU(GroupNorm(x)) applied as the
+// activation transform loads x (stats = (mean, rstd) per (n, group)); PostOp: y += addvec[n][k] +
+// residual in the output transform.  Null pointers switch a part off.
+struct PreOp {
+    const float* stats = nullptr;     // [N][groups][2]
+    const float* gamma = nullptr;     // [C]
+    const float* beta = nullptr;      // [C]
+    int groups = 1;
+    int cpg = 1;                      // channels per group
+};
+struct PostOp {
+    const float* addvec = nullptr;    // [N][K]
+    const void* residual = nullptr;   // like y
+};
+
+// per-lane constants of the fused GroupNorm: v = x*sc + sh, then SiLU; zero outside the image
+struct PreLane { float sc, sh; bool on; };
+__device__ __forceinline__ PreLane pre_lane(const PreOp& pre, int n, int c, int C) {
+    PreLane l; l.on = c < C; l.sc = 0.f; l.sh = 0.f;
+    if (l.on) {
+        const float* st = pre.stats + ((size_t)n * pre.groups + c / pre.cpg) * 2;
+        l.sc = pre.gamma[c] * st[1];
+        l.sh = pre.beta[c] - st[0] * l.sc;
+    }
+    return l;
+}
+__device__ __forceinline__ float pre_apply(float x, const PreLane& l, bool in_image) {
+    if (!(l.on && in_image)) return 0.f;
+    const float v = fmaf(x, l.sc, l.sh);
+    return __fdividef(v, 1.f + __expf(-v));
+}
+
 // launchers (each enqueues on `s`, returns the launch status)
 hipError_t launch_filter_transform(const void* w, void* U, int K, int C, int Cp, int m, bool f16, hipStream_t s);
-hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, bool nhwc, hipStream_t s);
+hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, bool nhwc, const PreOp* pre, hipStream_t s);
 hipError_t launch_batched_gemm(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, bool f16, hipStream_t s);
-hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, bool nhwc, hipStream_t s);
+hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, bool nhwc, const PostOp* post, hipStream_t s);
+hipError_t launch_groupnorm_stats(const void* x, float* stats, int N, int C, int H, int W, int groups, float eps,
+                                  bool f16, bool nhwc, hipStream_t s);
+size_t groupnorm_stats_bytes(int N, int groups);
 hipError_t launch_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
                                 int N, int C, int H, int W, int K, bool f16, hipStream_t s);
 

@@ -106,6 +106,30 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.wino_direct_conv2d(vp(0x8000), good, None, vp(0x8000), 1, 8, 4, 4, 8, B.WINO_F16, None) == B.WINO_ERR_ALIAS
 
 
+def test_fused_entry_points_validate_on_the_host(L):
+    vp = ctypes.c_void_p
+    assert B.wino_groupnorm_stats_bytes(2, 32) >= 2 * 32 * 8
+    assert B.wino_groupnorm_stats_bytes(0, 32) == 0
+    good = vp(0x1000)
+    f32 = ctypes.c_float(1e-5)
+    assert L.wino_groupnorm_stats(None, good, 1, 8, 4, 4, 2, f32, B.WINO_F16, 0, None) == B.WINO_ERR_NULL
+    assert L.wino_groupnorm_stats(good, good, 1, 8, 4, 4, 3, f32, B.WINO_F16, 0, None) == B.WINO_ERR_DIM      # 3 does not divide 8
+    assert L.wino_groupnorm_stats(good, good, 1, 8, 4, 4, 2, f32, B.WINO_F16, 5, None) == B.WINO_ERR_LAYOUT
+    desc = B.wino_filter(); desc.data, desc.K, desc.C, desc.dtype, desc.variant = 0x2000, 8, 8, B.WINO_F16, B.WINO_F4
+    f = B.wino_fusion()
+    call = lambda fus, y=vp(0x9000): L.wino_conv2d_fused(vp(0x8000), ctypes.byref(desc), None, y, 1, 8, 4, 4, 8, 0,
+                                                        fus, vp(0x100000), 1 << 30, None)
+    assert call(None) == B.WINO_ERR_NULL
+    f.gn_stats = 0x3000                                   # GroupNorm on, gamma/beta missing
+    assert call(ctypes.byref(f)) == B.WINO_ERR_NULL
+    f.gn_gamma, f.gn_beta, f.gn_groups = 0x4000, 0x5000, 3
+    assert call(ctypes.byref(f)) == B.WINO_ERR_DIM
+    f.gn_groups = 2; f.residual = 0x9010                  # overlaps y without being y
+    assert call(ctypes.byref(f)) == B.WINO_ERR_ALIAS
+    f.residual = 0x9004
+    assert call(ctypes.byref(f)) == B.WINO_ERR_ALIGN
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))

@@ -1,0 +1,102 @@
+"""Parity of the fused entry point (GroupNorm + SiLU on the way in, vector and residual adds on the
+way out) against the fp64 oracle; same tolerances as the plain path (relative L2 <= 1e-5 fp32,
+<= 5e-3 fp16)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import fused_ops as fo
+from paper_2412_05781_amd import binding as B
+from paper_2412_05781_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = {"f32": 1e-5, "f16": 5e-3}
+
+
+def _np(t):
+    return None if t is None else t.float().numpy().astype(np.float64)
+
+
+def _extras(N, C, K, H, W, dtype, seed):
+    g = torch.Generator().manual_seed(seed)
+    gamma = 1.0 + 0.2 * torch.randn(C, generator=g)
+    beta = 0.3 * torch.randn(C, generator=g)
+    addvec = 0.5 * torch.randn(N, K, generator=g)
+    residual = torch.randn(N, K, H, W, generator=g).to(synth.TORCH_DTYPE[dtype])
+    return gamma, beta, addvec, residual
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("groups", [1, 4])
+def test_groupnorm_stats(dtype, groups):
+    for layout in (B.WINO_NCHW, B.WINO_NHWC):
+        for (N, C, H, W) in [(2, 8, 5, 7), (1, 32, 64, 64), (3, 12, 1, 1), (1, 64, 200, 200)]:
+            x = (torch.randn(N, C, H, W, generator=torch.Generator().manual_seed(C + H)) * 1.7 + 0.4).to(synth.TORCH_DTYPE[dtype])
+            xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+            st = B.stats_view(B.wino_groupnorm_stats(xd, groups, 1e-5, layout), N, groups).cpu().numpy().astype(np.float64)
+            mean, rstd = fo.groupnorm_stats(_np(x), groups, 1e-5)
+            assert np.abs(st[:, :, 0] - mean).max() <= 2e-6 * (1 + np.abs(mean).max())
+            assert np.abs(st[:, :, 1] / rstd - 1).max() <= 5e-6
+
+
+CASES = [(1, 8, 8, 4, 4, 4), (2, 24, 40, 9, 13, 4), (1, 64, 130, 17, 30, 32), (2, 96, 40, 16, 16, 32), (1, 40, 33, 33, 6, 8)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("case", CASES)
+def test_fused_full_tensor(case, layout, variant, dtype):
+    N, C, K, H, W, G = case
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=3000 + sum(case))
+    gamma, beta, addvec, residual = _extras(N, C, K, H, W, dtype, 77 + sum(case))
+    ref = fo.conv2d_fused(_np(x), _np(w), _np(b), _np(gamma), _np(beta), G, 1e-5, _np(addvec), _np(residual))
+    perm = (lambda t: t.permute(0, 2, 3, 1).contiguous()) if layout == B.WINO_NHWC else (lambda t: t)
+    y = B.conv2d_fused(perm(x).to(DEV), w.to(DEV), b.to(DEV), variant, layout, gamma.to(DEV), beta.to(DEV), G, 1e-5,
+                       addvec.to(DEV), perm(residual).to(DEV))
+    torch.cuda.synchronize()
+    y = y.float().cpu()
+    if layout == B.WINO_NHWC:
+        y = y.permute(0, 3, 1, 2)
+    err = oracle.rel_l2(y.numpy(), ref)
+    assert err <= TOL[dtype], (case, layout, variant, dtype, err)
+
+
+def test_each_part_alone_and_in_place_residual():
+    N, C, K, H, W, G = 2, 32, 32, 12, 12, 8
+    x, w, b = synth.make_inputs(N, C, K, H, W, "f16", seed=11)
+    gamma, beta, addvec, residual = _extras(N, C, K, H, W, "f16", 12)
+    xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
+    # nothing switched on: identical to the plain entry point
+    assert torch.equal(B.conv2d_fused(xd, wd, bd, B.WINO_F4), B.conv2d(xd, wd, bd, B.WINO_F4))
+    # only the pre-op
+    y = B.conv2d_fused(xd, wd, bd, B.WINO_F4, gn_gamma=gamma.to(DEV), gn_beta=beta.to(DEV), gn_groups=G)
+    ref = fo.conv2d_fused(_np(x), _np(w), _np(b), _np(gamma), _np(beta), G)
+    assert oracle.rel_l2(y.float().cpu().numpy(), ref) <= 5e-3
+    # only the post-ops
+    y = B.conv2d_fused(xd, wd, bd, B.WINO_F4, addvec=addvec.to(DEV), residual=residual.to(DEV))
+    ref = fo.conv2d_fused(_np(x), _np(w), _np(b), addvec=_np(addvec), residual=_np(residual))
+    assert oracle.rel_l2(y.float().cpu().numpy(), ref) <= 5e-3
+    # residual may be y itself
+    w_t = B.wino_filter_transform(wd, B.WINO_F4)
+    ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, B.WINO_F4), dtype=torch.uint8, device=DEV)
+    acc = residual.to(DEV).clone()
+    B.wino_conv2d_fused(xd, w_t, bd, acc, ws, residual=acc)
+    torch.cuda.synchronize()
+    assert torch.equal(acc, B.conv2d_fused(xd, wd, bd, B.WINO_F4, residual=residual.to(DEV)))
+
+
+def test_fused_resblock_layer_full_size():
+    """Layer B as it sits in a residual block: GroupNorm(32) + SiLU in, time-embedding vector and skip tensor out."""
+    layer = synth.LAYERS["B_resblock"]
+    x, w, b = synth.make_layer_inputs(layer)
+    gamma, beta, addvec, residual = _extras(layer.N, layer.C, layer.K, layer.H, layer.W, "f16", 5)
+    y = B.conv2d_fused(x.to(DEV), w.to(DEV), b.to(DEV), B.WINO_AUTO, B.WINO_NCHW, gamma.to(DEV), beta.to(DEV), 32, 1e-5,
+                       addvec.to(DEV), residual.to(DEV))
+    torch.cuda.synchronize()
+    ref = fo.conv2d_fused(_np(x), _np(w), _np(b), _np(gamma), _np(beta), 32, 1e-5, _np(addvec), _np(residual))
+    err = oracle.rel_l2(y.float().cpu().numpy(), ref)
+    print(f"fused B layer: relL2 {err:.3e}")
+    assert err <= 5e-3
