@@ -15,6 +15,36 @@ size_t groupnorm_stats_bytes(int N, int groups) {
     return ((ng * 2 * sizeof(float) + 255) / 256) * 256 + ng * kMaxSplit * 2 * sizeof(double);
 }
 
+// block reduction of (s, q): fp32 inside a wave (shuffles), fp64 across the four waves
+__device__ __forceinline__ void block_reduce_store(float s, float q, double* dst) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) { s += __shfl_down(s, off, 64); q += __shfl_down(q, off, 64); }
+    __shared__ double ws[4], wq[4];
+    if ((threadIdx.x & 63) == 0) { ws[threadIdx.x >> 6] = (double)s; wq[threadIdx.x >> 6] = (double)q; }
+    __syncthreads();
+    if (threadIdx.x == 0) { dst[0] = ws[0] + ws[1] + ws[2] + ws[3]; dst[1] = wq[0] + wq[1] + wq[2] + wq[3]; }
+}
+
+// NCHW fast path: a group is one contiguous run of cpg*H*W elements; 16-byte loads.
+template <typename E>
+__global__ void __launch_bounds__(256)
+groupnorm_partial_vec_kernel(const E* __restrict__ x, double* __restrict__ partial, size_t group_elems, int split,
+                             size_t per_slice) {
+    constexpr int EPC = 16 / (int)sizeof(E);
+    const int ng = blockIdx.x, sl = blockIdx.y;
+    const E* base = x + (size_t)ng * group_elems;          // groups of all images are laid end to end
+    const size_t lo = (size_t)sl * per_slice;
+    size_t hi = lo + per_slice; hi = hi < group_elems ? hi : group_elems;
+    float s = 0.f, q = 0.f;
+    for (size_t e = lo + (size_t)threadIdx.x * EPC; e < hi; e += 256 * EPC) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(base + e);
+        const E* v = reinterpret_cast<const E*>(&raw);
+#pragma unroll
+        for (int u = 0; u < EPC; ++u) { const float f = to_f32<E>(v[u]); s += f; q = fmaf(f, f, q); }
+    }
+    block_reduce_store(s, q, partial + ((size_t)ng * split + sl) * 2);
+}
+
 template <typename E, bool NHWC>
 __global__ void __launch_bounds__(256)
 groupnorm_partial_kernel(const E* __restrict__ x, double* __restrict__ partial, int C, int HW, int groups, int cpg,
@@ -32,17 +62,7 @@ groupnorm_partial_kernel(const E* __restrict__ x, double* __restrict__ partial, 
         const float v = to_f32<E>(x[idx]);
         s += v; q = fmaf(v, v, q);
     }
-    __shared__ double ss[256], qq[256];
-    ss[threadIdx.x] = (double)s; qq[threadIdx.x] = (double)q;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) { ss[threadIdx.x] += ss[threadIdx.x + w]; qq[threadIdx.x] += qq[threadIdx.x + w]; }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        partial[((size_t)ng * split + sl) * 2 + 0] = ss[0];
-        partial[((size_t)ng * split + sl) * 2 + 1] = qq[0];
-    }
+    block_reduce_store(s, q, partial + ((size_t)ng * split + sl) * 2);
 }
 
 __global__ void groupnorm_finalize_kernel(const double* __restrict__ partial, float* __restrict__ stats, int total,
@@ -62,13 +82,21 @@ hipError_t launch_groupnorm_stats(const void* x, float* stats, int N, int C, int
                                   bool f16, bool nhwc, hipStream_t s) {
     const int cpg = C / groups, HW = H * W, total = N * groups;
     const size_t elems = (size_t)cpg * HW;
-    int split = (int)((elems + 16383) / 16384);
+    const size_t esz = f16 ? 2 : 4, epc = 16 / esz;
+    // slices are whole numbers of block-wide 16-byte loads (256 lanes x 16 bytes)
+    const size_t quantum = 256 * epc;
+    int split = (int)((elems + 2 * quantum - 1) / (2 * quantum));
     split = split < 1 ? 1 : (split > kMaxSplit ? kMaxSplit : split);
-    const size_t per_slice = (elems + split - 1) / split;
+    size_t per_slice = (elems + split - 1) / split;
+    per_slice = (per_slice + quantum - 1) / quantum * quantum;
     double* partial = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(stats) +
                                                 (((size_t)total * 2 * sizeof(float) + 255) / 256) * 256);
     dim3 grid((unsigned)total, (unsigned)split), block(256);
-    if (f16) {
+    const bool vec = !nhwc && (elems * esz) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+    if (vec) {
+        if (f16) hipLaunchKernelGGL((groupnorm_partial_vec_kernel<__half>), grid, block, 0, s, (const __half*)x, partial, elems, split, per_slice);
+        else     hipLaunchKernelGGL((groupnorm_partial_vec_kernel<float>), grid, block, 0, s, (const float*)x, partial, elems, split, per_slice);
+    } else if (f16) {
         if (nhwc) hipLaunchKernelGGL((groupnorm_partial_kernel<__half, true>), grid, block, 0, s, (const __half*)x, partial, C, HW, groups, cpg, split, per_slice);
         else      hipLaunchKernelGGL((groupnorm_partial_kernel<__half, false>), grid, block, 0, s, (const __half*)x, partial, C, HW, groups, cpg, split, per_slice);
     } else {
