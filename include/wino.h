@@ -130,6 +130,10 @@ int wino_conv2d_ex(const void *x, const wino_filter *w_t, const float *bias, voi
  *   U[alpha^2][K][Cp]  e     as produced by wino_filter_transform
  *   M[alpha^2][K][T]   fp32  step (ii): M[xi,nu,k,t] = sum_c U[xi,nu,k,c] * V[xi,nu,t,c]
  *   y[N][K][H][W]      e     step (iii): y tile = A^T M[.,.,k,t] A (+ bias[k]), cropped to HxW
+ * Channel-last (WINO_NHWC): the product is kept transposed, M[alpha^2][T][K], so that the channel
+ * index stays contiguous from x to y.  wino_batched_gemm is symmetric in its two operands: called
+ * as (V, U, M, T, C, K) it writes exactly that tensor, and wino_output_transform with
+ * layout = WINO_NHWC reads it (and only it).  wino_conv2d_ex does the same internally.
  */
 int wino_input_transform(const void *x, void *V, int N, int C, int H, int W,
                          int dtype, int variant, int layout, void *stream);

@@ -225,10 +225,13 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
 template <int M, typename E, int CPT, bool PRE>
 __global__ void __launch_bounds__(256)
 input_transform_nhwc_kernel(const E* __restrict__ x, E* __restrict__ V,
-                            int N, int C, int H, int W, int th, int tw, int T, int Cp, PreOp pre) {
+                            int N, int C, int H, int W, int th, int tw, int T, int Cp, int per_xcd, PreOp pre) {
     constexpr int A = M + 2;
     const int groups = Cp / CPT;                               // Cp is a multiple of 8
-    const size_t item = (size_t)blockIdx.x * 256 + threadIdx.x;
+    // workgroups go round-robin to the 8 XCDs: give each XCD one contiguous range of tiles, so
+    // that the window overlap between neighbouring tiles is served by that XCD's own L2
+    const size_t logical = (size_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const size_t item = logical * 256 + threadIdx.x;
     if (item >= (size_t)T * groups) return;
     const int gidx = (int)(item % groups);
     int t = (int)(item / groups);
@@ -240,25 +243,39 @@ input_transform_nhwc_kernel(const E* __restrict__ x, E* __restrict__ V,
     PreLane pl[CPT];
 #pragma unroll
     for (int u = 0; u < CPT; ++u) { pl[u].sc = 0.f; pl[u].sh = 0.f; pl[u].on = false; if (PRE) pl[u] = pre_lane(pre, n, c + u, C); }
+    // Every load is issued unconditionally from a clamped (always valid) address and the loaded
+    // bits are ANDed with an all-ones / all-zeros mask, so that the alpha^2 loads of a lane are all
+    // in flight together.  The masks pass through an empty asm statement: seen as a select on the
+    // bounds test, the compiler moves each load into a branch of its own and waits for it there.
+    const E* xb = x + (size_t)n * H * W * C + (live ? c : 0);
+    uint32_t rmask[A], cmask[A];
+#pragma unroll
+    for (int a = 0; a < A; ++a) {
+        const int r = M * ti - 1 + a, col = M * tj - 1 + a;
+        rmask[a] = (live && r >= 0 && r < H) ? 0xffffffffu : 0u;
+        cmask[a] = (col >= 0 && col < W) ? 0xffffffffu : 0u;
+        asm("" : "+v"(rmask[a]));
+        asm("" : "+v"(cmask[a]));
+    }
     float d[CPT][A][A];
 #pragma unroll
     for (int a = 0; a < A; ++a) {
         const int r = M * ti - 1 + a;
+        const E* xr = xb + (size_t)min(max(r, 0), H - 1) * W * C;
 #pragma unroll
         for (int b = 0; b < A; ++b) {
             const int col = M * tj - 1 + b;
-            E v[CPT];
-#pragma unroll
-            for (int u = 0; u < CPT; ++u) v[u] = from_f32<E>(0.f);
-            if (live && r >= 0 && r < H && col >= 0 && col < W) {
-                const E* p = x + (((size_t)n * H + r) * W + col) * C + c;
-                if constexpr (CPT == 2) { *reinterpret_cast<uint32_t*>(v) = *reinterpret_cast<const uint32_t*>(p); }
-                else { v[0] = p[0]; }
-            }
+            const E* p = xr + (size_t)min(max(col, 0), W - 1) * C;
+            const uint32_t msk = rmask[a] & cmask[b];
+            union { uint32_t w; E e[4 / sizeof(E)]; } v;
+            if constexpr (CPT == 2) v.w = *reinterpret_cast<const uint32_t*>(p);
+            else if constexpr (sizeof(E) == 4) v.w = *reinterpret_cast<const uint32_t*>(p);
+            else v.w = *reinterpret_cast<const uint16_t*>(p);
+            v.w &= msk;
 #pragma unroll
             for (int u = 0; u < CPT; ++u) {
-                d[u][a][b] = to_f32<E>(v[u]);
-                if (PRE) d[u][a][b] = pre_apply(d[u][a][b], pl[u], r >= 0 && r < H && col >= 0 && col < W);
+                d[u][a][b] = to_f32<E>(v.e[u]);
+                if (PRE) d[u][a][b] = pre_apply(d[u][a][b], pl[u], msk != 0u);
             }
         }
     }
@@ -301,16 +318,17 @@ static hipError_t launch_it_nhwc(const void* x, void* V, const Geom& g, const Pr
     const int cpt = pair ? 2 : 1;
     const size_t items = (size_t)g.T * (g.Cp / cpt);
     const size_t blocks = (items + 255) / 256;
-    if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
-    dim3 block(256), grid((unsigned)blocks);
+    if (blocks > 0x3fffffffULL) return hipErrorInvalidValue;
+    const int per_xcd = (int)((blocks + 7) / 8);
+    dim3 block(256), grid((unsigned)per_xcd * 8);
     if (pair) {
         if constexpr (sizeof(E) == 2) {
-            if (pre) hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2, true>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, po);
-            else     hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2, false>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, po);
+            if (pre) hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2, true>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, per_xcd, po);
+            else     hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2, false>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, per_xcd, po);
         }
     } else {
-        if (pre) hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1, true>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, po);
-        else     hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1, false>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, po);
+        if (pre) hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1, true>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, per_xcd, po);
+        else     hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1, false>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, per_xcd, po);
     }
     return hipGetLastError();
 }

@@ -4,6 +4,7 @@
 // contiguous across lanes and the m-wide row stores of neighbouring tiles abut.
 // Bound by HBM/L2 traffic: reads alpha^2 fp32 per m^2 outputs.
 #include "wino_internal.h"
+#include <type_traits>
 #include "wino_transforms.h"
 #include <stdlib.h>
 
@@ -134,82 +135,100 @@ static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const G
     return launch_ot_cfg<M, E, 1>(Mt, bias, y, g, post, s);
 }
 
-// NHWC output (y[N][H][W][K], channels contiguous).  M is read exactly as in the NCHW kernel
-// (lanes along t), the m x m results are parked in LDS as [tile][a][b][k] and written out with
-// lanes along k, so both sides are contiguous runs.  A workgroup owns KB channels x TB tiles.
-template <int M, typename E, int KB, int TB>
+// NHWC output (y[N][H][W][K], channels contiguous).  Here the product arrives transposed,
+// Mt[alpha^2][T][K] (the batched GEMM is symmetric in its operands: called with V and U swapped it
+// leaves the channel index contiguous), so reads and writes both run along k and nothing has to be
+// transposed on the way.  One lane owns KPT adjacent channels of one tile.
+template <int M, typename E, int KPT>
 __global__ void __launch_bounds__(256)
 output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
-                             int N, int K, int H, int W, int th, int tw, int T, int tblocks, PostOp post) {
+                             int N, int K, int H, int W, int th, int tw, int T, PostOp post) {
     constexpr int A = M + 2;
-    constexpr int KP = KB + (sizeof(E) == 2 ? 2 : 1);          // odd number of 32-bit words per row: no bank conflicts
-    __shared__ E park[TB * M * M * KP];
-    const int tb = blockIdx.x % tblocks, kb = blockIdx.x / tblocks;
-    const int k0 = kb * KB, t0 = tb * TB;
-    const size_t KT = (size_t)K * T;
-    // phase 1: lanes along t (TB consecutive tiles), waves along k
-    for (int it = threadIdx.x; it < KB * TB; it += 256) {
-        const int tl = it % TB, kl = it / TB;
-        const int k = k0 + kl, t = t0 + tl;
-        if (k >= K || t >= T) continue;
-        const size_t f = (size_t)k * T + t;
-        float v[A][A];
+    const int groups = (K + KPT - 1) / KPT;
+    const size_t item = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= (size_t)T * groups) return;
+    const int k = (int)(item % groups) * KPT;                  // KPT divides K on this path
+    const int t = (int)(item / groups);
+    const int tj = t % tw; const int q0 = t / tw;
+    const int ti = q0 % th;
+    const int n = q0 / th;
+    const size_t TK = (size_t)T * K;
+    const float* src = Mt + (size_t)t * K + k;
+    float v[KPT][A][A];
 #pragma unroll
-        for (int xi = 0; xi < A; ++xi)
+    for (int xi = 0; xi < A; ++xi)
 #pragma unroll
-            for (int nu = 0; nu < A; ++nu) v[xi][nu] = Mt[(size_t)(xi * A + nu) * KT + f];
+        for (int nu = 0; nu < A; ++nu) {
+            const float* p = src + (size_t)(xi * A + nu) * TK;
+            if constexpr (KPT == 2) { const float2 f = *reinterpret_cast<const float2*>(p); v[0][xi][nu] = f.x; v[1][xi][nu] = f.y; }
+            else v[0][xi][nu] = p[0];
+        }
+    // residual: loaded up front from clamped (always valid) positions so that the loads overlap;
+    // positions outside the image are never stored
+    // KPT channels move as one 4- or 8-byte word
+    union Pack { E e[KPT]; typename std::conditional<sizeof(E) * KPT == 8, uint2, typename std::conditional<sizeof(E) * KPT == 4, uint32_t, uint16_t>::type>::type w; };
+    Pack res[M][M];
+    if (post.residual) {
+        const E* rb = static_cast<const E*>(post.residual) + (size_t)n * H * W * K + k;
+#pragma unroll
+        for (int a = 0; a < M; ++a)
+#pragma unroll
+            for (int q = 0; q < M; ++q) {
+                const E* p = rb + ((size_t)min(M * ti + a, H - 1) * W + min(M * tj + q, W - 1)) * K;
+                res[a][q].w = *reinterpret_cast<const decltype(Pack::w)*>(p);
+            }
+    }
+    float b[KPT];
+#pragma unroll
+    for (int u = 0; u < KPT; ++u)
+        b[u] = (bias ? bias[k + u] : 0.f) + (post.addvec ? post.addvec[(size_t)n * K + k + u] : 0.f);
+    float out[KPT][M][M];
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
         float tmp[M][A];
 #pragma unroll
         for (int nu = 0; nu < A; ++nu) {
-            float in[A], out[M];
+            float in[A], o[M];
 #pragma unroll
-            for (int xi = 0; xi < A; ++xi) in[xi] = v[xi][nu];
-            at_1d<M>(in, out);
+            for (int xi = 0; xi < A; ++xi) in[xi] = v[u][xi][nu];
+            at_1d<M>(in, o);
 #pragma unroll
-            for (int a = 0; a < M; ++a) tmp[a][nu] = out[a];
+            for (int a = 0; a < M; ++a) tmp[a][nu] = o[a];
         }
-        const float b = (bias ? bias[k] : 0.f) + (post.addvec ? post.addvec[(size_t)(t / (th * tw)) * K + k] : 0.f);
 #pragma unroll
-        for (int a = 0; a < M; ++a) {
-            float out[M];
-            at_1d<M>(tmp[a], out);
-#pragma unroll
-            for (int q = 0; q < M; ++q) park[((tl * M + a) * M + q) * KP + kl] = from_f32<E>(out[q] + b);
-        }
+        for (int a = 0; a < M; ++a) at_1d<M>(tmp[a], out[u][a]);
     }
-    __syncthreads();
-    // phase 2: lanes along k
-    for (int it = threadIdx.x; it < TB * M * M * KB; it += 256) {
-        const int kl = it % KB;
-        const int pix = it / KB;                               // (tl, a, q)
-        const int q = pix % M, a = (pix / M) % M, tl = pix / (M * M);
-        const int k = k0 + kl;
-        int t = t0 + tl;
-        if (k >= K || t >= T) continue;
-        const int tj = t % tw; t /= tw;
-        const int ti = t % th;
-        const int n = t / th;
-        const int i = M * ti + a, j = M * tj + q;
-        if (i < H && j < W) {
-            const size_t o = (((size_t)n * H + i) * W + j) * K + k;
-            // the residual is added after the parked value was rounded to E (one extra rounding)
-            y[o] = post.residual ? from_f32<E>(to_f32<E>(park[pix * KP + kl]) + to_f32<E>(static_cast<const E*>(post.residual)[o]))
-                                 : park[pix * KP + kl];
+    E* yb = y + (size_t)n * H * W * K + k;
+#pragma unroll
+    for (int a = 0; a < M; ++a) {
+        const int i = M * ti + a;
+#pragma unroll
+        for (int q = 0; q < M; ++q) {
+            const int j = M * tj + q;
+            if (i < H && j < W) {
+                Pack o;
+#pragma unroll
+                for (int u = 0; u < KPT; ++u) {
+                    float f = out[u][a][q] + b[u];
+                    if (post.residual) f += to_f32<E>(res[a][q].e[u]);
+                    o.e[u] = from_f32<E>(f);
+                }
+                *reinterpret_cast<decltype(Pack::w)*>(yb + ((size_t)i * W + j) * K) = o.w;
+            }
         }
     }
 }
 
 template <int M, typename E>
 static hipError_t launch_ot_nhwc(const float* Mt, const float* bias, void* y, const Geom& g, const PostOp& post, hipStream_t s) {
-    // 32 tiles per block keep the fp32 reads of M in 128-byte runs (they are 4-9x the bytes of
-    // y); 32 channels per block give 64/128-byte runs on the store side.  LDS: 34-68 KB.
-    constexpr int KB = 32;
-    constexpr int TB = (M == 4 && sizeof(E) == 4) ? 16 : ((M == 4) ? 32 : 64);
-    const int tblocks = (g.T + TB - 1) / TB, kblocks = (g.K + KB - 1) / KB;
-    const long long total = (long long)tblocks * kblocks;
-    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, KB, TB>), dim3((unsigned)total), dim3(256), 0, s,
-                       Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, tblocks, post);
+    const bool pair = g.K % 2 == 0;               // rows of Mt, y and the residual then keep channel pairs aligned
+    const size_t items = (size_t)g.T * ((g.K + (pair ? 1 : 0)) / (pair ? 2 : 1));
+    const size_t blocks = (items + 255) / 256;
+    if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+    if (pair) hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, 2>), dim3((unsigned)blocks), dim3(256), 0, s,
+                                 Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, post);
+    else      hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, 1>), dim3((unsigned)blocks), dim3(256), 0, s,
+                                 Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, post);
     return hipGetLastError();
 }
 

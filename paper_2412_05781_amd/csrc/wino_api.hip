@@ -53,7 +53,10 @@ int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y,
     void* V = workspace;
     float* M = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + ws.v_bytes);
     if (launch_input_transform(x, V, g, f16, nhwc, pre, s) != hipSuccess) return WINO_ERR_HIP;
-    if (launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, g.alpha * g.alpha, f16, s) != hipSuccess) return WINO_ERR_HIP;
+    // channel-last: operands swapped, so the product comes out as M[alpha^2][T][K], k contiguous
+    const hipError_t ge = nhwc ? launch_batched_gemm(V, w_t->data, M, g.T, g.Cp, g.K, g.alpha * g.alpha, f16, s)
+                               : launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, g.alpha * g.alpha, f16, s);
+    if (ge != hipSuccess) return WINO_ERR_HIP;
     if (launch_output_transform(M, bias, y, g, f16, nhwc, post, s) != hipSuccess) return WINO_ERR_HIP;
     return WINO_OK;
 }

@@ -229,16 +229,19 @@ static const BlockShape kMenu[4] = {{128, 128, 1.00}, {128, 64, 0.85}, {64, 128,
 
 // Pick the shape with the least padded MFMA work per unit of (operand reuse x machine fill).
 // Images of 8x8 and 16x16 give T <= 32 columns: the stage is then a pure stream of U, which a
-// 128x32 block with four waves stacked along K and a three-slot ring serves best.
-// WINO_GEMM_SHAPE=0..5 (read once) pins an entry, for tuning runs.
+// 128x32 block with four waves stacked along K and a three-slot ring serves best.  Both rules
+// have a mirror image for the call with the operands swapped (rows of V x rows of U, which
+// leaves the product transposed for channel-last outputs).
+// WINO_GEMM_SHAPE=0..6 (read once) pins an entry, for tuning runs.
 static int pick_shape(int K, int T, int nbatch) {
     static const int forced = [] {
         const char* e = getenv("WINO_GEMM_SHAPE");
-        return (e && e[0] >= '0' && e[0] <= '5' && e[1] == 0) ? e[0] - '0' : -1;
+        return (e && e[0] >= '0' && e[0] <= '6' && e[1] == 0) ? e[0] - '0' : -1;
     }();
     if (forced >= 0) return forced;
-    if (K % 256 == 0 && T >= 4096) return 4;
+    if ((K % 256 == 0 && T >= 4096) || (T % 256 == 0 && K >= 4096)) return 4;
     if (T <= 32) return 5;
+    if (K <= 32) return 6;
     int best = 0; double best_score = 1e300;
     for (int i = 0; i < 4; ++i) {
         const double tm = (K + kMenu[i].bm - 1) / kMenu[i].bm, tn = (T + kMenu[i].bn - 1) / kMenu[i].bn;
@@ -259,6 +262,7 @@ static hipError_t launch_gemm_t(const void* U, const void* V, float* M, int K, i
         case 2: return launch_gemm_cfg<E, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
         case 3: return launch_gemm_cfg<E, 64, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
         case 5: return launch_gemm_cfg<E, 128, 32, 128, 3, 4, 1>(U, V, M, K, Cp, T, nbatch, s);
+        case 6: return launch_gemm_cfg<E, 32, 128, 128, 3, 1, 4>(U, V, M, K, Cp, T, nbatch, s);
         default: return launch_gemm_cfg<E, 256, 256, 128, 2, 4, 4>(U, V, M, K, Cp, T, nbatch, s);
     }
 }

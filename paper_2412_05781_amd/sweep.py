@@ -69,7 +69,10 @@ def run_layer(layer, variant, dev, layout=B.WINO_NCHW):
     reps = max(2, min(2 * nsets, 40))
     t_all = graph_time(lambda i: B.wino_conv2d_ex(sets[i % nsets][0], sets[i % nsets][1], bd, sets[i % nsets][2], ws, layout), reps)
     t_in = graph_time(lambda i: B.wino_input_transform(sets[i % nsets][0], variant, layout, out=V), reps)
-    t_g = graph_time(lambda i: B.wino_batched_gemm(sets[i % nsets][1].buf.view(tdt), V, K, C, T, variant, out=M), reps)
+    if layout == B.WINO_NHWC:       # channel-last keeps the product transposed: operands swapped
+        t_g = graph_time(lambda i: B.wino_batched_gemm(V, sets[i % nsets][1].buf.view(tdt), T, C, K, variant, out=M), reps)
+    else:
+        t_g = graph_time(lambda i: B.wino_batched_gemm(sets[i % nsets][1].buf.view(tdt), V, K, C, T, variant, out=M), reps)
     t_out = graph_time(lambda i: B.wino_output_transform(M, bd, N, K, H, W, tdt, variant, layout, out=sets[i % nsets][2]), reps)
     fl = 2 * a2 * K * C * T
     return {
