@@ -217,6 +217,135 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
     }
 }
 
+// Long rows: a workgroup slides along one tile row.  The row is cut into 64-byte bodies (TJ tiles
+// wide); LDS keeps the last two bodies of every (channel, patch row), and step s transforms the
+// TJ tiles that straddle the seam between bodies s-1 and s, whose windows lie wholly inside those
+// two bodies.  Every body is therefore fetched from memory once per workgroup, as aligned 64-byte
+// runs, instead of once per strip plus halo chunks on either side; body s+1 is in flight while
+// step s computes and stores.  Tiles outside [0, tw) are replaced by the nearest tile inside, which
+// the same step computes anyway: the duplicate writes the same values, and every wave issues the
+// same number of stores per step, so the wait for the prefetched body leaves those stores pending.
+// Needs Cp % 64 == 0 (no lane is idle) and rows of whole 16-byte chunks.
+template <int M, typename E, int TJ, bool PRE>
+__global__ void __launch_bounds__(256)
+input_transform_nchw_slide_kernel(const E* __restrict__ x, E* __restrict__ V,
+                                  int N, int C, int H, int W, int th, int tw, int T, int Cp, int steps_per_row,
+                                  int spb, int total_blocks, int blocks_per_xcd, PreOp pre) {
+    constexpr int A = M + 2;
+    constexpr int EPC = 16 / (int)sizeof(E);             // elements per 16-byte chunk
+    constexpr int BODYE = 64 / (int)sizeof(E);           // elements per body
+    constexpr int EPW = 4 / (int)sizeof(E);              // elements per 32-bit word
+    static_assert(TJ * M == BODYE && TJ % 4 == 0, "a body is TJ tiles wide, TJ/4 tiles per wave");
+    constexpr int ROWW = 32;                             // words per patch row: two bodies
+    constexpr int CSW = (A * ROWW) | 1;                  // words per channel, odd: lanes = channels hit distinct banks
+    __shared__ uint32_t patch[64 * CSW];
+
+    const int tid = threadIdx.x;
+    const int logical = (blockIdx.x % 8) * blocks_per_xcd + blockIdx.x / 8;   // one contiguous range per XCD
+    if (logical >= total_blocks) return;                 // uniform, before any barrier
+    const int groups_per_row = (steps_per_row + spb - 1) / spb;
+    int sidx = logical;
+    const int jg = sidx % groups_per_row; sidx /= groups_per_row;
+    const int ti = sidx % th; sidx /= th;
+    const int n = sidx % N;
+    const int c0 = (sidx / N) * 64;
+    const int s0 = jg * spb;
+    const int s1 = min(s0 + spb, steps_per_row);
+    const int row0 = M * ti - 1;
+
+    const unsigned char* xb = reinterpret_cast<const unsigned char*>(x + ((size_t)n * C + c0) * H * W);
+    // loader role: lane = (channel, chunk of the body), walks the alpha patch rows
+    const int lc = tid >> 2, lch = tid & 3;
+    const bool lc_ok = (c0 + lc) < C;
+    uint4 reg[A];
+    auto fetch = [&](int body) {
+        const int col = body * BODYE + lch * EPC;
+        const bool ok = lc_ok && body >= 0 && col < W;   // W is a multiple of EPC: a chunk is inside or outside as a whole
+        const unsigned off0 = (unsigned)(((lc * H + row0) * W + col) * (int)sizeof(E));   // only used when row and col are valid
+#pragma unroll
+        for (int a = 0; a < A; ++a) {
+            const int r = row0 + a;
+            reg[a] = make_uint4(0, 0, 0, 0);
+            if (ok && r >= 0 && r < H)
+                reg[a] = *reinterpret_cast<const uint4*>(xb + (off0 + (unsigned)(a * W * (int)sizeof(E))));
+        }
+    };
+    auto stash = [&](int body) {
+        uint32_t* dst = patch + lc * CSW + (body & 1) * 16 + lch * 4;
+#pragma unroll
+        for (int a = 0; a < A; ++a) {
+            dst[a * ROWW + 0] = reg[a].x; dst[a * ROWW + 1] = reg[a].y;
+            dst[a * ROWW + 2] = reg[a].z; dst[a * ROWW + 3] = reg[a].w;
+        }
+    };
+
+    // transform role: lane = channel, TJ/4 tiles per wave and step
+    const int cc = tid & 63;
+    const int c = c0 + cc;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const size_t plane_bytes = (size_t)T * Cp * sizeof(E);
+    const E* pch = reinterpret_cast<const E*>(patch + cc * CSW);
+    const unsigned coff = (unsigned)c * (unsigned)sizeof(E);
+    PreLane pl = {0.f, 0.f, false};
+    if (PRE) pl = pre_lane(pre, n, c, C);
+
+    fetch(s0 - 1);
+    stash(s0 - 1);
+    fetch(s0);
+    stash(s0);
+    __syncthreads();
+    for (int s = s0; s < s1; ++s) {
+        if (s + 1 < s1) fetch(s + 1);                     // in flight while this step is transformed
+#pragma unroll
+        for (int i = 0; i < TJ / 4; ++i) {
+            int tj = TJ * s - TJ / 2 + wave + 4 * i;
+            tj = min(max(tj, 0), tw - 1);                 // wave-uniform; duplicates write identical values
+            const int g0 = M * tj - 1;                    // first window column (global), -1 for the left border
+            int colofs[A];
+#pragma unroll
+            for (int b = 0; b < A; ++b) colofs[b] = (g0 + b) & (2 * BODYE - 1);
+            float d[A][A];
+#pragma unroll
+            for (int a = 0; a < A; ++a)
+#pragma unroll
+                for (int b = 0; b < A; ++b) {
+                    d[a][b] = to_f32<E>(pch[a * (ROWW * EPW) + colofs[b]]);
+                    if (PRE) {
+                        const int r = M * ti - 1 + a, q = g0 + b;
+                        d[a][b] = pre_apply(d[a][b], pl, r >= 0 && r < H && q >= 0 && q < W);
+                    }
+                }
+            float tmp[A][A];
+#pragma unroll
+            for (int b = 0; b < A; ++b) {
+                float in[A], out[A];
+#pragma unroll
+                for (int a = 0; a < A; ++a) in[a] = d[a][b];
+                bt_1d<M>(in, out);
+#pragma unroll
+                for (int a = 0; a < A; ++a) tmp[a][b] = out[a];
+            }
+            const size_t t = ((size_t)n * th + ti) * tw + tj;                  // wave-uniform
+            unsigned char* pp = reinterpret_cast<unsigned char*>(V + t * Cp);  // walks the alpha^2 planes
+#pragma unroll
+            for (int xi = 0; xi < A; ++xi) {
+                float out[A];
+                bt_1d<M>(tmp[xi], out);
+#pragma unroll
+                for (int nu = 0; nu < A; ++nu) {
+                    *reinterpret_cast<E*>(pp + coff) = from_f32<E>(out[nu]);
+                    pp += plane_bytes;
+                }
+            }
+        }
+        if (s + 1 < s1) {
+            __syncthreads();                              // everyone is done with body s-1
+            stash(s + 1);                                 // overwrites it
+            __syncthreads();
+        }
+    }
+}
+
 // NHWC activations (channels contiguous): no transposition is needed, V's rows are channel-
 // contiguous too.  One lane owns CPT adjacent channels of one tile, reads its alpha x alpha window
 // straight from global memory (neighbouring lanes read neighbouring channels, so every load is
@@ -341,6 +470,26 @@ static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, const Pre
     // fast path: rows are whole 16-byte chunks and a 64-channel slab of x spans < 2 GB (32-bit lane offsets)
     const bool rows_are_chunks = ((size_t)g.W * sizeof(E)) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0 &&
                                  (size_t)CB * g.H * g.W * sizeof(E) < ((size_t)1 << 31);
+    static const int slide_cfg = [] { const char* e = getenv("WINO_IT_SLIDE"); return e ? atoi(e) : -1; }();   // tuning knob: 0 = off, n = steps per workgroup
+    constexpr int STJ = 64 / (int)sizeof(E) / M;          // tiles per 64-byte body
+    if (rows_are_chunks && g.Cp % 64 == 0 && slide_cfg != 0) {
+        const int steps = (g.tw + STJ / 2 + STJ - 1) / STJ;
+        // Measured over the SD-shaped layers: with fp16 F(2x2) (16 tiles per body) the aligned fetch
+        // alone pays from 16 tiles per row on; otherwise the strip kernel wins until a row has
+        // eight steps.  Two steps per workgroup keep the grid large and the tail short.
+        const bool wide_body = sizeof(E) == 2 && M == 2;
+        const bool pays = wide_body ? g.tw >= STJ : steps >= 8;
+        const int spb = slide_cfg > 0 ? slide_cfg : (steps >= 8 ? 2 : 1);
+        const long long total = (long long)g.N * g.th * (g.Cp / 64) * ((steps + spb - 1) / spb);
+        if ((slide_cfg > 0 || pays) && total <= 0x3fffffffLL) {
+            const int per_xcd = (int)((total + 7) / 8);
+            if (pre) hipLaunchKernelGGL((input_transform_nchw_slide_kernel<M, E, STJ, true>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
+                                        (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, steps, spb, (int)total, per_xcd, po);
+            else     hipLaunchKernelGGL((input_transform_nchw_slide_kernel<M, E, STJ, false>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
+                                        (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, steps, spb, (int)total, per_xcd, po);
+            return hipGetLastError();
+        }
+    }
     if (rows_are_chunks) {
         const long long total = (long long)grid.x * grid.y;
         if (total > 0x3fffffffLL) return hipErrorInvalidValue;

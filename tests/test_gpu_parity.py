@@ -213,6 +213,30 @@ def test_nhwc_full_layer():
     assert err <= TOL["f16"] and FP16_BAND[B.WINO_F4][0] <= err
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+@pytest.mark.parametrize("shape", [(2, 60, 8, 10, 216), (1, 128, 5, 7, 108), (1, 64, 4, 3, 40), (1, 64, 3, 9, 1000)])
+def test_long_rows(shape, variant, dtype):
+    """Rows of whole 16-byte chunks with C padded to a multiple of 64: the shapes on which the activation
+    transform slides along a tile row in 64-byte bodies (ragged last step, clamped duplicate tiles, one or
+    two steps per workgroup, channels beyond C)."""
+    N, C, K, H, W = shape
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=4000 + sum(shape))
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    y = B.conv2d(x.to(DEV), w.to(DEV), b.to(DEV), variant)
+    torch.cuda.synchronize()
+    err = oracle.rel_l2(y.float().cpu().numpy(), ref)
+    assert err <= TOL[dtype], (shape, variant, dtype, err)
+    # stage check of V itself against the fp64 transform
+    V = B.wino_input_transform(x.to(DEV), variant)
+    alpha, Cp, T = B.wino_transformed_dims(N, C, H, W, K, variant)
+    V_ref = wr.input_transform(_np(x), variant).reshape(alpha * alpha, C, T).transpose(0, 2, 1)
+    Vh = V.float().cpu().numpy().astype(np.float64)
+    eps = 2.0 ** -11 if dtype == "f16" else 2.0 ** -24
+    assert np.all(Vh[:, :, C:] == 0)
+    assert np.abs(Vh[:, :, :C] - V_ref).max() <= 4 * eps * np.abs(V_ref).max()
+
+
 def test_random_shapes_against_oracle():
     """Seeded random small problems (all variants, both dtypes, both layouts): ragged tiles in both
     directions, channel counts off every block size, batch > 1."""
