@@ -52,7 +52,7 @@ template <> struct FVec<4> { using type = float4; };
 template <int M, typename E, int TPT>
 __global__ void __launch_bounds__(256)
 output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
-                             int N, int K, int H, int W, int th, int tw, int T, int vec_ok, PostOp post) {
+                             int N, int K, int H, int W, int th, int tw, int T, int vec_ok, int nsplit, PostOp post) {
     constexpr int A = M + 2;
     const size_t KT = (size_t)K * T;
     const int Tq = T / TPT;
@@ -69,6 +69,17 @@ output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restri
         const float* qf = reinterpret_cast<const float*>(&q);
 #pragma unroll
         for (int u = 0; u < TPT; ++u) v[p][u] = qf[u];
+    }
+    // partial products of a reduction cut into nsplit ranges: summed here, in a fixed order
+    for (int sp = 1; sp < nsplit; ++sp) {
+        const float* Ms = Mt + (size_t)sp * (A * A) * KT + f;
+#pragma unroll
+        for (int p = 0; p < A * A; ++p) {
+            const typename FVec<TPT>::type q = *reinterpret_cast<const typename FVec<TPT>::type*>(Ms + (size_t)p * KT);
+            const float* qf = reinterpret_cast<const float*>(&q);
+#pragma unroll
+            for (int u = 0; u < TPT; ++u) v[p][u] += qf[u];
+        }
     }
     const float b = bias ? bias[k] : 0.f;
 #pragma unroll
@@ -114,25 +125,25 @@ output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restri
 }
 
 template <int M, typename E, int TPT>
-static hipError_t launch_ot_cfg(const float* Mt, const float* bias, void* y, const Geom& g, const PostOp& post, hipStream_t s) {
+static hipError_t launch_ot_cfg(const float* Mt, const float* bias, void* y, const Geom& g, int nsplit, const PostOp& post, hipStream_t s) {
     const size_t items = (size_t)g.K * (g.T / TPT);
     dim3 block(256), grid((unsigned)((items + 255) / 256));
     const int vec_ok = (g.W % M == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0) &&
                        ((reinterpret_cast<uintptr_t>(post.residual) & 15u) == 0);
     hipLaunchKernelGGL((output_transform_nchw_kernel<M, E, TPT>), grid, block, 0, s,
-                       Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, vec_ok, post);
+                       Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, vec_ok, nsplit, post);
     return hipGetLastError();
 }
 
 template <int M, typename E>
-static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const Geom& g, const PostOp& post, hipStream_t s) {
+static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const Geom& g, int nsplit, const PostOp& post, hipStream_t s) {
     static const int cfg = [] { const char* e = getenv("WINO_OT_TPT"); return e ? atoi(e) : 0; }();   // tuning knob
     // measured over the layer sweep: one tile per lane is never worse in the chained path
     int tpt = cfg ? cfg : 1;
     const bool aligned = (reinterpret_cast<uintptr_t>(Mt) & 15u) == 0;
-    if (tpt == 4 && g.T % 4 == 0 && aligned) return launch_ot_cfg<M, E, 4>(Mt, bias, y, g, post, s);
-    if (tpt >= 2 && g.T % 2 == 0 && aligned) return launch_ot_cfg<M, E, 2>(Mt, bias, y, g, post, s);
-    return launch_ot_cfg<M, E, 1>(Mt, bias, y, g, post, s);
+    if (tpt == 4 && g.T % 4 == 0 && aligned) return launch_ot_cfg<M, E, 4>(Mt, bias, y, g, nsplit, post, s);
+    if (tpt >= 2 && g.T % 2 == 0 && aligned) return launch_ot_cfg<M, E, 2>(Mt, bias, y, g, nsplit, post, s);
+    return launch_ot_cfg<M, E, 1>(Mt, bias, y, g, nsplit, post, s);
 }
 
 // NHWC output (y[N][H][W][K], channels contiguous).  Here the product arrives transposed,
@@ -142,7 +153,7 @@ static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const G
 template <int M, typename E, int KPT>
 __global__ void __launch_bounds__(256)
 output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
-                             int N, int K, int H, int W, int th, int tw, int T, PostOp post) {
+                             int N, int K, int H, int W, int th, int tw, int T, int nsplit, PostOp post) {
     constexpr int A = M + 2;
     const int groups = (K + KPT - 1) / KPT;
     const size_t item = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -163,6 +174,17 @@ output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restri
             if constexpr (KPT == 2) { const float2 f = *reinterpret_cast<const float2*>(p); v[0][xi][nu] = f.x; v[1][xi][nu] = f.y; }
             else v[0][xi][nu] = p[0];
         }
+    for (int sp = 1; sp < nsplit; ++sp) {                      // partial products, summed in a fixed order
+        const float* ss = src + (size_t)sp * (A * A) * TK;
+#pragma unroll
+        for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+            for (int nu = 0; nu < A; ++nu) {
+                const float* p = ss + (size_t)(xi * A + nu) * TK;
+                if constexpr (KPT == 2) { const float2 f = *reinterpret_cast<const float2*>(p); v[0][xi][nu] += f.x; v[1][xi][nu] += f.y; }
+                else v[0][xi][nu] += p[0];
+            }
+    }
     // residual: loaded up front from clamped (always valid) positions so that the loads overlap;
     // positions outside the image are never stored
     // KPT channels move as one 4- or 8-byte word
@@ -220,26 +242,26 @@ output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restri
 }
 
 template <int M, typename E>
-static hipError_t launch_ot_nhwc(const float* Mt, const float* bias, void* y, const Geom& g, const PostOp& post, hipStream_t s) {
+static hipError_t launch_ot_nhwc(const float* Mt, const float* bias, void* y, const Geom& g, int nsplit, const PostOp& post, hipStream_t s) {
     const bool pair = g.K % 2 == 0;               // rows of Mt, y and the residual then keep channel pairs aligned
     const size_t items = (size_t)g.T * ((g.K + (pair ? 1 : 0)) / (pair ? 2 : 1));
     const size_t blocks = (items + 255) / 256;
     if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
     if (pair) hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, 2>), dim3((unsigned)blocks), dim3(256), 0, s,
-                                 Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, post);
+                                 Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, nsplit, post);
     else      hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, 1>), dim3((unsigned)blocks), dim3(256), 0, s,
-                                 Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, post);
+                                 Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, nsplit, post);
     return hipGetLastError();
 }
 
-hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, bool f16, bool nhwc, const PostOp* postp, hipStream_t s) {
+hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, int nsplit, bool f16, bool nhwc, const PostOp* postp, hipStream_t s) {
     const PostOp post = postp ? *postp : PostOp();
     if (nhwc) {
-        if (g.m == 2) return f16 ? launch_ot_nhwc<2, __half>(M, bias, y, g, post, s) : launch_ot_nhwc<2, float>(M, bias, y, g, post, s);
-        return f16 ? launch_ot_nhwc<4, __half>(M, bias, y, g, post, s) : launch_ot_nhwc<4, float>(M, bias, y, g, post, s);
+        if (g.m == 2) return f16 ? launch_ot_nhwc<2, __half>(M, bias, y, g, nsplit, post, s) : launch_ot_nhwc<2, float>(M, bias, y, g, nsplit, post, s);
+        return f16 ? launch_ot_nhwc<4, __half>(M, bias, y, g, nsplit, post, s) : launch_ot_nhwc<4, float>(M, bias, y, g, nsplit, post, s);
     }
-    if (g.m == 2) return f16 ? launch_ot<2, __half>(M, bias, y, g, post, s) : launch_ot<2, float>(M, bias, y, g, post, s);
-    return f16 ? launch_ot<4, __half>(M, bias, y, g, post, s) : launch_ot<4, float>(M, bias, y, g, post, s);
+    if (g.m == 2) return f16 ? launch_ot<2, __half>(M, bias, y, g, nsplit, post, s) : launch_ot<2, float>(M, bias, y, g, nsplit, post, s);
+    return f16 ? launch_ot<4, __half>(M, bias, y, g, nsplit, post, s) : launch_ot<4, float>(M, bias, y, g, nsplit, post, s);
 }
 
 }  // namespace wino

@@ -41,7 +41,10 @@ Workspace workspace_layout(const Geom& g, int dtype) {
     Workspace ws;
     const size_t a2 = (size_t)g.alpha * g.alpha;
     ws.v_bytes = align_up(a2 * (size_t)g.T * g.Cp * esize(dtype));
-    ws.m_bytes = align_up(a2 * (size_t)g.K * g.T * sizeof(float));
+    // the product, times the number of partial copies the GEMM stage writes for this shape (the
+    // policy depends on the operand order only through the block shape; take the larger of the two)
+    const int sp_a = gemm_split(g.K, g.T, g.Cp, (int)a2, dtype == WINO_F16), sp_b = gemm_split(g.T, g.K, g.Cp, (int)a2, dtype == WINO_F16);
+    ws.m_bytes = align_up(a2 * (size_t)g.K * g.T * sizeof(float) * (size_t)(sp_a > sp_b ? sp_a : sp_b));
     ws.total = ws.v_bytes + ws.m_bytes;
     return ws;
 }
@@ -54,10 +57,12 @@ int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y,
     float* M = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + ws.v_bytes);
     if (launch_input_transform(x, V, g, f16, nhwc, pre, s) != hipSuccess) return WINO_ERR_HIP;
     // channel-last: operands swapped, so the product comes out as M[alpha^2][T][K], k contiguous
-    const hipError_t ge = nhwc ? launch_batched_gemm(V, w_t->data, M, g.T, g.Cp, g.K, g.alpha * g.alpha, f16, s)
-                               : launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, g.alpha * g.alpha, f16, s);
+    const int a2 = g.alpha * g.alpha;
+    const int nsplit = nhwc ? gemm_split(g.T, g.K, g.Cp, a2, f16) : gemm_split(g.K, g.T, g.Cp, a2, f16);
+    const hipError_t ge = nhwc ? launch_batched_gemm(V, w_t->data, M, g.T, g.Cp, g.K, a2, nsplit, f16, s)
+                               : launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, a2, nsplit, f16, s);
     if (ge != hipSuccess) return WINO_ERR_HIP;
-    if (launch_output_transform(M, bias, y, g, f16, nhwc, post, s) != hipSuccess) return WINO_ERR_HIP;
+    if (launch_output_transform(M, bias, y, g, nsplit, f16, nhwc, post, s) != hipSuccess) return WINO_ERR_HIP;
     return WINO_OK;
 }
 
@@ -252,7 +257,7 @@ int wino_batched_gemm(const void* U, const void* V, float* M, int K, int C, int 
     if (a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)round_up(C, 8) ||
         a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)K) return WINO_ERR_DIM;
     if (!aligned16(U) || !aligned16(V) || !aligned16(M)) return WINO_ERR_ALIGN;
-    return launch_batched_gemm(U, V, M, K, round_up(C, 8), T, (int)a2, dtype == WINO_F16,
+    return launch_batched_gemm(U, V, M, K, round_up(C, 8), T, (int)a2, 1, dtype == WINO_F16,
                                static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
@@ -265,7 +270,7 @@ int wino_output_transform(const float* M, const float* bias, void* y, int N, int
     if (!dims_ok(N, 1, H, W, K, variant)) return WINO_ERR_DIM;
     if (!aligned16(M) || !aligned16(y)) return WINO_ERR_ALIGN;
     const Geom g = make_geom(N, 1, H, W, K, variant);
-    return launch_output_transform(M, bias, y, g, dtype == WINO_F16, layout == WINO_NHWC, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_output_transform(M, bias, y, g, 1, dtype == WINO_F16, layout == WINO_NHWC, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
 

@@ -59,7 +59,8 @@ __device__ __forceinline__ void dma_load_1k(const void* src, unsigned char* lds_
 template <typename E, int BM, int BN, int RB, int NST, int WGM, int WGN>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __restrict__ Mo,
-                 int K, int Cp, int T, int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd) {
+                 int K, int Cp, int T, int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd,
+                 int nbatch, int nsplit) {
     constexpr int CPR = RB / 16;                          // 16-byte chunks per row per stage
     constexpr int BKE = RB / (int)sizeof(E);              // reduction elements per stage
     constexpr int EPC = 16 / (int)sizeof(E);              // elements per chunk
@@ -86,8 +87,11 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     // Inside a batch the shorter tile dimension runs fastest: the workgroups resident together
     // then sweep ALL blocks of the smaller operand (which stays in L2) against a few blocks of
     // the larger one, which is streamed from memory once.
-    const int batch = logical / (tiles_n * tiles_m);
-    const int in_batch = logical - batch * (tiles_n * tiles_m);
+    // With nsplit > 1 the reduction over c is cut into nsplit ranges of whole stages, one workgroup
+    // each, and split i writes its partial product to the i-th copy of M (summed by the reader).
+    const int bs = logical / (tiles_n * tiles_m);
+    const int in_batch = logical - bs * (tiles_n * tiles_m);
+    const int batch = bs / nsplit, split = bs - batch * nsplit;
     int tm, tn;
     if (tiles_m <= tiles_n) { tm = in_batch % tiles_m; tn = in_batch / tiles_m; }
     else { tn = in_batch % tiles_n; tm = in_batch / tiles_n; }
@@ -117,12 +121,13 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
         }
     }
 
-    const int nk = (Cp + BKE - 1) / BKE;
+    const int nk_all = (Cp + BKE - 1) / BKE;
     const bool ragged = (Cp % BKE) != 0;
+    const int kt0 = (int)((long long)split * nk_all / nsplit), nk = (int)((long long)(split + 1) * nk_all / nsplit);
 
     auto issue_stage = [&](int kt) {
-        unsigned char* slot = lds + (kt % NST) * STAGE_BYTES;
-        if (ragged && kt == nk - 1) {
+        unsigned char* slot = lds + ((kt - kt0) % NST) * STAGE_BYTES;
+        if (ragged && kt == nk_all - 1) {
             // last, partial stage: through registers, chunks beyond Cp become zeros
 #pragma unroll
             for (int i = 0; i < LPW; ++i) {
@@ -147,10 +152,10 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
 
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
-        if (s < nk) issue_stage(s);
+        if (kt0 + s < nk) issue_stage(kt0 + s);
 
     const int frag_row = lane & 31, frag_half = lane >> 5;
-    for (int kt = 0; kt < nk; ++kt) {
+    for (int kt = kt0; kt < nk; ++kt) {
         // Stage kt must have landed.  Transfers complete in issue order, so it is enough to allow
         // as many outstanding as were issued after it: NST-2 stages in steady state, and once the
         // ring stops refilling simply everything.
@@ -160,7 +165,7 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
         if (kt + NST - 1 < nk) issue_stage(kt + NST - 1);   // refills the slot stage kt-1 used
 
         // all fragment reads of the stage first, then the MFMAs, so LDS latency is paid once
-        const unsigned char* slot = lds + (kt % NST) * STAGE_BYTES;
+        const unsigned char* slot = lds + ((kt - kt0) % NST) * STAGE_BYTES;
         uint4 fa[CPR / 2][FM], fb[CPR / 2][FN];
 #pragma unroll
         for (int ks = 0; ks < CPR / 2; ++ks) {
@@ -186,7 +191,7 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     }
 
     // 32x32 accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
-    float* Mb = Mo + (size_t)batch * K * T;
+    float* Mb = Mo + ((size_t)split * nbatch + batch) * K * T;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -201,9 +206,9 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
 }
 
 template <typename E, int BM, int BN, int RB, int NST, int WGM = 2, int WGN = 2>
-static hipError_t launch_gemm_cfg(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, hipStream_t s) {
+static hipError_t launch_gemm_cfg(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
     const int tiles_m = (K + BM - 1) / BM, tiles_n = (T + BN - 1) / BN;
-    const long long total = (long long)tiles_m * tiles_n * nbatch;
+    const long long total = (long long)tiles_m * tiles_n * nbatch * nsplit;
     if (total > 0x3fffffffLL) return hipErrorInvalidValue;
     const int per_xcd = (int)((total + 7) / 8);
     constexpr int lds_bytes = (BM + BN) * RB * NST;
@@ -217,7 +222,7 @@ static hipError_t launch_gemm_cfg(const void* U, const void* V, float* M, int K,
     }
     dim3 block(WGM * WGN * 64), grid((unsigned)(per_xcd * 8));
     hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, (const E*)U, (const E*)V, M,
-                       K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd);
+                       K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd, nbatch, nsplit);
     return hipGetLastError();
 }
 
@@ -232,16 +237,23 @@ static const BlockShape kMenu[4] = {{128, 128, 1.00}, {128, 64, 0.85}, {64, 128,
 // 128x32 block with four waves stacked along K and a three-slot ring serves best.  Both rules
 // have a mirror image for the call with the operands swapped (rows of V x rows of U, which
 // leaves the product transposed for channel-last outputs).
-// WINO_GEMM_SHAPE=0..6 (read once) pins an entry, for tuning runs.
-static int pick_shape(int K, int T, int nbatch) {
+// WINO_GEMM_SHAPE=0..7 (read once) pins an entry, for tuning runs.
+static int pick_shape(int K, int T, int nbatch, bool f16) {
     static const int forced = [] {
         const char* e = getenv("WINO_GEMM_SHAPE");
-        return (e && e[0] >= '0' && e[0] <= '6' && e[1] == 0) ? e[0] - '0' : -1;
+        return e ? atoi(e) : -1;
     }();
     if (forced >= 0) return forced;
     if ((K % 256 == 0 && T >= 4096) || (T % 256 == 0 && K >= 4096)) return 4;
     if (T <= 32) return 5;
     if (K <= 32) return 6;
+    // fp16, at most one 128x128 workgroup per compute unit and next to no padding: nothing else
+    // hides a workgroup's load latency, so it gets a third ring slot (measured 10-15 % over the
+    // two-slot 128x128 and 64x64; the MFMA-bound fp32 path loses from the lower occupancy)
+    if (f16) {
+        const long long tm = (K + 127) / 128, tn = (T + 127) / 128;
+        if (tm * tn * nbatch <= 256 && tm * tn * 128 * 128 * 20 <= (long long)K * T * 21) return 7;
+    }
     int best = 0; double best_score = 1e300;
     for (int i = 0; i < 4; ++i) {
         const double tm = (K + kMenu[i].bm - 1) / kMenu[i].bm, tn = (T + kMenu[i].bn - 1) / kMenu[i].bn;
@@ -255,20 +267,54 @@ static int pick_shape(int K, int T, int nbatch) {
 }
 
 template <typename E>
-static hipError_t launch_gemm_t(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, hipStream_t s) {
-    switch (pick_shape(K, T, nbatch)) {
-        case 0: return launch_gemm_cfg<E, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
-        case 1: return launch_gemm_cfg<E, 128, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
-        case 2: return launch_gemm_cfg<E, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
-        case 3: return launch_gemm_cfg<E, 64, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, s);
-        case 5: return launch_gemm_cfg<E, 128, 32, 128, 3, 4, 1>(U, V, M, K, Cp, T, nbatch, s);
-        case 6: return launch_gemm_cfg<E, 32, 128, 128, 3, 1, 4>(U, V, M, K, Cp, T, nbatch, s);
-        default: return launch_gemm_cfg<E, 256, 256, 128, 2, 4, 4>(U, V, M, K, Cp, T, nbatch, s);
+static hipError_t launch_gemm_t(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
+    switch (pick_shape(K, T, nbatch, sizeof(E) == 2)) {
+        case 0: return launch_gemm_cfg<E, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 1: return launch_gemm_cfg<E, 128, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 2: return launch_gemm_cfg<E, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 3: return launch_gemm_cfg<E, 64, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 5: return launch_gemm_cfg<E, 128, 32, 128, 3, 4, 1>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 6: return launch_gemm_cfg<E, 32, 128, 128, 3, 1, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 7: return launch_gemm_cfg<E, 128, 128, 128, 3>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        default: return launch_gemm_cfg<E, 256, 256, 128, 2, 4, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s);
     }
 }
 
-hipError_t launch_batched_gemm(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, bool f16, hipStream_t s) {
-    return f16 ? launch_gemm_t<__half>(U, V, M, K, Cp, T, nbatch, s) : launch_gemm_t<float>(U, V, M, K, Cp, T, nbatch, s);
+// Stages are 128 bytes of reduction per row in every block shape.
+int gemm_max_split(int Cp, bool f16) {
+    const int bke = f16 ? 64 : 32;
+    const int stages = (Cp + bke - 1) / bke;
+    return stages < 1 ? 1 : stages;
+}
+
+// Few workgroups and a long reduction (deep UNet layers: 8x8 and 16x16 images, 1280+ channels): the
+// stage is a stream of U that one workgroup per compute unit, each waiting on its own loads, cannot
+// keep busy.  Cutting the reduction multiplies the workgroups in flight; the price is nsplit
+// copies of the (small) product.
+int gemm_split(int rows, int cols, int Cp, int nbatch, bool f16) {
+    static const int forced = [] { const char* e = getenv("WINO_GEMM_SPLIT"); return e ? atoi(e) : 0; }();   // tuning knob
+    const int shape = pick_shape(rows, cols, nbatch, f16);
+    const int bm = shape == 4 ? 256 : (shape == 6 ? 32 : ((shape == 2 || shape == 3) ? 64 : 128));
+    const int bn = shape == 4 ? 256 : (shape == 5 ? 32 : ((shape == 1 || shape == 3) ? 64 : 128));
+    const long long blocks = (long long)((rows + bm - 1) / bm) * ((cols + bn - 1) / bn) * nbatch;
+    const int max_split = gemm_max_split(Cp, f16);
+    int sp = 1;
+    if (forced > 0) sp = forced;
+    else if (nbatch <= 16 && (bm < 128 || bn < 128) && blocks <= 320) {
+        // measured: pays 6-10 % for F(2x2) with narrow blocks (images of 8x8, and 16x16 at batch 1)
+        // while there are about as many workgroups as compute units; with the 36 batches of
+        // F(4x4) the extra copies of the product cost more than the GEMM stage gains
+        sp = (int)(640 / blocks);
+        if (sp > 3) sp = 3;
+        if (sp > max_split / 4) sp = max_split / 4;               // at least four stages per workgroup
+    }
+    if (sp > max_split) sp = max_split;
+    return sp < 1 ? 1 : sp;
+}
+
+hipError_t launch_batched_gemm(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, int nsplit, bool f16, hipStream_t s) {
+    if (nsplit < 1 || nsplit > gemm_max_split(Cp, f16)) return hipErrorInvalidValue;
+    return f16 ? launch_gemm_t<__half>(U, V, M, K, Cp, T, nbatch, nsplit, s) : launch_gemm_t<float>(U, V, M, K, Cp, T, nbatch, nsplit, s);
 }
 
 }  // namespace wino
