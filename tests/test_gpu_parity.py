@@ -237,6 +237,26 @@ def test_long_rows(shape, variant, dtype):
     assert np.abs(Vh[:, :, :C] - V_ref).max() <= 4 * eps * np.abs(V_ref).max()
 
 
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("dtype,shape", [("f16", (1, 1024, 256, 8, 8)), ("f16", (2, 576, 200, 8, 8)), ("f32", (1, 512, 160, 8, 8)),
+                                         ("f16", (1, 640, 384, 16, 16))])
+def test_deep_layers_split_reduction(dtype, shape, layout):
+    """Small images with many channels: the GEMM stage cuts the reduction over c into ranges and the output
+    transform sums the partial products (F(2x2), either operand order)."""
+    N, C, K, H, W = shape
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=5000 + sum(shape))
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+    for variant in (B.WINO_F2, B.WINO_F4):
+        y = B.conv2d(xd, w.to(DEV), b.to(DEV), variant, layout=layout)
+        torch.cuda.synchronize()
+        y = y.float().cpu()
+        if layout == B.WINO_NHWC:
+            y = y.permute(0, 3, 1, 2)
+        err = oracle.rel_l2(y.numpy(), ref)
+        assert err <= TOL[dtype], (shape, variant, dtype, layout, err)
+
+
 def test_random_shapes_against_oracle():
     """Seeded random small problems (all variants, both dtypes, both layouts): ragged tiles in both
     directions, channel counts off every block size, batch > 1."""
