@@ -11,6 +11,9 @@ none of these operators, so the textbook definitions are written out here:
               v = (x - mean) / sqrt(var + eps) * gamma[c] + beta[c]
   SiLU:       s(v) = v / (1 + exp(-v))
 
+  Nearest-neighbour 2x upsampling (the step before the 3x3 convolution in the UNet's and the
+  VAE decoder's up-sampling blocks): u[n, c, i, j] = x[n, c, floor(i / 2), floor(j / 2)].
+
 Pinned by tests/test_oracle_pins_fused.py (library routine, closed forms, invariants).
 """
 from __future__ import annotations
@@ -47,13 +50,26 @@ def silu(v) -> np.ndarray:
     return v / (1.0 + np.exp(-v))
 
 
+def upsample_nearest2x(x) -> np.ndarray:
+    """u[n, c, i, j] = x[n, c, i // 2, j // 2], written as that index expression."""
+    x = np.asarray(x, dtype=np.float64)
+    N, C, H, W = x.shape
+    ii = np.arange(2 * H) // 2
+    jj = np.arange(2 * W) // 2
+    return x[:, :, ii[:, None], jj[None, :]]
+
+
 def conv2d_fused(x, w, bias, gamma=None, beta=None, groups: int = 32, eps: float = 1e-5,
-                 addvec=None, residual=None) -> np.ndarray:
-    """y = conv3x3(SiLU(GroupNorm(x))) + bias + addvec[n,k] + residual; every extra is optional
-    (gamma None = no GroupNorm/SiLU).  Zero padding applies to the activated tensor."""
+                 addvec=None, residual=None, upsample: bool = False) -> np.ndarray:
+    """y = conv3x3(up(SiLU(GroupNorm(x)))) + bias + addvec[n,k] + residual; every extra is optional
+    (gamma None = no GroupNorm/SiLU, upsample False = no 2x nearest-neighbour upsampling).  Zero
+    padding applies to the tensor the convolution sees; with upsampling y, addvec's image and the
+    residual have twice the height and width of x."""
     a = np.asarray(x, dtype=np.float64)
     if gamma is not None:
         a = silu(groupnorm(a, gamma, beta, groups, eps))
+    if upsample:
+        a = upsample_nearest2x(a)
     y = conv2d_direct(a, w, bias)
     if addvec is not None:
         y = y + np.asarray(addvec, dtype=np.float64)[:, :, None, None]

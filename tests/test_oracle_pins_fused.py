@@ -67,3 +67,36 @@ def test_fused_conv_reduces_to_its_parts():
     big = np.zeros((N, C, H + 2, W + 2)); big[:, :, 1:-1, 1:-1] = x
     wrong = fo.silu(fo.groupnorm(big, g, be, 4))
     assert not np.allclose(oracle.conv2d_direct(wrong, w, b)[:, :, 1:-1, 1:-1], fo.conv2d_fused(x, w, b, g, be, groups=4))
+
+
+def test_upsample_matches_library_routine_and_hand_case():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((2, 3, 4, 5))
+    ref = torch.nn.functional.interpolate(torch.from_numpy(x), scale_factor=2, mode="nearest").numpy()
+    u = fo.upsample_nearest2x(x)
+    assert u.shape == (2, 3, 8, 10) and np.array_equal(u, ref)
+    h = fo.upsample_nearest2x(np.array([[1.0, 2.0], [3.0, 4.0]]).reshape(1, 1, 2, 2))[0, 0]
+    assert np.array_equal(h, [[1, 1, 2, 2], [1, 1, 2, 2], [3, 3, 4, 4], [3, 3, 4, 4]])
+    # every 2x2 block is constant and sub-sampling undoes it
+    assert np.array_equal(u[:, :, ::2, ::2], x) and np.array_equal(u[:, :, 1::2, 1::2], x)
+
+
+def test_fused_upsample_conv_properties():
+    rng = np.random.default_rng(6)
+    N, C, K, H, W = 1, 3, 2, 4, 3
+    x = rng.standard_normal((N, C, H, W)); w = rng.standard_normal((K, C, 3, 3)); b = rng.standard_normal(K)
+    y = fo.conv2d_fused(x, w, b, upsample=True)
+    assert y.shape == (N, K, 2 * H, 2 * W)
+    # the same thing through the library: interpolate, then conv2d
+    xu = torch.nn.functional.interpolate(torch.from_numpy(x), scale_factor=2, mode="nearest")
+    ref = torch.nn.functional.conv2d(xu, torch.from_numpy(w), torch.from_numpy(b), padding=1).numpy()
+    assert np.abs(y - ref).max() < 1e-12
+    # an interior output of a constant image sees nine equal taps: y = c * sum(w) + b
+    c = np.full((1, C, H, W), 0.5)
+    yc = fo.conv2d_fused(c, w, b, upsample=True)
+    assert np.allclose(yc[0, :, 3, 2], 0.5 * w.sum(axis=(1, 2, 3)) + b, atol=1e-13)
+    # GroupNorm statistics do not change under upsampling, and the point-wise steps commute with it
+    g = rng.standard_normal(C); be = rng.standard_normal(C)
+    a = fo.conv2d_fused(x, w, b, g, be, groups=1, upsample=True)
+    bb = fo.conv2d_fused(fo.upsample_nearest2x(x), w, b, g, be, groups=1)
+    assert np.abs(a - bb).max() < 1e-12
