@@ -149,6 +149,10 @@ int wino_output_transform(const float *M, const float *bias, void *y, int N, int
  * textbook definitions apply):
  *   on the way in   x' = SiLU(GroupNorm(x)), GroupNorm over gn_groups equal channel groups per image
  *                   with affine gamma/beta; zero padding applies to x'.  Active iff gn_stats != NULL.
+ *   upsample != 0   the convolution reads x' through a 2x nearest-neighbour upsampling (the step before
+ *                   the 3x3 convolution in the UNet's and the VAE decoder's up-sampling blocks): x holds
+ *                   [H/2][W/2] pixels per channel, H and W (the arguments of the call, the size of y)
+ *                   must be even, and GroupNorm statistics, if used, are those of the stored x.
  *   on the way out  y = conv(x') + bias + addvec[n][k] + residual.  Each part optional.
  * All pointers are device memory.  residual has the layout, dtype and shape of y and may be y
  * itself (in-place accumulate) but must not otherwise overlap it.
@@ -160,6 +164,7 @@ typedef struct wino_fusion {
     int gn_groups;           /* must divide C */
     const float *addvec;     /* fp32 [N][K], or NULL */
     const void *residual;    /* like y, or NULL */
+    int upsample;            /* 0, or 1 = read x through a 2x nearest-neighbour upsampling */
 } wino_fusion;
 
 /* Bytes of the buffer wino_groupnorm_stats writes (statistics first, then its partial sums);

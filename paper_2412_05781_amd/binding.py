@@ -41,7 +41,8 @@ class wino_filter(ctypes.Structure):
 
 class wino_fusion(ctypes.Structure):
     _fields_ = [("gn_stats", ctypes.c_void_p), ("gn_gamma", ctypes.c_void_p), ("gn_beta", ctypes.c_void_p),
-                ("gn_groups", ctypes.c_int), ("addvec", ctypes.c_void_p), ("residual", ctypes.c_void_p)]
+                ("gn_groups", ctypes.c_int), ("addvec", ctypes.c_void_p), ("residual", ctypes.c_void_p),
+                ("upsample", ctypes.c_int)]
 
 
 class WinoError(RuntimeError):
@@ -130,9 +131,12 @@ def _act_shape(N, C, H, W, layout):
     return (N, H, W, C) if layout == WINO_NHWC else (N, C, H, W)
 
 
-def _conv_shapes(x, w_t, bias, y, layout=WINO_NCHW):
-    """Host-side shape/dtype agreement (the C side cannot see tensor extents)."""
+def _conv_shapes(x, w_t, bias, y, layout=WINO_NCHW, upsample=False):
+    """Host-side shape/dtype agreement (the C side cannot see tensor extents).  H and W are those
+    of y: twice x's when x is read through the 2x upsampling."""
     N, C, H, W = _unpack(x, layout)
+    if upsample:
+        H, W = 2 * H, 2 * W
     K = int(w_t.desc.K)
     dt = TORCH_OF[w_t.desc.dtype]
     if tuple(y.shape) != _act_shape(N, K, H, W, layout) or x.dtype != dt or y.dtype != dt:
@@ -301,11 +305,13 @@ def stats_view(buf: torch.Tensor, N: int, groups: int) -> torch.Tensor:
 
 
 def wino_conv2d_fused(x, w_t: Filter, bias, y, workspace, layout: int = WINO_NCHW, gn_stats=None, gn_gamma=None,
-                      gn_beta=None, gn_groups: int = 32, addvec=None, residual=None, stream=None):
-    """wino_conv2d_ex with SiLU(GroupNorm(x)) on the way in and + addvec[n,k] + residual on the way out."""
+                      gn_beta=None, gn_groups: int = 32, addvec=None, residual=None, upsample: bool = False, stream=None):
+    """wino_conv2d_ex with SiLU(GroupNorm(x)) and an optional 2x nearest-neighbour upsampling on the way in
+    and + addvec[n,k] + residual on the way out."""
     _dev(x, "x"); _dev(y, "y"); _dev(workspace, "workspace")
-    N, C, H, W, K = _conv_shapes(x, w_t, bias, y, layout)
+    N, C, H, W, K = _conv_shapes(x, w_t, bias, y, layout, upsample)
     f = wino_fusion()
+    f.upsample = 1 if upsample else 0
     if gn_stats is not None:
         for t, n, cnt in ((gn_gamma, "gn_gamma", C), (gn_beta, "gn_beta", C)):
             if t is None or not t.is_cuda or t.dtype != torch.float32 or t.numel() != cnt or not t.is_contiguous():
@@ -347,9 +353,11 @@ def conv2d(x: torch.Tensor, w: torch.Tensor, bias=None, variant: int = WINO_AUTO
 
 
 def conv2d_fused(x, w, bias=None, variant: int = WINO_AUTO, layout: int = WINO_NCHW, gn_gamma=None, gn_beta=None,
-                 gn_groups: int = 32, eps: float = 1e-5, addvec=None, residual=None) -> torch.Tensor:
+                 gn_groups: int = 32, eps: float = 1e-5, addvec=None, residual=None, upsample: bool = False) -> torch.Tensor:
     """Statistics (if GroupNorm is asked for), filter transform, workspace, then the fused call."""
     N, C, H, W = _unpack(x, layout)
+    if upsample:
+        H, W = 2 * H, 2 * W
     K = int(w.shape[0])
     y = torch.empty(_act_shape(N, K, H, W, layout), dtype=x.dtype, device=x.device)
     v = wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant)
@@ -358,4 +366,4 @@ def conv2d_fused(x, w, bias=None, variant: int = WINO_AUTO, layout: int = WINO_N
     stats = wino_groupnorm_stats(x, gn_groups, eps, layout) if gn_gamma is not None else None
     w_t = wino_filter_transform(w, v)
     ws = torch.empty(wino_workspace_bytes(N, C, H, W, K, DTYPE_OF[x.dtype], v), dtype=torch.uint8, device=x.device)
-    return wino_conv2d_fused(x, w_t, bias, y, ws, layout, stats, gn_gamma, gn_beta, gn_groups, addvec, residual)
+    return wino_conv2d_fused(x, w_t, bias, y, ws, layout, stats, gn_gamma, gn_beta, gn_groups, addvec, residual, upsample)

@@ -46,7 +46,7 @@ input_transform_nchw_kernel(const E* __restrict__ x, E* __restrict__ V,
         const int r = row0 + a, q = col0 + b, c = c0 + cc;
         E v = from_f32<E>(0.f);
         if (c < C && r >= 0 && r < H && q >= 0 && q < W)
-            v = x[(((size_t)n * C + c) * H + r) * W + q];
+            v = x[(((size_t)n * C + c) * (H >> pre.up) + (r >> pre.up)) * (W >> pre.up) + (q >> pre.up)];
         patch[cc * CS + rem] = v;
     }
     __syncthreads();
@@ -129,7 +129,8 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
 
     // 32-bit lane offsets against wave-uniform 64-bit bases keep the address arithmetic off the
     // vector ALU (the transform itself is only ~200 operations per tile and channel).
-    const unsigned char* xb = reinterpret_cast<const unsigned char*>(x + ((size_t)n * C + c0) * H * W);
+    const int Hs = H >> pre.up, Ws = W >> pre.up;         // the stored image (half size when it is read upsampled)
+    const unsigned char* xb = reinterpret_cast<const unsigned char*>(x + ((size_t)n * C + c0) * Hs * Ws);
     // a lane owns one (channel, chunk column) and walks the alpha patch rows: one add per load
     constexpr int ITEMS = CB * NCH;
     constexpr int PASSES = (ITEMS + 255) / 256;
@@ -145,8 +146,13 @@ input_transform_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ V,
         for (int a = 0; a < A; ++a) {
             const int r = row0 + a;
             reg[ps][a] = make_uint4(0, 0, 0, 0);
-            if (ok && r >= 0 && r < H)
-                reg[ps][a] = *reinterpret_cast<const uint4*>(xb + (off0 + (unsigned)(a * W * (int)sizeof(E))));
+            if (ok && r >= 0 && r < H) {
+                if (pre.up)   // 8 source bytes under the 16-byte chunk, every element twice
+                    reg[ps][a] = dup_elements<E>(*reinterpret_cast<const uint2*>(
+                        xb + (unsigned)(((cc * Hs + (r >> 1)) * Ws + (col >> 1)) * (int)sizeof(E))));
+                else
+                    reg[ps][a] = *reinterpret_cast<const uint4*>(xb + (off0 + (unsigned)(a * W * (int)sizeof(E))));
+            }
         }
     }
 #pragma unroll
@@ -253,7 +259,8 @@ input_transform_nchw_slide_kernel(const E* __restrict__ x, E* __restrict__ V,
     const int s1 = min(s0 + spb, steps_per_row);
     const int row0 = M * ti - 1;
 
-    const unsigned char* xb = reinterpret_cast<const unsigned char*>(x + ((size_t)n * C + c0) * H * W);
+    const int Hs = H >> pre.up, Ws = W >> pre.up;         // the stored image (half size when it is read upsampled)
+    const unsigned char* xb = reinterpret_cast<const unsigned char*>(x + ((size_t)n * C + c0) * Hs * Ws);
     // loader role: lane = (channel, chunk of the body), walks the alpha patch rows
     const int lc = tid >> 2, lch = tid & 3;
     const bool lc_ok = (c0 + lc) < C;
@@ -266,8 +273,13 @@ input_transform_nchw_slide_kernel(const E* __restrict__ x, E* __restrict__ V,
         for (int a = 0; a < A; ++a) {
             const int r = row0 + a;
             reg[a] = make_uint4(0, 0, 0, 0);
-            if (ok && r >= 0 && r < H)
-                reg[a] = *reinterpret_cast<const uint4*>(xb + (off0 + (unsigned)(a * W * (int)sizeof(E))));
+            if (ok && r >= 0 && r < H) {
+                if (pre.up)   // 8 source bytes under the 16-byte chunk, every element twice
+                    reg[a] = dup_elements<E>(*reinterpret_cast<const uint2*>(
+                        xb + (unsigned)(((lc * Hs + (r >> 1)) * Ws + (col >> 1)) * (int)sizeof(E))));
+                else
+                    reg[a] = *reinterpret_cast<const uint4*>(xb + (off0 + (unsigned)(a * W * (int)sizeof(E))));
+            }
         }
     };
     auto stash = [&](int body) {
@@ -376,7 +388,8 @@ input_transform_nhwc_kernel(const E* __restrict__ x, E* __restrict__ V,
     // bits are ANDed with an all-ones / all-zeros mask, so that the alpha^2 loads of a lane are all
     // in flight together.  The masks pass through an empty asm statement: seen as a select on the
     // bounds test, the compiler moves each load into a branch of its own and waits for it there.
-    const E* xb = x + (size_t)n * H * W * C + (live ? c : 0);
+    const int us = pre.up;                                      // 1: x is stored at half size and read upsampled
+    const E* xb = x + (size_t)n * (H >> us) * (W >> us) * C + (live ? c : 0);
     uint32_t rmask[A], cmask[A];
 #pragma unroll
     for (int a = 0; a < A; ++a) {
@@ -390,11 +403,11 @@ input_transform_nhwc_kernel(const E* __restrict__ x, E* __restrict__ V,
 #pragma unroll
     for (int a = 0; a < A; ++a) {
         const int r = M * ti - 1 + a;
-        const E* xr = xb + (size_t)min(max(r, 0), H - 1) * W * C;
+        const E* xr = xb + (size_t)(min(max(r, 0), H - 1) >> us) * (W >> us) * C;
 #pragma unroll
         for (int b = 0; b < A; ++b) {
             const int col = M * tj - 1 + b;
-            const E* p = xr + (size_t)min(max(col, 0), W - 1) * C;
+            const E* p = xr + (size_t)(min(max(col, 0), W - 1) >> us) * C;
             const uint32_t msk = rmask[a] & cmask[b];
             union { uint32_t w; E e[4 / sizeof(E)]; } v;
             if constexpr (CPT == 2) v.w = *reinterpret_cast<const uint32_t*>(p);
@@ -442,6 +455,7 @@ input_transform_nhwc_kernel(const E* __restrict__ x, E* __restrict__ V,
 template <int M, typename E>
 static hipError_t launch_it_nhwc(const void* x, void* V, const Geom& g, const PreOp* pre, hipStream_t s) {
     const PreOp po = pre ? *pre : PreOp();
+    const bool gn = po.stats != nullptr;
     // two fp16 channels per lane (4-byte accesses) when channel pairs never straddle C
     const bool pair = sizeof(E) == 2 && g.C % 2 == 0 && (reinterpret_cast<uintptr_t>(x) & 3u) == 0;
     const int cpt = pair ? 2 : 1;
@@ -452,11 +466,11 @@ static hipError_t launch_it_nhwc(const void* x, void* V, const Geom& g, const Pr
     dim3 block(256), grid((unsigned)per_xcd * 8);
     if (pair) {
         if constexpr (sizeof(E) == 2) {
-            if (pre) hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2, true>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, per_xcd, po);
+            if (gn) hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2, true>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, per_xcd, po);
             else     hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 2, false>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, per_xcd, po);
         }
     } else {
-        if (pre) hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1, true>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, per_xcd, po);
+        if (gn) hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1, true>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, per_xcd, po);
         else     hipLaunchKernelGGL((input_transform_nhwc_kernel<M, E, 1, false>), grid, block, 0, s, (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, per_xcd, po);
     }
     return hipGetLastError();
@@ -465,6 +479,7 @@ static hipError_t launch_it_nhwc(const void* x, void* V, const Geom& g, const Pr
 template <int M, typename E, int CB, int TJ>
 static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, const PreOp* pre, hipStream_t s) {
     const PreOp po = pre ? *pre : PreOp();
+    const bool gn = po.stats != nullptr;
     const int strips = (g.tw + TJ - 1) / TJ;
     dim3 block(256), grid((unsigned)(g.N * g.th * strips), (unsigned)((g.Cp + CB - 1) / CB));
     // fast path: rows are whole 16-byte chunks and a 64-channel slab of x spans < 2 GB (32-bit lane offsets)
@@ -483,7 +498,7 @@ static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, const Pre
         const long long total = (long long)g.N * g.th * (g.Cp / 64) * ((steps + spb - 1) / spb);
         if ((slide_cfg > 0 || pays) && total <= 0x3fffffffLL) {
             const int per_xcd = (int)((total + 7) / 8);
-            if (pre) hipLaunchKernelGGL((input_transform_nchw_slide_kernel<M, E, STJ, true>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
+            if (gn) hipLaunchKernelGGL((input_transform_nchw_slide_kernel<M, E, STJ, true>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
                                         (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, steps, spb, (int)total, per_xcd, po);
             else     hipLaunchKernelGGL((input_transform_nchw_slide_kernel<M, E, STJ, false>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
                                         (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, steps, spb, (int)total, per_xcd, po);
@@ -494,12 +509,12 @@ static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, const Pre
         const long long total = (long long)grid.x * grid.y;
         if (total > 0x3fffffffLL) return hipErrorInvalidValue;
         const int per_xcd = (int)((total + 7) / 8);
-        if (pre) hipLaunchKernelGGL((input_transform_nchw_vec_kernel<M, E, CB, TJ, true>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
+        if (gn) hipLaunchKernelGGL((input_transform_nchw_vec_kernel<M, E, CB, TJ, true>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
                                     (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips, (int)total, per_xcd, po);
         else     hipLaunchKernelGGL((input_transform_nchw_vec_kernel<M, E, CB, TJ, false>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
                                     (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips, (int)total, per_xcd, po);
     } else {
-        if (pre) hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ, true>), grid, block, 0, s,
+        if (gn) hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ, true>), grid, block, 0, s,
                                     (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips, po);
         else     hipLaunchKernelGGL((input_transform_nchw_kernel<M, E, CB, TJ, false>), grid, block, 0, s,
                                     (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, strips, po);

@@ -67,7 +67,7 @@ int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y,
 }
 
 int check_conv_args(const void* x, const wino_filter* w_t, const float* bias, const void* y,
-                    int N, int C, int H, int W, int K) {
+                    int N, int C, int H, int W, int K, int up = 0) {
     if (!x || !w_t || !y || !w_t->data) return WINO_ERR_NULL;
     if (!dtype_ok(w_t->dtype)) return WINO_ERR_DTYPE;
     if (!wino_variant_ok(w_t->variant)) return WINO_ERR_VARIANT;
@@ -76,7 +76,7 @@ int check_conv_args(const void* x, const wino_filter* w_t, const float* bias, co
     if (!aligned16(x) || !aligned16(y) || !aligned16(w_t->data) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)))
         return WINO_ERR_ALIGN;
     const size_t es = esize(w_t->dtype);
-    const uintptr_t xb = reinterpret_cast<uintptr_t>(x), xe = xb + (size_t)N * C * H * W * es;
+    const uintptr_t xb = reinterpret_cast<uintptr_t>(x), xe = xb + (size_t)N * C * (H >> up) * (W >> up) * es;
     const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + (size_t)N * K * H * W * es;
     if (xb < ye && yb < xe) return WINO_ERR_ALIAS;
     return WINO_OK;
@@ -203,11 +203,14 @@ int wino_groupnorm_stats(const void* x, float* stats, int N, int C, int H, int W
 int wino_conv2d_fused(const void* x, const wino_filter* w_t, const float* bias, void* y,
                       int N, int C, int H, int W, int K, int layout, const wino_fusion* f,
                       void* workspace, size_t workspace_bytes, void* stream) {
-    const int rc = check_conv_args(x, w_t, bias, y, N, C, H, W, K);
-    if (rc != WINO_OK) return rc;
     if (!f) return WINO_ERR_NULL;
+    if (f->upsample != 0 && f->upsample != 1) return WINO_ERR_DIM;
+    if (f->upsample && ((H | W) & 1)) return WINO_ERR_DIM;
+    const int rc = check_conv_args(x, w_t, bias, y, N, C, H, W, K, f->upsample);
+    if (rc != WINO_OK) return rc;
     if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
     PreOp pre; PostOp post;
+    pre.up = f->upsample;
     const bool has_pre = f->gn_stats != nullptr;
     if (has_pre) {
         if (!f->gn_gamma || !f->gn_beta) return WINO_ERR_NULL;
@@ -230,7 +233,7 @@ int wino_conv2d_fused(const void* x, const wino_filter* w_t, const float* bias, 
     const Workspace ws = workspace_layout(g, w_t->dtype);
     if (!workspace || workspace_bytes < ws.total) return WINO_ERR_WORKSPACE;
     if (!aligned16(workspace)) return WINO_ERR_ALIGN;
-    return run_chain(x, w_t, bias, y, g, workspace, layout == WINO_NHWC, has_pre ? &pre : nullptr, &post,
+    return run_chain(x, w_t, bias, y, g, workspace, layout == WINO_NHWC, (has_pre || pre.up) ? &pre : nullptr, &post,
                      static_cast<hipStream_t>(stream));
 }
 

@@ -46,7 +46,15 @@ struct PreOp {
     const float* beta = nullptr;      // [C]
     int groups = 1;
     int cpg = 1;                      // channels per group
+    int up = 0;                       // 1: x holds [H/2][W/2] pixels and is read as its 2x nearest-neighbour upsampling
 };
+// 16 bytes of an upsampled row from the 8 source bytes under them: every element twice
+template <typename E> __device__ __forceinline__ uint4 dup_elements(uint2 s);
+template <> __device__ __forceinline__ uint4 dup_elements<float>(uint2 s) { return make_uint4(s.x, s.x, s.y, s.y); }
+template <> __device__ __forceinline__ uint4 dup_elements<__half>(uint2 s) {
+    const uint32_t a = s.x & 0xffffu, b = s.x >> 16, c = s.y & 0xffffu, d = s.y >> 16;
+    return make_uint4(a | (a << 16), b | (b << 16), c | (c << 16), d | (d << 16));
+}
 struct PostOp {
     const float* addvec = nullptr;    // [N][K]
     const void* residual = nullptr;   // like y

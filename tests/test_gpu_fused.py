@@ -102,3 +102,50 @@ def test_fused_resblock_layer_full_size():
     err = oracle.rel_l2(y.float().cpu().numpy(), ref)
     print(f"fused B layer: relL2 {err:.3e}")
     assert err <= 5e-3
+
+
+# source shapes (N, C, K, h, w, groups); y is 2h x 2w.  They cover the scalar kernel (rows that are not whole
+# 16-byte chunks), the chunked strip kernel, and the sliding-window kernel for long rows.
+UP_CASES = [(1, 8, 8, 3, 5, 4), (2, 24, 16, 8, 12, 8), (1, 64, 8, 4, 108, 32), (1, 40, 6, 16, 16, 8)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("with_gn", [False, True])
+@pytest.mark.parametrize("case", UP_CASES)
+def test_upsample_fused(case, with_gn, layout, variant, dtype):
+    """2x nearest-neighbour upsampling read inside the activation transform, alone and together with the
+    GroupNorm + SiLU pre-op and both post-ops."""
+    N, C, K, h, w_, G = case
+    x, w, b = synth.make_inputs(N, C, K, h, w_, dtype, seed=6000 + sum(case))
+    gamma, beta, addvec, residual = _extras(N, C, K, 2 * h, 2 * w_, dtype, 99 + sum(case))
+    if with_gn:
+        ref = fo.conv2d_fused(_np(x), _np(w), _np(b), _np(gamma), _np(beta), G, 1e-5, _np(addvec), _np(residual), upsample=True)
+    else:
+        ref = fo.conv2d_fused(_np(x), _np(w), _np(b), upsample=True)
+    perm = (lambda t: t.permute(0, 2, 3, 1).contiguous()) if layout == B.WINO_NHWC else (lambda t: t)
+    if with_gn:
+        y = B.conv2d_fused(perm(x).to(DEV), w.to(DEV), b.to(DEV), variant, layout, gamma.to(DEV), beta.to(DEV), G, 1e-5,
+                           addvec.to(DEV), perm(residual).to(DEV), upsample=True)
+    else:
+        y = B.conv2d_fused(perm(x).to(DEV), w.to(DEV), b.to(DEV), variant, layout, upsample=True)
+    torch.cuda.synchronize()
+    y = y.float().cpu()
+    if layout == B.WINO_NHWC:
+        y = y.permute(0, 3, 1, 2)
+    assert tuple(y.shape) == (N, K, 2 * h, 2 * w_)
+    err = oracle.rel_l2(y.numpy(), ref)
+    assert err <= TOL[dtype], (case, with_gn, layout, variant, dtype, err)
+
+
+def test_upsample_rejects_odd_output_size():
+    x, w, b = synth.make_inputs(1, 8, 8, 4, 4, "f16", seed=1)
+    w_t = B.wino_filter_transform(w.to(DEV), B.WINO_F2)
+    y = torch.empty((1, 8, 7, 8), dtype=torch.float16, device=DEV)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
+    f = B.wino_fusion(); f.upsample = 1
+    import ctypes
+    rc = B.lib().wino_conv2d_fused(x.to(DEV).data_ptr(), ctypes.byref(w_t.desc), None, y.data_ptr(), 1, 8, 7, 8, 8, B.WINO_NCHW,
+                                   ctypes.byref(f), ws.data_ptr(), ws.numel(), None)
+    assert rc == B.WINO_ERR_DIM
