@@ -8,6 +8,7 @@ and never imports it.
 
   conv2d_direct      fp64 direct cross-correlation (C, OpenMP) — the definition.
   conv2d_direct_at   the same sum for selected output elements only.
+  conv2d_general     fp64 direct cross-correlation, R x R filter, stride, padding (C, OpenMP).
   winograd_ref       fp64 numpy Winograd algorithm, step by step (stage checks).
 
 Every function is pinned by ``tests/test_oracle_pins.py`` (hand cases, exact
@@ -23,15 +24,17 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "conv2d_direct.c")
+_SRC_GENERAL = os.path.join(_HERE, "conv2d_general.c")
 _LIB = os.path.join(_HERE, "liboracle_conv2d.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (no GPU toolchain involved)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_GENERAL))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
-               "-o", _LIB, _SRC]
+               "-o", _LIB, _SRC, _SRC_GENERAL]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -48,6 +51,8 @@ def _load():
         lib.oracle_conv2d_f64_at.restype = ctypes.c_int
         lib.oracle_conv2d_f64_at.argtypes = [dp, dp, dp, ip, ctypes.c_int64, dp] + [ctypes.c_int] * 5
         lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_conv2d_general_f64.restype = ctypes.c_int
+        lib.oracle_conv2d_general_f64.argtypes = [dp, dp, dp, dp] + [ctypes.c_int] * 8
         _lib = lib
     return _lib
 
@@ -85,6 +90,26 @@ def conv2d_direct(x, w, bias=None) -> np.ndarray:
                                    N, C, H, W, K)
     if rc != 0:
         raise RuntimeError("oracle_conv2d_f64 rejected its arguments")
+    return y
+
+
+def conv2d_general(x, w, bias=None, stride: int = 1, pad: int = None) -> np.ndarray:
+    """y[N,K,Ho,Wo] (fp64) from x[N,C,H,W], w[K,C,R,R], bias[K] or None; pad defaults to (R-1)//2."""
+    x = _f64(x)
+    N, C, H, W = x.shape
+    w = _f64(w)
+    K, R = w.shape[0], w.shape[2]
+    if w.shape != (K, C, R, R):
+        raise ValueError(f"w must be [K,{C},R,R], got {w.shape}")
+    if pad is None:
+        pad = (R - 1) // 2
+    b = None if bias is None else _f64(bias, (K,))
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    y = np.empty((N, K, Ho, Wo), dtype=np.float64)
+    rc = _load().oracle_conv2d_general_f64(_ptr(x), _ptr(w), None if b is None else _ptr(b), _ptr(y),
+                                           N, C, H, W, K, R, stride, pad)
+    if rc != 0:
+        raise RuntimeError("oracle_conv2d_general_f64 rejected its arguments")
     return y
 
 
