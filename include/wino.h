@@ -187,6 +187,29 @@ int wino_conv2d_fused(const void *x, const wino_filter *w_t, const float *bias, 
 int wino_direct_conv2d(const void *x, const void *w, const float *bias, void *y,
                        int N, int C, int H, int W, int K, int dtype, void *stream);
 
+/*
+ * The convolution flavours of a Stable-Diffusion UNet / VAE that the Winograd path does not cover
+ * (1x1 projections, 3x3 with stride 2), as an implicit GEMM on the MFMA units with fp32 accumulation,
+ * so that the library can stand in for the whole 2-D convolution operator that the paper's Section
+ * "Techniques" replaces (the paper defines none of these flavours; the textbook definition applies):
+ *
+ *     y[n,k,i,j] = bias[k] + sum_{c,r,s} xhat[n,c,i*stride+r-pad,j*stride+s-pad] * w[k,c,r,s]
+ *     R x R filter with R in {1, 3}, stride in {1, 2}, pad = (R-1)/2, Ho = (H+2*pad-R)/stride+1, Wo likewise
+ *
+ * The filter is re-laid once per weight tensor (wino_igemm_filter_repack: w[K][C][R][R] ->
+ * Wr[R*R][K][Cp] plus one row of zeros, wino_igemm_filter_bytes() bytes).  x[N][C][H][W] -> y[N][K][Ho][Wo]
+ * (WINO_NCHW) or x[N][H][W][C] -> y[N][Ho][Wo][K] (WINO_NHWC), all in `dtype`; bias fp32 [K] or NULL.
+ * The workspace (wino_igemm_workspace_bytes(), may be 0: channel-last x with C a multiple of 8 is read
+ * in place) holds x re-laid with the channel index contiguous.  Same conventions as above: device
+ * pointers 16-byte aligned, arguments validated on the host, work enqueued on `stream`, deterministic.
+ */
+size_t wino_igemm_filter_bytes(int K, int C, int R, int dtype);
+int wino_igemm_filter_repack(const void *w, void *w_r, int K, int C, int R, int dtype, void *stream);
+size_t wino_igemm_workspace_bytes(int N, int C, int H, int W, int dtype, int layout);
+int wino_igemm_conv2d(const void *x, const void *w_r, const float *bias, void *y,
+                      int N, int C, int H, int W, int K, int R, int stride, int dtype, int layout,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

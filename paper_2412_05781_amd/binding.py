@@ -31,6 +31,7 @@ EXPORTS = [
     "wino_filter_bytes", "wino_workspace_bytes", "wino_filter_transform", "wino_conv2d",
     "wino_conv2d_ex", "wino_input_transform", "wino_batched_gemm", "wino_output_transform",
     "wino_direct_conv2d", "wino_groupnorm_stats_bytes", "wino_groupnorm_stats", "wino_conv2d_fused",
+    "wino_igemm_filter_bytes", "wino_igemm_filter_repack", "wino_igemm_workspace_bytes", "wino_igemm_conv2d",
 ]
 
 
@@ -90,6 +91,12 @@ def lib() -> ctypes.CDLL:
         L.wino_groupnorm_stats.argtypes = [vp, vp, i, i, i, i, i, ctypes.c_float, i, i, vp]
         L.wino_conv2d_fused.restype = i
         L.wino_conv2d_fused.argtypes = [vp, fp, vp, vp, i, i, i, i, i, i, ctypes.POINTER(wino_fusion), vp, sz, vp]
+        L.wino_igemm_filter_bytes.restype = sz; L.wino_igemm_filter_bytes.argtypes = [i] * 4
+        L.wino_igemm_filter_repack.restype = i
+        L.wino_igemm_filter_repack.argtypes = [vp, vp, i, i, i, i, vp]
+        L.wino_igemm_workspace_bytes.restype = sz; L.wino_igemm_workspace_bytes.argtypes = [i] * 6
+        L.wino_igemm_conv2d.restype = i
+        L.wino_igemm_conv2d.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -334,7 +341,61 @@ def wino_conv2d_fused(x, w_t: Filter, bias, y, workspace, layout: int = WINO_NCH
     return y
 
 
+def wino_igemm_filter_bytes(K, C, R, dtype) -> int:
+    return lib().wino_igemm_filter_bytes(K, C, R, dtype)
+
+
+def wino_igemm_filter_repack(w: torch.Tensor, stream=None) -> torch.Tensor:
+    """w[K,C,R,R] -> the re-laid filter Wr[R*R,K,Cp] followed by a row of zeros (raw byte buffer)."""
+    _dev(w, "w")
+    K, C, R = int(w.shape[0]), int(w.shape[1]), int(w.shape[2])
+    if w.dim() != 4 or int(w.shape[3]) != R or w.dtype not in DTYPE_OF:
+        raise ValueError("w must be [K,C,R,R], fp16 or fp32")
+    nbytes = wino_igemm_filter_bytes(K, C, R, DTYPE_OF[w.dtype])
+    if nbytes == 0:
+        raise WinoError(WINO_ERR_DIM, "wino_igemm_filter_bytes")
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    _check(lib().wino_igemm_filter_repack(_ptr(w), _ptr(buf), K, C, R, DTYPE_OF[w.dtype], _stream(stream)),
+           "wino_igemm_filter_repack")
+    return buf
+
+
+def wino_igemm_workspace_bytes(N, C, H, W, dtype, layout) -> int:
+    return lib().wino_igemm_workspace_bytes(N, C, H, W, dtype, layout)
+
+
+def wino_igemm_conv2d(x: torch.Tensor, w_r: torch.Tensor, bias, y: torch.Tensor, K: int, R: int, stride: int,
+                      workspace: Optional[torch.Tensor], layout: int = WINO_NCHW, stream=None) -> torch.Tensor:
+    _dev(x, "x"); _dev(w_r, "w_r"); _dev(y, "y")
+    N, C, H, W = _unpack(x, layout)
+    pad = (R - 1) // 2
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    if tuple(y.shape) != _act_shape(N, K, Ho, Wo, layout) or y.dtype != x.dtype:
+        raise ValueError(f"expected y{_act_shape(N, K, Ho, Wo, layout)} of dtype {x.dtype}")
+    if w_r.numel() * w_r.element_size() < wino_igemm_filter_bytes(K, C, R, DTYPE_OF[x.dtype]):
+        raise ValueError("re-laid filter buffer too small")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != K or not bias.is_cuda):
+        raise ValueError("bias must be a GPU fp32 tensor of K elements")
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().wino_igemm_conv2d(_ptr(x), _ptr(w_r), _ptr(bias), _ptr(y), N, C, H, W, K, R, stride, DTYPE_OF[x.dtype],
+                                   layout, _ptr(workspace), wsb, _stream(stream)), "wino_igemm_conv2d")
+    return y
+
+
 # ---- convenience (allocation only) ------------------------------------------------------------
+def conv2d_igemm(x: torch.Tensor, w: torch.Tensor, bias=None, stride: int = 1, layout: int = WINO_NCHW) -> torch.Tensor:
+    """1x1 or 3x3 convolution with stride 1 or 2 through the implicit-GEMM path (filter re-layout, workspace, call)."""
+    N, C, H, W = _unpack(x, layout)
+    K, R = int(w.shape[0]), int(w.shape[2])
+    pad = (R - 1) // 2
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    y = torch.empty(_act_shape(N, K, Ho, Wo, layout), dtype=x.dtype, device=x.device)
+    w_r = wino_igemm_filter_repack(w)
+    nb = wino_igemm_workspace_bytes(N, C, H, W, DTYPE_OF[x.dtype], layout)
+    ws = torch.empty(nb, dtype=torch.uint8, device=x.device) if nb else None
+    return wino_igemm_conv2d(x, w_r, bias, y, K, R, stride, ws, layout)
+
+
 def conv2d(x: torch.Tensor, w: torch.Tensor, bias=None, variant: int = WINO_AUTO, layout: int = WINO_NCHW) -> torch.Tensor:
     """Transform the filter, allocate workspace and output, run the chosen variant."""
     N, C, H, W = _unpack(x, layout)

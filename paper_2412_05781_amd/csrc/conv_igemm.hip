@@ -1,0 +1,333 @@
+// Direct convolution as an implicit GEMM on the MFMA units, for the convolution flavours of a
+// Stable-Diffusion UNet / VAE that the Winograd path does not cover (1x1 projections, 3x3 with
+// stride 2), so that the library can stand in for the whole 2-D convolution operator the paper's
+// Section "Techniques" replaces.  Square R x R filter, stride st, zero padding (R-1)/2:
+//
+//   y[n,k,i,j] = bias[k] + sum_{tap=(r,s)} sum_c  xhat[n, i*st + r - pad, j*st + s - pad, c] * w[k,c,r,s]
+//
+// i.e. R*R accumulated matrix products  Y[k][t] += Wr[tap][k][:] . P_tap[t][:]  in which row t of
+// P_tap is the channel vector of one input pixel (or a row of zeros in the padding).  The kernel
+// has the structure of the Winograd GEMM stage (128-byte reduction stages, global -> LDS transfers
+// into a ring, XOR-swizzled chunks, 32x32 MFMA tiles, fp32 accumulation); what differs is that the
+// rows of the pixel operand are found by address arithmetic per filter tap instead of being stored,
+// and that the epilogue adds the bias and writes y in its storage type.
+//
+// The pixel operand needs the channel index contiguous: x[N][H][W][Cp].  Channel-last inputs with
+// C a multiple of 8 are used in place; otherwise (NCHW, or C not a multiple of 8) a re-layout
+// kernel writes that tensor into the workspace first.
+#include "wino_internal.h"
+#include "wino_mma.h"
+#include <stdlib.h>
+
+namespace wino {
+
+struct ConvGeom {
+    int N, C, Cp, H, W, K, R, st, pad, Ho, Wo, T;      // T = N*Ho*Wo output pixels
+};
+
+// PIX_A: the pixel operand supplies the rows of the block (outputs [t][k], channel-last y);
+// otherwise the filter does (outputs [k][t], NCHW y).
+template <typename E, int BM, int BN, int NST, bool PIX_A>
+__global__ void __launch_bounds__(256)
+conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* __restrict__ zero_row,
+                  const float* __restrict__ bias, E* __restrict__ y, ConvGeom g,
+                  int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd) {
+    constexpr int RB = 128;
+    constexpr int CPR = RB / 16;                          // 16-byte chunks per row per stage
+    constexpr int BKE = RB / (int)sizeof(E);              // reduction elements per stage
+    constexpr int EPC = 16 / (int)sizeof(E);
+    constexpr int ROWS = BM + BN;
+    constexpr int RPL = 1024 / RB;                        // rows covered by one wave-wide load
+    constexpr int NW = 4;
+    constexpr int LPW = ROWS / RPL / NW;                  // wave-wide loads per wave per stage
+    constexpr int WTM = BM / 2, WTN = BN / 2;
+    constexpr int FM = WTM / 32, FN = WTN / 32;
+    constexpr int STAGE_BYTES = ROWS * RB;
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && ROWS % (RPL * NW) == 0 && BM % RPL == 0, "tile shape");
+    static_assert(NST >= 2 && LPW * (NST - 1) < 64, "ring depth / vmcnt range");
+
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+
+    const int bid = blockIdx.x;
+    const int logical = (bid % 8) * blocks_per_xcd + bid / 8;   // one contiguous range per XCD
+    if (logical >= total_blocks) return;                        // uniform, before any barrier
+    int tm, tn;
+    if (tiles_m <= tiles_n) { tm = logical % tiles_m; tn = logical / tiles_m; }
+    else { tn = logical % tiles_n; tm = logical / tiles_n; }
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int row_a0 = tm * BM, row_b0 = tn * BN;
+    const int rowsA = PIX_A ? g.T : g.K, rowsB = PIX_A ? g.K : g.T;
+
+    // Per-lane description of its LPW loads.  Filter rows: a pointer that advances with the tap and
+    // the stage.  Pixel rows: the image, and the top-left input coordinate of the output pixel.
+    const int lrow = lane / CPR, lchunk = lane % CPR;
+    const E* fptr[LPW];                                   // filter row: Wr + k*Cp + chunk (tap 0, stage 0)
+    int pn[LPW], pi0[LPW], pj0[LPW];                       // pixel row: image offset (pixels), first input row / column
+    int chunk_of[LPW];
+    bool is_pix[LPW];
+    const int HoWo = g.Ho * g.Wo;
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        const int row = (wave + NW * i) * RPL + lrow;       // row inside the stage, A rows first
+        const int chunk = lchunk ^ ((row >> 1) & (CPR - 1));
+        chunk_of[i] = chunk;
+        const bool in_a = row < BM;
+        int gr = in_a ? row_a0 + row : row_b0 + (row - BM);
+        const int lim = in_a ? rowsA : rowsB;
+        gr = gr < lim ? gr : lim - 1;                       // rows beyond the end repeat the last one; never stored
+        is_pix[i] = (in_a == PIX_A);
+        fptr[i] = Wr + (size_t)gr * g.Cp + chunk * EPC;
+        const int n = gr / HoWo, p = gr - n * HoWo;
+        const int oi = p / g.Wo, oj = p - oi * g.Wo;
+        pn[i] = n * g.H * g.W; pi0[i] = oi * g.st - g.pad; pj0[i] = oj * g.st - g.pad;
+    }
+
+    const int nkc = (g.Cp + BKE - 1) / BKE;
+    const bool ragged = (g.Cp % BKE) != 0;
+    const int taps = g.R * g.R;
+    const int nstage = taps * nkc;
+
+    // issue side: the (tap, stage-in-tap) of the next stage to fetch, and that tap's row pointers
+    int itap = 0, ikc = 0, iq = 0;
+    const E* src[LPW];
+    auto set_tap = [&](int tap) {
+        const int r = tap / g.R, s = tap - r * g.R;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            if (is_pix[i]) {
+                const int ii = pi0[i] + r, jj = pj0[i] + s;
+                const bool in = ii >= 0 && ii < g.H && jj >= 0 && jj < g.W;
+                src[i] = in ? xh + ((size_t)pn[i] + (size_t)ii * g.W + jj) * g.Cp + chunk_of[i] * EPC
+                            : zero_row + chunk_of[i] * EPC;
+            } else {
+                src[i] = fptr[i] + (size_t)tap * g.K * g.Cp;
+            }
+        }
+    };
+    auto issue_next = [&]() {
+        if (ikc == 0) set_tap(itap);
+        unsigned char* slot = lds + (iq % NST) * STAGE_BYTES;
+        if (ragged && ikc == nkc - 1) {
+            // last, partial stage of a tap: through registers, chunks beyond Cp become zeros
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) {
+                const int gk = ikc * BKE + chunk_of[i] * EPC;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (gk < g.Cp) v = *reinterpret_cast<const uint4*>(src[i] + ikc * BKE);
+                *reinterpret_cast<uint4*>(slot + (wave + NW * i) * 1024 + lane * 16) = v;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) dma_load_1k(src[i] + ikc * BKE, slot + (wave + NW * i) * 1024);
+        }
+        ++iq;
+        if (++ikc == nkc) { ikc = 0; ++itap; }
+    };
+
+    float16_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < nstage) issue_next();
+
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    for (int q = 0; q < nstage; ++q) {
+        // transfers complete in issue order: allow as many outstanding as were issued after stage q
+        if (q + NST - 1 >= nstage) wait_vmcnt<0>();
+        else wait_vmcnt<(NST - 2) * LPW>();
+        __syncthreads();            // stage q visible to all waves; everyone is done with stage q-1
+        if (q + NST - 1 < nstage) issue_next();             // refills the slot stage q-1 used
+
+        const unsigned char* slot = lds + (q % NST) * STAGE_BYTES;
+        uint4 fa[CPR / 2][FM], fb[CPR / 2][FN];
+#pragma unroll
+        for (int ks = 0; ks < CPR / 2; ++ks) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                const int row = wm * WTM + i * 32 + frag_row;
+                const int chunk = (2 * ks + frag_half) ^ ((row >> 1) & (CPR - 1));
+                fa[ks][i] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
+            }
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int row = BM + wn * WTN + j * 32 + frag_row;
+                const int chunk = (2 * ks + frag_half) ^ ((row >> 1) & (CPR - 1));
+                fb[ks][j] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < CPR / 2; ++ks)
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j) Mma<E>::run(fa[ks][i], fb[ks][j], acc[i][j]);
+    }
+
+    // 32x32 accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+    // Bias is added in fp32 and the sum rounded once to the storage type.
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int cb = row_b0 + wn * WTN + j * 32 + frag_row;      // column of this lane
+            if (cb >= rowsB) continue;
+            if (PIX_A) {
+                // rows are output pixels, the column is k: y[t][k], lanes along k
+                const float b = bias ? bias[cb] : 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int t = row_a0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+                    if (t < g.T) y[(size_t)t * g.K + cb] = from_f32<E>(acc[i][j][r] + b);
+                }
+            } else {
+                // rows are k, the column is an output pixel: y[n][k][p], lanes along p
+                const int n = cb / HoWo, p = cb - n * HoWo;
+                E* yp = y + (size_t)n * g.K * HoWo + p;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int k = row_a0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+                    if (k < g.K) yp[(size_t)k * HoWo] = from_f32<E>(acc[i][j][r] + (bias ? bias[k] : 0.f));
+                }
+            }
+        }
+}
+
+// w[K][C][R][R] -> Wr[R*R][K][Cp] (channel index contiguous, zero-filled to Cp), followed by one row
+// of Cp zeros that stands in for the pixels of the padding.
+template <typename E>
+__global__ void __launch_bounds__(256)
+igemm_filter_repack_kernel(const E* __restrict__ w, E* __restrict__ Wr, int K, int C, int Cp, int taps) {
+    const size_t total = (size_t)taps * K * Cp + Cp;
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    E v = from_f32<E>(0.f);
+    if (e < (size_t)taps * K * Cp) {
+        const int c = (int)(e % Cp);
+        const size_t q = e / Cp;
+        const int k = (int)(q % K), tap = (int)(q / K);
+        if (c < C) v = w[((size_t)k * C + c) * taps + tap];
+    }
+    Wr[e] = v;
+}
+
+// x -> xh[N][H][W][Cp], zero-filled channels.  NCHW source: a 32 (w) x 64 (c) tile goes through LDS so
+// that reads run along w and writes along c.  Channel-last source (C not a multiple of 8): plain copy.
+template <typename E>
+__global__ void __launch_bounds__(256)
+igemm_relayout_nchw_kernel(const E* __restrict__ x, E* __restrict__ xh, int N, int C, int Cp, int H, int W, int wtiles) {
+    __shared__ E tile[64][33];
+    int b = blockIdx.x;
+    const int wt = b % wtiles; b /= wtiles;
+    const int h = b % H; const int n = b / H;
+    const int c0 = blockIdx.y * 64, w0 = wt * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int c = c0 + ty + 8 * k, wq = w0 + tx;
+        tile[ty + 8 * k][tx] = (c < C && wq < W) ? x[(((size_t)n * C + c) * H + h) * W + wq] : from_f32<E>(0.f);
+    }
+    __syncthreads();
+    const int cx = threadIdx.x & 63, wy = threadIdx.x >> 6;     // 64 x 4
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int wq = w0 + wy + 4 * k, c = c0 + cx;
+        if (wq < W && c < Cp) xh[(((size_t)n * H + h) * W + wq) * Cp + c] = tile[cx][wy + 4 * k];
+    }
+}
+
+template <typename E>
+__global__ void __launch_bounds__(256)
+igemm_pad_nhwc_kernel(const E* __restrict__ x, E* __restrict__ xh, size_t pixels, int C, int Cp) {
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= pixels * Cp) return;
+    const int c = (int)(e % Cp);
+    const size_t p = e / Cp;
+    xh[e] = c < C ? x[p * C + c] : from_f32<E>(0.f);
+}
+
+template <typename E, int BM, int BN, int NST, bool PIX_A>
+static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, E* y, const ConvGeom& g, hipStream_t s) {
+    const int rowsA = PIX_A ? g.T : g.K, rowsB = PIX_A ? g.K : g.T;
+    const int tiles_m = (rowsA + BM - 1) / BM, tiles_n = (rowsB + BN - 1) / BN;
+    const long long total = (long long)tiles_m * tiles_n;
+    if (total > 0x3fffffffLL) return hipErrorInvalidValue;
+    const int per_xcd = (int)((total + 7) / 8);
+    constexpr int lds_bytes = (BM + BN) * 128 * NST;
+    static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+    auto kern = conv_igemm_kernel<E, BM, BN, NST, PIX_A>;
+    static bool attr_set = false;                 // per instantiation; raising the limit is idempotent
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const E* zero_row = Wr + (size_t)g.R * g.R * g.K * g.Cp;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), lds_bytes, s,
+                       xh, Wr, zero_row, bias, y, g, tiles_m, tiles_n, (int)total, per_xcd);
+    return hipGetLastError();
+}
+
+template <typename E, bool PIX_A>
+static hipError_t launch_igemm_t(const E* xh, const E* Wr, const float* bias, E* y, const ConvGeom& g, hipStream_t s) {
+    static const int forced = [] { const char* e = getenv("WINO_IGEMM_SHAPE"); return e ? atoi(e) : -1; }();   // tuning knob
+    // 128x128 blocks while they still cover the chip twice, else 64x64
+    const long long big = (long long)((g.T + 127) / 128) * ((g.K + 127) / 128);
+    const int shape = forced >= 0 ? forced : (big >= 512 ? 0 : 1);
+    if (shape == 0) return launch_igemm_cfg<E, 128, 128, 2, PIX_A>(xh, Wr, bias, y, g, s);
+    return launch_igemm_cfg<E, 64, 64, 2, PIX_A>(xh, Wr, bias, y, g, s);
+}
+
+hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, bool f16, hipStream_t s) {
+    const int Cp = (C + 7) / 8 * 8, taps = R * R;
+    const size_t total = (size_t)taps * K * Cp + Cp;
+    const size_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+    if (f16) hipLaunchKernelGGL(igemm_filter_repack_kernel<__half>, dim3((unsigned)blocks), dim3(256), 0, s, (const __half*)w, (__half*)Wr, K, C, Cp, taps);
+    else     hipLaunchKernelGGL(igemm_filter_repack_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)w, (float*)Wr, K, C, Cp, taps);
+    return hipGetLastError();
+}
+
+template <typename E>
+static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias, void* y, const ConvGeom& g, bool nhwc,
+                               void* workspace, hipStream_t s) {
+    const E* xh = static_cast<const E*>(x);
+    if (!nhwc) {
+        const int wtiles = (g.W + 31) / 32;
+        const long long bx = (long long)g.N * g.H * wtiles;
+        if (bx > 0x7fffffffLL || (g.Cp + 63) / 64 > 65535) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(igemm_relayout_nchw_kernel<E>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
+                           (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.H, g.W, wtiles);
+        if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+        xh = static_cast<const E*>(workspace);
+    } else if (g.C != g.Cp) {
+        const size_t pixels = (size_t)g.N * g.H * g.W;
+        const size_t blocks = (pixels * g.Cp + 255) / 256;
+        if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(igemm_pad_nhwc_kernel<E>, dim3((unsigned)blocks), dim3(256), 0, s, (const E*)x, (E*)workspace, pixels, g.C, g.Cp);
+        if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+        xh = static_cast<const E*>(workspace);
+    }
+    return nhwc ? launch_igemm_t<E, true>(xh, (const E*)Wr, bias, (E*)y, g, s)
+                : launch_igemm_t<E, false>(xh, (const E*)Wr, bias, (E*)y, g, s);
+}
+
+hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias, void* y,
+                               int N, int C, int H, int W, int K, int R, int st, bool f16, bool nhwc,
+                               void* workspace, hipStream_t s) {
+    ConvGeom g;
+    g.N = N; g.C = C; g.Cp = (C + 7) / 8 * 8; g.H = H; g.W = W; g.K = K; g.R = R; g.st = st; g.pad = (R - 1) / 2;
+    g.Ho = (H + 2 * g.pad - R) / st + 1; g.Wo = (W + 2 * g.pad - R) / st + 1;
+    g.T = N * g.Ho * g.Wo;
+    return f16 ? igemm_conv_t<__half>(x, Wr, bias, y, g, nhwc, workspace, s)
+               : igemm_conv_t<float>(x, Wr, bias, y, g, nhwc, workspace, s);
+}
+
+}  // namespace wino

@@ -291,4 +291,63 @@ int wino_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
                                 static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
+namespace {
+bool igemm_dims_ok(int N, int C, int H, int W, int K, int R, int st) {
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1) return false;
+    if ((R != 1 && R != 3) || (st != 1 && st != 2)) return false;
+    if (C > (1 << 22) || K > (1 << 22)) return false;
+    const unsigned long long lim = 1ULL << 40;
+    const unsigned long long Cp = (unsigned long long)(C + 7) / 8 * 8;
+    if ((unsigned long long)N * H * W > (unsigned long long)INT_MAX / 2) return false;    // pixel indices are ints
+    if ((unsigned long long)N * H * W > lim / Cp) return false;
+    if ((unsigned long long)N * H * W > lim / (unsigned long long)K) return false;
+    if ((unsigned long long)R * R * K > lim / Cp) return false;
+    return true;
+}
+}  // namespace
+
+size_t wino_igemm_filter_bytes(int K, int C, int R, int dtype) {
+    if (!dtype_ok(dtype) || !igemm_dims_ok(1, C, 1, 1, K, R, 1)) return 0;
+    const size_t Cp = (size_t)round_up(C, 8);
+    return ((size_t)R * R * K * Cp + Cp) * esize(dtype);
+}
+
+int wino_igemm_filter_repack(const void* w, void* w_r, int K, int C, int R, int dtype, void* stream) {
+    if (!w || !w_r) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (!igemm_dims_ok(1, C, 1, 1, K, R, 1)) return WINO_ERR_DIM;
+    if (!aligned16(w) || !aligned16(w_r)) return WINO_ERR_ALIGN;
+    return launch_igemm_filter_repack(w, w_r, K, C, R, dtype == WINO_F16, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? WINO_OK : WINO_ERR_HIP;
+}
+
+size_t wino_igemm_workspace_bytes(int N, int C, int H, int W, int dtype, int layout) {
+    if (!dtype_ok(dtype) || !igemm_dims_ok(N, C, H, W, 1, 1, 1)) return 0;
+    if (layout == WINO_NHWC && C % 8 == 0) return 0;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return 0;
+    return align_up((size_t)N * H * W * (size_t)round_up(C, 8) * esize(dtype));
+}
+
+int wino_igemm_conv2d(const void* x, const void* w_r, const float* bias, void* y,
+                      int N, int C, int H, int W, int K, int R, int stride, int dtype, int layout,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    if (!x || !w_r || !y) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    if (!igemm_dims_ok(N, C, H, W, K, R, stride)) return WINO_ERR_DIM;
+    if (!aligned16(x) || !aligned16(w_r) || !aligned16(y) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)))
+        return WINO_ERR_ALIGN;
+    const int pad = (R - 1) / 2;
+    const int Ho = (H + 2 * pad - R) / stride + 1, Wo = (W + 2 * pad - R) / stride + 1;
+    const size_t es = esize(dtype);
+    const uintptr_t xb = reinterpret_cast<uintptr_t>(x), xe = xb + (size_t)N * C * H * W * es;
+    const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + (size_t)N * K * Ho * Wo * es;
+    if (xb < ye && yb < xe) return WINO_ERR_ALIAS;
+    const size_t need = wino_igemm_workspace_bytes(N, C, H, W, dtype, layout);
+    if (need && (!workspace || workspace_bytes < need)) return WINO_ERR_WORKSPACE;
+    if (need && !aligned16(workspace)) return WINO_ERR_ALIGN;
+    return launch_igemm_conv2d(x, w_r, bias, y, N, C, H, W, K, R, stride, dtype == WINO_F16, layout == WINO_NHWC,
+                               workspace, static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+}
+
 }  // extern "C"

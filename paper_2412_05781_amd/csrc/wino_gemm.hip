@@ -17,44 +17,10 @@
 // stored); a ragged last reduction stage (Cp not a multiple of the stage) goes
 // through registers with zero fill instead.
 #include "wino_internal.h"
+#include "wino_mma.h"
 #include <stdlib.h>
 
 namespace wino {
-
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef float float16_t __attribute__((ext_vector_type(16)));
-
-template <typename E> struct Mma;
-template <> struct Mma<__half> {
-    // one 16-byte chunk = 8 reduction elements; lanes 0-31 and 32-63 hold different chunks
-    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, float16_t& c) {
-        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const half8_t*>(&a),
-                                                    *reinterpret_cast<const half8_t*>(&b), c, 0, 0, 0);
-    }
-};
-template <> struct Mma<float> {
-    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, float16_t& c) {
-        const float* fa = reinterpret_cast<const float*>(&a);
-        const float* fb = reinterpret_cast<const float*>(&b);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j], fb[j], c, 0, 0, 0);
-    }
-};
-
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-// One wave-wide global -> LDS transfer: lane l's 16 bytes at `src` land at lds_dst + 16*l
-// (lds_dst wave-uniform).  Written as inline assembly on purpose: the compiler then does not
-// track the transfer and does not drain every outstanding one before each barrier and LDS read;
-// the kernel waits with explicit vmcnt values instead (see the reduction loop).
-typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
-__device__ __forceinline__ void dma_load_1k(const void* src, unsigned char* lds_dst) {
-    const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t*)lds_dst);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(m0v), "v"(src) : "memory");   // nothing else in these kernels reads m0
-}
 
 template <typename E, int BM, int BN, int RB, int NST, int WGM, int WGN>
 __global__ void __launch_bounds__(WGM * WGN * 64)

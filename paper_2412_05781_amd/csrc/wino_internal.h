@@ -90,6 +90,10 @@ hipError_t launch_output_transform(const float* M, const float* bias, void* y, c
 hipError_t launch_groupnorm_stats(const void* x, float* stats, int N, int C, int H, int W, int groups, float eps,
                                   bool f16, bool nhwc, hipStream_t s);
 size_t groupnorm_stats_bytes(int N, int groups);
+hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, bool f16, hipStream_t s);
+hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias, void* y,
+                               int N, int C, int H, int W, int K, int R, int st, bool f16, bool nhwc,
+                               void* workspace, hipStream_t s);
 hipError_t launch_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
                                 int N, int C, int H, int W, int K, bool f16, hipStream_t s);
 
