@@ -200,12 +200,13 @@ int wino_direct_conv2d(const void *x, const void *w, const float *bias, void *y,
  * Wr[R*R][K][Cp] plus one row of zeros, wino_igemm_filter_bytes() bytes).  x[N][C][H][W] -> y[N][K][Ho][Wo]
  * (WINO_NCHW) or x[N][H][W][C] -> y[N][Ho][Wo][K] (WINO_NHWC), all in `dtype`; bias fp32 [K] or NULL.
  * The workspace (wino_igemm_workspace_bytes(), may be 0: channel-last x with C a multiple of 8 is read
- * in place) holds x re-laid with the channel index contiguous.  Same conventions as above: device
+ * in place) holds x re-laid with the channel index contiguous and, for shapes with few output pixels and
+ * a long reduction, fp32 partial sums of a reduction that is cut into ranges.  Same conventions as above: device
  * pointers 16-byte aligned, arguments validated on the host, work enqueued on `stream`, deterministic.
  */
 size_t wino_igemm_filter_bytes(int K, int C, int R, int dtype);
 int wino_igemm_filter_repack(const void *w, void *w_r, int K, int C, int R, int dtype, void *stream);
-size_t wino_igemm_workspace_bytes(int N, int C, int H, int W, int dtype, int layout);
+size_t wino_igemm_workspace_bytes(int N, int C, int H, int W, int K, int R, int stride, int dtype, int layout);
 int wino_igemm_conv2d(const void *x, const void *w_r, const float *bias, void *y,
                       int N, int C, int H, int W, int K, int R, int stride, int dtype, int layout,
                       void *workspace, size_t workspace_bytes, void *stream);

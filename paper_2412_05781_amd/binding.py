@@ -94,7 +94,7 @@ def lib() -> ctypes.CDLL:
         L.wino_igemm_filter_bytes.restype = sz; L.wino_igemm_filter_bytes.argtypes = [i] * 4
         L.wino_igemm_filter_repack.restype = i
         L.wino_igemm_filter_repack.argtypes = [vp, vp, i, i, i, i, vp]
-        L.wino_igemm_workspace_bytes.restype = sz; L.wino_igemm_workspace_bytes.argtypes = [i] * 6
+        L.wino_igemm_workspace_bytes.restype = sz; L.wino_igemm_workspace_bytes.argtypes = [i] * 9
         L.wino_igemm_conv2d.restype = i
         L.wino_igemm_conv2d.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, vp, sz, vp]
         _lib = L
@@ -360,8 +360,8 @@ def wino_igemm_filter_repack(w: torch.Tensor, stream=None) -> torch.Tensor:
     return buf
 
 
-def wino_igemm_workspace_bytes(N, C, H, W, dtype, layout) -> int:
-    return lib().wino_igemm_workspace_bytes(N, C, H, W, dtype, layout)
+def wino_igemm_workspace_bytes(N, C, H, W, K, R, stride, dtype, layout) -> int:
+    return lib().wino_igemm_workspace_bytes(N, C, H, W, K, R, stride, dtype, layout)
 
 
 def wino_igemm_conv2d(x: torch.Tensor, w_r: torch.Tensor, bias, y: torch.Tensor, K: int, R: int, stride: int,
@@ -391,7 +391,7 @@ def conv2d_igemm(x: torch.Tensor, w: torch.Tensor, bias=None, stride: int = 1, l
     Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
     y = torch.empty(_act_shape(N, K, Ho, Wo, layout), dtype=x.dtype, device=x.device)
     w_r = wino_igemm_filter_repack(w)
-    nb = wino_igemm_workspace_bytes(N, C, H, W, DTYPE_OF[x.dtype], layout)
+    nb = wino_igemm_workspace_bytes(N, C, H, W, K, R, stride, DTYPE_OF[x.dtype], layout)
     ws = torch.empty(nb, dtype=torch.uint8, device=x.device) if nb else None
     return wino_igemm_conv2d(x, w_r, bias, y, K, R, stride, ws, layout)
 

@@ -30,8 +30,8 @@ struct ConvGeom {
 template <typename E, int BM, int BN, int NST, bool PIX_A>
 __global__ void __launch_bounds__(256)
 conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* __restrict__ zero_row,
-                  const float* __restrict__ bias, E* __restrict__ y, ConvGeom g,
-                  int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd) {
+                  const float* __restrict__ bias, E* __restrict__ y, float* __restrict__ part, ConvGeom g,
+                  int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd, int nsplit) {
     constexpr int RB = 128;
     constexpr int CPR = RB / 16;                          // 16-byte chunks per row per stage
     constexpr int BKE = RB / (int)sizeof(E);              // reduction elements per stage
@@ -51,9 +51,13 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
     const int bid = blockIdx.x;
     const int logical = (bid % 8) * blocks_per_xcd + bid / 8;   // one contiguous range per XCD
     if (logical >= total_blocks) return;                        // uniform, before any barrier
+    // With nsplit > 1 the reduction (taps x channel stages) is cut into nsplit ranges of whole stages;
+    // split i leaves its fp32 partial sums in the i-th copy of `part` and a second kernel adds them up.
+    const int split = logical % nsplit;
+    const int tile = logical / nsplit;
     int tm, tn;
-    if (tiles_m <= tiles_n) { tm = logical % tiles_m; tn = logical / tiles_m; }
-    else { tn = logical % tiles_n; tm = logical / tiles_n; }
+    if (tiles_m <= tiles_n) { tm = tile % tiles_m; tn = tile / tiles_m; }
+    else { tn = tile % tiles_n; tm = tile / tiles_n; }
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -87,10 +91,13 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
     const int nkc = (g.Cp + BKE - 1) / BKE;
     const bool ragged = (g.Cp % BKE) != 0;
     const int taps = g.R * g.R;
-    const int nstage = taps * nkc;
+    const int nstage_all = taps * nkc;
+    const int q0 = (int)((long long)split * nstage_all / nsplit), q1 = (int)((long long)(split + 1) * nstage_all / nsplit);
+    const int nstage = q1 - q0;
 
     // issue side: the (tap, stage-in-tap) of the next stage to fetch, and that tap's row pointers
-    int itap = 0, ikc = 0, iq = 0;
+    int itap = q0 / nkc, ikc = q0 - (q0 / nkc) * nkc, iq = 0;
+    bool tap_set = false;
     const E* src[LPW];
     auto set_tap = [&](int tap) {
         const int r = tap / g.R, s = tap - r * g.R;
@@ -107,7 +114,7 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
         }
     };
     auto issue_next = [&]() {
-        if (ikc == 0) set_tap(itap);
+        if (ikc == 0 || !tap_set) { set_tap(itap); tap_set = true; }
         unsigned char* slot = lds + (iq % NST) * STAGE_BYTES;
         if (ragged && ikc == nkc - 1) {
             // last, partial stage of a tap: through registers, chunks beyond Cp become zeros
@@ -172,6 +179,23 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
     }
 
     // 32x32 accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+    if (nsplit > 1) {
+        // partial sums, [split][rowsA][rowsB] fp32
+        float* pb = part + (size_t)split * rowsA * rowsB;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int cb = row_b0 + wn * WTN + j * 32 + frag_row;
+                if (cb >= rowsB) continue;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ra = row_a0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+                    if (ra < rowsA) pb[(size_t)ra * rowsB + cb] = acc[i][j][r];
+                }
+            }
+        return;
+    }
     // Bias is added in fp32 and the sum rounded once to the storage type.
 #pragma unroll
     for (int i = 0; i < FM; ++i)
@@ -198,6 +222,27 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
                 }
             }
         }
+}
+
+// Sum of the nsplit partial products (fixed order), bias, one rounding, y in its layout.
+// part is [nsplit][rowsA][rowsB]; PIX_A: (t, k) -> y[t][k]; otherwise (k, t) -> y[n][k][p].
+template <typename E, bool PIX_A>
+__global__ void __launch_bounds__(256)
+igemm_reduce_kernel(const float* __restrict__ part, const float* __restrict__ bias, E* __restrict__ y,
+                    int K, int T, int HoWo, int nsplit) {
+    const size_t total = (size_t)K * T;
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    float acc = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp) acc += part[(size_t)sp * total + e];
+    if (PIX_A) {
+        const int k = (int)(e % K);
+        y[e] = from_f32<E>(acc + (bias ? bias[k] : 0.f));
+    } else {
+        const int t = (int)(e % T), k = (int)(e / T);
+        const int n = t / HoWo, p = t - n * HoWo;
+        y[((size_t)n * K + k) * HoWo + p] = from_f32<E>(acc + (bias ? bias[k] : 0.f));
+    }
 }
 
 // w[K][C][R][R] -> Wr[R*R][K][Cp] (channel index contiguous, zero-filled to Cp), followed by one row
@@ -243,6 +288,48 @@ igemm_relayout_nchw_kernel(const E* __restrict__ x, E* __restrict__ xh, int N, i
     }
 }
 
+// The same re-layout with 16-byte accesses on both sides, for rows of whole 16-byte chunks: a tile of
+// 64 channels x TW pixels (TW = 8 chunks) of one image row goes through LDS; a lane reads one chunk
+// along w, and writes one chunk of EPC adjacent channels of one pixel, gathered element by element
+// from LDS (row pitch an odd number of words: conflict-free both ways).
+template <typename E>
+__global__ void __launch_bounds__(256)
+igemm_relayout_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ xh, int N, int C, int Cp, int H, int W, int wtiles) {
+    constexpr int EPC = 16 / (int)sizeof(E);
+    constexpr int EPW = 4 / (int)sizeof(E);
+    constexpr int TW = 8 * EPC;                            // pixels per tile
+    constexpr int PITCHW = TW / EPW + 1;                   // words per channel row, odd
+    __shared__ uint32_t tile[64 * PITCHW];
+    int b = blockIdx.x;
+    const int wt = b % wtiles; b /= wtiles;
+    const int h = b % H; const int n = b / H;
+    const int c0 = blockIdx.y * 64, w0 = wt * TW;
+    // in: 64 channels x 8 chunks = 512 chunks, two per lane
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int item = threadIdx.x + 256 * k;
+        const int cl = item >> 3, ch = item & 7;
+        const int c = c0 + cl, wq = w0 + ch * EPC;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (c < C && wq < W) v = *reinterpret_cast<const uint4*>(x + (((size_t)n * C + c) * H + h) * W + wq);
+        uint32_t* d = tile + cl * PITCHW + ch * 4;
+        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    }
+    __syncthreads();
+    // out: TW pixels x (64 / EPC) channel chunks
+    const E* te = reinterpret_cast<const E*>(tile);
+    constexpr int CCH = 64 / EPC;                          // chunks per pixel
+    for (int item = threadIdx.x; item < TW * CCH; item += 256) {
+        const int cg = item % CCH, wl = item / CCH;
+        const int wq = w0 + wl, c = c0 + cg * EPC;
+        if (wq >= W || c >= Cp) continue;
+        union { E e[EPC]; uint4 v; } o;
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) o.e[i] = te[(cg * EPC + i) * (PITCHW * EPW) + wl];
+        *reinterpret_cast<uint4*>(xh + (((size_t)n * H + h) * W + wq) * Cp + c) = o.v;
+    }
+}
+
 template <typename E>
 __global__ void __launch_bounds__(256)
 igemm_pad_nhwc_kernel(const E* __restrict__ x, E* __restrict__ xh, size_t pixels, int C, int Cp) {
@@ -254,10 +341,11 @@ igemm_pad_nhwc_kernel(const E* __restrict__ x, E* __restrict__ xh, size_t pixels
 }
 
 template <typename E, int BM, int BN, int NST, bool PIX_A>
-static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, E* y, const ConvGeom& g, hipStream_t s) {
+static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, E* y, float* part, int nsplit,
+                                   const ConvGeom& g, hipStream_t s) {
     const int rowsA = PIX_A ? g.T : g.K, rowsB = PIX_A ? g.K : g.T;
     const int tiles_m = (rowsA + BM - 1) / BM, tiles_n = (rowsB + BN - 1) / BN;
-    const long long total = (long long)tiles_m * tiles_n;
+    const long long total = (long long)tiles_m * tiles_n * nsplit;
     if (total > 0x3fffffffLL) return hipErrorInvalidValue;
     const int per_xcd = (int)((total + 7) / 8);
     constexpr int lds_bytes = (BM + BN) * 128 * NST;
@@ -271,18 +359,48 @@ static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, 
     }
     const E* zero_row = Wr + (size_t)g.R * g.R * g.K * g.Cp;
     hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), lds_bytes, s,
-                       xh, Wr, zero_row, bias, y, g, tiles_m, tiles_n, (int)total, per_xcd);
+                       xh, Wr, zero_row, bias, y, part, g, tiles_m, tiles_n, (int)total, per_xcd, nsplit);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    if (nsplit > 1) {
+        const size_t blocks = ((size_t)g.K * g.T + 255) / 256;
+        if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((igemm_reduce_kernel<E, PIX_A>), dim3((unsigned)blocks), dim3(256), 0, s, part, bias, y, g.K, g.T, g.Ho * g.Wo, nsplit);
+    }
     return hipGetLastError();
 }
 
-template <typename E, bool PIX_A>
-static hipError_t launch_igemm_t(const E* xh, const E* Wr, const float* bias, E* y, const ConvGeom& g, hipStream_t s) {
+// 128x128 blocks while they still cover the chip twice, else 64x64.
+static int igemm_shape(int T, int K) {
     static const int forced = [] { const char* e = getenv("WINO_IGEMM_SHAPE"); return e ? atoi(e) : -1; }();   // tuning knob
-    // 128x128 blocks while they still cover the chip twice, else 64x64
-    const long long big = (long long)((g.T + 127) / 128) * ((g.K + 127) / 128);
-    const int shape = forced >= 0 ? forced : (big >= 512 ? 0 : 1);
-    if (shape == 0) return launch_igemm_cfg<E, 128, 128, 2, PIX_A>(xh, Wr, bias, y, g, s);
-    return launch_igemm_cfg<E, 64, 64, 2, PIX_A>(xh, Wr, bias, y, g, s);
+    if (forced >= 0) return forced;
+    return (long long)((T + 127) / 128) * ((K + 127) / 128) >= 512 ? 0 : 1;
+}
+
+// Few blocks and a long reduction (deep down-sampling layers: 8x8 outputs, 9 x 1280 channels): cut the
+// reduction so that about two workgroups per compute unit are in flight, at least eight stages each
+// (the second kernel costs ~3 us, more than a short reduction gains).
+int igemm_split(int T, int K, int Cp, int R, bool f16) {
+    static const int forced = [] { const char* e = getenv("WINO_IGEMM_SPLIT"); return e ? atoi(e) : 0; }();       // tuning knob
+    const int bke = f16 ? 64 : 32;
+    const int nstage = R * R * ((Cp + bke - 1) / bke);
+    int sp = 1;
+    if (forced > 0) sp = forced;
+    else {
+        const int b = igemm_shape(T, K) == 0 ? 128 : 64;
+        const long long blocks = (long long)((T + b - 1) / b) * ((K + b - 1) / b);
+        if (blocks < 256) sp = (int)((512 + blocks - 1) / blocks);
+        if (sp > 16) sp = 16;
+        if (sp > nstage / 8) sp = nstage / 8;
+    }
+    if (sp > nstage) sp = nstage;
+    return sp < 1 ? 1 : sp;
+}
+
+template <typename E, bool PIX_A>
+static hipError_t launch_igemm_t(const E* xh, const E* Wr, const float* bias, E* y, float* part, int nsplit,
+                                 const ConvGeom& g, hipStream_t s) {
+    if (igemm_shape(g.T, g.K) == 0) return launch_igemm_cfg<E, 128, 128, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, s);
+    return launch_igemm_cfg<E, 64, 64, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, s);
 }
 
 hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, bool f16, hipStream_t s) {
@@ -297,14 +415,23 @@ hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int
 
 template <typename E>
 static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias, void* y, const ConvGeom& g, bool nhwc,
-                               void* workspace, hipStream_t s) {
+                               void* workspace, size_t xh_bytes, hipStream_t s) {
     const E* xh = static_cast<const E*>(x);
+    const int nsplit = igemm_split(g.T, g.K, g.Cp, g.R, sizeof(E) == 2);
+    float* part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + xh_bytes);   // only used when nsplit > 1
     if (!nhwc) {
-        const int wtiles = (g.W + 31) / 32;
+        constexpr int EPC = 16 / (int)sizeof(E);
+        const bool chunks = g.W % EPC == 0;                 // x and the workspace are 16-byte aligned, so every row then is
+        const int tw = chunks ? 8 * EPC : 32;
+        const int wtiles = (g.W + tw - 1) / tw;
         const long long bx = (long long)g.N * g.H * wtiles;
         if (bx > 0x7fffffffLL || (g.Cp + 63) / 64 > 65535) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(igemm_relayout_nchw_kernel<E>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
-                           (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.H, g.W, wtiles);
+        if (chunks)
+            hipLaunchKernelGGL(igemm_relayout_nchw_vec_kernel<E>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
+                               (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.H, g.W, wtiles);
+        else
+            hipLaunchKernelGGL(igemm_relayout_nchw_kernel<E>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
+                               (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.H, g.W, wtiles);
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
         xh = static_cast<const E*>(workspace);
     } else if (g.C != g.Cp) {
@@ -315,19 +442,19 @@ static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias,
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
         xh = static_cast<const E*>(workspace);
     }
-    return nhwc ? launch_igemm_t<E, true>(xh, (const E*)Wr, bias, (E*)y, g, s)
-                : launch_igemm_t<E, false>(xh, (const E*)Wr, bias, (E*)y, g, s);
+    return nhwc ? launch_igemm_t<E, true>(xh, (const E*)Wr, bias, (E*)y, part, nsplit, g, s)
+                : launch_igemm_t<E, false>(xh, (const E*)Wr, bias, (E*)y, part, nsplit, g, s);
 }
 
 hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias, void* y,
                                int N, int C, int H, int W, int K, int R, int st, bool f16, bool nhwc,
-                               void* workspace, hipStream_t s) {
+                               void* workspace, size_t xh_bytes, hipStream_t s) {
     ConvGeom g;
     g.N = N; g.C = C; g.Cp = (C + 7) / 8 * 8; g.H = H; g.W = W; g.K = K; g.R = R; g.st = st; g.pad = (R - 1) / 2;
     g.Ho = (H + 2 * g.pad - R) / st + 1; g.Wo = (W + 2 * g.pad - R) / st + 1;
     g.T = N * g.Ho * g.Wo;
-    return f16 ? igemm_conv_t<__half>(x, Wr, bias, y, g, nhwc, workspace, s)
-               : igemm_conv_t<float>(x, Wr, bias, y, g, nhwc, workspace, s);
+    return f16 ? igemm_conv_t<__half>(x, Wr, bias, y, g, nhwc, workspace, xh_bytes, s)
+               : igemm_conv_t<float>(x, Wr, bias, y, g, nhwc, workspace, xh_bytes, s);
 }
 
 }  // namespace wino

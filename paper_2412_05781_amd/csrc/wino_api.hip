@@ -321,11 +321,24 @@ int wino_igemm_filter_repack(const void* w, void* w_r, int K, int C, int R, int 
                ? WINO_OK : WINO_ERR_HIP;
 }
 
-size_t wino_igemm_workspace_bytes(int N, int C, int H, int W, int dtype, int layout) {
-    if (!dtype_ok(dtype) || !igemm_dims_ok(N, C, H, W, 1, 1, 1)) return 0;
+namespace {
+// bytes of the re-laid copy of x (0: x is used in place), and of the fp32 partial products
+size_t igemm_xh_bytes(int N, int C, int H, int W, int dtype, int layout) {
     if (layout == WINO_NHWC && C % 8 == 0) return 0;
-    if (layout != WINO_NCHW && layout != WINO_NHWC) return 0;
     return align_up((size_t)N * H * W * (size_t)round_up(C, 8) * esize(dtype));
+}
+size_t igemm_part_bytes(int N, int C, int H, int W, int K, int R, int stride, int dtype) {
+    const int pad = (R - 1) / 2;
+    const long long T = (long long)N * ((H + 2 * pad - R) / stride + 1) * ((W + 2 * pad - R) / stride + 1);
+    const int sp = igemm_split((int)T, K, round_up(C, 8), R, dtype == WINO_F16);
+    return sp > 1 ? align_up((size_t)sp * (size_t)K * (size_t)T * sizeof(float)) : 0;
+}
+}  // namespace
+
+size_t wino_igemm_workspace_bytes(int N, int C, int H, int W, int K, int R, int stride, int dtype, int layout) {
+    if (!dtype_ok(dtype) || !igemm_dims_ok(N, C, H, W, K, R, stride)) return 0;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return 0;
+    return igemm_xh_bytes(N, C, H, W, dtype, layout) + igemm_part_bytes(N, C, H, W, K, R, stride, dtype);
 }
 
 int wino_igemm_conv2d(const void* x, const void* w_r, const float* bias, void* y,
@@ -343,11 +356,12 @@ int wino_igemm_conv2d(const void* x, const void* w_r, const float* bias, void* y
     const uintptr_t xb = reinterpret_cast<uintptr_t>(x), xe = xb + (size_t)N * C * H * W * es;
     const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + (size_t)N * K * Ho * Wo * es;
     if (xb < ye && yb < xe) return WINO_ERR_ALIAS;
-    const size_t need = wino_igemm_workspace_bytes(N, C, H, W, dtype, layout);
+    const size_t need = wino_igemm_workspace_bytes(N, C, H, W, K, R, stride, dtype, layout);
     if (need && (!workspace || workspace_bytes < need)) return WINO_ERR_WORKSPACE;
     if (need && !aligned16(workspace)) return WINO_ERR_ALIGN;
     return launch_igemm_conv2d(x, w_r, bias, y, N, C, H, W, K, R, stride, dtype == WINO_F16, layout == WINO_NHWC,
-                               workspace, static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+                               workspace, igemm_xh_bytes(N, C, H, W, dtype, layout), static_cast<hipStream_t>(stream)) == hipSuccess
+               ? WINO_OK : WINO_ERR_HIP;
 }
 
 }  // extern "C"

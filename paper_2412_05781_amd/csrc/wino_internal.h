@@ -93,7 +93,8 @@ size_t groupnorm_stats_bytes(int N, int groups);
 hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, bool f16, hipStream_t s);
 hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias, void* y,
                                int N, int C, int H, int W, int K, int R, int st, bool f16, bool nhwc,
-                               void* workspace, hipStream_t s);
+                               void* workspace, size_t xh_bytes, hipStream_t s);
+int igemm_split(int T, int K, int Cp, int R, bool f16);   // number of partial products the path writes for a shape
 hipError_t launch_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
                                 int N, int C, int H, int W, int K, bool f16, hipStream_t s);
 

@@ -67,6 +67,26 @@ def test_igemm_no_bias_large_block_and_determinism():
     assert oracle.rel_l2(y1.float().cpu().numpy(), ref) <= 6e-4
 
 
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("dtype,shape,R,stride", [("f16", (2, 640, 200, 16, 16), 3, 2), ("f16", (1, 2048, 96, 8, 8), 1, 1),
+                                                  ("f32", (1, 264, 72, 12, 10), 3, 2), ("f16", (2, 328, 130, 9, 9), 3, 1)])
+def test_igemm_split_reduction(dtype, shape, R, stride, layout):
+    """Few output pixels and a long reduction: the stage is cut into ranges whose fp32 partial sums a second kernel
+    adds (ragged block tails, a channel count that is not a whole number of stages, both layouts)."""
+    N, C, K, H, W = shape
+    x, w, b = _inputs(N, C, K, H, W, R, dtype, seed=8000 + sum(shape))
+    ref = oracle.conv2d_general(_np(x), _np(w), _np(b), stride)
+    xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+    assert B.wino_igemm_workspace_bytes(N, C, H, W, K, R, stride, B.DTYPE_OF[x.dtype], B.WINO_NHWC) > 0     # partial sums are in use
+    y = B.conv2d_igemm(xd, w.to(DEV), b.to(DEV), stride, layout)
+    torch.cuda.synchronize()
+    y = y.float().cpu()
+    if layout == B.WINO_NHWC:
+        y = y.permute(0, 3, 1, 2)
+    err = oracle.rel_l2(y.numpy(), ref)
+    assert err <= (6e-4 if dtype == "f16" else 1e-5), (shape, R, stride, layout, dtype, err)
+
+
 def test_igemm_matches_winograd_and_direct_kernels():
     """3x3 / stride 1: the same operator as the Winograd path and the checking kernel."""
     N, C, K, H, W = 1, 48, 56, 20, 24
@@ -86,7 +106,7 @@ def test_igemm_argument_checks():
     w_r = B.wino_igemm_filter_repack(wd)
     y = torch.empty((1, 8, 4, 4), dtype=torch.float16, device=DEV)
     L = B.lib()
-    ws = torch.empty(B.wino_igemm_workspace_bytes(1, 8, 8, 8, B.WINO_F16, B.WINO_NCHW), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(B.wino_igemm_workspace_bytes(1, 8, 8, 8, 8, 3, 2, B.WINO_F16, B.WINO_NCHW), dtype=torch.uint8, device=DEV)
     args = lambda **kw: [kw.get("x", xd.data_ptr()), w_r.data_ptr(), None, y.data_ptr(), 1, 8, 8, 8, 8, kw.get("R", 3), kw.get("st", 2),
                          B.WINO_F16, kw.get("layout", B.WINO_NCHW), kw.get("ws", ws.data_ptr()), kw.get("wsb", ws.numel()), None]
     assert L.wino_igemm_conv2d(*args()) == B.WINO_OK
@@ -96,5 +116,5 @@ def test_igemm_argument_checks():
     assert L.wino_igemm_conv2d(*args(wsb=16)) == B.WINO_ERR_WORKSPACE
     assert L.wino_igemm_conv2d(*args(x=xd.data_ptr() + 2)) == B.WINO_ERR_ALIGN
     assert L.wino_igemm_conv2d(*args(x=None)) == B.WINO_ERR_NULL
-    assert B.wino_igemm_workspace_bytes(1, 8, 8, 8, B.WINO_F16, B.WINO_NHWC) == 0
+    assert B.wino_igemm_workspace_bytes(1, 8, 8, 8, 8, 1, 1, B.WINO_F16, B.WINO_NHWC) == 0   # read in place, one stage: nothing to hold
     torch.cuda.synchronize()
