@@ -138,12 +138,14 @@ def conv2d_winograd(x, w, bias, m: int) -> np.ndarray:
     return output_transform(M, bias, N, H, W, m)
 
 
-def conv2d_winograd_storage_model(x, w, bias, m: int, store_dtype=np.float16) -> np.ndarray:
+def conv2d_winograd_storage_model(x, w, bias, m: int, store_dtype=np.float16, product_dtype=None) -> np.ndarray:
     """Error model of a low-precision Winograd path (not the definition of the result): the
     same three steps, with U and V rounded once to `store_dtype` as a kernel that keeps them
     in that type would, the products accumulated exactly (fp64 stands in for fp32), and the
     output rounded once to `store_dtype`.  Used to predict the relative L2 error a correct
-    fp16-storage implementation must show - far above or far below means a different path ran."""
+    fp16-storage implementation must show - far above or far below means a different path ran.
+    `product_dtype` (None = exact) additionally rounds the intermediate product M once, as a path
+    that stores M in that type between its second and third step would."""
     x = np.asarray(x, dtype=np.float64)
     N, C, H, W = x.shape
     if np.dtype(store_dtype).itemsize >= 8:
@@ -153,4 +155,6 @@ def conv2d_winograd_storage_model(x, w, bias, m: int, store_dtype=np.float16) ->
     U = q(filter_transform(w, m))
     V = q(input_transform(x, m))
     M = multiply(U, V)
+    if product_dtype is not None:
+        M = M.astype(np.float32).astype(product_dtype).astype(np.float64)
     return q(output_transform(M, bias, N, H, W, m))

@@ -31,6 +31,28 @@ def test_fp16_storage_error_band(m, C):
     assert err <= 5e-3
 
 
+# with the intermediate product M also kept in fp16 (the library's opt-in "half product" mode)
+BANDS_HALF_PRODUCT = {2: (4.0e-4, 1.0e-3), 4: (3.0e-3, 4.8e-3)}
+
+
+@pytest.mark.parametrize("C", [32, 320, 1280])
+@pytest.mark.parametrize("m", [2, 4])
+def test_fp16_product_error_band(m, C):
+    """Rounding M to fp16 as well costs F(4x4) about a quarter more error (3.1e-3 -> 3.8..4.2e-3): still inside
+    5e-3, with less room - which is why the mode is opt-in."""
+    rng = np.random.default_rng(C + m)
+    N, K, H, W = 1, 16, 16, 16
+    x = rng.standard_normal((N, C, H, W)).astype(np.float16)
+    w = (rng.standard_normal((K, C, 3, 3)) / np.sqrt(9 * C)).astype(np.float16)
+    b = (0.01 * rng.standard_normal(K)).astype(np.float32)
+    ref = oracle.conv2d_direct(x, w, b)
+    x64, w64, b64 = x.astype(np.float64), w.astype(np.float64), b.astype(np.float64)
+    err = oracle.rel_l2(wr.conv2d_winograd_storage_model(x64, w64, b64, m, product_dtype=np.float16), ref)
+    base = oracle.rel_l2(wr.conv2d_winograd_storage_model(x64, w64, b64, m), ref)
+    lo, hi = BANDS_HALF_PRODUCT[m]
+    assert lo <= err <= hi and err > base and err <= 5e-3, (m, C, err, base)
+
+
 def test_model_without_rounding_is_exact():
     rng = np.random.default_rng(1)
     x = rng.standard_normal((1, 8, 9, 10)); w = rng.standard_normal((4, 8, 3, 3)); b = rng.standard_normal(4)
