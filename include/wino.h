@@ -154,6 +154,11 @@ int wino_output_transform(const float *M, const float *bias, void *y, int N, int
  *                   [H/2][W/2] pixels per channel, H and W (the arguments of the call, the size of y)
  *                   must be even, and GroupNorm statistics, if used, are those of the stored x.
  *   on the way out  y = conv(x') + bias + addvec[n][k] + residual.  Each part optional.
+ *   product_fp16    opt-in, fp16 storage only: the product M of step (ii) is written and read back as fp16
+ *                   instead of fp32, which halves the largest tensor of the path (1.2-1.4x on layers with
+ *                   large images).  Accumulation stays fp32.  The relative L2 error of F(4x4) grows from
+ *                   about 3.1e-3 to 3.8-4.2e-3 (F(2x2): 5e-4 to 6.4e-4), and |M| must stay below 65504.
+ *                   Ignored where the reduction is split into partial products, and for fp32 storage.
  * All pointers are device memory.  residual has the layout, dtype and shape of y and may be y
  * itself (in-place accumulate) but must not otherwise overlap it.
  */
@@ -165,6 +170,7 @@ typedef struct wino_fusion {
     const float *addvec;     /* fp32 [N][K], or NULL */
     const void *residual;    /* like y, or NULL */
     int upsample;            /* 0, or 1 = read x through a 2x nearest-neighbour upsampling */
+    int product_fp16;        /* 0, or 1 = keep the intermediate product M in fp16 (see below) */
 } wino_fusion;
 
 /* Bytes of the buffer wino_groupnorm_stats writes (statistics first, then its partial sums);

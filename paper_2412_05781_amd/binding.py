@@ -43,7 +43,7 @@ class wino_filter(ctypes.Structure):
 class wino_fusion(ctypes.Structure):
     _fields_ = [("gn_stats", ctypes.c_void_p), ("gn_gamma", ctypes.c_void_p), ("gn_beta", ctypes.c_void_p),
                 ("gn_groups", ctypes.c_int), ("addvec", ctypes.c_void_p), ("residual", ctypes.c_void_p),
-                ("upsample", ctypes.c_int)]
+                ("upsample", ctypes.c_int), ("product_fp16", ctypes.c_int)]
 
 
 class WinoError(RuntimeError):
@@ -312,13 +312,15 @@ def stats_view(buf: torch.Tensor, N: int, groups: int) -> torch.Tensor:
 
 
 def wino_conv2d_fused(x, w_t: Filter, bias, y, workspace, layout: int = WINO_NCHW, gn_stats=None, gn_gamma=None,
-                      gn_beta=None, gn_groups: int = 32, addvec=None, residual=None, upsample: bool = False, stream=None):
+                      gn_beta=None, gn_groups: int = 32, addvec=None, residual=None, upsample: bool = False,
+                      product_fp16: bool = False, stream=None):
     """wino_conv2d_ex with SiLU(GroupNorm(x)) and an optional 2x nearest-neighbour upsampling on the way in
     and + addvec[n,k] + residual on the way out."""
     _dev(x, "x"); _dev(y, "y"); _dev(workspace, "workspace")
     N, C, H, W, K = _conv_shapes(x, w_t, bias, y, layout, upsample)
     f = wino_fusion()
     f.upsample = 1 if upsample else 0
+    f.product_fp16 = 1 if product_fp16 else 0
     if gn_stats is not None:
         for t, n, cnt in ((gn_gamma, "gn_gamma", C), (gn_beta, "gn_beta", C)):
             if t is None or not t.is_cuda or t.dtype != torch.float32 or t.numel() != cnt or not t.is_contiguous():
@@ -414,7 +416,8 @@ def conv2d(x: torch.Tensor, w: torch.Tensor, bias=None, variant: int = WINO_AUTO
 
 
 def conv2d_fused(x, w, bias=None, variant: int = WINO_AUTO, layout: int = WINO_NCHW, gn_gamma=None, gn_beta=None,
-                 gn_groups: int = 32, eps: float = 1e-5, addvec=None, residual=None, upsample: bool = False) -> torch.Tensor:
+                 gn_groups: int = 32, eps: float = 1e-5, addvec=None, residual=None, upsample: bool = False,
+                 product_fp16: bool = False) -> torch.Tensor:
     """Statistics (if GroupNorm is asked for), filter transform, workspace, then the fused call."""
     N, C, H, W = _unpack(x, layout)
     if upsample:
@@ -427,4 +430,5 @@ def conv2d_fused(x, w, bias=None, variant: int = WINO_AUTO, layout: int = WINO_N
     stats = wino_groupnorm_stats(x, gn_groups, eps, layout) if gn_gamma is not None else None
     w_t = wino_filter_transform(w, v)
     ws = torch.empty(wino_workspace_bytes(N, C, H, W, K, DTYPE_OF[x.dtype], v), dtype=torch.uint8, device=x.device)
-    return wino_conv2d_fused(x, w_t, bias, y, ws, layout, stats, gn_gamma, gn_beta, gn_groups, addvec, residual, upsample)
+    return wino_conv2d_fused(x, w_t, bias, y, ws, layout, stats, gn_gamma, gn_beta, gn_groups, addvec, residual, upsample,
+                             product_fp16)

@@ -49,9 +49,10 @@ template <> struct FVec<4> { using type = float4; };
 
 // One lane handles TPT consecutive tiles of one output channel (TPT divides T), so each of the
 // alpha^2 reads is a TPT*4-byte vector and a wave reads TPT*256 contiguous bytes per plane.
-template <int M, typename E, int TPT>
+// MT = type the product is stored in (float; __half in the half-product mode, one tile per lane only).
+template <int M, typename E, int TPT, typename MT>
 __global__ void __launch_bounds__(256)
-output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
+output_transform_nchw_kernel(const MT* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
                              int N, int K, int H, int W, int th, int tw, int T, int vec_ok, int nsplit, PostOp post) {
     constexpr int A = M + 2;
     const size_t KT = (size_t)K * T;
@@ -63,22 +64,28 @@ output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restri
     const size_t f = (size_t)k * T + t0;
 
     float v[A * A][TPT];
+    if constexpr (sizeof(MT) == 2) {
+        static_assert(sizeof(MT) == 4 || TPT == 1, "half product: one tile per lane");
 #pragma unroll
-    for (int p = 0; p < A * A; ++p) {
-        const typename FVec<TPT>::type q = *reinterpret_cast<const typename FVec<TPT>::type*>(Mt + (size_t)p * KT + f);
-        const float* qf = reinterpret_cast<const float*>(&q);
-#pragma unroll
-        for (int u = 0; u < TPT; ++u) v[p][u] = qf[u];
-    }
-    // partial products of a reduction cut into nsplit ranges: summed here, in a fixed order
-    for (int sp = 1; sp < nsplit; ++sp) {
-        const float* Ms = Mt + (size_t)sp * (A * A) * KT + f;
+        for (int p = 0; p < A * A; ++p) v[p][0] = to_f32<MT>(Mt[(size_t)p * KT + f]);
+    } else {
 #pragma unroll
         for (int p = 0; p < A * A; ++p) {
-            const typename FVec<TPT>::type q = *reinterpret_cast<const typename FVec<TPT>::type*>(Ms + (size_t)p * KT);
+            const typename FVec<TPT>::type q = *reinterpret_cast<const typename FVec<TPT>::type*>(Mt + (size_t)p * KT + f);
             const float* qf = reinterpret_cast<const float*>(&q);
 #pragma unroll
-            for (int u = 0; u < TPT; ++u) v[p][u] += qf[u];
+            for (int u = 0; u < TPT; ++u) v[p][u] = qf[u];
+        }
+        // partial products of a reduction cut into nsplit ranges: summed here, in a fixed order
+        for (int sp = 1; sp < nsplit; ++sp) {
+            const MT* Ms = Mt + (size_t)sp * (A * A) * KT + f;
+#pragma unroll
+            for (int p = 0; p < A * A; ++p) {
+                const typename FVec<TPT>::type q = *reinterpret_cast<const typename FVec<TPT>::type*>(Ms + (size_t)p * KT);
+                const float* qf = reinterpret_cast<const float*>(&q);
+#pragma unroll
+                for (int u = 0; u < TPT; ++u) v[p][u] += qf[u];
+            }
         }
     }
     const float b = bias ? bias[k] : 0.f;
@@ -124,13 +131,13 @@ output_transform_nchw_kernel(const float* __restrict__ Mt, const float* __restri
     }
 }
 
-template <int M, typename E, int TPT>
-static hipError_t launch_ot_cfg(const float* Mt, const float* bias, void* y, const Geom& g, int nsplit, const PostOp& post, hipStream_t s) {
+template <int M, typename E, int TPT, typename MT = float>
+static hipError_t launch_ot_cfg(const MT* Mt, const float* bias, void* y, const Geom& g, int nsplit, const PostOp& post, hipStream_t s) {
     const size_t items = (size_t)g.K * (g.T / TPT);
     dim3 block(256), grid((unsigned)((items + 255) / 256));
     const int vec_ok = (g.W % M == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0) &&
                        ((reinterpret_cast<uintptr_t>(post.residual) & 15u) == 0);
-    hipLaunchKernelGGL((output_transform_nchw_kernel<M, E, TPT>), grid, block, 0, s,
+    hipLaunchKernelGGL((output_transform_nchw_kernel<M, E, TPT, MT>), grid, block, 0, s,
                        Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, vec_ok, nsplit, post);
     return hipGetLastError();
 }
@@ -150,9 +157,9 @@ static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const G
 // Mt[alpha^2][T][K] (the batched GEMM is symmetric in its operands: called with V and U swapped it
 // leaves the channel index contiguous), so reads and writes both run along k and nothing has to be
 // transposed on the way.  One lane owns KPT adjacent channels of one tile.
-template <int M, typename E, int KPT>
+template <int M, typename E, int KPT, typename MT>
 __global__ void __launch_bounds__(256)
-output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
+output_transform_nhwc_kernel(const MT* __restrict__ Mt, const float* __restrict__ bias, E* __restrict__ y,
                              int N, int K, int H, int W, int th, int tw, int T, int nsplit, PostOp post) {
     constexpr int A = M + 2;
     const int groups = (K + KPT - 1) / KPT;
@@ -164,26 +171,33 @@ output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restri
     const int ti = q0 % th;
     const int n = q0 / th;
     const size_t TK = (size_t)T * K;
-    const float* src = Mt + (size_t)t * K + k;
+    const MT* src = Mt + (size_t)t * K + k;
     float v[KPT][A][A];
 #pragma unroll
     for (int xi = 0; xi < A; ++xi)
 #pragma unroll
         for (int nu = 0; nu < A; ++nu) {
-            const float* p = src + (size_t)(xi * A + nu) * TK;
-            if constexpr (KPT == 2) { const float2 f = *reinterpret_cast<const float2*>(p); v[0][xi][nu] = f.x; v[1][xi][nu] = f.y; }
-            else v[0][xi][nu] = p[0];
-        }
-    for (int sp = 1; sp < nsplit; ++sp) {                      // partial products, summed in a fixed order
-        const float* ss = src + (size_t)sp * (A * A) * TK;
-#pragma unroll
-        for (int xi = 0; xi < A; ++xi)
-#pragma unroll
-            for (int nu = 0; nu < A; ++nu) {
-                const float* p = ss + (size_t)(xi * A + nu) * TK;
-                if constexpr (KPT == 2) { const float2 f = *reinterpret_cast<const float2*>(p); v[0][xi][nu] += f.x; v[1][xi][nu] += f.y; }
-                else v[0][xi][nu] += p[0];
+            const MT* p = src + (size_t)(xi * A + nu) * TK;
+            if constexpr (sizeof(MT) == 2) {
+                if constexpr (KPT == 2) { const float2 f = __half22float2(*reinterpret_cast<const __half2*>(p)); v[0][xi][nu] = f.x; v[1][xi][nu] = f.y; }
+                else v[0][xi][nu] = to_f32<MT>(p[0]);
+            } else {
+                if constexpr (KPT == 2) { const float2 f = *reinterpret_cast<const float2*>(p); v[0][xi][nu] = f.x; v[1][xi][nu] = f.y; }
+                else v[0][xi][nu] = p[0];
             }
+        }
+    if constexpr (sizeof(MT) == 4) {
+        for (int sp = 1; sp < nsplit; ++sp) {                  // partial products, summed in a fixed order
+            const float* ss = src + (size_t)sp * (A * A) * TK;
+#pragma unroll
+            for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+                for (int nu = 0; nu < A; ++nu) {
+                    const float* p = ss + (size_t)(xi * A + nu) * TK;
+                    if constexpr (KPT == 2) { const float2 f = *reinterpret_cast<const float2*>(p); v[0][xi][nu] += f.x; v[1][xi][nu] += f.y; }
+                    else v[0][xi][nu] += p[0];
+                }
+        }
     }
     // residual: loaded up front from clamped (always valid) positions so that the loads overlap;
     // positions outside the image are never stored
@@ -241,21 +255,29 @@ output_transform_nhwc_kernel(const float* __restrict__ Mt, const float* __restri
     }
 }
 
-template <int M, typename E>
-static hipError_t launch_ot_nhwc(const float* Mt, const float* bias, void* y, const Geom& g, int nsplit, const PostOp& post, hipStream_t s) {
+template <int M, typename E, typename MT = float>
+static hipError_t launch_ot_nhwc(const MT* Mt, const float* bias, void* y, const Geom& g, int nsplit, const PostOp& post, hipStream_t s) {
     const bool pair = g.K % 2 == 0;               // rows of Mt, y and the residual then keep channel pairs aligned
     const size_t items = (size_t)g.T * ((g.K + (pair ? 1 : 0)) / (pair ? 2 : 1));
     const size_t blocks = (items + 255) / 256;
     if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
-    if (pair) hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, 2>), dim3((unsigned)blocks), dim3(256), 0, s,
+    if (pair) hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, 2, MT>), dim3((unsigned)blocks), dim3(256), 0, s,
                                  Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, nsplit, post);
-    else      hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, 1>), dim3((unsigned)blocks), dim3(256), 0, s,
+    else      hipLaunchKernelGGL((output_transform_nhwc_kernel<M, E, 1, MT>), dim3((unsigned)blocks), dim3(256), 0, s,
                                  Mt, bias, (E*)y, g.N, g.K, g.H, g.W, g.th, g.tw, g.T, nsplit, post);
     return hipGetLastError();
 }
 
-hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, int nsplit, bool f16, bool nhwc, const PostOp* postp, hipStream_t s) {
+hipError_t launch_output_transform(const void* Mv, const float* bias, void* y, const Geom& g, int nsplit, bool f16, bool nhwc,
+                                   bool half_product, const PostOp* postp, hipStream_t s) {
     const PostOp post = postp ? *postp : PostOp();
+    if (half_product) {
+        if (!f16 || nsplit != 1) return hipErrorInvalidValue;
+        const __half* Mh = static_cast<const __half*>(Mv);
+        if (nhwc) return g.m == 2 ? launch_ot_nhwc<2, __half, __half>(Mh, bias, y, g, 1, post, s) : launch_ot_nhwc<4, __half, __half>(Mh, bias, y, g, 1, post, s);
+        return g.m == 2 ? launch_ot_cfg<2, __half, 1, __half>(Mh, bias, y, g, 1, post, s) : launch_ot_cfg<4, __half, 1, __half>(Mh, bias, y, g, 1, post, s);
+    }
+    const float* M = static_cast<const float*>(Mv);
     if (nhwc) {
         if (g.m == 2) return f16 ? launch_ot_nhwc<2, __half>(M, bias, y, g, nsplit, post, s) : launch_ot_nhwc<2, float>(M, bias, y, g, nsplit, post, s);
         return f16 ? launch_ot_nhwc<4, __half>(M, bias, y, g, nsplit, post, s) : launch_ot_nhwc<4, float>(M, bias, y, g, nsplit, post, s);

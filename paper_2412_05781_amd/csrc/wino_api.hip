@@ -50,7 +50,7 @@ Workspace workspace_layout(const Geom& g, int dtype) {
 }
 
 int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y, const Geom& g,
-              void* workspace, bool nhwc, const PreOp* pre, const PostOp* post, hipStream_t s) {
+              void* workspace, bool nhwc, const PreOp* pre, const PostOp* post, hipStream_t s, bool half_product = false) {
     const bool f16 = w_t->dtype == WINO_F16;
     const Workspace ws = workspace_layout(g, w_t->dtype);
     void* V = workspace;
@@ -59,10 +59,12 @@ int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y,
     // channel-last: operands swapped, so the product comes out as M[alpha^2][T][K], k contiguous
     const int a2 = g.alpha * g.alpha;
     const int nsplit = nhwc ? gemm_split(g.T, g.K, g.Cp, a2, f16) : gemm_split(g.K, g.T, g.Cp, a2, f16);
-    const hipError_t ge = nhwc ? launch_batched_gemm(V, w_t->data, M, g.T, g.Cp, g.K, a2, nsplit, f16, s)
-                               : launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, a2, nsplit, f16, s);
+    // the half-product mode applies to fp16 storage with an unsplit reduction; elsewhere M stays fp32
+    const bool hp = half_product && f16 && nsplit == 1;
+    const hipError_t ge = nhwc ? launch_batched_gemm(V, w_t->data, M, g.T, g.Cp, g.K, a2, nsplit, f16, hp, s)
+                               : launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, a2, nsplit, f16, hp, s);
     if (ge != hipSuccess) return WINO_ERR_HIP;
-    if (launch_output_transform(M, bias, y, g, nsplit, f16, nhwc, post, s) != hipSuccess) return WINO_ERR_HIP;
+    if (launch_output_transform(M, bias, y, g, nsplit, f16, nhwc, hp, post, s) != hipSuccess) return WINO_ERR_HIP;
     return WINO_OK;
 }
 
@@ -233,8 +235,9 @@ int wino_conv2d_fused(const void* x, const wino_filter* w_t, const float* bias, 
     const Workspace ws = workspace_layout(g, w_t->dtype);
     if (!workspace || workspace_bytes < ws.total) return WINO_ERR_WORKSPACE;
     if (!aligned16(workspace)) return WINO_ERR_ALIGN;
+    if (f->product_fp16 != 0 && f->product_fp16 != 1) return WINO_ERR_DIM;
     return run_chain(x, w_t, bias, y, g, workspace, layout == WINO_NHWC, (has_pre || pre.up) ? &pre : nullptr, &post,
-                     static_cast<hipStream_t>(stream));
+                     static_cast<hipStream_t>(stream), f->product_fp16 != 0);
 }
 
 int wino_input_transform(const void* x, void* V, int N, int C, int H, int W,
@@ -260,7 +263,7 @@ int wino_batched_gemm(const void* U, const void* V, float* M, int K, int C, int 
     if (a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)round_up(C, 8) ||
         a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)K) return WINO_ERR_DIM;
     if (!aligned16(U) || !aligned16(V) || !aligned16(M)) return WINO_ERR_ALIGN;
-    return launch_batched_gemm(U, V, M, K, round_up(C, 8), T, (int)a2, 1, dtype == WINO_F16,
+    return launch_batched_gemm(U, V, M, K, round_up(C, 8), T, (int)a2, 1, dtype == WINO_F16, false,
                                static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
@@ -273,7 +276,7 @@ int wino_output_transform(const float* M, const float* bias, void* y, int N, int
     if (!dims_ok(N, 1, H, W, K, variant)) return WINO_ERR_DIM;
     if (!aligned16(M) || !aligned16(y)) return WINO_ERR_ALIGN;
     const Geom g = make_geom(N, 1, H, W, K, variant);
-    return launch_output_transform(M, bias, y, g, 1, dtype == WINO_F16, layout == WINO_NHWC, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_output_transform(M, bias, y, g, 1, dtype == WINO_F16, layout == WINO_NHWC, false, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
 

@@ -22,9 +22,10 @@
 
 namespace wino {
 
-template <typename E, int BM, int BN, int RB, int NST, int WGM, int WGN>
+// MT = type the product is stored in: float, or __half for the opt-in half-product mode.
+template <typename E, typename MT, int BM, int BN, int RB, int NST, int WGM, int WGN>
 __global__ void __launch_bounds__(WGM * WGN * 64)
-wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __restrict__ Mo,
+wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __restrict__ Mo,
                  int K, int Cp, int T, int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd,
                  int nbatch, int nsplit) {
     constexpr int CPR = RB / 16;                          // 16-byte chunks per row per stage
@@ -157,7 +158,7 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
     }
 
     // 32x32 accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
-    float* Mb = Mo + ((size_t)split * nbatch + batch) * K * T;
+    MT* Mb = Mo + ((size_t)split * nbatch + batch) * K * T;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -166,20 +167,20 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, float* __rest
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int k = row_k0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
-                if (k < K && t < T) Mb[(size_t)k * T + t] = acc[i][j][r];
+                if (k < K && t < T) Mb[(size_t)k * T + t] = from_f32<MT>(acc[i][j][r]);
             }
         }
 }
 
-template <typename E, int BM, int BN, int RB, int NST, int WGM = 2, int WGN = 2>
-static hipError_t launch_gemm_cfg(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
+template <typename E, typename MT, int BM, int BN, int RB, int NST, int WGM = 2, int WGN = 2>
+static hipError_t launch_gemm_cfg(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
     const int tiles_m = (K + BM - 1) / BM, tiles_n = (T + BN - 1) / BN;
     const long long total = (long long)tiles_m * tiles_n * nbatch * nsplit;
     if (total > 0x3fffffffLL) return hipErrorInvalidValue;
     const int per_xcd = (int)((total + 7) / 8);
     constexpr int lds_bytes = (BM + BN) * RB * NST;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
-    auto kern = wino_gemm_kernel<E, BM, BN, RB, NST, WGM, WGN>;
+    auto kern = wino_gemm_kernel<E, MT, BM, BN, RB, NST, WGM, WGN>;
     static bool attr_set = false;                 // per instantiation; raising the limit is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
@@ -187,7 +188,7 @@ static hipError_t launch_gemm_cfg(const void* U, const void* V, float* M, int K,
         attr_set = true;
     }
     dim3 block(WGM * WGN * 64), grid((unsigned)(per_xcd * 8));
-    hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, (const E*)U, (const E*)V, M,
+    hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, (const E*)U, (const E*)V, (MT*)M,
                        K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd, nbatch, nsplit);
     return hipGetLastError();
 }
@@ -232,17 +233,17 @@ static int pick_shape(int K, int T, int nbatch, bool f16) {
     return best;
 }
 
-template <typename E>
-static hipError_t launch_gemm_t(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
+template <typename E, typename MT>
+static hipError_t launch_gemm_t(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
     switch (pick_shape(K, T, nbatch, sizeof(E) == 2)) {
-        case 0: return launch_gemm_cfg<E, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 1: return launch_gemm_cfg<E, 128, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 2: return launch_gemm_cfg<E, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 3: return launch_gemm_cfg<E, 64, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 5: return launch_gemm_cfg<E, 128, 32, 128, 3, 4, 1>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 6: return launch_gemm_cfg<E, 32, 128, 128, 3, 1, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 7: return launch_gemm_cfg<E, 128, 128, 128, 3>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        default: return launch_gemm_cfg<E, 256, 256, 128, 2, 4, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 0: return launch_gemm_cfg<E, MT, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 1: return launch_gemm_cfg<E, MT, 128, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 2: return launch_gemm_cfg<E, MT, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 3: return launch_gemm_cfg<E, MT, 64, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 5: return launch_gemm_cfg<E, MT, 128, 32, 128, 3, 4, 1>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 6: return launch_gemm_cfg<E, MT, 32, 128, 128, 3, 1, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 7: return launch_gemm_cfg<E, MT, 128, 128, 128, 3>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        default: return launch_gemm_cfg<E, MT, 256, 256, 128, 2, 4, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s);
     }
 }
 
@@ -278,9 +279,11 @@ int gemm_split(int rows, int cols, int Cp, int nbatch, bool f16) {
     return sp < 1 ? 1 : sp;
 }
 
-hipError_t launch_batched_gemm(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, int nsplit, bool f16, hipStream_t s) {
+hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, bool f16, bool half_product, hipStream_t s) {
     if (nsplit < 1 || nsplit > gemm_max_split(Cp, f16)) return hipErrorInvalidValue;
-    return f16 ? launch_gemm_t<__half>(U, V, M, K, Cp, T, nbatch, nsplit, s) : launch_gemm_t<float>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+    if (half_product && (!f16 || nsplit != 1)) return hipErrorInvalidValue;      // fp16 storage, unsplit reduction only
+    if (half_product) return launch_gemm_t<__half, __half>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+    return f16 ? launch_gemm_t<__half, float>(U, V, M, K, Cp, T, nbatch, nsplit, s) : launch_gemm_t<float, float>(U, V, M, K, Cp, T, nbatch, nsplit, s);
 }
 
 }  // namespace wino

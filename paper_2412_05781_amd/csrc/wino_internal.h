@@ -83,10 +83,12 @@ hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f1
 // nsplit > 1: the reduction is cut into nsplit ranges and M holds nsplit partial products
 // [nsplit][nbatch][K][T], which launch_output_transform sums.  gemm_split() is the policy the
 // whole path uses for a shape (rows = rows of the first operand, cols = rows of the second).
-hipError_t launch_batched_gemm(const void* U, const void* V, float* M, int K, int Cp, int T, int nbatch, int nsplit, bool f16, hipStream_t s);
+// half_product: M is stored as fp16 (fp16 storage and an unsplit reduction only)
+hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, bool f16, bool half_product, hipStream_t s);
 int gemm_max_split(int Cp, bool f16);
 int gemm_split(int rows, int cols, int Cp, int nbatch, bool f16);
-hipError_t launch_output_transform(const float* M, const float* bias, void* y, const Geom& g, int nsplit, bool f16, bool nhwc, const PostOp* post, hipStream_t s);
+hipError_t launch_output_transform(const void* M, const float* bias, void* y, const Geom& g, int nsplit, bool f16, bool nhwc,
+                                   bool half_product, const PostOp* post, hipStream_t s);
 hipError_t launch_groupnorm_stats(const void* x, float* stats, int N, int C, int H, int W, int groups, float eps,
                                   bool f16, bool nhwc, hipStream_t s);
 size_t groupnorm_stats_bytes(int N, int groups);

@@ -149,3 +149,41 @@ def test_upsample_rejects_odd_output_size():
     rc = B.lib().wino_conv2d_fused(x.to(DEV).data_ptr(), ctypes.byref(w_t.desc), None, y.data_ptr(), 1, 8, 7, 8, 8, B.WINO_NCHW,
                                    ctypes.byref(f), ws.data_ptr(), ws.numel(), None)
     assert rc == B.WINO_ERR_DIM
+
+
+# what a correct half-product path must show (tests/test_error_model.py derives these bands on the CPU)
+HALF_PRODUCT_BAND = {B.WINO_F2: (4.0e-4, 1.0e-3), B.WINO_F4: (3.0e-3, 4.8e-3)}
+
+
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+@pytest.mark.parametrize("shape", [(2, 24, 40, 18, 22), (1, 64, 130, 33, 40), (2, 320, 64, 32, 32), (1, 136, 72, 7, 216)])
+def test_half_product_mode(shape, variant, layout):
+    """Opt-in fp16 intermediate product: inside the 5e-3 tolerance, above the plain path's error, inside the band
+    the CPU model predicts (a path that silently kept M in fp32 would sit below it)."""
+    N, C, K, H, W = shape
+    x, w, b = synth.make_inputs(N, C, K, H, W, "f16", seed=9000 + sum(shape))
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    perm = (lambda t: t.permute(0, 2, 3, 1).contiguous()) if layout == B.WINO_NHWC else (lambda t: t)
+    unperm = (lambda t: t.permute(0, 3, 1, 2)) if layout == B.WINO_NHWC else (lambda t: t)
+    y_hp = B.conv2d_fused(perm(x).to(DEV), w.to(DEV), b.to(DEV), variant, layout, product_fp16=True)
+    y_fp = B.conv2d_fused(perm(x).to(DEV), w.to(DEV), b.to(DEV), variant, layout)
+    torch.cuda.synchronize()
+    e_hp = oracle.rel_l2(unperm(y_hp.float().cpu()).numpy(), ref)
+    e_fp = oracle.rel_l2(unperm(y_fp.float().cpu()).numpy(), ref)
+    lo, hi = HALF_PRODUCT_BAND[variant]
+    assert e_hp <= TOL["f16"] and lo <= e_hp <= hi and e_hp > e_fp, (shape, variant, layout, e_hp, e_fp)
+
+
+def test_half_product_mode_is_ignored_for_fp32_and_split_reductions():
+    # fp32 storage: same bits as the plain call
+    x, w, b = synth.make_inputs(1, 24, 16, 12, 12, "f32", seed=3)
+    a = B.conv2d_fused(x.to(DEV), w.to(DEV), b.to(DEV), B.WINO_F4, product_fp16=True)
+    c = B.conv2d(x.to(DEV), w.to(DEV), b.to(DEV), B.WINO_F4)
+    assert torch.equal(a, c)
+    # F(2x2) on an 8x8 image with 1024 channels splits its reduction: M stays fp32 there
+    x, w, b = synth.make_inputs(1, 1024, 256, 8, 8, "f16", seed=4)
+    a = B.conv2d_fused(x.to(DEV), w.to(DEV), b.to(DEV), B.WINO_F2, product_fp16=True)
+    c = B.conv2d(x.to(DEV), w.to(DEV), b.to(DEV), B.WINO_F2)
+    torch.cuda.synchronize()
+    assert torch.equal(a, c)
