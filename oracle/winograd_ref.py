@@ -138,6 +138,15 @@ def conv2d_winograd(x, w, bias, m: int) -> np.ndarray:
     return output_transform(M, bias, N, H, W, m)
 
 
+def round_to_bf16(a) -> np.ndarray:
+    """Round to the nearest bfloat16 (8 exponent bits, 7 stored mantissa bits), ties to even, written on the
+    bit pattern of the fp32 value: add 0x7fff plus the lowest kept bit, drop the low 16 bits.  Returned as fp64.
+    (Finite inputs only; the error model never feeds it anything else.)"""
+    bits = np.asarray(a, dtype=np.float64).astype(np.float32).view(np.uint32).astype(np.uint64)
+    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
 def conv2d_winograd_storage_model(x, w, bias, m: int, store_dtype=np.float16, product_dtype=None) -> np.ndarray:
     """Error model of a low-precision Winograd path (not the definition of the result): the
     same three steps, with U and V rounded once to `store_dtype` as a kernel that keeps them
@@ -148,7 +157,9 @@ def conv2d_winograd_storage_model(x, w, bias, m: int, store_dtype=np.float16, pr
     that stores M in that type between its second and third step would."""
     x = np.asarray(x, dtype=np.float64)
     N, C, H, W = x.shape
-    if np.dtype(store_dtype).itemsize >= 8:
+    if isinstance(store_dtype, str) and store_dtype == "bf16":
+        q = round_to_bf16
+    elif np.dtype(store_dtype).itemsize >= 8:
         q = lambda a: a
     else:                       # the kernels transform in fp32, then round once to the storage type
         q = lambda a: a.astype(np.float32).astype(store_dtype).astype(np.float64)

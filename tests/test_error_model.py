@@ -53,6 +53,37 @@ def test_fp16_product_error_band(m, C):
     assert lo <= err <= hi and err > base and err <= 5e-3, (m, C, err, base)
 
 
+# bfloat16 storage (7 stored mantissa bits): F(2x2) about 4.2e-3, F(4x4) about 2.5e-2, a direct path that
+# rounds only its output about 1.7e-3.  The library's tolerances for that type are set from these: 8e-3, 4e-2, 3e-3.
+BANDS_BF16 = {2: (3.0e-3, 6.0e-3), 4: (1.8e-2, 3.3e-2), "direct": (1.2e-3, 2.2e-3)}
+
+
+def test_round_to_bf16_matches_the_library_conversion():
+    import torch
+    rng = np.random.default_rng(0)
+    a = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-6, 6, 20000),
+                        [1.0, 1.00390625, 1.01171875, 1.0078125, 0.0, -0.0, 3.0e38, -1.0e-38]])   # ties both ways included
+    ref = torch.tensor(a, dtype=torch.float32).to(torch.bfloat16).float().numpy().astype(np.float64)
+    assert np.array_equal(wr.round_to_bf16(a), ref)
+    assert wr.round_to_bf16([1.00390625])[0] == 1.0 and wr.round_to_bf16([1.01171875])[0] == 1.015625   # ties go to even
+
+
+@pytest.mark.parametrize("C", [32, 320])
+@pytest.mark.parametrize("m", [2, 4])
+def test_bf16_storage_error_band(m, C):
+    rng = np.random.default_rng(C + m)
+    N, K, H, W = 1, 16, 16, 16
+    x = wr.round_to_bf16(rng.standard_normal((N, C, H, W)))
+    w = wr.round_to_bf16(rng.standard_normal((K, C, 3, 3)) / np.sqrt(9 * C))
+    b = (0.01 * rng.standard_normal(K)).astype(np.float32).astype(np.float64)
+    ref = oracle.conv2d_direct(x, w, b)
+    err = oracle.rel_l2(wr.conv2d_winograd_storage_model(x, w, b, m, store_dtype="bf16"), ref)
+    lo, hi = BANDS_BF16[m]
+    assert lo <= err <= hi, (m, C, err)
+    d = oracle.rel_l2(wr.round_to_bf16(ref), ref)
+    assert BANDS_BF16["direct"][0] <= d <= BANDS_BF16["direct"][1]
+
+
 def test_model_without_rounding_is_exact():
     rng = np.random.default_rng(1)
     x = rng.standard_normal((1, 8, 9, 10)); w = rng.standard_normal((4, 8, 3, 3)); b = rng.standard_normal(4)
