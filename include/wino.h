@@ -54,8 +54,11 @@ typedef enum wino_status {
     WINO_ERR_LAYOUT = 9      /* layout enum out of range or unsupported here       */
 } wino_status;
 
-/* Storage type of x, w, y and of the transformed tensors U and V. */
-typedef enum wino_dtype { WINO_F32 = 0, WINO_F16 = 1 } wino_dtype;
+/* Storage type of x, w, y and of the transformed tensors U and V.  Accumulation is fp32 for all three.
+ * Relative L2 error against an exact result on unit-variance data, from the rounding of U, V and y alone:
+ *   fp32  <= 1e-5;   fp16  F(2x2) ~5e-4, F(4x4) ~3e-3, direct ~2e-4  (<= 5e-3);
+ *   bf16  F(2x2) ~4e-3 (<= 8e-3), F(4x4) ~2.5e-2 (<= 4e-2; WINO_AUTO never picks it), direct ~1.7e-3 (<= 3e-3). */
+typedef enum wino_dtype { WINO_F32 = 0, WINO_F16 = 1, WINO_BF16 = 2 } wino_dtype;
 
 /*
  * WINO_F2 / WINO_F4: Winograd F(2x2,3x3) / F(4x4,3x3), three kernels (activation

@@ -19,12 +19,12 @@ LIB_PATH = os.path.join(_PKG, "libwino.so")
 WINO_OK = 0
 WINO_ERR_NULL, WINO_ERR_DIM, WINO_ERR_DTYPE, WINO_ERR_VARIANT = 1, 2, 3, 4
 WINO_ERR_ALIGN, WINO_ERR_WORKSPACE, WINO_ERR_ALIAS, WINO_ERR_HIP, WINO_ERR_LAYOUT = 5, 6, 7, 8, 9
-WINO_F32, WINO_F16 = 0, 1
+WINO_F32, WINO_F16, WINO_BF16 = 0, 1, 2
 WINO_AUTO, WINO_DIRECT, WINO_F2, WINO_F4 = 0, 1, 2, 4
 WINO_NCHW, WINO_NHWC = 0, 1
 
-DTYPE_OF = {torch.float32: WINO_F32, torch.float16: WINO_F16}
-TORCH_OF = {WINO_F32: torch.float32, WINO_F16: torch.float16}
+DTYPE_OF = {torch.float32: WINO_F32, torch.float16: WINO_F16, torch.bfloat16: WINO_BF16}
+TORCH_OF = {WINO_F32: torch.float32, WINO_F16: torch.float16, WINO_BF16: torch.bfloat16}
 
 EXPORTS = [
     "wino_version", "wino_status_string", "wino_resolve_variant", "wino_transformed_dims",

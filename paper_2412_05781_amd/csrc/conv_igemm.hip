@@ -379,7 +379,8 @@ static int igemm_shape(int T, int K) {
 // Few blocks and a long reduction (deep down-sampling layers: 8x8 outputs, 9 x 1280 channels): cut the
 // reduction so that about two workgroups per compute unit are in flight, at least eight stages each
 // (the second kernel costs ~3 us, more than a short reduction gains).
-int igemm_split(int T, int K, int Cp, int R, bool f16) {
+int igemm_split(int T, int K, int Cp, int R, int dt) {
+    const bool f16 = two_byte(dt);
     static const int forced = [] { const char* e = getenv("WINO_IGEMM_SPLIT"); return e ? atoi(e) : 0; }();       // tuning knob
     const int bke = f16 ? 64 : 32;
     const int nstage = R * R * ((Cp + bke - 1) / bke);
@@ -403,21 +404,23 @@ static hipError_t launch_igemm_t(const E* xh, const E* Wr, const float* bias, E*
     return launch_igemm_cfg<E, 64, 64, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, s);
 }
 
-hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, bool f16, hipStream_t s) {
+hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, int dt, hipStream_t s) {
     const int Cp = (C + 7) / 8 * 8, taps = R * R;
     const size_t total = (size_t)taps * K * Cp + Cp;
     const size_t blocks = (total + 255) / 256;
     if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
-    if (f16) hipLaunchKernelGGL(igemm_filter_repack_kernel<__half>, dim3((unsigned)blocks), dim3(256), 0, s, (const __half*)w, (__half*)Wr, K, C, Cp, taps);
-    else     hipLaunchKernelGGL(igemm_filter_repack_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)w, (float*)Wr, K, C, Cp, taps);
-    return hipGetLastError();
+    return with_dtype(dt, [&](auto* tag) {
+        using E = std::remove_pointer_t<decltype(tag)>;
+        hipLaunchKernelGGL(igemm_filter_repack_kernel<E>, dim3((unsigned)blocks), dim3(256), 0, s, (const E*)w, (E*)Wr, K, C, Cp, taps);
+        return hipGetLastError();
+    });
 }
 
 template <typename E>
 static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias, void* y, const ConvGeom& g, bool nhwc,
                                void* workspace, size_t xh_bytes, hipStream_t s) {
     const E* xh = static_cast<const E*>(x);
-    const int nsplit = igemm_split(g.T, g.K, g.Cp, g.R, sizeof(E) == 2);
+    const int nsplit = igemm_split(g.T, g.K, g.Cp, g.R, sizeof(E) == 2 ? DT_F16 : DT_F32);
     float* part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + xh_bytes);   // only used when nsplit > 1
     if (!nhwc) {
         constexpr int EPC = 16 / (int)sizeof(E);
@@ -447,14 +450,16 @@ static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias,
 }
 
 hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias, void* y,
-                               int N, int C, int H, int W, int K, int R, int st, bool f16, bool nhwc,
+                               int N, int C, int H, int W, int K, int R, int st, int dt, bool nhwc,
                                void* workspace, size_t xh_bytes, hipStream_t s) {
     ConvGeom g;
     g.N = N; g.C = C; g.Cp = (C + 7) / 8 * 8; g.H = H; g.W = W; g.K = K; g.R = R; g.st = st; g.pad = (R - 1) / 2;
     g.Ho = (H + 2 * g.pad - R) / st + 1; g.Wo = (W + 2 * g.pad - R) / st + 1;
     g.T = N * g.Ho * g.Wo;
-    return f16 ? igemm_conv_t<__half>(x, Wr, bias, y, g, nhwc, workspace, xh_bytes, s)
-               : igemm_conv_t<float>(x, Wr, bias, y, g, nhwc, workspace, xh_bytes, s);
+    return with_dtype(dt, [&](auto* tag) {
+        using E = std::remove_pointer_t<decltype(tag)>;
+        return igemm_conv_t<E>(x, Wr, bias, y, g, nhwc, workspace, xh_bytes, s);
+    });
 }
 
 }  // namespace wino

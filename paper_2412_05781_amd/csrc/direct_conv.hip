@@ -39,14 +39,16 @@ direct_conv2d_kernel(const E* __restrict__ x, const E* __restrict__ w, const flo
 }
 
 hipError_t launch_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
-                                int N, int C, int H, int W, int K, bool f16, hipStream_t s) {
+                                int N, int C, int H, int W, int K, int dt, hipStream_t s) {
     const size_t total = (size_t)N * K * H * W;
     size_t blocks = (total + 255) / 256;
     if (blocks > (size_t)1 << 20) blocks = (size_t)1 << 20;   // grid-stride beyond that
     dim3 block(256), grid((unsigned)blocks);
-    if (f16) hipLaunchKernelGGL((direct_conv2d_kernel<__half>), grid, block, 0, s, (const __half*)x, (const __half*)w, bias, (__half*)y, N, C, H, W, K);
-    else     hipLaunchKernelGGL((direct_conv2d_kernel<float>), grid, block, 0, s, (const float*)x, (const float*)w, bias, (float*)y, N, C, H, W, K);
-    return hipGetLastError();
+    return with_dtype(dt, [&](auto* tag) {
+        using E = std::remove_pointer_t<decltype(tag)>;
+        hipLaunchKernelGGL((direct_conv2d_kernel<E>), grid, block, 0, s, (const E*)x, (const E*)w, bias, (E*)y, N, C, H, W, K);
+        return hipGetLastError();
+    });
 }
 
 }  // namespace wino

@@ -48,16 +48,14 @@ filter_transform_kernel(const E* __restrict__ w, E* __restrict__ U, int K, int C
     }
 }
 
-hipError_t launch_filter_transform(const void* w, void* U, int K, int C, int Cp, int m, bool f16, hipStream_t s) {
+hipError_t launch_filter_transform(const void* w, void* U, int K, int C, int Cp, int m, int dt, hipStream_t s) {
     dim3 block(256), grid((Cp + 255) / 256, K);
-    if (m == 2) {
-        if (f16) hipLaunchKernelGGL((filter_transform_kernel<2, __half>), grid, block, 0, s, (const __half*)w, (__half*)U, K, C, Cp);
-        else     hipLaunchKernelGGL((filter_transform_kernel<2, float>), grid, block, 0, s, (const float*)w, (float*)U, K, C, Cp);
-    } else {
-        if (f16) hipLaunchKernelGGL((filter_transform_kernel<4, __half>), grid, block, 0, s, (const __half*)w, (__half*)U, K, C, Cp);
-        else     hipLaunchKernelGGL((filter_transform_kernel<4, float>), grid, block, 0, s, (const float*)w, (float*)U, K, C, Cp);
-    }
-    return hipGetLastError();
+    return with_dtype(dt, [&](auto* tag) {
+        using E = std::remove_pointer_t<decltype(tag)>;
+        if (m == 2) hipLaunchKernelGGL((filter_transform_kernel<2, E>), grid, block, 0, s, (const E*)w, (E*)U, K, C, Cp);
+        else        hipLaunchKernelGGL((filter_transform_kernel<4, E>), grid, block, 0, s, (const E*)w, (E*)U, K, C, Cp);
+        return hipGetLastError();
+    });
 }
 
 }  // namespace wino

@@ -79,10 +79,10 @@ __global__ void groupnorm_finalize_kernel(const double* __restrict__ partial, fl
 }
 
 hipError_t launch_groupnorm_stats(const void* x, float* stats, int N, int C, int H, int W, int groups, float eps,
-                                  bool f16, bool nhwc, hipStream_t s) {
+                                  int dt, bool nhwc, hipStream_t s) {
     const int cpg = C / groups, HW = H * W, total = N * groups;
     const size_t elems = (size_t)cpg * HW;
-    const size_t esz = f16 ? 2 : 4, epc = 16 / esz;
+    const size_t esz = two_byte(dt) ? 2 : 4, epc = 16 / esz;
     // slices are whole numbers of block-wide 16-byte loads (256 lanes x 16 bytes)
     const size_t quantum = 256 * epc;
     int split = (int)((elems + 2 * quantum - 1) / (2 * quantum));
@@ -93,16 +93,13 @@ hipError_t launch_groupnorm_stats(const void* x, float* stats, int N, int C, int
                                                 (((size_t)total * 2 * sizeof(float) + 255) / 256) * 256);
     dim3 grid((unsigned)total, (unsigned)split), block(256);
     const bool vec = !nhwc && (elems * esz) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
-    if (vec) {
-        if (f16) hipLaunchKernelGGL((groupnorm_partial_vec_kernel<__half>), grid, block, 0, s, (const __half*)x, partial, elems, split, per_slice);
-        else     hipLaunchKernelGGL((groupnorm_partial_vec_kernel<float>), grid, block, 0, s, (const float*)x, partial, elems, split, per_slice);
-    } else if (f16) {
-        if (nhwc) hipLaunchKernelGGL((groupnorm_partial_kernel<__half, true>), grid, block, 0, s, (const __half*)x, partial, C, HW, groups, cpg, split, per_slice);
-        else      hipLaunchKernelGGL((groupnorm_partial_kernel<__half, false>), grid, block, 0, s, (const __half*)x, partial, C, HW, groups, cpg, split, per_slice);
-    } else {
-        if (nhwc) hipLaunchKernelGGL((groupnorm_partial_kernel<float, true>), grid, block, 0, s, (const float*)x, partial, C, HW, groups, cpg, split, per_slice);
-        else      hipLaunchKernelGGL((groupnorm_partial_kernel<float, false>), grid, block, 0, s, (const float*)x, partial, C, HW, groups, cpg, split, per_slice);
-    }
+    with_dtype(dt, [&](auto* tag) {
+        using E = std::remove_pointer_t<decltype(tag)>;
+        if (vec)       hipLaunchKernelGGL((groupnorm_partial_vec_kernel<E>), grid, block, 0, s, (const E*)x, partial, elems, split, per_slice);
+        else if (nhwc) hipLaunchKernelGGL((groupnorm_partial_kernel<E, true>), grid, block, 0, s, (const E*)x, partial, C, HW, groups, cpg, split, per_slice);
+        else           hipLaunchKernelGGL((groupnorm_partial_kernel<E, false>), grid, block, 0, s, (const E*)x, partial, C, HW, groups, cpg, split, per_slice);
+        return hipSuccess;
+    });
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(groupnorm_finalize_kernel, dim3((unsigned)((total + 63) / 64)), dim3(64), 0, s,

@@ -534,13 +534,12 @@ static hipError_t launch_it(const void* x, void* V, const Geom& g, const PreOp* 
     }
 }
 
-hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, bool nhwc, const PreOp* pre, hipStream_t s) {
-    if (nhwc) {
-        if (g.m == 2) return f16 ? launch_it_nhwc<2, __half>(x, V, g, pre, s) : launch_it_nhwc<2, float>(x, V, g, pre, s);
-        return f16 ? launch_it_nhwc<4, __half>(x, V, g, pre, s) : launch_it_nhwc<4, float>(x, V, g, pre, s);
-    }
-    if (g.m == 2) return f16 ? launch_it<2, __half>(x, V, g, pre, s) : launch_it<2, float>(x, V, g, pre, s);
-    return f16 ? launch_it<4, __half>(x, V, g, pre, s) : launch_it<4, float>(x, V, g, pre, s);
+hipError_t launch_input_transform(const void* x, void* V, const Geom& g, int dt, bool nhwc, const PreOp* pre, hipStream_t s) {
+    return with_dtype(dt, [&](auto* tag) {
+        using E = std::remove_pointer_t<decltype(tag)>;
+        if (nhwc) return g.m == 2 ? launch_it_nhwc<2, E>(x, V, g, pre, s) : launch_it_nhwc<4, E>(x, V, g, pre, s);
+        return g.m == 2 ? launch_it<2, E>(x, V, g, pre, s) : launch_it<4, E>(x, V, g, pre, s);
+    });
 }
 
 }  // namespace wino

@@ -13,8 +13,17 @@ namespace wino {
 template <typename E, int M> struct RowVec;
 template <> struct RowVec<float, 2> { using type = float2; };
 template <> struct RowVec<float, 4> { using type = float4; };
-template <> struct RowVec<__half, 2> { using type = __half2; };
-template <> struct RowVec<__half, 4> { struct alignas(8) type { __half2 lo, hi; }; };
+template <> struct RowVec<__half, 2> { using type = uint32_t; };
+template <> struct RowVec<__half, 4> { using type = uint2; };
+template <> struct RowVec<bf16_t, 2> { using type = uint32_t; };
+template <> struct RowVec<bf16_t, 4> { using type = uint2; };
+// two 16-bit elements in one word, first element in the low half
+template <typename E> __device__ __forceinline__ uint32_t pack2(float a, float b) {
+    const E ea = from_f32<E>(a), eb = from_f32<E>(b);
+    return (uint32_t)*reinterpret_cast<const uint16_t*>(&ea) | ((uint32_t)*reinterpret_cast<const uint16_t*>(&eb) << 16);
+}
+template <typename E> __device__ __forceinline__ float unpack_lo(uint32_t w) { const uint16_t h = (uint16_t)(w & 0xffffu); return to_f32<E>(*reinterpret_cast<const E*>(&h)); }
+template <typename E> __device__ __forceinline__ float unpack_hi(uint32_t w) { const uint16_t h = (uint16_t)(w >> 16); return to_f32<E>(*reinterpret_cast<const E*>(&h)); }
 
 template <typename E, int M>
 __device__ __forceinline__ void store_row(E* p, const float* v) {
@@ -23,8 +32,8 @@ __device__ __forceinline__ void store_row(E* p, const float* v) {
         if constexpr (M == 2) { r.x = v[0]; r.y = v[1]; }
         else { r.x = v[0]; r.y = v[1]; r.z = v[2]; r.w = v[3]; }
     } else {
-        if constexpr (M == 2) { r = __floats2half2_rn(v[0], v[1]); }
-        else { r.lo = __floats2half2_rn(v[0], v[1]); r.hi = __floats2half2_rn(v[2], v[3]); }
+        if constexpr (M == 2) { r = pack2<E>(v[0], v[1]); }
+        else { r.x = pack2<E>(v[0], v[1]); r.y = pack2<E>(v[2], v[3]); }
     }
     *reinterpret_cast<typename RowVec<E, M>::type*>(p) = r;
 }
@@ -37,8 +46,8 @@ __device__ __forceinline__ void add_row(const E* p, float* v) {
         if constexpr (M == 2) { v[0] += r.x; v[1] += r.y; }
         else { v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w; }
     } else {
-        if constexpr (M == 2) { const float2 f = __half22float2(r); v[0] += f.x; v[1] += f.y; }
-        else { const float2 f = __half22float2(r.lo), g = __half22float2(r.hi); v[0] += f.x; v[1] += f.y; v[2] += g.x; v[3] += g.y; }
+        if constexpr (M == 2) { v[0] += unpack_lo<E>(r); v[1] += unpack_hi<E>(r); }
+        else { v[0] += unpack_lo<E>(r.x); v[1] += unpack_hi<E>(r.x); v[2] += unpack_lo<E>(r.y); v[3] += unpack_hi<E>(r.y); }
     }
 }
 
@@ -268,22 +277,21 @@ static hipError_t launch_ot_nhwc(const MT* Mt, const float* bias, void* y, const
     return hipGetLastError();
 }
 
-hipError_t launch_output_transform(const void* Mv, const float* bias, void* y, const Geom& g, int nsplit, bool f16, bool nhwc,
+hipError_t launch_output_transform(const void* Mv, const float* bias, void* y, const Geom& g, int nsplit, int dt, bool nhwc,
                                    bool half_product, const PostOp* postp, hipStream_t s) {
     const PostOp post = postp ? *postp : PostOp();
     if (half_product) {
-        if (!f16 || nsplit != 1) return hipErrorInvalidValue;
+        if (dt != DT_F16 || nsplit != 1) return hipErrorInvalidValue;
         const __half* Mh = static_cast<const __half*>(Mv);
         if (nhwc) return g.m == 2 ? launch_ot_nhwc<2, __half, __half>(Mh, bias, y, g, 1, post, s) : launch_ot_nhwc<4, __half, __half>(Mh, bias, y, g, 1, post, s);
         return g.m == 2 ? launch_ot_cfg<2, __half, 1, __half>(Mh, bias, y, g, 1, post, s) : launch_ot_cfg<4, __half, 1, __half>(Mh, bias, y, g, 1, post, s);
     }
     const float* M = static_cast<const float*>(Mv);
-    if (nhwc) {
-        if (g.m == 2) return f16 ? launch_ot_nhwc<2, __half>(M, bias, y, g, nsplit, post, s) : launch_ot_nhwc<2, float>(M, bias, y, g, nsplit, post, s);
-        return f16 ? launch_ot_nhwc<4, __half>(M, bias, y, g, nsplit, post, s) : launch_ot_nhwc<4, float>(M, bias, y, g, nsplit, post, s);
-    }
-    if (g.m == 2) return f16 ? launch_ot<2, __half>(M, bias, y, g, nsplit, post, s) : launch_ot<2, float>(M, bias, y, g, nsplit, post, s);
-    return f16 ? launch_ot<4, __half>(M, bias, y, g, nsplit, post, s) : launch_ot<4, float>(M, bias, y, g, nsplit, post, s);
+    return with_dtype(dt, [&](auto* tag) {
+        using E = std::remove_pointer_t<decltype(tag)>;
+        if (nhwc) return g.m == 2 ? launch_ot_nhwc<2, E>(M, bias, y, g, nsplit, post, s) : launch_ot_nhwc<4, E>(M, bias, y, g, nsplit, post, s);
+        return g.m == 2 ? launch_ot<2, E>(M, bias, y, g, nsplit, post, s) : launch_ot<4, E>(M, bias, y, g, nsplit, post, s);
+    });
 }
 
 }  // namespace wino

@@ -13,8 +13,8 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline bool dtype_ok(int d) { return d == WINO_F32 || d == WINO_F16; }
-inline size_t esize(int d) { return d == WINO_F16 ? 2 : 4; }
+inline bool dtype_ok(int d) { return d == WINO_F32 || d == WINO_F16 || d == WINO_BF16; }
+inline size_t esize(int d) { return d == WINO_F32 ? 4 : 2; }
 inline bool wino_variant_ok(int v) { return v == WINO_F2 || v == WINO_F4; }
 
 // products that must fit: element counts as size_t and tile counts as int
@@ -43,7 +43,7 @@ Workspace workspace_layout(const Geom& g, int dtype) {
     ws.v_bytes = align_up(a2 * (size_t)g.T * g.Cp * esize(dtype));
     // the product, times the number of partial copies the GEMM stage writes for this shape (the
     // policy depends on the operand order only through the block shape; take the larger of the two)
-    const int sp_a = gemm_split(g.K, g.T, g.Cp, (int)a2, dtype == WINO_F16), sp_b = gemm_split(g.T, g.K, g.Cp, (int)a2, dtype == WINO_F16);
+    const int sp_a = gemm_split(g.K, g.T, g.Cp, (int)a2, dtype), sp_b = gemm_split(g.T, g.K, g.Cp, (int)a2, dtype);
     ws.m_bytes = align_up(a2 * (size_t)g.K * g.T * sizeof(float) * (size_t)(sp_a > sp_b ? sp_a : sp_b));
     ws.total = ws.v_bytes + ws.m_bytes;
     return ws;
@@ -51,20 +51,20 @@ Workspace workspace_layout(const Geom& g, int dtype) {
 
 int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y, const Geom& g,
               void* workspace, bool nhwc, const PreOp* pre, const PostOp* post, hipStream_t s, bool half_product = false) {
-    const bool f16 = w_t->dtype == WINO_F16;
+    const int dt = w_t->dtype;
     const Workspace ws = workspace_layout(g, w_t->dtype);
     void* V = workspace;
     float* M = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + ws.v_bytes);
-    if (launch_input_transform(x, V, g, f16, nhwc, pre, s) != hipSuccess) return WINO_ERR_HIP;
+    if (launch_input_transform(x, V, g, dt, nhwc, pre, s) != hipSuccess) return WINO_ERR_HIP;
     // channel-last: operands swapped, so the product comes out as M[alpha^2][T][K], k contiguous
     const int a2 = g.alpha * g.alpha;
-    const int nsplit = nhwc ? gemm_split(g.T, g.K, g.Cp, a2, f16) : gemm_split(g.K, g.T, g.Cp, a2, f16);
+    const int nsplit = nhwc ? gemm_split(g.T, g.K, g.Cp, a2, dt) : gemm_split(g.K, g.T, g.Cp, a2, dt);
     // the half-product mode applies to fp16 storage with an unsplit reduction; elsewhere M stays fp32
-    const bool hp = half_product && f16 && nsplit == 1;
-    const hipError_t ge = nhwc ? launch_batched_gemm(V, w_t->data, M, g.T, g.Cp, g.K, a2, nsplit, f16, hp, s)
-                               : launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, a2, nsplit, f16, hp, s);
+    const bool hp = half_product && dt == WINO_F16 && nsplit == 1;
+    const hipError_t ge = nhwc ? launch_batched_gemm(V, w_t->data, M, g.T, g.Cp, g.K, a2, nsplit, dt, hp, s)
+                               : launch_batched_gemm(w_t->data, V, M, g.K, g.Cp, g.T, a2, nsplit, dt, hp, s);
     if (ge != hipSuccess) return WINO_ERR_HIP;
-    if (launch_output_transform(M, bias, y, g, nsplit, f16, nhwc, hp, post, s) != hipSuccess) return WINO_ERR_HIP;
+    if (launch_output_transform(M, bias, y, g, nsplit, dt, nhwc, hp, post, s) != hipSuccess) return WINO_ERR_HIP;
     return WINO_OK;
 }
 
@@ -120,6 +120,8 @@ int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int varia
     int pick = g4.T >= 64 ? WINO_F4 : WINO_F2;
     // fp32 storage promises 1e-5: F(4x4) rounding grows with the reduction length, keep a margin
     if (dtype == WINO_F32 && C > 640) pick = WINO_F2;
+    // bfloat16 has 8 significant bits: F(4x4) would sit near 2.5e-2, F(2x2) near 4e-3
+    if (dtype == WINO_BF16) pick = WINO_F2;
     return pick;
 }
 
@@ -151,7 +153,7 @@ int wino_filter_transform(const void* w, void* w_t_data, int K, int C, int dtype
     if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
     if (!dims_ok(1, C, 1, 1, K, variant) || K > 65535) return WINO_ERR_DIM;   // grid.y carries k
     if (!aligned16(w) || !aligned16(w_t_data)) return WINO_ERR_ALIGN;
-    if (launch_filter_transform(w, w_t_data, K, C, round_up(C, 8), variant, dtype == WINO_F16,
+    if (launch_filter_transform(w, w_t_data, K, C, round_up(C, 8), variant, dtype,
                                 static_cast<hipStream_t>(stream)) != hipSuccess)
         return WINO_ERR_HIP;
     out->data = w_t_data; out->K = K; out->C = C; out->dtype = dtype; out->variant = variant;
@@ -198,7 +200,7 @@ int wino_groupnorm_stats(const void* x, float* stats, int N, int C, int H, int W
     if (!dims_ok(N, C, H, W, 1, 2) || groups < 1 || C % groups != 0 || (long long)N * groups > (1LL << 24) ||
         (long long)H * W > INT_MAX || !(eps >= 0.f)) return WINO_ERR_DIM;
     if (!aligned16(x) || !aligned16(stats)) return WINO_ERR_ALIGN;
-    return launch_groupnorm_stats(x, stats, N, C, H, W, groups, eps, dtype == WINO_F16, layout == WINO_NHWC,
+    return launch_groupnorm_stats(x, stats, N, C, H, W, groups, eps, dtype, layout == WINO_NHWC,
                                   static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
@@ -249,7 +251,7 @@ int wino_input_transform(const void* x, void* V, int N, int C, int H, int W,
     if (!dims_ok(N, C, H, W, 1, variant)) return WINO_ERR_DIM;
     if (!aligned16(x) || !aligned16(V)) return WINO_ERR_ALIGN;
     const Geom g = make_geom(N, C, H, W, 1, variant);
-    return launch_input_transform(x, V, g, dtype == WINO_F16, layout == WINO_NHWC, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_input_transform(x, V, g, dtype, layout == WINO_NHWC, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
 
@@ -263,7 +265,7 @@ int wino_batched_gemm(const void* U, const void* V, float* M, int K, int C, int 
     if (a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)round_up(C, 8) ||
         a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)K) return WINO_ERR_DIM;
     if (!aligned16(U) || !aligned16(V) || !aligned16(M)) return WINO_ERR_ALIGN;
-    return launch_batched_gemm(U, V, M, K, round_up(C, 8), T, (int)a2, 1, dtype == WINO_F16, false,
+    return launch_batched_gemm(U, V, M, K, round_up(C, 8), T, (int)a2, 1, dtype, false,
                                static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
@@ -276,7 +278,7 @@ int wino_output_transform(const float* M, const float* bias, void* y, int N, int
     if (!dims_ok(N, 1, H, W, K, variant)) return WINO_ERR_DIM;
     if (!aligned16(M) || !aligned16(y)) return WINO_ERR_ALIGN;
     const Geom g = make_geom(N, 1, H, W, K, variant);
-    return launch_output_transform(M, bias, y, g, 1, dtype == WINO_F16, layout == WINO_NHWC, false, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_output_transform(M, bias, y, g, 1, dtype, layout == WINO_NHWC, false, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
 
@@ -290,7 +292,7 @@ int wino_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
     const uintptr_t xb = reinterpret_cast<uintptr_t>(x), xe = xb + (size_t)N * C * H * W * es;
     const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + (size_t)N * K * H * W * es;
     if (xb < ye && yb < xe) return WINO_ERR_ALIAS;
-    return launch_direct_conv2d(x, w, bias, y, N, C, H, W, K, dtype == WINO_F16,
+    return launch_direct_conv2d(x, w, bias, y, N, C, H, W, K, dtype,
                                 static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
@@ -320,7 +322,7 @@ int wino_igemm_filter_repack(const void* w, void* w_r, int K, int C, int R, int 
     if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
     if (!igemm_dims_ok(1, C, 1, 1, K, R, 1)) return WINO_ERR_DIM;
     if (!aligned16(w) || !aligned16(w_r)) return WINO_ERR_ALIGN;
-    return launch_igemm_filter_repack(w, w_r, K, C, R, dtype == WINO_F16, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_igemm_filter_repack(w, w_r, K, C, R, dtype, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
 
@@ -333,7 +335,7 @@ size_t igemm_xh_bytes(int N, int C, int H, int W, int dtype, int layout) {
 size_t igemm_part_bytes(int N, int C, int H, int W, int K, int R, int stride, int dtype) {
     const int pad = (R - 1) / 2;
     const long long T = (long long)N * ((H + 2 * pad - R) / stride + 1) * ((W + 2 * pad - R) / stride + 1);
-    const int sp = igemm_split((int)T, K, round_up(C, 8), R, dtype == WINO_F16);
+    const int sp = igemm_split((int)T, K, round_up(C, 8), R, dtype);
     return sp > 1 ? align_up((size_t)sp * (size_t)K * (size_t)T * sizeof(float)) : 0;
 }
 }  // namespace
@@ -362,7 +364,7 @@ int wino_igemm_conv2d(const void* x, const void* w_r, const float* bias, void* y
     const size_t need = wino_igemm_workspace_bytes(N, C, H, W, K, R, stride, dtype, layout);
     if (need && (!workspace || workspace_bytes < need)) return WINO_ERR_WORKSPACE;
     if (need && !aligned16(workspace)) return WINO_ERR_ALIGN;
-    return launch_igemm_conv2d(x, w_r, bias, y, N, C, H, W, K, R, stride, dtype == WINO_F16, layout == WINO_NHWC,
+    return launch_igemm_conv2d(x, w_r, bias, y, N, C, H, W, K, R, stride, dtype, layout == WINO_NHWC,
                                workspace, igemm_xh_bytes(N, C, H, W, dtype, layout), static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }

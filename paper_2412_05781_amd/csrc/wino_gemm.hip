@@ -248,8 +248,8 @@ static hipError_t launch_gemm_t(const void* U, const void* V, void* M, int K, in
 }
 
 // Stages are 128 bytes of reduction per row in every block shape.
-int gemm_max_split(int Cp, bool f16) {
-    const int bke = f16 ? 64 : 32;
+int gemm_max_split(int Cp, int dt) {
+    const int bke = two_byte(dt) ? 64 : 32;
     const int stages = (Cp + bke - 1) / bke;
     return stages < 1 ? 1 : stages;
 }
@@ -258,13 +258,14 @@ int gemm_max_split(int Cp, bool f16) {
 // stage is a stream of U that one workgroup per compute unit, each waiting on its own loads, cannot
 // keep busy.  Cutting the reduction multiplies the workgroups in flight; the price is nsplit
 // copies of the (small) product.
-int gemm_split(int rows, int cols, int Cp, int nbatch, bool f16) {
+int gemm_split(int rows, int cols, int Cp, int nbatch, int dt) {
+    const bool f16 = two_byte(dt);
     static const int forced = [] { const char* e = getenv("WINO_GEMM_SPLIT"); return e ? atoi(e) : 0; }();   // tuning knob
     const int shape = pick_shape(rows, cols, nbatch, f16);
     const int bm = shape == 4 ? 256 : (shape == 6 ? 32 : ((shape == 2 || shape == 3) ? 64 : 128));
     const int bn = shape == 4 ? 256 : (shape == 5 ? 32 : ((shape == 1 || shape == 3) ? 64 : 128));
     const long long blocks = (long long)((rows + bm - 1) / bm) * ((cols + bn - 1) / bn) * nbatch;
-    const int max_split = gemm_max_split(Cp, f16);
+    const int max_split = gemm_max_split(Cp, dt);
     int sp = 1;
     if (forced > 0) sp = forced;
     else if (nbatch <= 16 && (bm < 128 || bn < 128) && blocks <= 320) {
@@ -279,11 +280,14 @@ int gemm_split(int rows, int cols, int Cp, int nbatch, bool f16) {
     return sp < 1 ? 1 : sp;
 }
 
-hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, bool f16, bool half_product, hipStream_t s) {
-    if (nsplit < 1 || nsplit > gemm_max_split(Cp, f16)) return hipErrorInvalidValue;
-    if (half_product && (!f16 || nsplit != 1)) return hipErrorInvalidValue;      // fp16 storage, unsplit reduction only
+hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int dt, bool half_product, hipStream_t s) {
+    if (nsplit < 1 || nsplit > gemm_max_split(Cp, dt)) return hipErrorInvalidValue;
+    if (half_product && (dt != DT_F16 || nsplit != 1)) return hipErrorInvalidValue;      // fp16 storage, unsplit reduction only
     if (half_product) return launch_gemm_t<__half, __half>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-    return f16 ? launch_gemm_t<__half, float>(U, V, M, K, Cp, T, nbatch, nsplit, s) : launch_gemm_t<float, float>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+    return with_dtype(dt, [&](auto* tag) {
+        using E = std::remove_pointer_t<decltype(tag)>;
+        return launch_gemm_t<E, float>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+    });
 }
 
 }  // namespace wino

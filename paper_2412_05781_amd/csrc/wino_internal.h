@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+#include <hip/hip_bf16.h>
+#include <type_traits>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -29,13 +31,26 @@ inline Geom make_geom(int N, int C, int H, int W, int K, int m) {
     return g;
 }
 
+// Storage types (values of wino_dtype).  `with_dtype` calls f with a null pointer of the element
+// type, so that a generic lambda can name it:  using E = std::remove_pointer_t<decltype(tag)>.
+typedef __hip_bfloat16 bf16_t;
+enum { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
+inline bool two_byte(int dt) { return dt != DT_F32; }
+template <typename F> inline hipError_t with_dtype(int dt, F&& f) {
+    if (dt == DT_F16) return f(static_cast<__half*>(nullptr));
+    if (dt == DT_BF16) return f(static_cast<bf16_t*>(nullptr));
+    return f(static_cast<float*>(nullptr));
+}
+
 // element conversion helpers usable in kernels
 template <typename E> __device__ __forceinline__ float to_f32(E v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f32<__half>(__half v) { return __half2float(v); }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return __bfloat162float(v); }
 template <typename E> __device__ __forceinline__ E from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ __half from_f32<__half>(float v) { return __float2half_rn(v); }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return __float2bfloat16(v); }   // round to nearest even
 
 // Optional operators fused around the convolution.  PreOp: x' = SiLU(GroupNorm(x)) applied as the
 // activation transform loads x (stats = (mean, rstd) per (n, group)); PostOp: y += addvec[n][k] +
@@ -51,10 +66,12 @@ struct PreOp {
 // 16 bytes of an upsampled row from the 8 source bytes under them: every element twice
 template <typename E> __device__ __forceinline__ uint4 dup_elements(uint2 s);
 template <> __device__ __forceinline__ uint4 dup_elements<float>(uint2 s) { return make_uint4(s.x, s.x, s.y, s.y); }
-template <> __device__ __forceinline__ uint4 dup_elements<__half>(uint2 s) {
+__device__ __forceinline__ uint4 dup_elements_16bit(uint2 s) {
     const uint32_t a = s.x & 0xffffu, b = s.x >> 16, c = s.y & 0xffffu, d = s.y >> 16;
     return make_uint4(a | (a << 16), b | (b << 16), c | (c << 16), d | (d << 16));
 }
+template <> __device__ __forceinline__ uint4 dup_elements<__half>(uint2 s) { return dup_elements_16bit(s); }
+template <> __device__ __forceinline__ uint4 dup_elements<bf16_t>(uint2 s) { return dup_elements_16bit(s); }
 struct PostOp {
     const float* addvec = nullptr;    // [N][K]
     const void* residual = nullptr;   // like y
@@ -78,26 +95,26 @@ __device__ __forceinline__ float pre_apply(float x, const PreLane& l, bool in_im
 }
 
 // launchers (each enqueues on `s`, returns the launch status)
-hipError_t launch_filter_transform(const void* w, void* U, int K, int C, int Cp, int m, bool f16, hipStream_t s);
-hipError_t launch_input_transform(const void* x, void* V, const Geom& g, bool f16, bool nhwc, const PreOp* pre, hipStream_t s);
+hipError_t launch_filter_transform(const void* w, void* U, int K, int C, int Cp, int m, int dt, hipStream_t s);
+hipError_t launch_input_transform(const void* x, void* V, const Geom& g, int dt, bool nhwc, const PreOp* pre, hipStream_t s);
 // nsplit > 1: the reduction is cut into nsplit ranges and M holds nsplit partial products
 // [nsplit][nbatch][K][T], which launch_output_transform sums.  gemm_split() is the policy the
 // whole path uses for a shape (rows = rows of the first operand, cols = rows of the second).
 // half_product: M is stored as fp16 (fp16 storage and an unsplit reduction only)
-hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, bool f16, bool half_product, hipStream_t s);
-int gemm_max_split(int Cp, bool f16);
-int gemm_split(int rows, int cols, int Cp, int nbatch, bool f16);
-hipError_t launch_output_transform(const void* M, const float* bias, void* y, const Geom& g, int nsplit, bool f16, bool nhwc,
+hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int dt, bool half_product, hipStream_t s);
+int gemm_max_split(int Cp, int dt);
+int gemm_split(int rows, int cols, int Cp, int nbatch, int dt);
+hipError_t launch_output_transform(const void* M, const float* bias, void* y, const Geom& g, int nsplit, int dt, bool nhwc,
                                    bool half_product, const PostOp* post, hipStream_t s);
 hipError_t launch_groupnorm_stats(const void* x, float* stats, int N, int C, int H, int W, int groups, float eps,
-                                  bool f16, bool nhwc, hipStream_t s);
+                                  int dt, bool nhwc, hipStream_t s);
 size_t groupnorm_stats_bytes(int N, int groups);
-hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, bool f16, hipStream_t s);
+hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, int dt, hipStream_t s);
 hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias, void* y,
-                               int N, int C, int H, int W, int K, int R, int st, bool f16, bool nhwc,
+                               int N, int C, int H, int W, int K, int R, int st, int dt, bool nhwc,
                                void* workspace, size_t xh_bytes, hipStream_t s);
-int igemm_split(int T, int K, int Cp, int R, bool f16);   // number of partial products the path writes for a shape
+int igemm_split(int T, int K, int Cp, int R, int dt);   // number of partial products the path writes for a shape
 hipError_t launch_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
-                                int N, int C, int H, int W, int K, bool f16, hipStream_t s);
+                                int N, int C, int H, int W, int K, int dt, hipStream_t s);
 
 }  // namespace wino

@@ -17,6 +17,13 @@ template <> struct Mma<__half> {
                                                     *reinterpret_cast<const half8_t*>(&b), c, 0, 0, 0);
     }
 };
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+template <> struct Mma<bf16_t> {
+    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, float16_t& c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(&a),
+                                                     *reinterpret_cast<const bf16x8_t*>(&b), c, 0, 0, 0);
+    }
+};
 template <> struct Mma<float> {
     static __device__ __forceinline__ void run(const uint4& a, const uint4& b, float16_t& c) {
         const float* fa = reinterpret_cast<const float*>(&a);

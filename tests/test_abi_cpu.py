@@ -101,7 +101,7 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.wino_batched_gemm(good, good, None, 8, 8, 4, B.WINO_F16, B.WINO_F4, None) == B.WINO_ERR_NULL
     assert L.wino_batched_gemm(good, good, good, 8, 8, 0, B.WINO_F16, B.WINO_F4, None) == B.WINO_ERR_DIM
     assert L.wino_output_transform(good, None, None, 1, 8, 4, 4, B.WINO_F16, B.WINO_F4, 0, None) == B.WINO_ERR_NULL
-    assert L.wino_output_transform(good, None, good, 1, 8, 4, 4, 2, B.WINO_F4, 0, None) == B.WINO_ERR_DTYPE
+    assert L.wino_output_transform(good, None, good, 1, 8, 4, 4, 7, B.WINO_F4, 0, None) == B.WINO_ERR_DTYPE
     assert L.wino_direct_conv2d(good, None, None, good, 1, 8, 4, 4, 8, B.WINO_F16, None) == B.WINO_ERR_NULL
     assert L.wino_direct_conv2d(vp(0x8000), good, None, vp(0x8000), 1, 8, 4, 4, 8, B.WINO_F16, None) == B.WINO_ERR_ALIAS
 
