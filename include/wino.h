@@ -62,8 +62,13 @@ typedef enum wino_dtype { WINO_F32 = 0, WINO_F16 = 1, WINO_BF16 = 2 } wino_dtype
 
 /*
  * WINO_F2 / WINO_F4: Winograd F(2x2,3x3) / F(4x4,3x3), three kernels (activation
- * transform, batched MFMA GEMM, output transform).  WINO_DIRECT: plain direct
- * correlation, for checking.  WINO_AUTO: the library picks F2 or F4 per shape.
+ * transform, batched MFMA GEMM, output transform).  WINO_AUTO: the library picks F2
+ * or F4 per shape.  WINO_DIRECT: direct correlation; a filter prepared with it
+ * (wino_filter_transform) makes wino_conv2d / wino_conv2d_ex run the implicit-GEMM
+ * MFMA kernel described at the end of this header (no transformed tensors, output
+ * rounding only; faster than the Winograd path where there are few channels and
+ * many pixels, see wino_recommend_variant).  wino_direct_conv2d is a third thing:
+ * a one-lane-per-output checking kernel.
  */
 typedef enum wino_variant { WINO_AUTO = 0, WINO_DIRECT = 1, WINO_F2 = 2, WINO_F4 = 4 } wino_variant;
 
@@ -86,16 +91,22 @@ const char *wino_status_string(int status);     /* static string, never NULL    
  * are; -1 on bad arguments. */
 int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int variant);
 
+/* WINO_F2, WINO_F4 or WINO_DIRECT, whichever was measured faster for 3x3 / stride 1 on shapes like this one
+ * (the direct path where sqrt(C*K) is small and the image large, e.g. 128 channels at 1024x1024); -1 on bad
+ * arguments.  wino_resolve_variant(WINO_AUTO) keeps to the two Winograd variants, which alone support
+ * the fused operators of wino_conv2d_fused. */
+int wino_recommend_variant(int N, int C, int H, int W, int K, int dtype);
+
 /* Sizes (elements, not bytes) of the transformed tensors for a resolved variant:
  * *Cp = C rounded up to a multiple of 8 (zero-filled), *T = N*ceil(H/m)*ceil(W/m).
  * Returns WINO_OK or an error; outputs may be NULL. */
 int wino_transformed_dims(int N, int C, int H, int W, int K, int variant, int *alpha, int *Cp, int *T);
 
-/* Bytes of the device buffer that holds U.  0 on bad arguments / AUTO / DIRECT. */
+/* Bytes of the device buffer that holds U (WINO_DIRECT: the re-laid filter).  0 on bad arguments / AUTO. */
 size_t wino_filter_bytes(int K, int C, int dtype, int variant);
 
-/* Bytes of scratch (V then M, each 256-byte aligned) that wino_conv2d_ex needs for
- * a resolved Winograd variant; 0 for WINO_DIRECT and on bad arguments. */
+/* Bytes of scratch (V then M, each 256-byte aligned; WINO_DIRECT: the re-laid copy of x and any
+ * partial sums) that wino_conv2d_ex needs for a resolved variant; 0 on bad arguments. */
 size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int dtype, int variant);
 
 /*
@@ -103,7 +114,7 @@ size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int dtype, int va
  * rounded once to `dtype`.  Done once per weight tensor.
  *   w         device, [K][C][3][3] in `dtype`
  *   w_t_data  device, at least wino_filter_bytes(K,C,dtype,variant) bytes
- *   variant   WINO_F2 or WINO_F4 (AUTO is rejected: the shape is not known here)
+ *   variant   WINO_F2, WINO_F4 or WINO_DIRECT (AUTO is rejected: the shape is not known here)
  *   out       host, filled on success
  */
 int wino_filter_transform(const void *w, void *w_t_data, int K, int C, int dtype, int variant,

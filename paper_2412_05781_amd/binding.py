@@ -32,6 +32,7 @@ EXPORTS = [
     "wino_conv2d_ex", "wino_input_transform", "wino_batched_gemm", "wino_output_transform",
     "wino_direct_conv2d", "wino_groupnorm_stats_bytes", "wino_groupnorm_stats", "wino_conv2d_fused",
     "wino_igemm_filter_bytes", "wino_igemm_filter_repack", "wino_igemm_workspace_bytes", "wino_igemm_conv2d",
+    "wino_recommend_variant",
 ]
 
 
@@ -91,6 +92,7 @@ def lib() -> ctypes.CDLL:
         L.wino_groupnorm_stats.argtypes = [vp, vp, i, i, i, i, i, ctypes.c_float, i, i, vp]
         L.wino_conv2d_fused.restype = i
         L.wino_conv2d_fused.argtypes = [vp, fp, vp, vp, i, i, i, i, i, i, ctypes.POINTER(wino_fusion), vp, sz, vp]
+        L.wino_recommend_variant.restype = i; L.wino_recommend_variant.argtypes = [i] * 6
         L.wino_igemm_filter_bytes.restype = sz; L.wino_igemm_filter_bytes.argtypes = [i] * 4
         L.wino_igemm_filter_repack.restype = i
         L.wino_igemm_filter_repack.argtypes = [vp, vp, i, i, i, i, vp]
@@ -169,6 +171,10 @@ def wino_resolve_variant(N, C, H, W, K, dtype, variant) -> int:
     return lib().wino_resolve_variant(N, C, H, W, K, dtype, variant)
 
 
+def wino_recommend_variant(N, C, H, W, K, dtype) -> int:
+    return lib().wino_recommend_variant(N, C, H, W, K, dtype)
+
+
 def wino_transformed_dims(N, C, H, W, K, variant):
     a, cp, t = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     _check(lib().wino_transformed_dims(N, C, H, W, K, variant, ctypes.byref(a), ctypes.byref(cp), ctypes.byref(t)),
@@ -196,7 +202,7 @@ class Filter:
 
 
 def wino_filter_transform(w: torch.Tensor, variant: int, stream=None) -> Filter:
-    """w[K,C,3,3] (GPU) -> Filter holding U[alpha^2][K][Cp]."""
+    """w[K,C,3,3] (GPU) -> Filter holding U[alpha^2][K][Cp] (WINO_DIRECT: the re-laid filter of the direct path)."""
     _dev(w, "w")
     K, C = int(w.shape[0]), int(w.shape[1])
     if tuple(w.shape) != (K, C, 3, 3):
@@ -406,11 +412,7 @@ def conv2d(x: torch.Tensor, w: torch.Tensor, bias=None, variant: int = WINO_AUTO
     v = wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant)
     if v < 0:
         raise WinoError(WINO_ERR_DIM, "wino_resolve_variant")
-    if v == WINO_DIRECT:
-        if layout != WINO_NCHW:
-            raise WinoError(WINO_ERR_LAYOUT, "wino_direct_conv2d is NCHW only")
-        return wino_direct_conv2d(x, w, bias, y)
-    w_t = wino_filter_transform(w, v)
+    w_t = wino_filter_transform(w, v)          # WINO_DIRECT: the re-laid filter of the implicit-GEMM path
     ws = torch.empty(wino_workspace_bytes(N, C, H, W, K, DTYPE_OF[x.dtype], v), dtype=torch.uint8, device=x.device)
     return wino_conv2d_ex(x, w_t, bias, y, ws, layout)
 

@@ -36,6 +36,19 @@ bool dims_ok(int N, int C, int H, int W, int K, int m) {
     return true;
 }
 
+bool igemm_dims_ok(int N, int C, int H, int W, int K, int R, int st) {
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1) return false;
+    if ((R != 1 && R != 3) || (st != 1 && st != 2)) return false;
+    if (C > (1 << 22) || K > (1 << 22)) return false;
+    const unsigned long long lim = 1ULL << 40;
+    const unsigned long long Cp = (unsigned long long)(C + 7) / 8 * 8;
+    if ((unsigned long long)N * H * W > (unsigned long long)INT_MAX / 2) return false;    // pixel indices are ints
+    if ((unsigned long long)N * H * W > lim / Cp) return false;
+    if ((unsigned long long)N * H * W > lim / (unsigned long long)K) return false;
+    if ((unsigned long long)R * R * K > lim / Cp) return false;
+    return true;
+}
+
 struct Workspace { size_t v_bytes, m_bytes, total; };
 Workspace workspace_layout(const Geom& g, int dtype) {
     Workspace ws;
@@ -72,8 +85,12 @@ int check_conv_args(const void* x, const wino_filter* w_t, const float* bias, co
                     int N, int C, int H, int W, int K, int up = 0) {
     if (!x || !w_t || !y || !w_t->data) return WINO_ERR_NULL;
     if (!dtype_ok(w_t->dtype)) return WINO_ERR_DTYPE;
-    if (!wino_variant_ok(w_t->variant)) return WINO_ERR_VARIANT;
-    if (!dims_ok(N, C, H, W, K, w_t->variant)) return WINO_ERR_DIM;
+    if (w_t->variant == WINO_DIRECT) {
+        if (!igemm_dims_ok(N, C, H, W, K, 3, 1)) return WINO_ERR_DIM;
+    } else {
+        if (!wino_variant_ok(w_t->variant)) return WINO_ERR_VARIANT;
+        if (!dims_ok(N, C, H, W, K, w_t->variant)) return WINO_ERR_DIM;
+    }
     if (w_t->K != K || w_t->C != C) return WINO_ERR_DIM;
     if (!aligned16(x) || !aligned16(y) || !aligned16(w_t->data) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)))
         return WINO_ERR_ALIGN;
@@ -125,6 +142,19 @@ int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int varia
     return pick;
 }
 
+int wino_recommend_variant(int N, int C, int H, int W, int K, int dtype) {
+    const int v = wino_resolve_variant(N, C, H, W, K, dtype, WINO_AUTO);
+    if (v < 0 || !igemm_dims_ok(N, C, H, W, K, 3, 1)) return v;
+    // Measured on the VAE-sized layers: with few channels and many pixels the Winograd path is bound by the
+    // traffic of V and M (about 27 bytes per output pixel and channel for F(4x4), 48 for F(2x2)), the direct
+    // path by its 18*C*K flops per pixel at ~600 TFLOP/s; they cross near sqrt(C*K) = 160 (F(4x4)) / 320 (F(2x2)).
+    const long long pixels = (long long)N * H * W;
+    const long long ck = (long long)C * K;
+    const long long cross = v == WINO_F4 ? 160LL * 160LL : 320LL * 320LL;
+    if (pixels >= 65536 && ck <= cross && K >= 32) return WINO_DIRECT;
+    return v;
+}
+
 int wino_transformed_dims(int N, int C, int H, int W, int K, int variant, int* alpha, int* Cp, int* T) {
     if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
     if (!dims_ok(N, C, H, W, K, variant)) return WINO_ERR_DIM;
@@ -136,12 +166,15 @@ int wino_transformed_dims(int N, int C, int H, int W, int K, int variant, int* a
 }
 
 size_t wino_filter_bytes(int K, int C, int dtype, int variant) {
+    if (variant == WINO_DIRECT) return wino_igemm_filter_bytes(K, C, 3, dtype);
     if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !dims_ok(1, C, 1, 1, K, variant)) return 0;
     const size_t a = variant + 2;
     return a * a * (size_t)K * (size_t)round_up(C, 8) * esize(dtype);
 }
 
 size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int dtype, int variant) {
+    // the direct path: what the NCHW call needs (the channel-last call needs no more than that)
+    if (variant == WINO_DIRECT) return wino_igemm_workspace_bytes(N, C, H, W, K, 3, 1, dtype, WINO_NCHW);
     if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !dims_ok(N, C, H, W, K, variant)) return 0;
     return workspace_layout(make_geom(N, C, H, W, K, variant), dtype).total;
 }
@@ -150,6 +183,12 @@ int wino_filter_transform(const void* w, void* w_t_data, int K, int C, int dtype
                           wino_filter* out, void* stream) {
     if (!w || !w_t_data || !out) return WINO_ERR_NULL;
     if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (variant == WINO_DIRECT) {
+        const int rc = wino_igemm_filter_repack(w, w_t_data, K, C, 3, dtype, stream);
+        if (rc != WINO_OK) return rc;
+        out->data = w_t_data; out->K = K; out->C = C; out->dtype = dtype; out->variant = variant;
+        return WINO_OK;
+    }
     if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
     if (!dims_ok(1, C, 1, 1, K, variant) || K > 65535) return WINO_ERR_DIM;   // grid.y carries k
     if (!aligned16(w) || !aligned16(w_t_data)) return WINO_ERR_ALIGN;
@@ -166,6 +205,8 @@ int wino_conv2d_ex(const void* x, const wino_filter* w_t, const float* bias, voi
     const int rc = check_conv_args(x, w_t, bias, y, N, C, H, W, K);
     if (rc != WINO_OK) return rc;
     if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    if (w_t->variant == WINO_DIRECT)
+        return wino_igemm_conv2d(x, w_t->data, bias, y, N, C, H, W, K, 3, 1, w_t->dtype, layout, workspace, workspace_bytes, stream);
     const Geom g = make_geom(N, C, H, W, K, w_t->variant);
     const Workspace ws = workspace_layout(g, w_t->dtype);
     if (!workspace || workspace_bytes < ws.total) return WINO_ERR_WORKSPACE;
@@ -177,10 +218,17 @@ int wino_conv2d(const void* x, const wino_filter* w_t, const float* bias, void* 
                 int N, int C, int H, int W, int K, void* stream) {
     const int rc = check_conv_args(x, w_t, bias, y, N, C, H, W, K);
     if (rc != WINO_OK) return rc;
-    const Geom g = make_geom(N, C, H, W, K, w_t->variant);
-    const Workspace ws = workspace_layout(g, w_t->dtype);
     hipStream_t s = static_cast<hipStream_t>(stream);
     void* workspace = nullptr;
+    if (w_t->variant == WINO_DIRECT) {
+        const size_t need = wino_igemm_workspace_bytes(N, C, H, W, K, 3, 1, w_t->dtype, WINO_NCHW);
+        if (hipMallocAsync(&workspace, need, s) != hipSuccess || !workspace) return WINO_ERR_HIP;
+        const int rc2 = wino_igemm_conv2d(x, w_t->data, bias, y, N, C, H, W, K, 3, 1, w_t->dtype, WINO_NCHW, workspace, need, stream);
+        if (hipFreeAsync(workspace, s) != hipSuccess) return WINO_ERR_HIP;
+        return rc2;
+    }
+    const Geom g = make_geom(N, C, H, W, K, w_t->variant);
+    const Workspace ws = workspace_layout(g, w_t->dtype);
     if (hipMallocAsync(&workspace, ws.total, s) != hipSuccess || !workspace) return WINO_ERR_HIP;
     const int rc2 = run_chain(x, w_t, bias, y, g, workspace, false, nullptr, nullptr, s);
     if (hipFreeAsync(workspace, s) != hipSuccess) return WINO_ERR_HIP;
@@ -213,6 +261,11 @@ int wino_conv2d_fused(const void* x, const wino_filter* w_t, const float* bias, 
     const int rc = check_conv_args(x, w_t, bias, y, N, C, H, W, K, f->upsample);
     if (rc != WINO_OK) return rc;
     if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    if (w_t->variant == WINO_DIRECT) {
+        // the direct path has no fused operators: accepted only when none is switched on
+        if (f->gn_stats || f->upsample || f->addvec || f->residual) return WINO_ERR_VARIANT;
+        return wino_igemm_conv2d(x, w_t->data, bias, y, N, C, H, W, K, 3, 1, w_t->dtype, layout, workspace, workspace_bytes, stream);
+    }
     PreOp pre; PostOp post;
     pre.up = f->upsample;
     const bool has_pre = f->gn_stats != nullptr;
@@ -296,20 +349,6 @@ int wino_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
                                 static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
-namespace {
-bool igemm_dims_ok(int N, int C, int H, int W, int K, int R, int st) {
-    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1) return false;
-    if ((R != 1 && R != 3) || (st != 1 && st != 2)) return false;
-    if (C > (1 << 22) || K > (1 << 22)) return false;
-    const unsigned long long lim = 1ULL << 40;
-    const unsigned long long Cp = (unsigned long long)(C + 7) / 8 * 8;
-    if ((unsigned long long)N * H * W > (unsigned long long)INT_MAX / 2) return false;    // pixel indices are ints
-    if ((unsigned long long)N * H * W > lim / Cp) return false;
-    if ((unsigned long long)N * H * W > lim / (unsigned long long)K) return false;
-    if ((unsigned long long)R * R * K > lim / Cp) return false;
-    return true;
-}
-}  // namespace
 
 size_t wino_igemm_filter_bytes(int K, int C, int R, int dtype) {
     if (!dtype_ok(dtype) || !igemm_dims_ok(1, C, 1, 1, K, R, 1)) return 0;

@@ -51,7 +51,16 @@ def test_sizes(L):
     assert B.wino_transformed_dims(1, 5, 7, 9, 3, B.WINO_F4) == (6, 8, 2 * 3)
     ws = B.wino_workspace_bytes(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_F4)
     assert ws == 36 * 512 * 320 * 2 + 36 * 320 * 512 * 4
-    assert B.wino_workspace_bytes(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_DIRECT) == 0
+    # the direct variant: the channel-last copy of x (2*64*64*320 fp16 elements), no partial sums for this shape
+    assert B.wino_workspace_bytes(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_DIRECT) == 2 * 64 * 64 * 320 * 2
+    assert B.wino_filter_bytes(320, 320, B.WINO_F16, B.WINO_DIRECT) == (9 * 320 * 320 + 320) * 2
+    # what the library recommends: Winograd for the UNet layers, the direct path for few channels on huge images
+    assert B.wino_recommend_variant(2, 320, 64, 64, 320, B.WINO_F16) == B.WINO_F4
+    assert B.wino_recommend_variant(1, 128, 1024, 1024, 128, B.WINO_F16) == B.WINO_DIRECT
+    assert B.wino_recommend_variant(1, 512, 256, 256, 512, B.WINO_F16) == B.WINO_F4
+    assert B.wino_recommend_variant(1, 256, 512, 512, 256, B.WINO_BF16) == B.WINO_DIRECT
+    assert B.wino_recommend_variant(2, 1280, 8, 8, 1280, B.WINO_F16) == B.WINO_F2
+    assert B.wino_recommend_variant(0, 1, 1, 1, 1, B.WINO_F16) == -1
     assert B.wino_workspace_bytes(2, 320, 64, -1, 320, B.WINO_F16, B.WINO_F4) == 0
 
 

@@ -50,6 +50,49 @@ def test_small_shapes_full_tensor(shape, variant, dtype):
     assert err <= TOL[dtype], (shape, variant, dtype, err)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("shape", SMALL)
+def test_checking_kernel_small_shapes(shape, dtype):
+    """wino_direct_conv2d, the one-lane-per-output kernel kept for checking (WINO_DIRECT through the filter-based
+    entry points runs the implicit-GEMM kernel instead, covered by the test above)."""
+    N, C, K, H, W = shape
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=1000 + sum(shape))
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    y = B.wino_direct_conv2d(x.to(DEV), w.to(DEV), b.to(DEV), torch.empty((N, K, H, W), dtype=x.dtype, device=DEV))
+    torch.cuda.synchronize()
+    assert oracle.rel_l2(y.float().cpu().numpy(), ref) <= (1e-5 if dtype == "f32" else 6e-4)
+
+
+def test_direct_variant_through_every_entry_point():
+    """A filter prepared with WINO_DIRECT: explicit workspace (both layouts), the stream-ordered entry point, and the
+    fused entry point, which takes it only while no fused operator is switched on."""
+    import ctypes
+    N, C, K, H, W = 2, 40, 72, 13, 18
+    x, w, b = synth.make_inputs(N, C, K, H, W, "f16", seed=12)
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
+    w_t = B.wino_filter_transform(wd, B.WINO_DIRECT)
+    assert w_t.desc.variant == B.WINO_DIRECT
+    ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, B.WINO_DIRECT), dtype=torch.uint8, device=DEV)
+    y1 = B.wino_conv2d_ex(xd, w_t, bd, torch.empty((N, K, H, W), dtype=xd.dtype, device=DEV), ws)
+    y2 = B.wino_conv2d(xd, w_t, bd, torch.empty((N, K, H, W), dtype=xd.dtype, device=DEV))
+    y3 = B.wino_conv2d_ex(xd.permute(0, 2, 3, 1).contiguous(), w_t, bd, torch.empty((N, H, W, K), dtype=xd.dtype, device=DEV), ws,
+                          layout=B.WINO_NHWC)
+    y4 = B.wino_conv2d_fused(xd, w_t, bd, torch.empty((N, K, H, W), dtype=xd.dtype, device=DEV), ws)
+    torch.cuda.synchronize()
+    for y in (y1, y2, y3.permute(0, 3, 1, 2), y4):
+        err = oracle.rel_l2(y.float().cpu().numpy(), ref)
+        assert FP16_BAND[B.WINO_DIRECT][0] <= err <= FP16_BAND[B.WINO_DIRECT][1], err
+    assert torch.equal(y1, y2) and torch.equal(y1, y4)
+    with pytest.raises(B.WinoError) as e:
+        B.wino_conv2d_fused(xd, w_t, bd, torch.empty((N, K, H, W), dtype=xd.dtype, device=DEV), ws,
+                            addvec=torch.zeros((N, K), device=DEV))
+    assert e.value.status == B.WINO_ERR_VARIANT
+    # the recommendation is what the binding's convenience call can be given directly
+    v = B.wino_recommend_variant(1, 64, 256, 256, 64, B.WINO_F16)
+    assert v == B.WINO_DIRECT
+
+
 @pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
 def test_no_bias_and_zero_input(variant):
     x, w, b = synth.make_inputs(2, 16, 24, 10, 11, "f32", seed=5)
