@@ -30,7 +30,8 @@
  *  - bias is always fp32 [K] and may be NULL.  Accumulation is always fp32.
  *  - Results are deterministic run to run (no atomics).
  *  - fp16 range: the F4 activation transform can grow values by up to 100x, so
- *    |x| must stay below ~650 on the fp16 F4 path (F2: 4x, ~16000).
+ *    |x| must stay below ~650 on the fp16 F4 path (F2: 4x, ~16000).  bf16 and fp32
+ *    have the range of fp32.
  */
 #ifndef WINO_H
 #define WINO_H

@@ -7,6 +7,10 @@
 // W, then each lane takes one channel of one tile, transforms it in fp32 and
 // stores with lanes running along c.  Out-of-image taps and channels >= C are
 // staged as zeros, so V's padded reduction columns are exact zeros.
+// Four kernels: a scalar one for any row length, the chunked strip kernel, the
+// sliding-window kernel for long rows, and the channel-last kernel, which needs no
+// transposition.  All of them can apply SiLU(GroupNorm(.)) to what they load and
+// read x through a 2x nearest-neighbour upsampling.
 // Bound by HBM/L2 traffic: reads x once (plus the 2-row/2-column halo), writes V.
 #include "wino_internal.h"
 #include "wino_transforms.h"

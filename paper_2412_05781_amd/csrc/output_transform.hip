@@ -1,7 +1,11 @@
 // Step (iii) (Section "Techniques"): y tile = A^T M A per (k, tile), plus bias,
 // cropped to the image, rounded once to the storage type.
-// One lane per (k, t), t fastest, so the alpha^2 reads of M[alpha^2][K][T] are
+// NCHW: one lane per (k, t), t fastest, so the alpha^2 reads of M[alpha^2][K][T] are
 // contiguous across lanes and the m-wide row stores of neighbouring tiles abut.
+// Channel-last: the product arrives transposed, M[alpha^2][T][K], one lane per
+// (t, channel pair), so reads and writes both run along k.
+// Both also add the optional per-(image, channel) vector and the residual, sum the
+// partial products of a split reduction, and can read M stored as fp16.
 // Bound by HBM/L2 traffic: reads alpha^2 fp32 per m^2 outputs.
 #include "wino_internal.h"
 #include <type_traits>
