@@ -27,8 +27,8 @@ struct ConvGeom {
 
 // PIX_A: the pixel operand supplies the rows of the block (outputs [t][k], channel-last y);
 // otherwise the filter does (outputs [k][t], NCHW y).
-template <typename E, int BM, int BN, int NST, bool PIX_A>
-__global__ void __launch_bounds__(256)
+template <typename E, int BM, int BN, int NST, bool PIX_A, int WGM = 2, int WGN = 2>
+__global__ void __launch_bounds__(WGM * WGN * 64)
 conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* __restrict__ zero_row,
                   const float* __restrict__ bias, E* __restrict__ y, float* __restrict__ part, ConvGeom g,
                   int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd, int nsplit) {
@@ -38,9 +38,9 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
     constexpr int EPC = 16 / (int)sizeof(E);
     constexpr int ROWS = BM + BN;
     constexpr int RPL = 1024 / RB;                        // rows covered by one wave-wide load
-    constexpr int NW = 4;
+    constexpr int NW = WGM * WGN;                         // waves per workgroup
     constexpr int LPW = ROWS / RPL / NW;                  // wave-wide loads per wave per stage
-    constexpr int WTM = BM / 2, WTN = BN / 2;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int FM = WTM / 32, FN = WTN / 32;
     constexpr int STAGE_BYTES = ROWS * RB;
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && ROWS % (RPL * NW) == 0 && BM % RPL == 0, "tile shape");
@@ -60,7 +60,7 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
     else { tn = tile % tiles_n; tm = tile / tiles_n; }
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int row_a0 = tm * BM, row_b0 = tn * BN;
     const int rowsA = PIX_A ? g.T : g.K, rowsB = PIX_A ? g.K : g.T;
 
@@ -340,7 +340,7 @@ igemm_pad_nhwc_kernel(const E* __restrict__ x, E* __restrict__ xh, size_t pixels
     xh[e] = c < C ? x[p * C + c] : from_f32<E>(0.f);
 }
 
-template <typename E, int BM, int BN, int NST, bool PIX_A>
+template <typename E, int BM, int BN, int NST, bool PIX_A, int WGM = 2, int WGN = 2>
 static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, E* y, float* part, int nsplit,
                                    const ConvGeom& g, hipStream_t s) {
     const int rowsA = PIX_A ? g.T : g.K, rowsB = PIX_A ? g.K : g.T;
@@ -350,7 +350,7 @@ static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, 
     const int per_xcd = (int)((total + 7) / 8);
     constexpr int lds_bytes = (BM + BN) * 128 * NST;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
-    auto kern = conv_igemm_kernel<E, BM, BN, NST, PIX_A>;
+    auto kern = conv_igemm_kernel<E, BM, BN, NST, PIX_A, WGM, WGN>;
     static bool attr_set = false;                 // per instantiation; raising the limit is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
@@ -358,7 +358,7 @@ static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, 
         attr_set = true;
     }
     const E* zero_row = Wr + (size_t)g.R * g.R * g.K * g.Cp;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), lds_bytes, s,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(WGM * WGN * 64), lds_bytes, s,
                        xh, Wr, zero_row, bias, y, part, g, tiles_m, tiles_n, (int)total, per_xcd, nsplit);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     if (nsplit > 1) {
@@ -369,11 +369,21 @@ static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, 
     return hipGetLastError();
 }
 
-// 128x128 blocks while they still cover the chip twice, else 64x64.
-static int igemm_shape(int T, int K) {
+// Block shape as (pixels x output channels).  The stage is bound by what a compute unit can pull from L2
+// into LDS (26-37 bytes per clock measured), so the block with the fewest operand bytes per flop that
+// still fills the chip wins: 256x256 (16 waves; 1.0 PFLOP/s on 512 channels at 256x256) when K is a
+// multiple of 256, 256x128 (8 waves) when K is a multiple of 128, each while >= 256 blocks remain;
+// then 128x128 while >= 256 blocks remain, else 64x64.
+struct IgemmShape { int tp, tk; };
+static IgemmShape igemm_shape(int T, int K) {
     static const int forced = [] { const char* e = getenv("WINO_IGEMM_SHAPE"); return e ? atoi(e) : -1; }();   // tuning knob
-    if (forced >= 0) return forced;
-    return (long long)((T + 127) / 128) * ((K + 127) / 128) >= 512 ? 0 : 1;
+    static const IgemmShape menu[5] = {{128, 128}, {64, 64}, {256, 256}, {256, 128}, {128, 256}};
+    if (forced >= 0 && forced < 5) return menu[forced];
+    auto blocks = [&](int tp, int tk) { return (long long)((T + tp - 1) / tp) * ((K + tk - 1) / tk); };
+    if (K % 256 == 0 && blocks(256, 256) >= 256) return menu[2];
+    if (K % 128 == 0 && blocks(256, 128) >= 256) return menu[3];
+    if (blocks(128, 128) >= 256) return menu[0];
+    return menu[1];
 }
 
 // Few blocks and a long reduction (deep down-sampling layers: 8x8 outputs, 9 x 1280 channels): cut the
@@ -387,8 +397,8 @@ int igemm_split(int T, int K, int Cp, int R, int dt) {
     int sp = 1;
     if (forced > 0) sp = forced;
     else {
-        const int b = igemm_shape(T, K) == 0 ? 128 : 64;
-        const long long blocks = (long long)((T + b - 1) / b) * ((K + b - 1) / b);
+        const IgemmShape sh = igemm_shape(T, K);
+        const long long blocks = (long long)((T + sh.tp - 1) / sh.tp) * ((K + sh.tk - 1) / sh.tk);
         if (blocks < 256) sp = (int)((512 + blocks - 1) / blocks);
         if (sp > 16) sp = 16;
         if (sp > nstage / 8) sp = nstage / 8;
@@ -400,7 +410,13 @@ int igemm_split(int T, int K, int Cp, int R, int dt) {
 template <typename E, bool PIX_A>
 static hipError_t launch_igemm_t(const E* xh, const E* Wr, const float* bias, E* y, float* part, int nsplit,
                                  const ConvGeom& g, hipStream_t s) {
-    if (igemm_shape(g.T, g.K) == 0) return launch_igemm_cfg<E, 128, 128, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, s);
+    // rows of the block: pixels when y is channel-last, output channels otherwise
+    const IgemmShape sh = igemm_shape(g.T, g.K);
+    const int bm = PIX_A ? sh.tp : sh.tk, bn = PIX_A ? sh.tk : sh.tp;
+    if (bm == 256 && bn == 256) return launch_igemm_cfg<E, 256, 256, 2, PIX_A, 4, 4>(xh, Wr, bias, y, part, nsplit, g, s);
+    if (bm == 256 && bn == 128) return launch_igemm_cfg<E, 256, 128, 2, PIX_A, 4, 2>(xh, Wr, bias, y, part, nsplit, g, s);
+    if (bm == 128 && bn == 256) return launch_igemm_cfg<E, 128, 256, 2, PIX_A, 2, 4>(xh, Wr, bias, y, part, nsplit, g, s);
+    if (bm == 128) return launch_igemm_cfg<E, 128, 128, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, s);
     return launch_igemm_cfg<E, 64, 64, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, s);
 }
 

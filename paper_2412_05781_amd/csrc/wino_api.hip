@@ -147,10 +147,12 @@ int wino_recommend_variant(int N, int C, int H, int W, int K, int dtype) {
     if (v < 0 || !igemm_dims_ok(N, C, H, W, K, 3, 1)) return v;
     // Measured on the VAE-sized layers: with few channels and many pixels the Winograd path is bound by the
     // traffic of V and M (about 27 bytes per output pixel and channel for F(4x4), 48 for F(2x2)), the direct
-    // path by its 18*C*K flops per pixel at ~600 TFLOP/s; they cross near sqrt(C*K) = 160 (F(4x4)) / 320 (F(2x2)).
+    // path by its 18*C*K flops per pixel at 0.6-1.0 PFLOP/s.  256 channels at 512x512: direct 1.25x faster;
+    // 512 channels at 256x256: Winograd 1.18x faster.  The crossing is put at sqrt(C*K) = 320 against
+    // F(4x4) and 448 against F(2x2).
     const long long pixels = (long long)N * H * W;
     const long long ck = (long long)C * K;
-    const long long cross = v == WINO_F4 ? 160LL * 160LL : 320LL * 320LL;
+    const long long cross = v == WINO_F4 ? 320LL * 320LL : 448LL * 448LL;
     if (pixels >= 65536 && ck <= cross && K >= 32) return WINO_DIRECT;
     return v;
 }
