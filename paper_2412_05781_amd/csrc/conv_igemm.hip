@@ -23,6 +23,13 @@ namespace wino {
 
 struct ConvGeom {
     int N, C, Cp, H, W, K, R, st, pad, Ho, Wo, T;      // T = N*Ho*Wo output pixels
+    int up, Hs, Ws;                                    // up = 1: x is stored at Hs x Ws = H/2 x W/2 and read upsampled
+};
+// Optional additions in the epilogue (fp32, before the one rounding): a per-(image, channel) vector and a
+// tensor of y's shape and layout.
+struct IgemmPost {
+    const float* addvec = nullptr;    // [N][K]
+    const void* residual = nullptr;   // like y
 };
 
 // PIX_A: the pixel operand supplies the rows of the block (outputs [t][k], channel-last y);
@@ -30,7 +37,7 @@ struct ConvGeom {
 template <typename E, int BM, int BN, int NST, bool PIX_A, int WGM = 2, int WGN = 2>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* __restrict__ zero_row,
-                  const float* __restrict__ bias, E* __restrict__ y, float* __restrict__ part, ConvGeom g,
+                  const float* __restrict__ bias, E* __restrict__ y, float* __restrict__ part, ConvGeom g, IgemmPost post,
                   int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd, int nsplit) {
     constexpr int RB = 128;
     constexpr int CPR = RB / 16;                          // 16-byte chunks per row per stage
@@ -85,7 +92,7 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
         fptr[i] = Wr + (size_t)gr * g.Cp + chunk * EPC;
         const int n = gr / HoWo, p = gr - n * HoWo;
         const int oi = p / g.Wo, oj = p - oi * g.Wo;
-        pn[i] = n * g.H * g.W; pi0[i] = oi * g.st - g.pad; pj0[i] = oj * g.st - g.pad;
+        pn[i] = n * g.Hs * g.Ws; pi0[i] = oi * g.st - g.pad; pj0[i] = oj * g.st - g.pad;
     }
 
     const int nkc = (g.Cp + BKE - 1) / BKE;
@@ -106,7 +113,7 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
             if (is_pix[i]) {
                 const int ii = pi0[i] + r, jj = pj0[i] + s;
                 const bool in = ii >= 0 && ii < g.H && jj >= 0 && jj < g.W;
-                src[i] = in ? xh + ((size_t)pn[i] + (size_t)ii * g.W + jj) * g.Cp + chunk_of[i] * EPC
+                src[i] = in ? xh + ((size_t)pn[i] + (size_t)(ii >> g.up) * g.Ws + (jj >> g.up)) * g.Cp + chunk_of[i] * EPC
                             : zero_row + chunk_of[i] * EPC;
             } else {
                 src[i] = fptr[i] + (size_t)tap * g.K * g.Cp;
@@ -206,19 +213,31 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
             if (PIX_A) {
                 // rows are output pixels, the column is k: y[t][k], lanes along k
                 const float b = bias ? bias[cb] : 0.f;
+                const E* res = static_cast<const E*>(post.residual);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int t = row_a0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
-                    if (t < g.T) y[(size_t)t * g.K + cb] = from_f32<E>(acc[i][j][r] + b);
+                    if (t < g.T) {
+                        float v = acc[i][j][r] + b;
+                        if (post.addvec) v += post.addvec[(size_t)(t / HoWo) * g.K + cb];
+                        if (res) v += to_f32<E>(res[(size_t)t * g.K + cb]);
+                        y[(size_t)t * g.K + cb] = from_f32<E>(v);
+                    }
                 }
             } else {
                 // rows are k, the column is an output pixel: y[n][k][p], lanes along p
                 const int n = cb / HoWo, p = cb - n * HoWo;
                 E* yp = y + (size_t)n * g.K * HoWo + p;
+                const E* rp = post.residual ? static_cast<const E*>(post.residual) + (size_t)n * g.K * HoWo + p : nullptr;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int k = row_a0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
-                    if (k < g.K) yp[(size_t)k * HoWo] = from_f32<E>(acc[i][j][r] + (bias ? bias[k] : 0.f));
+                    if (k < g.K) {
+                        float v = acc[i][j][r] + (bias ? bias[k] : 0.f);
+                        if (post.addvec) v += post.addvec[(size_t)n * g.K + k];
+                        if (rp) v += to_f32<E>(rp[(size_t)k * HoWo]);
+                        yp[(size_t)k * HoWo] = from_f32<E>(v);
+                    }
                 }
             }
         }
@@ -229,19 +248,27 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
 template <typename E, bool PIX_A>
 __global__ void __launch_bounds__(256)
 igemm_reduce_kernel(const float* __restrict__ part, const float* __restrict__ bias, E* __restrict__ y,
-                    int K, int T, int HoWo, int nsplit) {
+                    int K, int T, int HoWo, int nsplit, IgemmPost post) {
     const size_t total = (size_t)K * T;
     const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= total) return;
     float acc = 0.f;
     for (int sp = 0; sp < nsplit; ++sp) acc += part[(size_t)sp * total + e];
+    const E* res = static_cast<const E*>(post.residual);
     if (PIX_A) {
-        const int k = (int)(e % K);
-        y[e] = from_f32<E>(acc + (bias ? bias[k] : 0.f));
+        const int k = (int)(e % K), t = (int)(e / K);
+        acc += bias ? bias[k] : 0.f;
+        if (post.addvec) acc += post.addvec[(size_t)(t / HoWo) * K + k];
+        if (res) acc += to_f32<E>(res[e]);
+        y[e] = from_f32<E>(acc);
     } else {
         const int t = (int)(e % T), k = (int)(e / T);
         const int n = t / HoWo, p = t - n * HoWo;
-        y[((size_t)n * K + k) * HoWo + p] = from_f32<E>(acc + (bias ? bias[k] : 0.f));
+        const size_t o = ((size_t)n * K + k) * HoWo + p;
+        acc += bias ? bias[k] : 0.f;
+        if (post.addvec) acc += post.addvec[(size_t)n * K + k];
+        if (res) acc += to_f32<E>(res[o]);
+        y[o] = from_f32<E>(acc);
     }
 }
 
@@ -342,7 +369,7 @@ igemm_pad_nhwc_kernel(const E* __restrict__ x, E* __restrict__ xh, size_t pixels
 
 template <typename E, int BM, int BN, int NST, bool PIX_A, int WGM = 2, int WGN = 2>
 static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, E* y, float* part, int nsplit,
-                                   const ConvGeom& g, hipStream_t s) {
+                                   const ConvGeom& g, const IgemmPost& post, hipStream_t s) {
     const int rowsA = PIX_A ? g.T : g.K, rowsB = PIX_A ? g.K : g.T;
     const int tiles_m = (rowsA + BM - 1) / BM, tiles_n = (rowsB + BN - 1) / BN;
     const long long total = (long long)tiles_m * tiles_n * nsplit;
@@ -359,12 +386,12 @@ static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, 
     }
     const E* zero_row = Wr + (size_t)g.R * g.R * g.K * g.Cp;
     hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(WGM * WGN * 64), lds_bytes, s,
-                       xh, Wr, zero_row, bias, y, part, g, tiles_m, tiles_n, (int)total, per_xcd, nsplit);
+                       xh, Wr, zero_row, bias, y, part, g, post, tiles_m, tiles_n, (int)total, per_xcd, nsplit);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     if (nsplit > 1) {
         const size_t blocks = ((size_t)g.K * g.T + 255) / 256;
         if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((igemm_reduce_kernel<E, PIX_A>), dim3((unsigned)blocks), dim3(256), 0, s, part, bias, y, g.K, g.T, g.Ho * g.Wo, nsplit);
+        hipLaunchKernelGGL((igemm_reduce_kernel<E, PIX_A>), dim3((unsigned)blocks), dim3(256), 0, s, part, bias, y, g.K, g.T, g.Ho * g.Wo, nsplit, post);
     }
     return hipGetLastError();
 }
@@ -409,15 +436,15 @@ int igemm_split(int T, int K, int Cp, int R, int dt) {
 
 template <typename E, bool PIX_A>
 static hipError_t launch_igemm_t(const E* xh, const E* Wr, const float* bias, E* y, float* part, int nsplit,
-                                 const ConvGeom& g, hipStream_t s) {
+                                 const ConvGeom& g, const IgemmPost& post, hipStream_t s) {
     // rows of the block: pixels when y is channel-last, output channels otherwise
     const IgemmShape sh = igemm_shape(g.T, g.K);
     const int bm = PIX_A ? sh.tp : sh.tk, bn = PIX_A ? sh.tk : sh.tp;
-    if (bm == 256 && bn == 256) return launch_igemm_cfg<E, 256, 256, 2, PIX_A, 4, 4>(xh, Wr, bias, y, part, nsplit, g, s);
-    if (bm == 256 && bn == 128) return launch_igemm_cfg<E, 256, 128, 2, PIX_A, 4, 2>(xh, Wr, bias, y, part, nsplit, g, s);
-    if (bm == 128 && bn == 256) return launch_igemm_cfg<E, 128, 256, 2, PIX_A, 2, 4>(xh, Wr, bias, y, part, nsplit, g, s);
-    if (bm == 128) return launch_igemm_cfg<E, 128, 128, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, s);
-    return launch_igemm_cfg<E, 64, 64, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, s);
+    if (bm == 256 && bn == 256) return launch_igemm_cfg<E, 256, 256, 2, PIX_A, 4, 4>(xh, Wr, bias, y, part, nsplit, g, post, s);
+    if (bm == 256 && bn == 128) return launch_igemm_cfg<E, 256, 128, 2, PIX_A, 4, 2>(xh, Wr, bias, y, part, nsplit, g, post, s);
+    if (bm == 128 && bn == 256) return launch_igemm_cfg<E, 128, 256, 2, PIX_A, 2, 4>(xh, Wr, bias, y, part, nsplit, g, post, s);
+    if (bm == 128) return launch_igemm_cfg<E, 128, 128, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, post, s);
+    return launch_igemm_cfg<E, 64, 64, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, post, s);
 }
 
 hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, int dt, hipStream_t s) {
@@ -433,48 +460,50 @@ hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int
 }
 
 template <typename E>
-static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias, void* y, const ConvGeom& g, bool nhwc,
-                               void* workspace, size_t xh_bytes, hipStream_t s) {
+static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias, void* y, const ConvGeom& g, const IgemmPost& post,
+                               bool nhwc, void* workspace, size_t xh_bytes, hipStream_t s) {
     const E* xh = static_cast<const E*>(x);
     const int nsplit = igemm_split(g.T, g.K, g.Cp, g.R, sizeof(E) == 2 ? DT_F16 : DT_F32);
     float* part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + xh_bytes);   // only used when nsplit > 1
     if (!nhwc) {
         constexpr int EPC = 16 / (int)sizeof(E);
-        const bool chunks = g.W % EPC == 0;                 // x and the workspace are 16-byte aligned, so every row then is
+        const bool chunks = g.Ws % EPC == 0;                 // x and the workspace are 16-byte aligned, so every row then is
         const int tw = chunks ? 8 * EPC : 32;
-        const int wtiles = (g.W + tw - 1) / tw;
-        const long long bx = (long long)g.N * g.H * wtiles;
+        const int wtiles = (g.Ws + tw - 1) / tw;
+        const long long bx = (long long)g.N * g.Hs * wtiles;
         if (bx > 0x7fffffffLL || (g.Cp + 63) / 64 > 65535) return hipErrorInvalidValue;
         if (chunks)
             hipLaunchKernelGGL(igemm_relayout_nchw_vec_kernel<E>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
-                               (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.H, g.W, wtiles);
+                               (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.Hs, g.Ws, wtiles);
         else
             hipLaunchKernelGGL(igemm_relayout_nchw_kernel<E>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
-                               (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.H, g.W, wtiles);
+                               (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.Hs, g.Ws, wtiles);
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
         xh = static_cast<const E*>(workspace);
     } else if (g.C != g.Cp) {
-        const size_t pixels = (size_t)g.N * g.H * g.W;
+        const size_t pixels = (size_t)g.N * g.Hs * g.Ws;
         const size_t blocks = (pixels * g.Cp + 255) / 256;
         if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
         hipLaunchKernelGGL(igemm_pad_nhwc_kernel<E>, dim3((unsigned)blocks), dim3(256), 0, s, (const E*)x, (E*)workspace, pixels, g.C, g.Cp);
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
         xh = static_cast<const E*>(workspace);
     }
-    return nhwc ? launch_igemm_t<E, true>(xh, (const E*)Wr, bias, (E*)y, part, nsplit, g, s)
-                : launch_igemm_t<E, false>(xh, (const E*)Wr, bias, (E*)y, part, nsplit, g, s);
+    return nhwc ? launch_igemm_t<E, true>(xh, (const E*)Wr, bias, (E*)y, part, nsplit, g, post, s)
+                : launch_igemm_t<E, false>(xh, (const E*)Wr, bias, (E*)y, part, nsplit, g, post, s);
 }
 
 hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias, void* y,
                                int N, int C, int H, int W, int K, int R, int st, int dt, bool nhwc,
-                               void* workspace, size_t xh_bytes, hipStream_t s) {
+                               void* workspace, size_t xh_bytes, int up, const float* addvec, const void* residual, hipStream_t s) {
+    IgemmPost post; post.addvec = addvec; post.residual = residual;
     ConvGeom g;
+    g.up = up; g.Hs = H >> up; g.Ws = W >> up;
     g.N = N; g.C = C; g.Cp = (C + 7) / 8 * 8; g.H = H; g.W = W; g.K = K; g.R = R; g.st = st; g.pad = (R - 1) / 2;
     g.Ho = (H + 2 * g.pad - R) / st + 1; g.Wo = (W + 2 * g.pad - R) / st + 1;
     g.T = N * g.Ho * g.Wo;
     return with_dtype(dt, [&](auto* tag) {
         using E = std::remove_pointer_t<decltype(tag)>;
-        return igemm_conv_t<E>(x, Wr, bias, y, g, nhwc, workspace, xh_bytes, s);
+        return igemm_conv_t<E>(x, Wr, bias, y, g, post, nhwc, workspace, xh_bytes, s);
     });
 }
 

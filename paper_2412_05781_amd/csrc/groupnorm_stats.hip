@@ -93,7 +93,7 @@ hipError_t launch_groupnorm_stats(const void* x, float* stats, int N, int C, int
                                                 (((size_t)total * 2 * sizeof(float) + 255) / 256) * 256);
     dim3 grid((unsigned)total, (unsigned)split), block(256);
     const bool vec = !nhwc && (elems * esz) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
-    with_dtype(dt, [&](auto* tag) {
+    (void)with_dtype(dt, [&](auto* tag) {
         using E = std::remove_pointer_t<decltype(tag)>;
         if (vec)       hipLaunchKernelGGL((groupnorm_partial_vec_kernel<E>), grid, block, 0, s, (const E*)x, partial, elems, split, per_slice);
         else if (nhwc) hipLaunchKernelGGL((groupnorm_partial_kernel<E, true>), grid, block, 0, s, (const E*)x, partial, C, HW, groups, cpg, split, per_slice);

@@ -49,6 +49,18 @@ bool igemm_dims_ok(int N, int C, int H, int W, int K, int R, int st) {
     return true;
 }
 
+// bytes of the re-laid copy of x (0: x is used in place), and of the fp32 partial products
+size_t igemm_xh_bytes(int N, int C, int H, int W, int dtype, int layout) {
+    if (layout == WINO_NHWC && C % 8 == 0) return 0;
+    return align_up((size_t)N * H * W * (size_t)round_up(C, 8) * esize(dtype));
+}
+size_t igemm_part_bytes(int N, int C, int H, int W, int K, int R, int stride, int dtype) {
+    const int pad = (R - 1) / 2;
+    const long long T = (long long)N * ((H + 2 * pad - R) / stride + 1) * ((W + 2 * pad - R) / stride + 1);
+    const int sp = igemm_split((int)T, K, round_up(C, 8), R, dtype);
+    return sp > 1 ? align_up((size_t)sp * (size_t)K * (size_t)T * sizeof(float)) : 0;
+}
+
 struct Workspace { size_t v_bytes, m_bytes, total; };
 Workspace workspace_layout(const Geom& g, int dtype) {
     Workspace ws;
@@ -264,9 +276,25 @@ int wino_conv2d_fused(const void* x, const wino_filter* w_t, const float* bias, 
     if (rc != WINO_OK) return rc;
     if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
     if (w_t->variant == WINO_DIRECT) {
-        // the direct path has no fused operators: accepted only when none is switched on
-        if (f->gn_stats || f->upsample || f->addvec || f->residual) return WINO_ERR_VARIANT;
-        return wino_igemm_conv2d(x, w_t->data, bias, y, N, C, H, W, K, 3, 1, w_t->dtype, layout, workspace, workspace_bytes, stream);
+        // the direct path reads x through the upsampling and adds the vector and the residual in its epilogue;
+        // it has no GroupNorm + SiLU on the way in
+        if (f->gn_stats) return WINO_ERR_VARIANT;
+        if (f->addvec && (reinterpret_cast<uintptr_t>(f->addvec) & 3u)) return WINO_ERR_ALIGN;
+        const int dt = w_t->dtype;
+        const size_t es = esize(dt);
+        if (f->residual) {
+            if (!aligned16(f->residual)) return WINO_ERR_ALIGN;
+            const uintptr_t rb = reinterpret_cast<uintptr_t>(f->residual), re = rb + (size_t)N * K * H * W * es;
+            const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + (size_t)N * K * H * W * es;
+            if (rb != yb && rb < ye && yb < re) return WINO_ERR_ALIAS;
+        }
+        const int up = f->upsample;
+        const size_t xh = igemm_xh_bytes(N, C, H >> up, W >> up, dt, layout);
+        const size_t need = xh + igemm_part_bytes(N, C, H, W, K, 3, 1, dt);
+        if (need && (!workspace || workspace_bytes < need)) return WINO_ERR_WORKSPACE;
+        if (need && !aligned16(workspace)) return WINO_ERR_ALIGN;
+        return launch_igemm_conv2d(x, w_t->data, bias, y, N, C, H, W, K, 3, 1, dt, layout == WINO_NHWC, workspace, xh, up,
+                                   f->addvec, f->residual, static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
     }
     PreOp pre; PostOp post;
     pre.up = f->upsample;
@@ -367,19 +395,6 @@ int wino_igemm_filter_repack(const void* w, void* w_r, int K, int C, int R, int 
                ? WINO_OK : WINO_ERR_HIP;
 }
 
-namespace {
-// bytes of the re-laid copy of x (0: x is used in place), and of the fp32 partial products
-size_t igemm_xh_bytes(int N, int C, int H, int W, int dtype, int layout) {
-    if (layout == WINO_NHWC && C % 8 == 0) return 0;
-    return align_up((size_t)N * H * W * (size_t)round_up(C, 8) * esize(dtype));
-}
-size_t igemm_part_bytes(int N, int C, int H, int W, int K, int R, int stride, int dtype) {
-    const int pad = (R - 1) / 2;
-    const long long T = (long long)N * ((H + 2 * pad - R) / stride + 1) * ((W + 2 * pad - R) / stride + 1);
-    const int sp = igemm_split((int)T, K, round_up(C, 8), R, dtype);
-    return sp > 1 ? align_up((size_t)sp * (size_t)K * (size_t)T * sizeof(float)) : 0;
-}
-}  // namespace
 
 size_t wino_igemm_workspace_bytes(int N, int C, int H, int W, int K, int R, int stride, int dtype, int layout) {
     if (!dtype_ok(dtype) || !igemm_dims_ok(N, C, H, W, K, R, stride)) return 0;
@@ -406,7 +421,8 @@ int wino_igemm_conv2d(const void* x, const void* w_r, const float* bias, void* y
     if (need && (!workspace || workspace_bytes < need)) return WINO_ERR_WORKSPACE;
     if (need && !aligned16(workspace)) return WINO_ERR_ALIGN;
     return launch_igemm_conv2d(x, w_r, bias, y, N, C, H, W, K, R, stride, dtype, layout == WINO_NHWC,
-                               workspace, igemm_xh_bytes(N, C, H, W, dtype, layout), static_cast<hipStream_t>(stream)) == hipSuccess
+                               workspace, igemm_xh_bytes(N, C, H, W, dtype, layout), 0, nullptr, nullptr,
+                               static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
 

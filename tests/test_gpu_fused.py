@@ -187,3 +187,39 @@ def test_half_product_mode_is_ignored_for_fp32_and_split_reductions():
     c = B.conv2d(x.to(DEV), w.to(DEV), b.to(DEV), B.WINO_F2)
     torch.cuda.synchronize()
     assert torch.equal(a, c)
+
+
+# (N, C, K, h, w): the direct variant reads x through the upsampling by address arithmetic and adds the vector and the
+# residual in its epilogue; the third shape has few pixels and a long reduction, so the adds happen in the kernel that
+# sums the partial products
+DIRECT_UP_CASES = [(1, 24, 40, 5, 7), (2, 64, 72, 8, 12), (1, 640, 96, 4, 4)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("upsample", [False, True])
+@pytest.mark.parametrize("case", DIRECT_UP_CASES)
+def test_direct_variant_fused(case, upsample, layout, dtype):
+    N, C, K, h, w_ = case
+    x, w, b = synth.make_inputs(N, C, K, h, w_, dtype, seed=12000 + sum(case))
+    H, W = (2 * h, 2 * w_) if upsample else (h, w_)
+    _, _, addvec, residual = _extras(N, C, K, H, W, dtype, 13 + sum(case))
+    ref = fo.conv2d_fused(_np(x), _np(w), _np(b), addvec=_np(addvec), residual=_np(residual), upsample=upsample)
+    perm = (lambda t: t.permute(0, 2, 3, 1).contiguous()) if layout == B.WINO_NHWC else (lambda t: t)
+    y = B.conv2d_fused(perm(x).to(DEV), w.to(DEV), b.to(DEV), B.WINO_DIRECT, layout, addvec=addvec.to(DEV),
+                       residual=perm(residual).to(DEV), upsample=upsample)
+    torch.cuda.synchronize()
+    y = y.float().cpu()
+    if layout == B.WINO_NHWC:
+        y = y.permute(0, 3, 1, 2)
+    assert tuple(y.shape) == (N, K, H, W)
+    err = oracle.rel_l2(y.numpy(), ref)
+    assert err <= {"f32": 1e-5, "f16": 6e-4, "bf16": 3e-3}[dtype], (case, upsample, layout, dtype, err)
+
+
+def test_direct_variant_rejects_groupnorm():
+    x, w, b = synth.make_inputs(1, 8, 8, 4, 4, "f16", seed=2)
+    with pytest.raises(B.WinoError) as e:
+        B.conv2d_fused(x.to(DEV), w.to(DEV), b.to(DEV), B.WINO_DIRECT, gn_gamma=torch.ones(8, device=DEV), gn_beta=torch.zeros(8, device=DEV),
+                       gn_groups=2)
+    assert e.value.status == B.WINO_ERR_VARIANT

@@ -65,7 +65,7 @@ def test_checking_kernel_small_shapes(shape, dtype):
 
 def test_direct_variant_through_every_entry_point():
     """A filter prepared with WINO_DIRECT: explicit workspace (both layouts), the stream-ordered entry point, and the
-    fused entry point, which takes it only while no fused operator is switched on."""
+    fused entry point (which takes it with everything but GroupNorm; tests/test_gpu_fused.py covers those operators)."""
     import ctypes
     N, C, K, H, W = 2, 40, 72, 13, 18
     x, w, b = synth.make_inputs(N, C, K, H, W, "f16", seed=12)
@@ -84,9 +84,10 @@ def test_direct_variant_through_every_entry_point():
         err = oracle.rel_l2(y.float().cpu().numpy(), ref)
         assert FP16_BAND[B.WINO_DIRECT][0] <= err <= FP16_BAND[B.WINO_DIRECT][1], err
     assert torch.equal(y1, y2) and torch.equal(y1, y4)
-    with pytest.raises(B.WinoError) as e:
-        B.wino_conv2d_fused(xd, w_t, bd, torch.empty((N, K, H, W), dtype=xd.dtype, device=DEV), ws,
-                            addvec=torch.zeros((N, K), device=DEV))
+    with pytest.raises(B.WinoError) as e:           # no GroupNorm + SiLU on the direct path
+        st = B.wino_groupnorm_stats(xd, 8)
+        B.wino_conv2d_fused(xd, w_t, bd, torch.empty((N, K, H, W), dtype=xd.dtype, device=DEV), ws, gn_stats=st,
+                            gn_gamma=torch.ones(C, device=DEV), gn_beta=torch.zeros(C, device=DEV), gn_groups=8)
     assert e.value.status == B.WINO_ERR_VARIANT
     # the recommendation is what the binding's convenience call can be given directly
     v = B.wino_recommend_variant(1, 64, 256, 256, 64, B.WINO_F16)
