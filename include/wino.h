@@ -174,8 +174,9 @@ int wino_output_transform(const float *M, const float *bias, void *y, int N, int
  *                   large images).  Accumulation stays fp32.  The relative L2 error of F(4x4) grows from
  *                   about 3.1e-3 to 3.8-4.2e-3 (F(2x2): 5e-4 to 6.4e-4), and |M| must stay below 65504.
  *                   Ignored where the reduction is split into partial products, and for fp32 storage.
- * A filter prepared with WINO_DIRECT is accepted with upsample, addvec and residual (the direct path reads x through
- * the upsampling by address arithmetic and adds in its epilogue); with gn_stats it is WINO_ERR_VARIANT.
+ * A filter prepared with WINO_DIRECT is accepted too: the direct path reads x through the upsampling by address
+ * arithmetic, adds in its epilogue, and applies GroupNorm + SiLU while it re-lays x into its workspace (the activated
+ * tensor is rounded once to the storage type there; a channel-last x is then copied once instead of read in place).
  * All pointers are device memory.  residual has the layout, dtype and shape of y and may be y
  * itself (in-place accumulate) but must not otherwise overlap it.
  */

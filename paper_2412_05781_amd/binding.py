@@ -427,8 +427,8 @@ def conv2d_fused(x, w, bias=None, variant: int = WINO_AUTO, layout: int = WINO_N
     K = int(w.shape[0])
     y = torch.empty(_act_shape(N, K, H, W, layout), dtype=x.dtype, device=x.device)
     v = wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant)
-    if v not in (WINO_F2, WINO_F4, WINO_DIRECT) or (v == WINO_DIRECT and gn_gamma is not None):
-        raise WinoError(WINO_ERR_VARIANT, "conv2d_fused: GroupNorm needs a Winograd variant")
+    if v not in (WINO_F2, WINO_F4, WINO_DIRECT):
+        raise WinoError(WINO_ERR_VARIANT, "conv2d_fused")
     stats = wino_groupnorm_stats(x, gn_groups, eps, layout) if gn_gamma is not None else None
     w_t = wino_filter_transform(w, v)
     ws = torch.empty(wino_workspace_bytes(N, C, H, W, K, DTYPE_OF[x.dtype], v), dtype=torch.uint8, device=x.device)

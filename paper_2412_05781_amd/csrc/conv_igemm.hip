@@ -14,7 +14,9 @@
 //
 // The pixel operand needs the channel index contiguous: x[N][H][W][Cp].  Channel-last inputs with
 // C a multiple of 8 are used in place; otherwise (NCHW, or C not a multiple of 8) a re-layout
-// kernel writes that tensor into the workspace first.
+// kernel writes that tensor into the workspace first.  That kernel is also where the optional
+// SiLU(GroupNorm(x)) is applied (the GEMM kernel's loads go straight to LDS and cannot), so with it
+// even a channel-last input is copied once.  The optional 2x upsampling is pure address arithmetic.
 #include "wino_internal.h"
 #include "wino_mma.h"
 #include <stdlib.h>
@@ -294,7 +296,7 @@ igemm_filter_repack_kernel(const E* __restrict__ w, E* __restrict__ Wr, int K, i
 // that reads run along w and writes along c.  Channel-last source (C not a multiple of 8): plain copy.
 template <typename E>
 __global__ void __launch_bounds__(256)
-igemm_relayout_nchw_kernel(const E* __restrict__ x, E* __restrict__ xh, int N, int C, int Cp, int H, int W, int wtiles) {
+igemm_relayout_nchw_kernel(const E* __restrict__ x, E* __restrict__ xh, int N, int C, int Cp, int H, int W, int wtiles, PreOp pre) {
     __shared__ E tile[64][33];
     int b = blockIdx.x;
     const int wt = b % wtiles; b /= wtiles;
@@ -304,7 +306,9 @@ igemm_relayout_nchw_kernel(const E* __restrict__ x, E* __restrict__ xh, int N, i
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const int c = c0 + ty + 8 * k, wq = w0 + tx;
-        tile[ty + 8 * k][tx] = (c < C && wq < W) ? x[(((size_t)n * C + c) * H + h) * W + wq] : from_f32<E>(0.f);
+        E v = (c < C && wq < W) ? x[(((size_t)n * C + c) * H + h) * W + wq] : from_f32<E>(0.f);
+        if (pre.stats && c < C) v = from_f32<E>(pre_apply(to_f32<E>(v), pre_lane(pre, n, c, C), true));   // SiLU(GroupNorm(x)), rounded once
+        tile[ty + 8 * k][tx] = v;
     }
     __syncthreads();
     const int cx = threadIdx.x & 63, wy = threadIdx.x >> 6;     // 64 x 4
@@ -321,7 +325,7 @@ igemm_relayout_nchw_kernel(const E* __restrict__ x, E* __restrict__ xh, int N, i
 // from LDS (row pitch an odd number of words: conflict-free both ways).
 template <typename E>
 __global__ void __launch_bounds__(256)
-igemm_relayout_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ xh, int N, int C, int Cp, int H, int W, int wtiles) {
+igemm_relayout_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ xh, int N, int C, int Cp, int H, int W, int wtiles, PreOp pre) {
     constexpr int EPC = 16 / (int)sizeof(E);
     constexpr int EPW = 4 / (int)sizeof(E);
     constexpr int TW = 8 * EPC;                            // pixels per tile
@@ -337,10 +341,18 @@ igemm_relayout_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ xh, int 
         const int item = threadIdx.x + 256 * k;
         const int cl = item >> 3, ch = item & 7;
         const int c = c0 + cl, wq = w0 + ch * EPC;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (c < C && wq < W) v = *reinterpret_cast<const uint4*>(x + (((size_t)n * C + c) * H + h) * W + wq);
+        union { uint4 q; E e[EPC]; } v;
+        v.q = make_uint4(0, 0, 0, 0);
+        if (c < C && wq < W) {
+            v.q = *reinterpret_cast<const uint4*>(x + (((size_t)n * C + c) * H + h) * W + wq);
+            if (pre.stats) {                                  // SiLU(GroupNorm(x)), rounded once to the storage type
+                const PreLane pl = pre_lane(pre, n, c, C);
+#pragma unroll
+                for (int i = 0; i < EPC; ++i) v.e[i] = from_f32<E>(pre_apply(to_f32<E>(v.e[i]), pl, true));
+            }
+        }
         uint32_t* d = tile + cl * PITCHW + ch * 4;
-        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+        d[0] = v.q.x; d[1] = v.q.y; d[2] = v.q.z; d[3] = v.q.w;
     }
     __syncthreads();
     // out: TW pixels x (64 / EPC) channel chunks
@@ -359,12 +371,14 @@ igemm_relayout_nchw_vec_kernel(const E* __restrict__ x, E* __restrict__ xh, int 
 
 template <typename E>
 __global__ void __launch_bounds__(256)
-igemm_pad_nhwc_kernel(const E* __restrict__ x, E* __restrict__ xh, size_t pixels, int C, int Cp) {
+igemm_pad_nhwc_kernel(const E* __restrict__ x, E* __restrict__ xh, size_t pixels, size_t pixels_per_image, int C, int Cp, PreOp pre) {
     const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= pixels * Cp) return;
     const int c = (int)(e % Cp);
     const size_t p = e / Cp;
-    xh[e] = c < C ? x[p * C + c] : from_f32<E>(0.f);
+    E v = c < C ? x[p * C + c] : from_f32<E>(0.f);
+    if (pre.stats && c < C) v = from_f32<E>(pre_apply(to_f32<E>(v), pre_lane(pre, (int)(p / pixels_per_image), c, C), true));
+    xh[e] = v;
 }
 
 template <typename E, int BM, int BN, int NST, bool PIX_A, int WGM = 2, int WGN = 2>
@@ -461,7 +475,7 @@ hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int
 
 template <typename E>
 static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias, void* y, const ConvGeom& g, const IgemmPost& post,
-                               bool nhwc, void* workspace, size_t xh_bytes, hipStream_t s) {
+                               const PreOp& pre, bool nhwc, void* workspace, size_t xh_bytes, hipStream_t s) {
     const E* xh = static_cast<const E*>(x);
     const int nsplit = igemm_split(g.T, g.K, g.Cp, g.R, sizeof(E) == 2 ? DT_F16 : DT_F32);
     float* part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + xh_bytes);   // only used when nsplit > 1
@@ -474,17 +488,17 @@ static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias,
         if (bx > 0x7fffffffLL || (g.Cp + 63) / 64 > 65535) return hipErrorInvalidValue;
         if (chunks)
             hipLaunchKernelGGL(igemm_relayout_nchw_vec_kernel<E>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
-                               (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.Hs, g.Ws, wtiles);
+                               (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.Hs, g.Ws, wtiles, pre);
         else
             hipLaunchKernelGGL(igemm_relayout_nchw_kernel<E>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
-                               (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.Hs, g.Ws, wtiles);
+                               (const E*)x, (E*)workspace, g.N, g.C, g.Cp, g.Hs, g.Ws, wtiles, pre);
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
         xh = static_cast<const E*>(workspace);
-    } else if (g.C != g.Cp) {
+    } else if (g.C != g.Cp || pre.stats) {               // padding needed, or GroupNorm + SiLU to apply: a copy in the workspace
         const size_t pixels = (size_t)g.N * g.Hs * g.Ws;
         const size_t blocks = (pixels * g.Cp + 255) / 256;
         if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(igemm_pad_nhwc_kernel<E>, dim3((unsigned)blocks), dim3(256), 0, s, (const E*)x, (E*)workspace, pixels, g.C, g.Cp);
+        hipLaunchKernelGGL(igemm_pad_nhwc_kernel<E>, dim3((unsigned)blocks), dim3(256), 0, s, (const E*)x, (E*)workspace, pixels, (size_t)g.Hs * g.Ws, g.C, g.Cp, pre);
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
         xh = static_cast<const E*>(workspace);
     }
@@ -494,8 +508,10 @@ static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias,
 
 hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias, void* y,
                                int N, int C, int H, int W, int K, int R, int st, int dt, bool nhwc,
-                               void* workspace, size_t xh_bytes, int up, const float* addvec, const void* residual, hipStream_t s) {
+                               void* workspace, size_t xh_bytes, int up, const PreOp* prep, const float* addvec, const void* residual,
+                               hipStream_t s) {
     IgemmPost post; post.addvec = addvec; post.residual = residual;
+    const PreOp pre = prep ? *prep : PreOp();
     ConvGeom g;
     g.up = up; g.Hs = H >> up; g.Ws = W >> up;
     g.N = N; g.C = C; g.Cp = (C + 7) / 8 * 8; g.H = H; g.W = W; g.K = K; g.R = R; g.st = st; g.pad = (R - 1) / 2;
@@ -503,7 +519,7 @@ hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias,
     g.T = N * g.Ho * g.Wo;
     return with_dtype(dt, [&](auto* tag) {
         using E = std::remove_pointer_t<decltype(tag)>;
-        return igemm_conv_t<E>(x, Wr, bias, y, g, post, nhwc, workspace, xh_bytes, s);
+        return igemm_conv_t<E>(x, Wr, bias, y, g, post, pre, nhwc, workspace, xh_bytes, s);
     });
 }
 

@@ -276,9 +276,17 @@ int wino_conv2d_fused(const void* x, const wino_filter* w_t, const float* bias, 
     if (rc != WINO_OK) return rc;
     if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
     if (w_t->variant == WINO_DIRECT) {
-        // the direct path reads x through the upsampling and adds the vector and the residual in its epilogue;
-        // it has no GroupNorm + SiLU on the way in
-        if (f->gn_stats) return WINO_ERR_VARIANT;
+        // the direct path reads x through the upsampling by address arithmetic, adds the vector and the residual
+        // in its epilogue, and applies GroupNorm + SiLU while it re-lays x (a channel-last x is then copied once)
+        PreOp dpre;
+        if (f->gn_stats) {
+            if (!f->gn_gamma || !f->gn_beta) return WINO_ERR_NULL;
+            if (f->gn_groups < 1 || C % f->gn_groups != 0) return WINO_ERR_DIM;
+            if ((reinterpret_cast<uintptr_t>(f->gn_stats) | reinterpret_cast<uintptr_t>(f->gn_gamma) |
+                 reinterpret_cast<uintptr_t>(f->gn_beta)) & 3u) return WINO_ERR_ALIGN;
+            dpre.stats = f->gn_stats; dpre.gamma = f->gn_gamma; dpre.beta = f->gn_beta;
+            dpre.groups = f->gn_groups; dpre.cpg = C / f->gn_groups;
+        }
         if (f->addvec && (reinterpret_cast<uintptr_t>(f->addvec) & 3u)) return WINO_ERR_ALIGN;
         const int dt = w_t->dtype;
         const size_t es = esize(dt);
@@ -289,12 +297,13 @@ int wino_conv2d_fused(const void* x, const wino_filter* w_t, const float* bias, 
             if (rb != yb && rb < ye && yb < re) return WINO_ERR_ALIAS;
         }
         const int up = f->upsample;
-        const size_t xh = igemm_xh_bytes(N, C, H >> up, W >> up, dt, layout);
+        const size_t xh = f->gn_stats ? igemm_xh_bytes(N, C, H >> up, W >> up, dt, WINO_NCHW)      // always a copy
+                                      : igemm_xh_bytes(N, C, H >> up, W >> up, dt, layout);
         const size_t need = xh + igemm_part_bytes(N, C, H, W, K, 3, 1, dt);
         if (need && (!workspace || workspace_bytes < need)) return WINO_ERR_WORKSPACE;
         if (need && !aligned16(workspace)) return WINO_ERR_ALIGN;
         return launch_igemm_conv2d(x, w_t->data, bias, y, N, C, H, W, K, 3, 1, dt, layout == WINO_NHWC, workspace, xh, up,
-                                   f->addvec, f->residual, static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+                                   f->gn_stats ? &dpre : nullptr, f->addvec, f->residual, static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
     }
     PreOp pre; PostOp post;
     pre.up = f->upsample;
@@ -421,7 +430,7 @@ int wino_igemm_conv2d(const void* x, const void* w_r, const float* bias, void* y
     if (need && (!workspace || workspace_bytes < need)) return WINO_ERR_WORKSPACE;
     if (need && !aligned16(workspace)) return WINO_ERR_ALIGN;
     return launch_igemm_conv2d(x, w_r, bias, y, N, C, H, W, K, R, stride, dtype, layout == WINO_NHWC,
-                               workspace, igemm_xh_bytes(N, C, H, W, dtype, layout), 0, nullptr, nullptr,
+                               workspace, igemm_xh_bytes(N, C, H, W, dtype, layout), 0, nullptr, nullptr, nullptr,
                                static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }

@@ -112,7 +112,8 @@ size_t groupnorm_stats_bytes(int N, int groups);
 hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, int dt, hipStream_t s);
 hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias, void* y,
                                int N, int C, int H, int W, int K, int R, int st, int dt, bool nhwc,
-                               void* workspace, size_t xh_bytes, int up, const float* addvec, const void* residual, hipStream_t s);
+                               void* workspace, size_t xh_bytes, int up, const PreOp* pre, const float* addvec, const void* residual,
+                               hipStream_t s);
 int igemm_split(int T, int K, int Cp, int R, int dt);   // number of partial products the path writes for a shape
 hipError_t launch_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
                                 int N, int C, int H, int W, int K, int dt, hipStream_t s);

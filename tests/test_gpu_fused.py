@@ -217,9 +217,24 @@ def test_direct_variant_fused(case, upsample, layout, dtype):
     assert err <= {"f32": 1e-5, "f16": 6e-4, "bf16": 3e-3}[dtype], (case, upsample, layout, dtype, err)
 
 
-def test_direct_variant_rejects_groupnorm():
-    x, w, b = synth.make_inputs(1, 8, 8, 4, 4, "f16", seed=2)
-    with pytest.raises(B.WinoError) as e:
-        B.conv2d_fused(x.to(DEV), w.to(DEV), b.to(DEV), B.WINO_DIRECT, gn_gamma=torch.ones(8, device=DEV), gn_beta=torch.zeros(8, device=DEV),
-                       gn_groups=2)
-    assert e.value.status == B.WINO_ERR_VARIANT
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("case", [(2, 24, 40, 9, 13, 4, False), (1, 64, 72, 8, 16, 32, True), (1, 40, 16, 6, 6, 8, True), (1, 640, 96, 4, 4, 32, False)])
+def test_direct_variant_groupnorm(case, layout, dtype):
+    """GroupNorm + SiLU applied while the direct path re-lays x (rows of whole chunks and not, C padded to 8 and not,
+    channel-last inputs that would otherwise be read in place, with and without the upsampling)."""
+    N, C, K, h, w_, G, upsample = case
+    x, w, b = synth.make_inputs(N, C, K, h, w_, dtype, seed=14000 + sum(case[:6]))
+    H, W = (2 * h, 2 * w_) if upsample else (h, w_)
+    gamma, beta, addvec, residual = _extras(N, C, K, H, W, dtype, 15 + sum(case[:6]))
+    ref = fo.conv2d_fused(_np(x), _np(w), _np(b), _np(gamma), _np(beta), G, 1e-5, _np(addvec), _np(residual), upsample=upsample)
+    perm = (lambda t: t.permute(0, 2, 3, 1).contiguous()) if layout == B.WINO_NHWC else (lambda t: t)
+    y = B.conv2d_fused(perm(x).to(DEV), w.to(DEV), b.to(DEV), B.WINO_DIRECT, layout, gamma.to(DEV), beta.to(DEV), G, 1e-5,
+                       addvec.to(DEV), perm(residual).to(DEV), upsample=upsample)
+    torch.cuda.synchronize()
+    y = y.float().cpu()
+    if layout == B.WINO_NHWC:
+        y = y.permute(0, 3, 1, 2)
+    err = oracle.rel_l2(y.numpy(), ref)
+    # the activated tensor is rounded once more than on the plain direct path
+    assert err <= {"f32": 1e-5, "f16": 1.2e-3, "bf16": 5e-3}[dtype], (case, layout, dtype, err)

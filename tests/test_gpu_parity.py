@@ -84,11 +84,6 @@ def test_direct_variant_through_every_entry_point():
         err = oracle.rel_l2(y.float().cpu().numpy(), ref)
         assert FP16_BAND[B.WINO_DIRECT][0] <= err <= FP16_BAND[B.WINO_DIRECT][1], err
     assert torch.equal(y1, y2) and torch.equal(y1, y4)
-    with pytest.raises(B.WinoError) as e:           # no GroupNorm + SiLU on the direct path
-        st = B.wino_groupnorm_stats(xd, 8)
-        B.wino_conv2d_fused(xd, w_t, bd, torch.empty((N, K, H, W), dtype=xd.dtype, device=DEV), ws, gn_stats=st,
-                            gn_gamma=torch.ones(C, device=DEV), gn_beta=torch.zeros(C, device=DEV), gn_groups=8)
-    assert e.value.status == B.WINO_ERR_VARIANT
     # the recommendation is what the binding's convenience call can be given directly
     v = B.wino_recommend_variant(1, 64, 256, 256, 64, B.WINO_F16)
     assert v == B.WINO_DIRECT
