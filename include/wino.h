@@ -235,6 +235,29 @@ int wino_igemm_conv2d(const void *x, const void *w_r, const float *bias, void *y
                       int N, int C, int H, int W, int K, int R, int stride, int dtype, int layout,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The same direct convolution with 8-bit floating-point operands (OCP E4M3: 4 exponent and 3 mantissa bits, largest
+ * value 448), fp32 accumulation on the 8-bit MFMA path of the chip.  The paper only remarks that its stack supports
+ * quantised operators and defines no scheme; this one is the plainest: one power-of-two scale per tensor,
+ *
+ *     xq = e4m3(clamp(x' * scale_x, +-448)),  wq = e4m3(clamp(w * scale_w, +-448)),
+ *     y  = conv(xq, wq) / (scale_x * scale_w) + bias (+ addvec + residual),        x' = x or SiLU(GroupNorm(x))
+ *
+ * with scales chosen by the caller (largest power of two that keeps max|.| * scale <= 448; activations after
+ * GroupNorm + SiLU are bounded, which makes a fixed scale safe).  Relative L2 error against the exact convolution on
+ * unit-variance data: about 3.8e-2 (tolerance of this path: 6e-2).  x and y are in `dtype` (any of the three storage
+ * types), NCHW or NHWC; R in {1, 3}, stride in {1, 2}.  The filter is quantised once (wino_fp8_filter_quantize, re-laid
+ * as for the implicit-GEMM path, wino_fp8_filter_bytes() bytes); the workspace (wino_fp8_workspace_bytes()) holds xq and
+ * any partial sums.  `f` may be NULL; its fused operators work as with a WINO_DIRECT filter (product_fp16 is ignored).
+ */
+size_t wino_fp8_filter_bytes(int K, int C, int R);
+int wino_fp8_filter_quantize(const void *w, void *w_q, int K, int C, int R, int dtype, float scale_w, void *stream);
+size_t wino_fp8_workspace_bytes(int N, int C, int H, int W, int K, int R, int stride);
+int wino_fp8_conv2d(const void *x, const void *w_q, const float *bias, void *y,
+                    int N, int C, int H, int W, int K, int R, int stride, int dtype, int layout,
+                    float scale_x, float scale_w, const wino_fusion *f,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

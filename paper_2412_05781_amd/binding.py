@@ -33,6 +33,7 @@ EXPORTS = [
     "wino_direct_conv2d", "wino_groupnorm_stats_bytes", "wino_groupnorm_stats", "wino_conv2d_fused",
     "wino_igemm_filter_bytes", "wino_igemm_filter_repack", "wino_igemm_workspace_bytes", "wino_igemm_conv2d",
     "wino_recommend_variant",
+    "wino_fp8_filter_bytes", "wino_fp8_filter_quantize", "wino_fp8_workspace_bytes", "wino_fp8_conv2d",
 ]
 
 
@@ -92,6 +93,12 @@ def lib() -> ctypes.CDLL:
         L.wino_groupnorm_stats.argtypes = [vp, vp, i, i, i, i, i, ctypes.c_float, i, i, vp]
         L.wino_conv2d_fused.restype = i
         L.wino_conv2d_fused.argtypes = [vp, fp, vp, vp, i, i, i, i, i, i, ctypes.POINTER(wino_fusion), vp, sz, vp]
+        L.wino_fp8_filter_bytes.restype = sz; L.wino_fp8_filter_bytes.argtypes = [i] * 3
+        L.wino_fp8_filter_quantize.restype = i
+        L.wino_fp8_filter_quantize.argtypes = [vp, vp, i, i, i, i, ctypes.c_float, vp]
+        L.wino_fp8_workspace_bytes.restype = sz; L.wino_fp8_workspace_bytes.argtypes = [i] * 7
+        L.wino_fp8_conv2d.restype = i
+        L.wino_fp8_conv2d.argtypes = [vp, vp, vp, vp] + [i] * 9 + [ctypes.c_float, ctypes.c_float, ctypes.POINTER(wino_fusion), vp, sz, vp]
         L.wino_recommend_variant.restype = i; L.wino_recommend_variant.argtypes = [i] * 6
         L.wino_igemm_filter_bytes.restype = sz; L.wino_igemm_filter_bytes.argtypes = [i] * 4
         L.wino_igemm_filter_repack.restype = i
@@ -390,7 +397,85 @@ def wino_igemm_conv2d(x: torch.Tensor, w_r: torch.Tensor, bias, y: torch.Tensor,
     return y
 
 
+def wino_fp8_filter_bytes(K, C, R) -> int:
+    return lib().wino_fp8_filter_bytes(K, C, R)
+
+
+def wino_fp8_filter_quantize(w: torch.Tensor, scale_w: float, stream=None) -> torch.Tensor:
+    """w[K,C,R,R] -> e4m3(w * scale_w), re-laid [R*R,K,Cq] plus a row of zeros (raw byte buffer)."""
+    _dev(w, "w")
+    K, C, R = int(w.shape[0]), int(w.shape[1]), int(w.shape[2])
+    if w.dim() != 4 or int(w.shape[3]) != R or w.dtype not in DTYPE_OF:
+        raise ValueError("w must be [K,C,R,R] in one of the storage types")
+    nbytes = wino_fp8_filter_bytes(K, C, R)
+    if nbytes == 0:
+        raise WinoError(WINO_ERR_DIM, "wino_fp8_filter_bytes")
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    _check(lib().wino_fp8_filter_quantize(_ptr(w), _ptr(buf), K, C, R, DTYPE_OF[w.dtype], ctypes.c_float(scale_w), _stream(stream)),
+           "wino_fp8_filter_quantize")
+    return buf
+
+
+def wino_fp8_workspace_bytes(N, C, H, W, K, R, stride) -> int:
+    return lib().wino_fp8_workspace_bytes(N, C, H, W, K, R, stride)
+
+
+def wino_fp8_conv2d(x: torch.Tensor, w_q: torch.Tensor, bias, y: torch.Tensor, K: int, R: int, stride: int, scale_x: float,
+                    scale_w: float, workspace: torch.Tensor, layout: int = WINO_NCHW, gn_stats=None, gn_gamma=None, gn_beta=None,
+                    gn_groups: int = 32, addvec=None, residual=None, upsample: bool = False, stream=None) -> torch.Tensor:
+    _dev(x, "x"); _dev(w_q, "w_q"); _dev(y, "y"); _dev(workspace, "workspace")
+    N, C, H, W = _unpack(x, layout)
+    if upsample:
+        H, W = 2 * H, 2 * W
+    pad = (R - 1) // 2
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    if tuple(y.shape) != _act_shape(N, K, Ho, Wo, layout) or y.dtype != x.dtype:
+        raise ValueError(f"expected y{_act_shape(N, K, Ho, Wo, layout)} of dtype {x.dtype}")
+    if w_q.numel() * w_q.element_size() < wino_fp8_filter_bytes(K, C, R):
+        raise ValueError("quantised filter buffer too small")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != K or not bias.is_cuda):
+        raise ValueError("bias must be a GPU fp32 tensor of K elements")
+    f = wino_fusion()
+    f.upsample = 1 if upsample else 0
+    if gn_stats is not None:
+        for t, cnt in ((gn_gamma, C), (gn_beta, C)):
+            if t is None or not t.is_cuda or t.dtype != torch.float32 or t.numel() != cnt or not t.is_contiguous():
+                raise ValueError("gn_gamma / gn_beta must be contiguous GPU fp32 tensors of C elements")
+        f.gn_stats, f.gn_gamma, f.gn_beta, f.gn_groups = gn_stats.data_ptr(), gn_gamma.data_ptr(), gn_beta.data_ptr(), gn_groups
+    if addvec is not None:
+        if not addvec.is_cuda or addvec.dtype != torch.float32 or tuple(addvec.shape) != (N, K) or not addvec.is_contiguous():
+            raise ValueError("addvec must be a contiguous GPU fp32 tensor [N, K]")
+        f.addvec = addvec.data_ptr()
+    if residual is not None:
+        _dev(residual, "residual")
+        if tuple(residual.shape) != tuple(y.shape) or residual.dtype != y.dtype:
+            raise ValueError("residual must have the shape and dtype of y")
+        f.residual = residual.data_ptr()
+    _check(lib().wino_fp8_conv2d(_ptr(x), _ptr(w_q), _ptr(bias), _ptr(y), N, C, H, W, K, R, stride, DTYPE_OF[x.dtype], layout,
+                                 ctypes.c_float(scale_x), ctypes.c_float(scale_w), ctypes.byref(f), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream)), "wino_fp8_conv2d")
+    return y
+
+
 # ---- convenience (allocation only) ------------------------------------------------------------
+def conv2d_fp8(x: torch.Tensor, w: torch.Tensor, bias, scale_x: float, scale_w: float, stride: int = 1, layout: int = WINO_NCHW,
+               **fused) -> torch.Tensor:
+    """Quantise the filter, allocate workspace and output, run the 8-bit direct path (fused operators by keyword)."""
+    N, C, H, W = _unpack(x, layout)
+    if fused.get("upsample"):
+        H, W = 2 * H, 2 * W
+    K, R = int(w.shape[0]), int(w.shape[2])
+    pad = (R - 1) // 2
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    y = torch.empty(_act_shape(N, K, Ho, Wo, layout), dtype=x.dtype, device=x.device)
+    w_q = wino_fp8_filter_quantize(w, scale_w)
+    ws = torch.empty(max(16, wino_fp8_workspace_bytes(N, C, H, W, K, R, stride)), dtype=torch.uint8, device=x.device)
+    if fused.get("gn_gamma") is not None and fused.get("gn_stats") is None:
+        fused["gn_stats"] = wino_groupnorm_stats(x, fused.get("gn_groups", 32), fused.pop("eps", 1e-5), layout)
+    fused.pop("eps", None)
+    return wino_fp8_conv2d(x, w_q, bias, y, K, R, stride, scale_x, scale_w, ws, layout, **fused)
+
+
 def conv2d_igemm(x: torch.Tensor, w: torch.Tensor, bias=None, stride: int = 1, layout: int = WINO_NCHW) -> torch.Tensor:
     """1x1 or 3x3 convolution with stride 1 or 2 through the implicit-GEMM path (filter re-layout, workspace, call)."""
     N, C, H, W = _unpack(x, layout)

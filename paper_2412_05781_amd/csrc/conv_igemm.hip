@@ -32,14 +32,16 @@ struct ConvGeom {
 struct IgemmPost {
     const float* addvec = nullptr;    // [N][K]
     const void* residual = nullptr;   // like y
+    float scale = 1.f;                // the accumulated sum is multiplied by this first (quantised operands: 1 / (sx * sw))
 };
 
 // PIX_A: the pixel operand supplies the rows of the block (outputs [t][k], channel-last y);
 // otherwise the filter does (outputs [k][t], NCHW y).
-template <typename E, int BM, int BN, int NST, bool PIX_A, int WGM = 2, int WGN = 2>
+// E = operand type (fp16, bf16, fp32, or fp8_t for the quantised path), EO = type of y and of the residual.
+template <typename E, typename EO, int BM, int BN, int NST, bool PIX_A, int WGM = 2, int WGN = 2>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* __restrict__ zero_row,
-                  const float* __restrict__ bias, E* __restrict__ y, float* __restrict__ part, ConvGeom g, IgemmPost post,
+                  const float* __restrict__ bias, EO* __restrict__ y, float* __restrict__ part, ConvGeom g, IgemmPost post,
                   int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd, int nsplit) {
     constexpr int RB = 128;
     constexpr int CPR = RB / 16;                          // 16-byte chunks per row per stage
@@ -163,28 +165,36 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
         if (q + NST - 1 < nstage) issue_next();             // refills the slot stage q-1 used
 
         const unsigned char* slot = lds + (q % NST) * STAGE_BYTES;
-        uint4 fa[CPR / 2][FM], fb[CPR / 2][FN];
+        constexpr int KCH = MmaChunks<E>::value;          // chunks per lane and MFMA step
+        constexpr int STEPS = CPR / (2 * KCH);
+        uint4 fa[STEPS][FM][KCH], fb[STEPS][FN][KCH];
 #pragma unroll
-        for (int ks = 0; ks < CPR / 2; ++ks) {
+        for (int ks = 0; ks < STEPS; ++ks) {
 #pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                const int row = wm * WTM + i * 32 + frag_row;
-                const int chunk = (2 * ks + frag_half) ^ ((row >> 1) & (CPR - 1));
-                fa[ks][i] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
-            }
+            for (int c = 0; c < KCH; ++c) {
 #pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int row = BM + wn * WTN + j * 32 + frag_row;
-                const int chunk = (2 * ks + frag_half) ^ ((row >> 1) & (CPR - 1));
-                fb[ks][j] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
+                for (int i = 0; i < FM; ++i) {
+                    const int row = wm * WTM + i * 32 + frag_row;
+                    const int chunk = (2 * KCH * ks + KCH * frag_half + c) ^ ((row >> 1) & (CPR - 1));
+                    fa[ks][i][c] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
+                }
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    const int row = BM + wn * WTN + j * 32 + frag_row;
+                    const int chunk = (2 * KCH * ks + KCH * frag_half + c) ^ ((row >> 1) & (CPR - 1));
+                    fb[ks][j][c] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
+                }
             }
         }
 #pragma unroll
-        for (int ks = 0; ks < CPR / 2; ++ks)
+        for (int ks = 0; ks < STEPS; ++ks)
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int j = 0; j < FN; ++j) Mma<E>::run(fa[ks][i], fb[ks][j], acc[i][j]);
+                for (int j = 0; j < FN; ++j) {
+                    if constexpr (KCH == 2) Mma<E>::run2(fa[ks][i][0], fa[ks][i][1], fb[ks][j][0], fb[ks][j][1], acc[i][j]);
+                    else Mma<E>::run(fa[ks][i][0], fb[ks][j][0], acc[i][j]);
+                }
     }
 
     // 32x32 accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
@@ -215,30 +225,30 @@ conv_igemm_kernel(const E* __restrict__ xh, const E* __restrict__ Wr, const E* _
             if (PIX_A) {
                 // rows are output pixels, the column is k: y[t][k], lanes along k
                 const float b = bias ? bias[cb] : 0.f;
-                const E* res = static_cast<const E*>(post.residual);
+                const EO* res = static_cast<const EO*>(post.residual);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int t = row_a0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
                     if (t < g.T) {
-                        float v = acc[i][j][r] + b;
+                        float v = acc[i][j][r] * post.scale + b;
                         if (post.addvec) v += post.addvec[(size_t)(t / HoWo) * g.K + cb];
-                        if (res) v += to_f32<E>(res[(size_t)t * g.K + cb]);
-                        y[(size_t)t * g.K + cb] = from_f32<E>(v);
+                        if (res) v += to_f32<EO>(res[(size_t)t * g.K + cb]);
+                        y[(size_t)t * g.K + cb] = from_f32<EO>(v);
                     }
                 }
             } else {
                 // rows are k, the column is an output pixel: y[n][k][p], lanes along p
                 const int n = cb / HoWo, p = cb - n * HoWo;
-                E* yp = y + (size_t)n * g.K * HoWo + p;
-                const E* rp = post.residual ? static_cast<const E*>(post.residual) + (size_t)n * g.K * HoWo + p : nullptr;
+                EO* yp = y + (size_t)n * g.K * HoWo + p;
+                const EO* rp = post.residual ? static_cast<const EO*>(post.residual) + (size_t)n * g.K * HoWo + p : nullptr;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int k = row_a0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
                     if (k < g.K) {
-                        float v = acc[i][j][r] + (bias ? bias[k] : 0.f);
+                        float v = acc[i][j][r] * post.scale + (bias ? bias[k] : 0.f);
                         if (post.addvec) v += post.addvec[(size_t)n * g.K + k];
-                        if (rp) v += to_f32<E>(rp[(size_t)k * HoWo]);
-                        yp[(size_t)k * HoWo] = from_f32<E>(v);
+                        if (rp) v += to_f32<EO>(rp[(size_t)k * HoWo]);
+                        yp[(size_t)k * HoWo] = from_f32<EO>(v);
                     }
                 }
             }
@@ -256,6 +266,7 @@ igemm_reduce_kernel(const float* __restrict__ part, const float* __restrict__ bi
     if (e >= total) return;
     float acc = 0.f;
     for (int sp = 0; sp < nsplit; ++sp) acc += part[(size_t)sp * total + e];
+    acc *= post.scale;
     const E* res = static_cast<const E*>(post.residual);
     if (PIX_A) {
         const int k = (int)(e % K), t = (int)(e / K);
@@ -381,8 +392,8 @@ igemm_pad_nhwc_kernel(const E* __restrict__ x, E* __restrict__ xh, size_t pixels
     xh[e] = v;
 }
 
-template <typename E, int BM, int BN, int NST, bool PIX_A, int WGM = 2, int WGN = 2>
-static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, E* y, float* part, int nsplit,
+template <typename E, typename EO, int BM, int BN, int NST, bool PIX_A, int WGM = 2, int WGN = 2>
+static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, EO* y, float* part, int nsplit,
                                    const ConvGeom& g, const IgemmPost& post, hipStream_t s) {
     const int rowsA = PIX_A ? g.T : g.K, rowsB = PIX_A ? g.K : g.T;
     const int tiles_m = (rowsA + BM - 1) / BM, tiles_n = (rowsB + BN - 1) / BN;
@@ -391,7 +402,7 @@ static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, 
     const int per_xcd = (int)((total + 7) / 8);
     constexpr int lds_bytes = (BM + BN) * 128 * NST;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
-    auto kern = conv_igemm_kernel<E, BM, BN, NST, PIX_A, WGM, WGN>;
+    auto kern = conv_igemm_kernel<E, EO, BM, BN, NST, PIX_A, WGM, WGN>;
     static bool attr_set = false;                 // per instantiation; raising the limit is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
@@ -405,7 +416,7 @@ static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, 
     if (nsplit > 1) {
         const size_t blocks = ((size_t)g.K * g.T + 255) / 256;
         if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((igemm_reduce_kernel<E, PIX_A>), dim3((unsigned)blocks), dim3(256), 0, s, part, bias, y, g.K, g.T, g.Ho * g.Wo, nsplit, post);
+        hipLaunchKernelGGL((igemm_reduce_kernel<EO, PIX_A>), dim3((unsigned)blocks), dim3(256), 0, s, part, bias, y, g.K, g.T, g.Ho * g.Wo, nsplit, post);
     }
     return hipGetLastError();
 }
@@ -431,7 +442,9 @@ static IgemmShape igemm_shape(int T, int K) {
 // reduction so that about two workgroups per compute unit are in flight, at least eight stages each
 // (the second kernel costs ~3 us, more than a short reduction gains).
 int igemm_split(int T, int K, int Cp, int R, int dt) {
+    // dt < 0: 8-bit operands, 128 reduction elements per stage
     const bool f16 = two_byte(dt);
+    if (dt < 0) Cp = (Cp + 1) / 2;                        // same stage count as 64-element stages over half the channels
     static const int forced = [] { const char* e = getenv("WINO_IGEMM_SPLIT"); return e ? atoi(e) : 0; }();       // tuning knob
     const int bke = f16 ? 64 : 32;
     const int nstage = R * R * ((Cp + bke - 1) / bke);
@@ -448,17 +461,17 @@ int igemm_split(int T, int K, int Cp, int R, int dt) {
     return sp < 1 ? 1 : sp;
 }
 
-template <typename E, bool PIX_A>
-static hipError_t launch_igemm_t(const E* xh, const E* Wr, const float* bias, E* y, float* part, int nsplit,
+template <typename E, typename EO, bool PIX_A>
+static hipError_t launch_igemm_t(const E* xh, const E* Wr, const float* bias, EO* y, float* part, int nsplit,
                                  const ConvGeom& g, const IgemmPost& post, hipStream_t s) {
     // rows of the block: pixels when y is channel-last, output channels otherwise
     const IgemmShape sh = igemm_shape(g.T, g.K);
     const int bm = PIX_A ? sh.tp : sh.tk, bn = PIX_A ? sh.tk : sh.tp;
-    if (bm == 256 && bn == 256) return launch_igemm_cfg<E, 256, 256, 2, PIX_A, 4, 4>(xh, Wr, bias, y, part, nsplit, g, post, s);
-    if (bm == 256 && bn == 128) return launch_igemm_cfg<E, 256, 128, 2, PIX_A, 4, 2>(xh, Wr, bias, y, part, nsplit, g, post, s);
-    if (bm == 128 && bn == 256) return launch_igemm_cfg<E, 128, 256, 2, PIX_A, 2, 4>(xh, Wr, bias, y, part, nsplit, g, post, s);
-    if (bm == 128) return launch_igemm_cfg<E, 128, 128, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, post, s);
-    return launch_igemm_cfg<E, 64, 64, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, post, s);
+    if (bm == 256 && bn == 256) return launch_igemm_cfg<E, EO, 256, 256, 2, PIX_A, 4, 4>(xh, Wr, bias, y, part, nsplit, g, post, s);
+    if (bm == 256 && bn == 128) return launch_igemm_cfg<E, EO, 256, 128, 2, PIX_A, 4, 2>(xh, Wr, bias, y, part, nsplit, g, post, s);
+    if (bm == 128 && bn == 256) return launch_igemm_cfg<E, EO, 128, 256, 2, PIX_A, 2, 4>(xh, Wr, bias, y, part, nsplit, g, post, s);
+    if (bm == 128) return launch_igemm_cfg<E, EO, 128, 128, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, post, s);
+    return launch_igemm_cfg<E, EO, 64, 64, 2, PIX_A>(xh, Wr, bias, y, part, nsplit, g, post, s);
 }
 
 hipError_t launch_igemm_filter_repack(const void* w, void* Wr, int K, int C, int R, int dt, hipStream_t s) {
@@ -502,8 +515,8 @@ static hipError_t igemm_conv_t(const void* x, const void* Wr, const float* bias,
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
         xh = static_cast<const E*>(workspace);
     }
-    return nhwc ? launch_igemm_t<E, true>(xh, (const E*)Wr, bias, (E*)y, part, nsplit, g, post, s)
-                : launch_igemm_t<E, false>(xh, (const E*)Wr, bias, (E*)y, part, nsplit, g, post, s);
+    return nhwc ? launch_igemm_t<E, E, true>(xh, (const E*)Wr, bias, (E*)y, part, nsplit, g, post, s)
+                : launch_igemm_t<E, E, false>(xh, (const E*)Wr, bias, (E*)y, part, nsplit, g, post, s);
 }
 
 hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias, void* y,
@@ -520,6 +533,132 @@ hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias,
     return with_dtype(dt, [&](auto* tag) {
         using E = std::remove_pointer_t<decltype(tag)>;
         return igemm_conv_t<E>(x, Wr, bias, y, g, post, pre, nhwc, workspace, xh_bytes, s);
+    });
+}
+
+// ---- quantised operands (E4M3, one power-of-two scale per tensor) ---------------------------------------------
+// w[K][C][R][R] -> e4m3(w * sw) as Wq[R*R][K][Cq] (Cq = C rounded up to 16), followed by a row of Cq zeros.
+template <typename E>
+__global__ void __launch_bounds__(256)
+igemm_filter_quant_kernel(const E* __restrict__ w, uint8_t* __restrict__ Wq, int K, int C, int Cq, int taps, float sw) {
+    const size_t total = (size_t)taps * K * Cq + Cq;
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    uint32_t v = 0;
+    if (e < (size_t)taps * K * Cq) {
+        const int c = (int)(e % Cq);
+        const size_t q = e / Cq;
+        const int k = (int)(q % K), tap = (int)(q / K);
+        if (c < C) v = quant_e4m3(to_f32<E>(w[((size_t)k * C + c) * taps + tap]) * sw);
+    }
+    Wq[e] = (uint8_t)v;
+}
+
+// x -> e4m3(x' * sx) as xq[N][H][W][Cq], x' = x or SiLU(GroupNorm(x)); four channels (one 32-bit store) per lane.
+template <typename E>
+__global__ void __launch_bounds__(256)
+igemm_quant_nhwc_kernel(const E* __restrict__ x, uint32_t* __restrict__ xq, size_t pixels, size_t pixels_per_image, int C, int Cq,
+                        float sx, PreOp pre) {
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int quads = Cq / 4;
+    if (e >= pixels * quads) return;
+    const int c0 = (int)(e % quads) * 4;
+    const size_t p = e / quads;
+    uint32_t out = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = c0 + i;
+        if (c < C) {
+            float v = to_f32<E>(x[p * C + c]);
+            if (pre.stats) v = pre_apply(v, pre_lane(pre, (int)(p / pixels_per_image), c, C), true);
+            out |= quant_e4m3(v * sx) << (8 * i);
+        }
+    }
+    xq[e] = out;
+}
+
+// NCHW source: a 32 (w) x 64 (c) tile of quantised bytes goes through LDS; reads run along w, 32-bit stores along c.
+template <typename E>
+__global__ void __launch_bounds__(256)
+igemm_quant_nchw_kernel(const E* __restrict__ x, uint32_t* __restrict__ xq, int N, int C, int Cq, int H, int W, int wtiles,
+                        float sx, PreOp pre) {
+    __shared__ uint8_t tile[64][36];
+    int b = blockIdx.x;
+    const int wt = b % wtiles; b /= wtiles;
+    const int h = b % H; const int n = b / H;
+    const int c0 = blockIdx.y * 64, w0 = wt * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int c = c0 + ty + 8 * k, wq = w0 + tx;
+        uint32_t q = 0;
+        if (c < C && wq < W) {
+            float v = to_f32<E>(x[(((size_t)n * C + c) * H + h) * W + wq]);
+            if (pre.stats) v = pre_apply(v, pre_lane(pre, n, c, C), true);
+            q = quant_e4m3(v * sx);
+        }
+        tile[ty + 8 * k][tx] = (uint8_t)q;
+    }
+    __syncthreads();
+    // 32 pixels x 16 channel quads
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int item = threadIdx.x + 256 * k;
+        const int cq = item & 15, wl = item >> 4;
+        const int wq = w0 + wl, c = c0 + cq * 4;
+        if (wq < W && c < Cq) {
+            const uint32_t v = (uint32_t)tile[cq * 4][wl] | ((uint32_t)tile[cq * 4 + 1][wl] << 8) |
+                               ((uint32_t)tile[cq * 4 + 2][wl] << 16) | ((uint32_t)tile[cq * 4 + 3][wl] << 24);
+            xq[((((size_t)n * H + h) * W + wq) * Cq + c) / 4] = v;
+        }
+    }
+}
+
+hipError_t launch_igemm_fp8_filter_quant(const void* w, void* Wq, int K, int C, int R, int dt, float sw, hipStream_t s) {
+    const int Cq = (C + 15) / 16 * 16, taps = R * R;
+    const size_t total = (size_t)taps * K * Cq + Cq;
+    const size_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+    return with_dtype(dt, [&](auto* tag) {
+        using E = std::remove_pointer_t<decltype(tag)>;
+        hipLaunchKernelGGL(igemm_filter_quant_kernel<E>, dim3((unsigned)blocks), dim3(256), 0, s, (const E*)w, (uint8_t*)Wq, K, C, Cq, taps, sw);
+        return hipGetLastError();
+    });
+}
+
+// x and y in `dt`; the workspace holds xq (xq_bytes) and then any partial sums.
+hipError_t launch_igemm_fp8_conv2d(const void* x, const void* Wq, const float* bias, void* y,
+                                   int N, int C, int H, int W, int K, int R, int st, int dt, bool nhwc,
+                                   void* workspace, size_t xq_bytes, int up, const PreOp* prep, const float* addvec,
+                                   const void* residual, float sx, float sw, hipStream_t s) {
+    IgemmPost post; post.addvec = addvec; post.residual = residual; post.scale = 1.f / (sx * sw);
+    const PreOp pre = prep ? *prep : PreOp();
+    ConvGeom g;
+    g.up = up; g.Hs = H >> up; g.Ws = W >> up;
+    g.N = N; g.C = C; g.Cp = (C + 15) / 16 * 16; g.H = H; g.W = W; g.K = K; g.R = R; g.st = st; g.pad = (R - 1) / 2;
+    g.Ho = (H + 2 * g.pad - R) / st + 1; g.Wo = (W + 2 * g.pad - R) / st + 1;
+    g.T = N * g.Ho * g.Wo;
+    return with_dtype(dt, [&](auto* tag) {
+        using EO = std::remove_pointer_t<decltype(tag)>;
+        const size_t pixels = (size_t)g.N * g.Hs * g.Ws;
+        if (nhwc) {
+            const size_t blocks = (pixels * (g.Cp / 4) + 255) / 256;
+            if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+            hipLaunchKernelGGL(igemm_quant_nhwc_kernel<EO>, dim3((unsigned)blocks), dim3(256), 0, s, (const EO*)x, (uint32_t*)workspace,
+                               pixels, (size_t)g.Hs * g.Ws, g.C, g.Cp, sx, pre);
+        } else {
+            const int wtiles = (g.Ws + 31) / 32;
+            const long long bx = (long long)g.N * g.Hs * wtiles;
+            if (bx > 0x7fffffffLL || (g.Cp + 63) / 64 > 65535) return hipErrorInvalidValue;
+            hipLaunchKernelGGL(igemm_quant_nchw_kernel<EO>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
+                               (const EO*)x, (uint32_t*)workspace, g.N, g.C, g.Cp, g.Hs, g.Ws, wtiles, sx, pre);
+        }
+        if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+        const int nsplit = igemm_split(g.T, g.K, g.Cp, g.R, -1);
+        float* part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + xq_bytes);
+        const fp8_t* xq = static_cast<const fp8_t*>(workspace);
+        return nhwc ? launch_igemm_t<fp8_t, EO, true>(xq, (const fp8_t*)Wq, bias, (EO*)y, part, nsplit, g, post, s)
+                    : launch_igemm_t<fp8_t, EO, false>(xq, (const fp8_t*)Wq, bias, (EO*)y, part, nsplit, g, post, s);
     });
 }
 

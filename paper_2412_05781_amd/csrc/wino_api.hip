@@ -435,4 +435,82 @@ int wino_igemm_conv2d(const void* x, const void* w_r, const float* bias, void* y
                ? WINO_OK : WINO_ERR_HIP;
 }
 
+namespace {
+bool scale_ok(float v) { return v > 0.f && v < 3.0e38f && v == v; }
+size_t fp8_xq_bytes(int N, int C, int H, int W) { return align_up((size_t)N * H * W * (size_t)round_up(C, 16)); }
+size_t fp8_part_bytes(int N, int C, int H, int W, int K, int R, int stride) {
+    const int pad = (R - 1) / 2;
+    const long long T = (long long)N * ((H + 2 * pad - R) / stride + 1) * ((W + 2 * pad - R) / stride + 1);
+    const int sp = igemm_split((int)T, K, round_up(C, 16), R, -1);
+    return sp > 1 ? align_up((size_t)sp * (size_t)K * (size_t)T * sizeof(float)) : 0;
+}
+}  // namespace
+
+size_t wino_fp8_filter_bytes(int K, int C, int R) {
+    if (!igemm_dims_ok(1, C, 1, 1, K, R, 1)) return 0;
+    const size_t Cq = (size_t)round_up(C, 16);
+    return (size_t)R * R * K * Cq + Cq;
+}
+
+int wino_fp8_filter_quantize(const void* w, void* w_q, int K, int C, int R, int dtype, float scale_w, void* stream) {
+    if (!w || !w_q) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (!igemm_dims_ok(1, C, 1, 1, K, R, 1) || !scale_ok(scale_w)) return WINO_ERR_DIM;
+    if (!aligned16(w) || !aligned16(w_q)) return WINO_ERR_ALIGN;
+    return launch_igemm_fp8_filter_quant(w, w_q, K, C, R, dtype, scale_w, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? WINO_OK : WINO_ERR_HIP;
+}
+
+size_t wino_fp8_workspace_bytes(int N, int C, int H, int W, int K, int R, int stride) {
+    if (!igemm_dims_ok(N, C, H, W, K, R, stride)) return 0;
+    return fp8_xq_bytes(N, C, H, W) + fp8_part_bytes(N, C, H, W, K, R, stride);
+}
+
+int wino_fp8_conv2d(const void* x, const void* w_q, const float* bias, void* y,
+                    int N, int C, int H, int W, int K, int R, int stride, int dtype, int layout,
+                    float scale_x, float scale_w, const wino_fusion* f,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+    if (!x || !w_q || !y) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    if (!igemm_dims_ok(N, C, H, W, K, R, stride) || !scale_ok(scale_x) || !scale_ok(scale_w)) return WINO_ERR_DIM;
+    const int up = f ? f->upsample : 0;
+    if (up != 0 && up != 1) return WINO_ERR_DIM;
+    if (up && ((H | W) & 1)) return WINO_ERR_DIM;
+    if (!aligned16(x) || !aligned16(w_q) || !aligned16(y) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)))
+        return WINO_ERR_ALIGN;
+    const int pad = (R - 1) / 2;
+    const int Ho = (H + 2 * pad - R) / stride + 1, Wo = (W + 2 * pad - R) / stride + 1;
+    const size_t es = esize(dtype);
+    const uintptr_t xb = reinterpret_cast<uintptr_t>(x), xe = xb + (size_t)N * C * (H >> up) * (W >> up) * es;
+    const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + (size_t)N * K * Ho * Wo * es;
+    if (xb < ye && yb < xe) return WINO_ERR_ALIAS;
+    PreOp pre;
+    const float* addvec = nullptr; const void* residual = nullptr;
+    if (f) {
+        if (f->gn_stats) {
+            if (!f->gn_gamma || !f->gn_beta) return WINO_ERR_NULL;
+            if (f->gn_groups < 1 || C % f->gn_groups != 0) return WINO_ERR_DIM;
+            if ((reinterpret_cast<uintptr_t>(f->gn_stats) | reinterpret_cast<uintptr_t>(f->gn_gamma) |
+                 reinterpret_cast<uintptr_t>(f->gn_beta)) & 3u) return WINO_ERR_ALIGN;
+            pre.stats = f->gn_stats; pre.gamma = f->gn_gamma; pre.beta = f->gn_beta;
+            pre.groups = f->gn_groups; pre.cpg = C / f->gn_groups;
+        }
+        if (f->addvec && (reinterpret_cast<uintptr_t>(f->addvec) & 3u)) return WINO_ERR_ALIGN;
+        if (f->residual) {
+            if (!aligned16(f->residual)) return WINO_ERR_ALIGN;
+            const uintptr_t rb = reinterpret_cast<uintptr_t>(f->residual), re = rb + (size_t)N * K * Ho * Wo * es;
+            if (rb != yb && rb < ye && yb < re) return WINO_ERR_ALIAS;
+        }
+        addvec = f->addvec; residual = f->residual;
+    }
+    const size_t xq = fp8_xq_bytes(N, C, H >> up, W >> up);
+    const size_t need = xq + fp8_part_bytes(N, C, H, W, K, R, stride);
+    if (!workspace || workspace_bytes < need) return WINO_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return WINO_ERR_ALIGN;
+    return launch_igemm_fp8_conv2d(x, w_q, bias, y, N, C, H, W, K, R, stride, dtype, layout == WINO_NHWC, workspace, xq, up,
+                                   pre.stats ? &pre : nullptr, addvec, residual, scale_x, scale_w,
+                                   static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+}
+
 }  // extern "C"

@@ -42,6 +42,14 @@ template <typename F> inline hipError_t with_dtype(int dt, F&& f) {
     return f(static_cast<float*>(nullptr));
 }
 
+// 8-bit floating-point operand (OCP E4M3) of the quantised direct path: storage only.
+struct fp8_t { uint8_t v; };
+// nearest E4M3 value of v after clamping to the format's range (+-448), ties to even
+__device__ __forceinline__ uint32_t quant_e4m3(float v) {
+    v = fminf(fmaxf(v, -448.f), 448.f);
+    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(v, v, 0, false) & 0xffu;
+}
+
 // element conversion helpers usable in kernels
 template <typename E> __device__ __forceinline__ float to_f32(E v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
@@ -114,7 +122,12 @@ hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias,
                                int N, int C, int H, int W, int K, int R, int st, int dt, bool nhwc,
                                void* workspace, size_t xh_bytes, int up, const PreOp* pre, const float* addvec, const void* residual,
                                hipStream_t s);
-int igemm_split(int T, int K, int Cp, int R, int dt);   // number of partial products the path writes for a shape
+int igemm_split(int T, int K, int Cp, int R, int dt);   // number of partial products the path writes for a shape (dt < 0: 8-bit operands)
+hipError_t launch_igemm_fp8_filter_quant(const void* w, void* Wq, int K, int C, int R, int dt, float sw, hipStream_t s);
+hipError_t launch_igemm_fp8_conv2d(const void* x, const void* Wq, const float* bias, void* y,
+                                   int N, int C, int H, int W, int K, int R, int st, int dt, bool nhwc,
+                                   void* workspace, size_t xq_bytes, int up, const PreOp* pre, const float* addvec,
+                                   const void* residual, float sx, float sw, hipStream_t s);
 hipError_t launch_direct_conv2d(const void* x, const void* w, const float* bias, void* y,
                                 int N, int C, int H, int W, int K, int dt, hipStream_t s);
 

@@ -33,6 +33,22 @@ template <> struct Mma<float> {
     }
 };
 
+// 8-bit operands: one 32x32x64 step takes 32 bytes per lane and operand, i.e. two 16-byte chunks (lanes 0-31
+// and 32-63 hold different chunk pairs).  Which byte lands on which k inside the instruction does not matter as
+// long as both operands are loaded the same way.  Format selectors 0 = E4M3; scale bytes 0x7f = 2^0.
+typedef int int8v_t __attribute__((ext_vector_type(8)));
+template <> struct Mma<fp8_t> {
+    static __device__ __forceinline__ void run2(const uint4& a0, const uint4& a1, const uint4& b0, const uint4& b1, float16_t& c) {
+        int8v_t a, b;
+        a[0] = a0.x; a[1] = a0.y; a[2] = a0.z; a[3] = a0.w; a[4] = a1.x; a[5] = a1.y; a[6] = a1.z; a[7] = a1.w;
+        b[0] = b0.x; b[1] = b0.y; b[2] = b0.z; b[3] = b0.w; b[4] = b1.x; b[5] = b1.y; b[6] = b1.z; b[7] = b1.w;
+        c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+    }
+};
+// chunks per lane, operand and MFMA step
+template <typename E> struct MmaChunks { static constexpr int value = 1; };
+template <> struct MmaChunks<fp8_t> { static constexpr int value = 2; };
+
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
