@@ -100,6 +100,32 @@ def test_fp8_fused_operators(dtype, layout):
     assert oracle.rel_l2(y.numpy(), exact) <= 6e-2
 
 
+@pytest.mark.parametrize("name,layout", [("E2_vae", B.WINO_NHWC), ("E3_vae", B.WINO_NCHW), ("C6_unet", B.WINO_NCHW)])
+def test_fp8_full_size_layers_sampled(name, layout):
+    """Full-size layers (256x256 blocks of 16 waves; a split reduction on the 8x8 one): 4096 sampled outputs and the
+    image corners against the quantisation model, evaluated one output at a time."""
+    layer = synth.LAYERS[name]
+    x, w, b = synth.make_layer_inputs(layer)
+    xn, wn = _np(x), _np(w)
+    sx, sw = f8.power_of_two_scale(xn), f8.power_of_two_scale(wn)
+    xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+    y = B.conv2d_fp8(xd, w.to(DEV), b.to(DEV), sx, sw, 1, layout)
+    torch.cuda.synchronize()
+    y = y.float().cpu()
+    if layout == B.WINO_NHWC:
+        y = y.permute(0, 3, 1, 2)
+    y = y.contiguous().numpy()
+    rng = np.random.default_rng(layer.index)
+    idx = rng.integers(0, y.size, size=4096)
+    H, W = layer.H, layer.W
+    idx[:5] = [0, W - 1, (H - 1) * W, H * W - 1, y.size - 1]
+    xq, wq = f8.round_to_e4m3(xn * sx), f8.round_to_e4m3(wn * sw)
+    ref = oracle.conv2d_direct_at(xq, wq, None, idx) / (sx * sw) + _np(b)[(idx // (H * W)) % layer.K]
+    err = np.linalg.norm(y.ravel()[idx] - ref) / np.linalg.norm(ref)
+    assert err <= OUT_TOL["f16"], (name, err)
+    assert np.isfinite(y).all()
+
+
 def test_fp8_argument_checks_and_sizes():
     assert B.wino_fp8_filter_bytes(8, 20, 3) == 9 * 8 * 32 + 32          # C rounded up to 16
     assert B.wino_fp8_filter_bytes(8, 8, 2) == 0

@@ -200,7 +200,8 @@ def test_layer_sweep_sampled_outputs(name):
 
 
 @pytest.mark.parametrize("name,variant", [("E4_vae", B.WINO_F2), ("C5_unet", B.WINO_F4), ("D1_sdxl", B.WINO_F2),
-                                          ("E5_vae_out", B.WINO_F2)])
+                                          ("E5_vae_out", B.WINO_F2), ("E4_vae", B.WINO_DIRECT), ("E2_vae", B.WINO_DIRECT),
+                                          ("C6_unet", B.WINO_DIRECT)])
 def test_large_layers_other_variant(name, variant):
     """The variant AUTO does not pick, on the largest workspaces (E4/F2: M alone is 2.1 GB, so byte
     offsets pass 2^31) and the smallest images."""
