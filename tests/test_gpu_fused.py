@@ -238,3 +238,40 @@ def test_direct_variant_groupnorm(case, layout, dtype):
     err = oracle.rel_l2(y.numpy(), ref)
     # the activated tensor is rounded once more than on the plain direct path
     assert err <= {"f32": 1e-5, "f16": 1.2e-3, "bf16": 5e-3}[dtype], (case, layout, dtype, err)
+
+
+@pytest.mark.parametrize("path", ["winograd_f2", "winograd_f4", "direct", "fp8"])
+def test_residual_block_composition(path):
+    """A whole Stable-Diffusion residual block through the fused calls: h = conv1(SiLU(GN(x))) + b1 + temb[n, k];
+    y = conv2(SiLU(GN(h))) + b2 + x.  The intermediate h stays on the GPU in fp16; the oracle runs the same two steps in fp64."""
+    from oracle import fp8_model as f8
+    N, C, H, W, G = 2, 64, 24, 24, 8
+    g = torch.Generator().manual_seed(77)
+    x = torch.randn(N, C, H, W, generator=g).to(torch.float16)
+    w1 = (torch.randn(C, C, 3, 3, generator=g) / (9 * C) ** 0.5).to(torch.float16)
+    w2 = (torch.randn(C, C, 3, 3, generator=g) / (9 * C) ** 0.5).to(torch.float16)
+    b1, b2 = 0.1 * torch.randn(C, generator=g), 0.1 * torch.randn(C, generator=g)
+    g1, be1 = 1 + 0.2 * torch.randn(C, generator=g), 0.2 * torch.randn(C, generator=g)
+    g2, be2 = 1 + 0.2 * torch.randn(C, generator=g), 0.2 * torch.randn(C, generator=g)
+    temb = 0.5 * torch.randn(N, C, generator=g)
+    h_ref = fo.conv2d_fused(_np(x), _np(w1), _np(b1), _np(g1), _np(be1), G, 1e-5, addvec=_np(temb))
+    y_ref = fo.conv2d_fused(h_ref, _np(w2), _np(b2), _np(g2), _np(be2), G, 1e-5, residual=_np(x))
+    d = lambda t: t.to(DEV)
+    xd = d(x)
+    if path == "fp8":
+        a1 = fo.silu(fo.groupnorm(_np(x), _np(g1), _np(be1), G, 1e-5))
+        a2 = fo.silu(fo.groupnorm(h_ref, _np(g2), _np(be2), G, 1e-5))
+        h = B.conv2d_fp8(xd, d(w1), d(b1), f8.power_of_two_scale(a1), f8.power_of_two_scale(_np(w1)), gn_gamma=d(g1), gn_beta=d(be1),
+                         gn_groups=G, addvec=d(temb))
+        y = B.conv2d_fp8(h, d(w2), d(b2), f8.power_of_two_scale(a2) / 2, f8.power_of_two_scale(_np(w2)), gn_gamma=d(g2), gn_beta=d(be2),
+                         gn_groups=G, residual=xd)
+        tol = 6e-2
+    else:
+        v = {"winograd_f2": B.WINO_F2, "winograd_f4": B.WINO_F4, "direct": B.WINO_DIRECT}[path]
+        h = B.conv2d_fused(xd, d(w1), d(b1), v, B.WINO_NCHW, d(g1), d(be1), G, 1e-5, addvec=d(temb))
+        y = B.conv2d_fused(h, d(w2), d(b2), v, B.WINO_NCHW, d(g2), d(be2), G, 1e-5, residual=xd)
+        tol = {"winograd_f2": 2e-3, "winograd_f4": 8e-3, "direct": 2e-3}[path]
+    torch.cuda.synchronize()
+    err = oracle.rel_l2(y.float().cpu().numpy(), y_ref)
+    print(f"residual block via {path}: relL2 {err:.3e}")
+    assert err <= tol, (path, err)
