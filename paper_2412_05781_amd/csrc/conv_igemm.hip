@@ -577,6 +577,38 @@ igemm_quant_nhwc_kernel(const E* __restrict__ x, uint32_t* __restrict__ xq, size
     xq[e] = out;
 }
 
+// Channel-last source with C a multiple of 8 and 16-byte alignment: one 16-byte load (8 or 2x4 channels) and one
+// 8-byte store per lane.
+template <typename E>
+__global__ void __launch_bounds__(256)
+igemm_quant_nhwc_vec_kernel(const E* __restrict__ x, uint2* __restrict__ xq, size_t pixels, size_t pixels_per_image, int C, int Cq,
+                            float sx, PreOp pre) {
+    constexpr int EPC = 16 / (int)sizeof(E);               // elements per 16-byte load
+    constexpr int LOADS = 8 / EPC;                         // loads per 8 output channels
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int octs = Cq / 8;
+    if (e >= pixels * octs) return;
+    const int c0 = (int)(e % octs) * 8;
+    const size_t p = e / octs;
+    uint32_t out[2] = {0u, 0u};
+    if (c0 < C) {                                          // C is a multiple of 8: the whole octet is inside
+        const int n = (int)(p / pixels_per_image);
+#pragma unroll
+        for (int l = 0; l < LOADS; ++l) {
+            union { uint4 q; E e[EPC]; } v;
+            v.q = *reinterpret_cast<const uint4*>(x + p * C + c0 + l * EPC);
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) {
+                const int j = l * EPC + i;
+                float f = to_f32<E>(v.e[i]);
+                if (pre.stats) f = pre_apply(f, pre_lane(pre, n, c0 + j, C), true);
+                out[j >> 2] |= quant_e4m3(f * sx) << (8 * (j & 3));
+            }
+        }
+    }
+    xq[e] = make_uint2(out[0], out[1]);
+}
+
 // NCHW source: a 32 (w) x 64 (c) tile of quantised bytes goes through LDS; reads run along w, 32-bit stores along c.
 template <typename E>
 __global__ void __launch_bounds__(256)
@@ -641,7 +673,12 @@ hipError_t launch_igemm_fp8_conv2d(const void* x, const void* Wq, const float* b
     return with_dtype(dt, [&](auto* tag) {
         using EO = std::remove_pointer_t<decltype(tag)>;
         const size_t pixels = (size_t)g.N * g.Hs * g.Ws;
-        if (nhwc) {
+        if (nhwc && g.C % 8 == 0) {
+            const size_t blocks = (pixels * (g.Cp / 8) + 255) / 256;
+            if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+            hipLaunchKernelGGL(igemm_quant_nhwc_vec_kernel<EO>, dim3((unsigned)blocks), dim3(256), 0, s, (const EO*)x, (uint2*)workspace,
+                               pixels, (size_t)g.Hs * g.Ws, g.C, g.Cp, sx, pre);
+        } else if (nhwc) {
             const size_t blocks = (pixels * (g.Cp / 4) + 255) / 256;
             if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
             hipLaunchKernelGGL(igemm_quant_nhwc_kernel<EO>, dim3((unsigned)blocks), dim3(256), 0, s, (const EO*)x, (uint32_t*)workspace,
