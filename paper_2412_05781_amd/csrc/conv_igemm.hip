@@ -646,6 +646,57 @@ igemm_quant_nchw_kernel(const E* __restrict__ x, uint32_t* __restrict__ xq, int 
     }
 }
 
+// The same with 16-byte accesses on both sides, for rows of whole 16-byte chunks: a tile of 64 channels x TW pixels;
+// a lane quantises one chunk along w into LDS bytes and later writes 16 adjacent channels of one pixel.
+template <typename E>
+__global__ void __launch_bounds__(256)
+igemm_quant_nchw_vec_kernel(const E* __restrict__ x, uint4* __restrict__ xq, int N, int C, int Cq, int H, int W, int wtiles,
+                            float sx, PreOp pre) {
+    constexpr int EPC = 16 / (int)sizeof(E);
+    constexpr int TW = 8 * EPC;                            // pixels per tile
+    constexpr int PITCH = TW + 4;                          // bytes per channel row (a multiple of 4, an odd number of words)
+    __shared__ __attribute__((aligned(16))) uint8_t tile[64 * PITCH];
+    int b = blockIdx.x;
+    const int wt = b % wtiles; b /= wtiles;
+    const int h = b % H; const int n = b / H;
+    const int c0 = blockIdx.y * 64, w0 = wt * TW;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int item = threadIdx.x + 256 * k;            // 64 channels x 8 chunks
+        const int cl = item >> 3, ch = item & 7;
+        const int c = c0 + cl, wq = w0 + ch * EPC;
+        uint32_t out[EPC / 4];
+#pragma unroll
+        for (int i = 0; i < EPC / 4; ++i) out[i] = 0u;
+        if (c < C && wq < W) {
+            union { uint4 q; E e[EPC]; } v;
+            v.q = *reinterpret_cast<const uint4*>(x + (((size_t)n * C + c) * H + h) * W + wq);
+            PreLane pl = {0.f, 0.f, false};
+            if (pre.stats) pl = pre_lane(pre, n, c, C);
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) {
+                float f = to_f32<E>(v.e[i]);
+                if (pre.stats) f = pre_apply(f, pl, true);
+                out[i >> 2] |= quant_e4m3(f * sx) << (8 * (i & 3));
+            }
+        }
+        uint32_t* d = reinterpret_cast<uint32_t*>(tile + cl * PITCH + ch * EPC);
+#pragma unroll
+        for (int i = 0; i < EPC / 4; ++i) d[i] = out[i];
+    }
+    __syncthreads();
+    // out: TW pixels x 4 groups of 16 channels
+    for (int item = threadIdx.x; item < TW * 4; item += 256) {
+        const int wl = item % TW, cg = item / TW;
+        const int wq = w0 + wl, c = c0 + cg * 16;
+        if (wq >= W || c >= Cq) continue;
+        uint32_t o[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[i >> 2] |= (uint32_t)tile[(cg * 16 + i) * PITCH + wl] << (8 * (i & 3));
+        xq[((((size_t)n * H + h) * W + wq) * Cq + c) / 16] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
 hipError_t launch_igemm_fp8_filter_quant(const void* w, void* Wq, int K, int C, int R, int dt, float sw, hipStream_t s) {
     const int Cq = (C + 15) / 16 * 16, taps = R * R;
     const size_t total = (size_t)taps * K * Cq + Cq;
@@ -684,11 +735,18 @@ hipError_t launch_igemm_fp8_conv2d(const void* x, const void* Wq, const float* b
             hipLaunchKernelGGL(igemm_quant_nhwc_kernel<EO>, dim3((unsigned)blocks), dim3(256), 0, s, (const EO*)x, (uint32_t*)workspace,
                                pixels, (size_t)g.Hs * g.Ws, g.C, g.Cp, sx, pre);
         } else {
-            const int wtiles = (g.Ws + 31) / 32;
+            constexpr int EPC = 16 / (int)sizeof(EO);
+            const bool chunks = g.Ws % EPC == 0;            // x is 16-byte aligned, so every row then is
+            const int tw = chunks ? 8 * EPC : 32;
+            const int wtiles = (g.Ws + tw - 1) / tw;
             const long long bx = (long long)g.N * g.Hs * wtiles;
             if (bx > 0x7fffffffLL || (g.Cp + 63) / 64 > 65535) return hipErrorInvalidValue;
-            hipLaunchKernelGGL(igemm_quant_nchw_kernel<EO>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
-                               (const EO*)x, (uint32_t*)workspace, g.N, g.C, g.Cp, g.Hs, g.Ws, wtiles, sx, pre);
+            if (chunks)
+                hipLaunchKernelGGL(igemm_quant_nchw_vec_kernel<EO>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
+                                   (const EO*)x, (uint4*)workspace, g.N, g.C, g.Cp, g.Hs, g.Ws, wtiles, sx, pre);
+            else
+                hipLaunchKernelGGL(igemm_quant_nchw_kernel<EO>, dim3((unsigned)bx, (unsigned)((g.Cp + 63) / 64)), dim3(256), 0, s,
+                                   (const EO*)x, (uint32_t*)workspace, g.N, g.C, g.Cp, g.Hs, g.Ws, wtiles, sx, pre);
         }
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
         const int nsplit = igemm_split(g.T, g.K, g.Cp, g.R, -1);
