@@ -1,0 +1,195 @@
+"""Timing tables for the paths around the Winograd convolution, one MI355X, fp16, HIP-graph replay on rotating
+buffer sets (so that x, filters and y come from beyond the 256 MB memory-side cache).  Each sub-command prints
+the table that the file of the same topic under ``profiles/`` records:
+
+    python -m paper_2412_05781_amd.timing fused          GroupNorm + SiLU + adds around the Winograd call
+    python -m paper_2412_05781_amd.timing upsample       2x upsampling read inside the call (Winograd and direct)
+    python -m paper_2412_05781_amd.timing flavours       1x1 and stride-2 convolutions through the implicit GEMM
+    python -m paper_2412_05781_amd.timing direct         3x3 stride 1: Winograd vs direct vs 8-bit direct
+    python -m paper_2412_05781_amd.timing half-product   the opt-in fp16 intermediate product
+    python -m paper_2412_05781_amd.timing vendor-gemm    the framework's batched GEMM on the GEMM stage's shapes
+
+"framework" columns call the stock deep-learning framework's own operators on the same tensors, as context.
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+
+import torch
+
+from . import binding as B
+from . import synth
+from .sweep import graph_time
+
+DEV = "cuda:0"
+DT = torch.float16
+MALL = 320 << 20
+
+
+def _w(K, C, R=3):
+    return (torch.randn(K, C, R, R, device=DEV) / (R * R * C) ** 0.5).to(DT)
+
+
+def _nsets(bytes_per_set, lo=2, hi=16):
+    return max(lo, min(hi, MALL // max(1, bytes_per_set) + 1))
+
+
+def _shape(N, C, H, W, layout):
+    return (N, H, W, C) if layout == B.WINO_NHWC else (N, C, H, W)
+
+
+def _lname(layout):
+    return "NHWC" if layout == B.WINO_NHWC else "NCHW"
+
+
+def cmd_fused(_):
+    for name in ("B_resblock", "D2_sdxl", "E1_vae"):
+        L = synth.LAYERS[name]
+        N, C, K, H, W = L.N, L.C, L.K, L.H, L.W
+        v = B.wino_resolve_variant(N, C, H, W, K, B.WINO_F16, B.WINO_AUTO)
+        wd, bd = _w(K, C), torch.randn(K, device=DEV) * 0.01
+        gamma, beta = torch.rand(C, device=DEV) + 0.5, torch.randn(C, device=DEV) * 0.1
+        n = _nsets((N * C * H * W + 2 * N * K * H * W) * 2 + B.wino_filter_bytes(K, C, B.WINO_F16, v), hi=24)
+        sets = [(torch.randn(N, C, H, W, device=DEV).to(DT), B.wino_filter_transform(wd, v), torch.empty(N, K, H, W, device=DEV, dtype=DT),
+                 torch.randn(N, K, H, W, device=DEV).to(DT), torch.randn(N, K, device=DEV)) for _ in range(n)]
+        ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v), dtype=torch.uint8, device=DEV)
+        st = torch.empty(B.wino_groupnorm_stats_bytes(N, 32), dtype=torch.uint8, device=DEV)
+        t_plain = graph_time(lambda i: B.wino_conv2d_ex(sets[i % n][0], sets[i % n][1], bd, sets[i % n][2], ws), 2 * n)
+        t_stats = graph_time(lambda i: B.wino_groupnorm_stats(sets[i % n][0], 32, out=st), 2 * n)
+
+        def fused(i):
+            x, wt, y, res, add = sets[i % n]
+            B.wino_groupnorm_stats(x, 32, out=st)
+            B.wino_conv2d_fused(x, wt, bd, y, ws, gn_stats=st, gn_gamma=gamma, gn_beta=beta, gn_groups=32, addvec=add, residual=res)
+        t_fused = graph_time(fused, 2 * n)
+        print(f"{name:12s} F{v}: plain call {t_plain*1e6:7.2f} us | groupnorm stats {t_stats*1e6:6.2f} us | stats + fused call "
+              f"{t_fused*1e6:7.2f} us | extra for GN+SiLU+adds {1e6*(t_fused-t_plain):+.1f} us", flush=True)
+
+
+def cmd_upsample(_):
+    cases = [("UNet up 2x1280 16->32", 2, 1280, 1280, 16, 16), ("UNet up 2x640 32->64", 2, 640, 640, 32, 32),
+             ("VAE up 512 128->256", 1, 512, 512, 128, 128), ("VAE up 256 256->512", 1, 256, 256, 256, 256)]
+    for name, N, C, K, h, w in cases:
+        H, W = 2 * h, 2 * w
+        v = B.wino_resolve_variant(N, C, H, W, K, B.WINO_F16, B.WINO_AUTO)
+        wd, bd = _w(K, C), torch.randn(K, device=DEV) * 0.01
+        n = _nsets((N * C * h * w + N * C * H * W + N * K * H * W) * 2 + B.wino_filter_bytes(K, C, B.WINO_F16, v), hi=12)
+        sets = [(torch.randn(N, C, h, w, device=DEV).to(DT), B.wino_filter_transform(wd, v), torch.empty(N, K, H, W, device=DEV, dtype=DT),
+                 torch.randn(N, C, H, W, device=DEV).to(DT)) for _ in range(n)]
+        ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v), dtype=torch.uint8, device=DEV)
+        t_f = graph_time(lambda i: B.wino_conv2d_fused(sets[i % n][0], sets[i % n][1], bd, sets[i % n][2], ws, upsample=True), 2 * n)
+        t_c = graph_time(lambda i: B.wino_conv2d_ex(sets[i % n][3], sets[i % n][1], bd, sets[i % n][2], ws), 2 * n)
+        t_u = graph_time(lambda i: torch.nn.functional.interpolate(sets[i % n][0], scale_factor=2, mode="nearest"), 2 * n)
+        x, wt, y, _ = sets[0]
+        B.wino_conv2d_fused(x, wt, bd, y, ws, upsample=True); torch.cuda.synchronize(); y1 = y.clone()
+        B.wino_conv2d_ex(torch.nn.functional.interpolate(x, scale_factor=2, mode="nearest"), wt, bd, y, ws); torch.cuda.synchronize()
+        same = torch.equal(y1, y)
+        wtd = B.wino_filter_transform(wd, B.WINO_DIRECT)
+        wsd = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, B.WINO_DIRECT), dtype=torch.uint8, device=DEV)
+        t_d = graph_time(lambda i: B.wino_conv2d_fused(sets[i % n][0], wtd, bd, sets[i % n][2], wsd, upsample=True), 2 * n)
+        xh = [s[0].permute(0, 2, 3, 1).contiguous() for s in sets]
+        yh = [torch.empty(N, H, W, K, device=DEV, dtype=DT) for _ in sets]
+        t_dh = graph_time(lambda i: B.wino_conv2d_fused(xh[i % n], wtd, bd, yh[i % n], wsd, B.WINO_NHWC, upsample=True), 2 * n)
+        rec = B.wino_recommend_variant(N, C, H, W, K, B.WINO_F16)
+        print(f"{name:22s} Winograd F{v} fused {t_f*1e6:8.2f} us | two-step: conv {t_c*1e6:8.2f} + framework upsample {t_u*1e6:6.2f} us "
+              f"(bitwise equal: {same}) | direct variant fused NCHW {t_d*1e6:8.2f} NHWC {t_dh*1e6:8.2f} us | recommended variant {rec}",
+              flush=True)
+
+
+def _igemm_case(name, N, C, K, H, W, R, st, framework=True, fp8=False, winograd=False):
+    pad = (R - 1) // 2
+    Ho, Wo = (H + 2 * pad - R) // st + 1, (W + 2 * pad - R) // st + 1
+    fl = 2 * N * K * C * Ho * Wo * R * R
+    wd, bd = _w(K, C, R), torch.randn(K, device=DEV) * 0.01
+    sw = 2.0 ** torch.floor(torch.log2(448.0 / wd.abs().max())).item()
+    out = [f"{name:26s}"]
+    for layout in (B.WINO_NCHW, B.WINO_NHWC):
+        n = _nsets((N * C * H * W + N * K * Ho * Wo) * 2 + 2 * K * C * R * R, hi=12)
+        sets = [(torch.randn(_shape(N, C, H, W, layout), device=DEV).to(DT), B.wino_igemm_filter_repack(wd), B.wino_fp8_filter_quantize(wd, sw),
+                 torch.empty(_shape(N, K, Ho, Wo, layout), device=DEV, dtype=DT)) for _ in range(n)]
+        ws = torch.empty(max(16, B.wino_igemm_workspace_bytes(N, C, H, W, K, R, st, B.WINO_F16, layout)), dtype=torch.uint8, device=DEV)
+        t = graph_time(lambda i: B.wino_igemm_conv2d(sets[i % n][0], sets[i % n][1], bd, sets[i % n][3], K, R, st, ws, layout), 2 * n)
+        out.append(f"direct {_lname(layout)} {t*1e6:8.2f} us ({fl/t/1e12:6.1f} TF)")
+        if fp8:
+            ws8 = torch.empty(max(16, B.wino_fp8_workspace_bytes(N, C, H, W, K, R, st)), dtype=torch.uint8, device=DEV)
+            t8 = graph_time(lambda i: B.wino_fp8_conv2d(sets[i % n][0], sets[i % n][2], bd, sets[i % n][3], K, R, st, 64.0, sw, ws8, layout), 2 * n)
+            out.append(f"8-bit {_lname(layout)} {t8*1e6:8.2f} us ({fl/t8/1e12:6.1f} TF)")
+        if winograd and R == 3 and st == 1:
+            v = B.wino_resolve_variant(N, C, H, W, K, B.WINO_F16, B.WINO_AUTO)
+            wt = B.wino_filter_transform(wd, v)
+            wsw = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v), dtype=torch.uint8, device=DEV)
+            tw = graph_time(lambda i: B.wino_conv2d_ex(sets[i % n][0], wt, bd, sets[i % n][3], wsw, layout), 2 * n)
+            out.append(f"Winograd F{v} {_lname(layout)} {tw*1e6:8.2f} us")
+        if framework and layout == B.WINO_NCHW:
+            for _ in range(2):
+                torch.nn.functional.conv2d(sets[0][0], wd, bd.to(DT), stride=st, padding=pad)
+            tt = graph_time(lambda i: torch.nn.functional.conv2d(sets[i % n][0], wd, bd.to(DT), stride=st, padding=pad), 2 * n)
+            out.append(f"framework conv2d {tt*1e6:8.2f} us")
+    print(" | ".join(out), flush=True)
+
+
+def cmd_flavours(_):
+    for c in [("3x3 s2 2x320 64->32", 2, 320, 320, 64, 64, 3, 2), ("3x3 s2 2x640 32->16", 2, 640, 640, 32, 32, 3, 2),
+              ("3x3 s2 2x1280 16->8", 2, 1280, 1280, 16, 16, 3, 2), ("3x3 s2 128 512->256", 1, 128, 128, 512, 512, 3, 2),
+              ("1x1 2x320->640 @32", 2, 320, 640, 32, 32, 1, 1), ("1x1 2x640->1280 @16", 2, 640, 1280, 16, 16, 1, 1),
+              ("1x1 2x1920->640 @32", 2, 1920, 640, 32, 32, 1, 1), ("1x1 512->512 @64", 1, 512, 512, 64, 64, 1, 1)]:
+        _igemm_case(*c, framework=True, fp8=True)
+
+
+def cmd_direct(_):
+    for c in [("E4 128@1024", 1, 128, 128, 1024, 1024, 3, 1), ("E3 256@512", 1, 256, 256, 512, 512, 3, 1),
+              ("E2 512@256", 1, 512, 512, 256, 256, 3, 1), ("E1 512@128", 1, 512, 512, 128, 128, 3, 1),
+              ("D2 2x640@64", 2, 640, 640, 64, 64, 3, 1), ("B 2x320@64", 2, 320, 320, 64, 64, 3, 1),
+              ("C4 2x1280@16", 2, 1280, 1280, 16, 16, 3, 1)]:
+        _igemm_case(*c, framework=False, fp8=True, winograd=True)
+
+
+def cmd_half_product(_):
+    for name in ("B_resblock", "C8_unet", "D2_sdxl", "E1_vae", "E2_vae", "E3_vae", "E4_vae"):
+        L = synth.LAYERS[name]
+        N, C, K, H, W = L.N, L.C, L.K, L.H, L.W
+        v = B.wino_resolve_variant(N, C, H, W, K, B.WINO_F16, B.WINO_AUTO)
+        wd, bd = _w(K, C), torch.randn(K, device=DEV) * 0.01
+        n = _nsets((N * C * H * W + N * K * H * W) * 2 + B.wino_filter_bytes(K, C, B.WINO_F16, v))
+        for layout in (B.WINO_NCHW, B.WINO_NHWC):
+            sets = [(torch.randn(_shape(N, C, H, W, layout), device=DEV).to(DT), B.wino_filter_transform(wd, v),
+                     torch.empty(_shape(N, K, H, W, layout), device=DEV, dtype=DT)) for _ in range(n)]
+            ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v), dtype=torch.uint8, device=DEV)
+            t0 = graph_time(lambda i: B.wino_conv2d_fused(sets[i % n][0], sets[i % n][1], bd, sets[i % n][2], ws, layout), 2 * n)
+            t1 = graph_time(lambda i: B.wino_conv2d_fused(sets[i % n][0], sets[i % n][1], bd, sets[i % n][2], ws, layout, product_fp16=True), 2 * n)
+            print(f"{name:12s} F{v} {_lname(layout)}: fp32 product {t0*1e6:8.2f} us ({L.direct_flops/t0/1e12:7.1f} TF) | fp16 product "
+                  f"{t1*1e6:8.2f} us ({L.direct_flops/t1/1e12:7.1f} TF)  x{t0/t1:.2f}", flush=True)
+
+
+def cmd_vendor_gemm(_):
+    for (K, T, C, b) in [(512, 4096, 512, 36), (320, 512, 320, 36), (1280, 512, 1280, 36), (640, 512, 640, 36), (1280, 128, 1280, 36)]:
+        n = _nsets(b * (K * C * 2 + T * C * 2 + K * T * 4))
+        Us = [torch.randn((b, K, C), device=DEV).to(DT) for _ in range(n)]
+        Vs = [torch.randn((b, T, C), device=DEV).to(DT) for _ in range(n)]
+        Ms = [torch.empty((b, K, T), device=DEV, dtype=torch.float32) for _ in range(n)]
+        Mh = [torch.empty((b, K, T), device=DEV, dtype=DT) for _ in range(n)]
+        variant = 4 if b == 36 else 2
+        t = graph_time(lambda i: B.wino_batched_gemm(Us[i % n], Vs[i % n], K, C, T, variant, out=Ms[i % n]), 2 * n)
+        for _ in range(2):
+            torch.bmm(Us[0], Vs[0].transpose(1, 2), out=Mh[0])
+        tv = graph_time(lambda i: torch.bmm(Us[i % n], Vs[i % n].transpose(1, 2), out=Mh[i % n]), 2 * n)
+        fl = 2 * b * K * T * C
+        print(f"K={K:5d} T={T:5d} C={C:5d} x{b}: this build (fp32 product) {t*1e6:8.2f} us ({fl/t/1e12:6.1f} TF) | framework bmm (fp16 product) "
+              f"{tv*1e6:8.2f} us ({fl/tv/1e12:6.1f} TF)", flush=True)
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("what", choices=["fused", "upsample", "flavours", "direct", "half-product", "vendor-gemm"])
+    a = ap.parse_args(argv)
+    if not torch.cuda.is_available():
+        print("timing: no GPU visible", file=sys.stderr)
+        return 2
+    {"fused": cmd_fused, "upsample": cmd_upsample, "flavours": cmd_flavours, "direct": cmd_direct,
+     "half-product": cmd_half_product, "vendor-gemm": cmd_vendor_gemm}[a.what](a)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
