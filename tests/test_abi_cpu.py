@@ -144,3 +144,11 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         B.lib()
+
+
+def test_measurement_tools_import_without_a_gpu():
+    """The timing and calibration tools are part of the package: they import on a CPU-only box, and the calibration
+    sources they name exist."""
+    from paper_2412_05781_amd import calibrate, sweep, timing
+    assert calibrate.names() == ["hbm_stream_few_workgroups", "l2_to_cu", "mfma_rates", "stream"]
+    assert callable(timing.main) and callable(sweep.main)
