@@ -1,0 +1,93 @@
+// Calibration: do MFMA work and L2 -> CU streaming overlap inside a compute unit?
+// One 16-wave workgroup per compute unit.  Eight waves run a register-only fp16 MFMA loop, eight stream an L2-resident
+// region (LDS-DMA loads, or plain loads into registers), each keeping 16 KB in flight.  Modes: MFMA waves only; streaming
+// waves only; both, the two kinds sharing every SIMD (waves 0-7 / 8-15); both, on different SIMDs (wave & 3 < 2 / >= 2);
+// both, on different compute units (even / odd workgroups, twice the work each).
+// In-bounds by construction: streaming addresses stay inside a 2 MB region of a 64 MB buffer, LDS slots inside 8 x 16 KB.
+#include <hip/hip_runtime.h>
+#include <cstdio>
+#include <cstdint>
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+
+template <int PLAIN>
+__global__ void __launch_bounds__(1024) k(const unsigned char* __restrict__ buf, float* out, int mode, int mfma_iters, int steps) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    bool do_mfma = true, do_stream = true, mfma_role = wave < 8;
+    int w = wave - 8;
+    if (mode == 1) do_stream = false;
+    if (mode == 2) do_mfma = false;
+    if (mode == 4) { mfma_role = (wave & 3) < 2; w = (wave >> 2) * 2 + (wave & 1); }
+    if (mode == 5) { do_mfma = !(blockIdx.x & 1); do_stream = (blockIdx.x & 1); mfma_iters *= 2; steps *= 2; }
+    if (mfma_role) {
+        if (!do_mfma) return;
+        half8_t a, b;
+        for (int i = 0; i < 8; ++i) { a[i] = (_Float16)1.0f; b[i] = (_Float16)0.5f; }
+        float16_t c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+        for (int it = 0; it < mfma_iters; ++it) {
+            c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c1, 0, 0, 0);
+            c2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c2, 0, 0, 0);
+            c3 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c3, 0, 0, 0);
+        }
+        float s = 0; for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+        if (s == 12345.678f) out[0] = s;
+    } else {
+        if (!do_stream) return;
+        constexpr int DEPTH = 16;
+        unsigned char* slot = lds + w * (DEPTH * 1024);
+        const size_t region = (size_t)2 << 20;
+        const unsigned char* base = buf + (size_t)(blockIdx.x % 16) * region;
+        if (PLAIN == 0) {
+            auto dma = [&](int s) {
+                const size_t off = ((size_t)s * 8 + w) * 1024 % region;
+                const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t*)(slot + (s % DEPTH) * 1024));
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(m0v), "v"(base + off + lane * 16) : "memory");
+            };
+            for (int d = 0; d < DEPTH; ++d) dma(d);
+            for (int s = 0; s < steps; ++s) { wait_vmcnt<DEPTH - 1>(); dma(s + DEPTH); }
+            wait_vmcnt<0>();
+            if (lds[tid] == 77 && lane == 99) out[1] = 1.f;
+        } else {
+            uint4 r[DEPTH];
+            auto ld = [&](int s) { const size_t off = ((size_t)s * 8 + w) * 1024 % region; return *reinterpret_cast<const uint4*>(base + off + lane * 16); };
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) r[d] = ld(d);
+            uint4 acc = make_uint4(0, 0, 0, 0);
+            for (int s = 0; s < steps; s += DEPTH) {
+#pragma unroll
+                for (int d = 0; d < DEPTH; ++d) { const uint4 v = r[d]; r[d] = ld(s + DEPTH + d); acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w; }
+            }
+            if (acc.x == 0x12345678u && acc.y == 77u) out[2] = 1.f;
+        }
+    }
+}
+
+int main() {
+    unsigned char* buf; float* out;
+    (void)hipMalloc(&buf, (size_t)64 << 20); (void)hipMalloc(&out, 64); (void)hipMemset(buf, 1, (size_t)64 << 20);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k<0>), hipFuncAttributeMaxDynamicSharedMemorySize, 8 * 16 * 1024);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k<1>), hipFuncAttributeMaxDynamicSharedMemorySize, 8 * 16 * 1024);
+    hipEvent_t e0, e1; (void)hipEventCreate(&e0); (void)hipEventCreate(&e1);
+    const char* names[6] = {"", "MFMA only", "streaming only", "both, sharing every SIMD", "both, on different SIMDs", "both, on different CUs"};
+    for (int plain = 0; plain < 2; ++plain) for (int mfma_iters : {10000, 2500}) for (int mode = 1; mode <= 5; ++mode) {
+        const int steps = 20000;
+        float best = 1e9f;
+        for (int rep = 0; rep < 3; ++rep) {
+            (void)hipEventRecord(e0);
+            if (plain) hipLaunchKernelGGL(k<1>, dim3(256), dim3(1024), 8 * 16 * 1024, 0, buf, out, mode, mfma_iters, steps);
+            else hipLaunchKernelGGL(k<0>, dim3(256), dim3(1024), 8 * 16 * 1024, 0, buf, out, mode, mfma_iters, steps);
+            (void)hipEventRecord(e1); (void)hipEventSynchronize(e1);
+            float ms; (void)hipEventElapsedTime(&ms, e0, e1); if (ms < best) best = ms;
+        }
+        const double flops = 256.0 * 8 * mfma_iters * 4 * 32768.0, bytes = 256.0 * 8 * (double)(steps + 16) * 1024.0;
+        printf("%-18s MFMA iterations %5d  %-26s %8.1f us", plain ? "loads to registers" : "LDS-DMA loads", mfma_iters, names[mode], best * 1e3);
+        if (mode == 1) printf("   %7.1f TFLOP/s", flops / (best * 1e-3) / 1e12);
+        if (mode == 2) printf("   %6.2f TB/s from L2", bytes / (best * 1e-3) / 1e12);
+        printf("\n");
+    }
+    return 0;
+}
