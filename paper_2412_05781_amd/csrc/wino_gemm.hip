@@ -281,10 +281,11 @@ int gemm_split(int rows, int cols, int Cp, int nbatch, int dt) {
     const int max_split = gemm_max_split(Cp, dt);
     int sp = 1;
     if (forced > 0) sp = forced;
-    else if (nbatch <= 16 && (bm < 128 || bn < 128) && blocks <= 320) {
+    else if (nbatch <= 16 && (bm < 128 || bn < 128) && blocks <= 320 && rows >= cols) {
         // measured: pays 6-10 % for F(2x2) with narrow blocks (images of 8x8, and 16x16 at batch 1)
         // while there are about as many workgroups as compute units; with the 36 batches of
-        // F(4x4) the extra copies of the product cost more than the GEMM stage gains
+        // F(4x4) the extra copies of the product cost more than the GEMM stage gains, and so they do with the
+        // operands swapped (channel-last: few rows, many columns)
         sp = (int)(640 / blocks);
         if (sp > 3) sp = 3;
         if (sp > max_split / 4) sp = max_split / 4;               // at least four stages per workgroup

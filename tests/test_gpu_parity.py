@@ -281,8 +281,8 @@ def test_long_rows(shape, variant, dtype):
 @pytest.mark.parametrize("dtype,shape", [("f16", (1, 1024, 256, 8, 8)), ("f16", (2, 576, 200, 8, 8)), ("f32", (1, 512, 160, 8, 8)),
                                          ("f16", (1, 640, 384, 16, 16))])
 def test_deep_layers_split_reduction(dtype, shape, layout):
-    """Small images with many channels: the GEMM stage cuts the reduction over c into ranges and the output
-    transform sums the partial products (F(2x2), either operand order)."""
+    """Small images with many channels: in NCHW the GEMM stage cuts the reduction over c into ranges and the output
+    transform sums the partial products (F(2x2)); channel-last (operands swapped) keeps the reduction whole."""
     N, C, K, H, W = shape
     x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=5000 + sum(shape))
     ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
