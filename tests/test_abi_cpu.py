@@ -150,5 +150,5 @@ def test_measurement_tools_import_without_a_gpu():
     """The timing and calibration tools are part of the package: they import on a CPU-only box, and the calibration
     sources they name exist."""
     from paper_2412_05781_amd import calibrate, sweep, timing
-    assert calibrate.names() == ["hbm_stream_few_workgroups", "l2_to_cu", "mfma_rates", "stream"]
+    assert calibrate.names() == ["hbm_stream_few_workgroups", "l2_to_cu", "mfma_rates", "mfma_vs_streaming_overlap", "stream"]
     assert callable(timing.main) and callable(sweep.main)
