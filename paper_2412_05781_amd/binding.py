@@ -494,7 +494,9 @@ def conv2d(x: torch.Tensor, w: torch.Tensor, bias=None, variant: int = WINO_AUTO
     N, C, H, W = _unpack(x, layout)
     K = int(w.shape[0])
     y = torch.empty(_act_shape(N, K, H, W, layout), dtype=x.dtype, device=x.device)
-    v = wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant)
+    # WINO_AUTO here means "whatever the library recommends for this shape", the direct variant included
+    v = (wino_recommend_variant(N, C, H, W, K, DTYPE_OF[x.dtype]) if variant == WINO_AUTO
+         else wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant))
     if v < 0:
         raise WinoError(WINO_ERR_DIM, "wino_resolve_variant")
     w_t = wino_filter_transform(w, v)          # WINO_DIRECT: the re-laid filter of the implicit-GEMM path
@@ -511,7 +513,8 @@ def conv2d_fused(x, w, bias=None, variant: int = WINO_AUTO, layout: int = WINO_N
         H, W = 2 * H, 2 * W
     K = int(w.shape[0])
     y = torch.empty(_act_shape(N, K, H, W, layout), dtype=x.dtype, device=x.device)
-    v = wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant)
+    v = (wino_recommend_variant(N, C, H, W, K, DTYPE_OF[x.dtype]) if variant == WINO_AUTO
+         else wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant))
     if v not in (WINO_F2, WINO_F4, WINO_DIRECT):
         raise WinoError(WINO_ERR_VARIANT, "conv2d_fused")
     stats = wino_groupnorm_stats(x, gn_groups, eps, layout) if gn_gamma is not None else None

@@ -179,6 +179,9 @@ SWEEP = [l.name for l in synth.ALL_LAYERS if l.name not in ("A_conv_in", "B_resb
 def _sampled_check(name, variant, n_samples=4096):
     layer = synth.LAYERS[name]
     x, w, b = synth.make_layer_inputs(layer)
+    if variant == B.WINO_AUTO:      # the Winograd variant the bench and the sweep time (the binding's own AUTO may pick the direct path)
+        variant = B.wino_resolve_variant(layer.N, layer.C, layer.H, layer.W, layer.K, B.DTYPE_OF[synth.TORCH_DTYPE[layer.dtype]], B.WINO_AUTO)
+        assert variant in (B.WINO_F2, B.WINO_F4)
     y = _run(x, w, b, variant)
     rng = np.random.default_rng(layer.index)
     idx = rng.integers(0, y.size, size=n_samples)
