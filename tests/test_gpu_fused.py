@@ -275,3 +275,46 @@ def test_residual_block_composition(path):
     err = oracle.rel_l2(y.float().cpu().numpy(), y_ref)
     print(f"residual block via {path}: relL2 {err:.3e}")
     assert err <= tol, (path, err)
+
+
+def test_entry_points_replay_correctly_from_a_hip_graph():
+    """Every entry point only enqueues kernels on the stream it is given (no allocation, no memset nodes), so a captured
+    sequence can be replayed; each replay, with fresh inputs copied in and eager work in between, must equal the eager result."""
+    N, C, K, H, W, G = 2, 64, 64, 16, 16, 8
+    g = torch.Generator().manual_seed(5)
+    wd = (torch.randn(K, C, 3, 3, generator=g) / (9 * C) ** 0.5).to(torch.float16).to(DEV)
+    bd = (0.1 * torch.randn(K, generator=g)).to(DEV)
+    gamma, beta = (1 + 0.2 * torch.randn(C, generator=g)).to(DEV), (0.2 * torch.randn(C, generator=g)).to(DEV)
+    x = torch.empty(N, C, H, W, dtype=torch.float16, device=DEV)
+    w_t, w_d, w_q = B.wino_filter_transform(wd, B.WINO_F4), B.wino_filter_transform(wd, B.WINO_DIRECT), B.wino_fp8_filter_quantize(wd, 1024.0)
+    ys = [torch.empty(N, K, H, W, dtype=torch.float16, device=DEV) for _ in range(3)]
+    ws = [torch.empty(max(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, B.WINO_F4), B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, B.WINO_DIRECT),
+                          B.wino_fp8_workspace_bytes(N, C, H, W, K, 3, 1)), dtype=torch.uint8, device=DEV) for _ in range(3)]
+    st = torch.empty(B.wino_groupnorm_stats_bytes(N, G), dtype=torch.uint8, device=DEV)
+
+    def run():
+        B.wino_groupnorm_stats(x, G, out=st)
+        B.wino_conv2d_fused(x, w_t, bd, ys[0], ws[0], gn_stats=st, gn_gamma=gamma, gn_beta=beta, gn_groups=G, residual=x)
+        B.wino_conv2d_fused(x, w_d, bd, ys[1], ws[1], gn_stats=st, gn_gamma=gamma, gn_beta=beta, gn_groups=G)
+        B.wino_fp8_conv2d(x, w_q, bd, ys[2], K, 3, 1, 32.0, 1024.0, ws[2])
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        x.copy_(torch.randn(N, C, H, W, generator=g).to(torch.float16))
+        run()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run()
+        for rep in range(3):
+            xin = torch.randn(N, C, H, W, generator=g).to(torch.float16)
+            x.copy_(xin)
+            graph.replay()
+            side.synchronize()
+            got = [y.clone() for y in ys]
+            for y in ys:
+                y.zero_()                                   # eager work between the replays
+            run()
+            side.synchronize()
+            for a, b in zip(got, ys):
+                assert torch.equal(a, b), rep
