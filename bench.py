@@ -1,16 +1,19 @@
 #!/usr/bin/env python3
 """Throughput of the Winograd 3x3 convolution path on one MI355X.
 
-A step is one pass of the whole activation-side path over one synthetic layer:
-activation transform -> alpha^2 batched MFMA GEMMs -> output transform + bias
-(one wino_conv2d_ex call).  The filter transform runs once per weight tensor,
-outside the timed region, and is reported separately.  Inputs are resident in
-HBM before the timed region; by default the step rotates over enough (x, U, y)
-sets to exceed the 256 MB Infinity Cache, so x and U come from HBM.
+A step is one pass of the whole activation-side path over one synthetic layer (one wino_conv2d_ex call): activation
+transform -> alpha^2 batched MFMA products -> output transform + bias, in the variant WINO_AUTO resolves to (for most
+layers the last two run as ONE kernel).  The filter transform runs once per weight tensor, outside the timed region,
+and is reported separately.  Inputs are resident in HBM before the timed region; every step rotates over enough
+(x, U, y) sets to exceed the 256 MB Infinity Cache, so x and U come from HBM.
 
-Prints ONE JSON line: direct-equivalent TFLOP/s = 2*N*K*C*H*W*9 / t, the
-roofline of the dominant kernel (from per-kernel HIP-event timings taken on
-the launch stream), and the CPU oracle timed on the host cores.
+The headline (`value`, `ms_per_step`, `roofline`, `cpu_baseline`) is the SDv1.5 residual-block layer at batch 2, timed
+with the host clock over exactly --steps steps.  `layers` then carries every layer of the workload groups (18), each
+timed by HIP-graph replay with HIP events on the launch stream: microseconds per call, direct-equivalent TFLOP/s =
+2*N*K*C*H*W*9 / t, the per-kernel durations, the kernel that holds the MFMA work as a fraction of the dense MFMA peak and
+of its binding roof, and the whole-tensor relative L2 error against the CPU oracle.
+
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -27,10 +30,13 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"f16": 2500.0, "f32": 157.3}     # dense MFMA, published
 PEAK_HBM_GBS = 8000.0
 MALL_BYTES = 256 << 20
-# HBM bytes per GEMM launch from rocprofv3 --pmc (FETCH_SIZE x 1.99 + WRITE_SIZE, both KiB per
-# dispatch; the factors come from a plain copy kernel of known size in the same runs), see
-# profiles/B_resblock_f4_pmc_traffic.txt.  Only for workloads that were profiled.
-MEASURED_TRAFFIC = {("B_resblock", 4): int((10135.0 * 1.99 + 23040.0) * 1024)}
+HEADLINE = "B_resblock"
+WORKLOAD_LAYERS = ["A_conv_in", "B_resblock", "C1_unet", "C2_unet", "C3_unet", "C4_unet", "C5_unet", "C6_unet", "C7_unet",
+                   "C8_unet", "D1_sdxl", "D2_sdxl", "D3_sdxl", "E1_vae", "E2_vae", "E3_vae", "E4_vae", "E5_vae_out"]
+# HBM bytes per launch of the headline's dominant kernel, from two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE), scaled by
+# what the same counters read for a plain copy of known size; typed in from the profile named beside it (not measured in
+# this run).  Keyed by (layer, variant); absent -> null.
+PROFILED_TRAFFIC = {}
 
 
 def parse():
@@ -38,11 +44,114 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--layer", default="B_resblock", help="name from paper_2412_05781_amd.synth.LAYERS")
-    ap.add_argument("--variant", default="auto", choices=["auto", "f2", "f4"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layer", default=HEADLINE, help="headline layer, a name from paper_2412_05781_amd.synth.LAYERS")
+    ap.add_argument("--layers", default="all", help="'all' (the 18 layers of the workload groups), 'none', or a comma-separated list")
+    ap.add_argument("--variant", default="auto", choices=["auto", "f2", "f4", "fused_f2"])
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip every oracle run (baseline timing and parity figures)")
     ap.add_argument("--no-rotate", action="store_true", help="reuse one buffer set (cache-warm x, U, y)")
     return ap.parse_args()
+
+
+class LayerRun:
+    """Device buffers of one layer in one variant: rotating (x, U, y) sets, workspace, per-stage buffers."""
+
+    def __init__(self, layer, want, dev, rotate=True, cpu_inputs=None):
+        import torch
+        from paper_2412_05781_amd import binding as B
+        from paper_2412_05781_amd import synth
+        self.B, self.torch, self.layer = B, torch, layer
+        N, C, K, H, W = layer.N, layer.C, layer.K, layer.H, layer.W
+        self.tdt = synth.TORCH_DTYPE[layer.dtype]
+        self.dt = B.DTYPE_OF[self.tdt]
+        self.esz = 2 if layer.dtype == "f16" else 4
+        self.variant = B.wino_resolve_variant(N, C, H, W, K, self.dt, want)
+        assert self.variant in (B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2), self.variant
+        self.alpha, self.Cp, self.T = B.wino_transformed_dims(N, C, H, W, K, self.variant)
+        self.a2 = self.alpha * self.alpha
+        if cpu_inputs is not None:                   # the seeded CPU recipe (needed where the oracle checks the result)
+            x, w, b = cpu_inputs
+            xd, wd, self.bd = x.to(dev), w.to(dev), b.to(dev)
+        else:                                        # same distributions, drawn on the device from the layer's seed
+            g = torch.Generator(device=dev); g.manual_seed(synth.BASE_SEED + layer.index)
+            xd = torch.randn((N, C, H, W), device=dev, generator=g).to(self.tdt)
+            wd = (torch.randn((K, C, 3, 3), device=dev, generator=g) / (9.0 * C) ** 0.5).to(self.tdt)
+            self.bd = torch.randn((K,), device=dev, generator=g) * 0.01
+        self.wd = wd
+        w_t = B.wino_filter_transform(wd, self.variant)
+        set_bytes = (N * C * H * W + N * K * H * W) * self.esz + w_t.buf.numel()
+        self.nsets = max(2, min(24, -(-(MALL_BYTES + (64 << 20)) // set_bytes))) if rotate else 1
+        self.sets = []
+        for i in range(self.nsets):
+            xi = xd if i == 0 else xd.clone()
+            wti = w_t if i == 0 else B.Filter(w_t.buf.clone(), B.wino_filter())
+            if i:
+                d = wti.desc
+                d.data, d.K, d.C, d.dtype, d.variant = wti.buf.data_ptr(), K, C, self.dt, self.variant
+            self.sets.append((xi, wti, torch.empty((N, K, H, W), dtype=self.tdt, device=dev)))
+        self.ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, self.dt, self.variant), dtype=torch.uint8, device=dev)
+        self.dev = dev
+
+    def step(self, i):
+        xi, wti, yi = self.sets[i % self.nsets]
+        self.B.wino_conv2d_ex(xi, wti, self.bd, yi, self.ws)
+
+    def filter_ms(self):
+        torch, B = self.torch, self.B
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            B.wino_filter_transform(self.wd, self.variant)
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / 10
+
+    def stage_times(self):
+        """Each kernel launched back to back on rotating buffers (its input comes from beyond the caches), averaged over a
+        HIP-graph replay between two HIP events on the launch stream.  Returns ({kernel: seconds}, name of the kernel
+        that holds the MFMA work)."""
+        from paper_2412_05781_amd.gputime import graph_time
+        torch, B, L = self.torch, self.B, self.layer
+        N, C, K, H, W = L.N, L.C, L.K, L.H, L.W
+        n, v = self.nsets, self.variant
+        per_set = self.a2 * self.T * self.Cp * self.esz + (0 if v == B.WINO_FUSED_F2 else self.a2 * K * self.T * 4)
+        nv = max(2, min(n, (8 << 30) // max(1, per_set)))          # V / M sets: rotate, within 8 GB
+        Vb = [torch.empty((self.a2, self.T, self.Cp), dtype=self.tdt, device=self.dev) for _ in range(nv)]
+        for i in range(nv):
+            B.wino_input_transform(self.sets[i % n][0], v, out=Vb[i])
+        out = {"input_transform": graph_time(lambda i: B.wino_input_transform(self.sets[i % n][0], v, out=Vb[i % nv]), 2 * n)}
+        U = lambda i: self.sets[i % n][1].buf.view(self.tdt)
+        if v == B.WINO_FUSED_F2:
+            out["fused_gemm_output"] = graph_time(
+                lambda i: B.wino_fused_gemm_output(U(i), Vb[i % nv], self.bd, N, C, H, W, K, out=self.sets[i % n][2]), 2 * n)
+            return out, "fused_gemm_output"
+        Mb = [torch.empty((self.a2, K, self.T), dtype=torch.float32, device=self.dev) for _ in range(nv)]
+        for i in range(nv):
+            B.wino_batched_gemm(U(i), Vb[i], K, C, self.T, v, out=Mb[i])
+        out["batched_gemm"] = graph_time(lambda i: B.wino_batched_gemm(U(i), Vb[i % nv], K, C, self.T, v, out=Mb[i % nv]), 2 * n)
+        out["output_transform"] = graph_time(
+            lambda i: B.wino_output_transform(Mb[i % nv], self.bd, N, K, H, W, self.tdt, v, out=self.sets[i % n][2]), 2 * n)
+        return out, "batched_gemm"
+
+    def report(self, t_layer, stages, main_kernel):
+        """Per-layer record: times, direct-equivalent rate, the MFMA kernel against both roofs."""
+        B, L = self.B, self.layer
+        N, C, K, H, W = L.N, L.C, L.K, L.H, L.W
+        e, a2, T, Cp = self.esz, self.a2, self.T, self.Cp
+        flops = 2 * a2 * K * C * T
+        b_u, b_v, b_m, b_y = a2 * K * Cp * e, a2 * T * Cp * e, a2 * K * T * 4, N * K * H * W * e
+        kbytes = {"input_transform": N * C * H * W * e + b_v, "batched_gemm": b_u + b_v + b_m,
+                  "output_transform": b_m + b_y + 4 * K, "fused_gemm_output": b_u + b_v + b_y + 4 * K}
+        t = stages[main_kernel]
+        t_mfma, t_hbm = flops / (PEAK_TFLOPS[L.dtype] * 1e12), kbytes[main_kernel] / (PEAK_HBM_GBS * 1e9)
+        mfma_frac, hbm_frac = t_mfma / t, t_hbm / t
+        rec = {"name": L.name, "variant": {B.WINO_F2: "F2", B.WINO_F4: "F4", B.WINO_FUSED_F2: "FUSED_F2"}[self.variant],
+               "us": t_layer * 1e6, "tflops": L.direct_flops / t_layer / 1e12,
+               "kernel_us": {k: v * 1e6 for k, v in stages.items()},
+               "kernel_GBs": {k: kbytes[k] / v / 1e9 for k, v in stages.items()},
+               "gemm_kernel": main_kernel, "gemm_us": t * 1e6, "gemm_tflops": flops / t / 1e12, "gemm_mfma_frac": mfma_frac,
+               "bound": "hbm" if t_hbm >= t_mfma else "mfma", "frac": max(mfma_frac, hbm_frac),
+               "rotating_buffer_sets": self.nsets}
+        return rec, flops, kbytes[main_kernel]
 
 
 def main():
@@ -56,145 +165,62 @@ def main():
     import torch
     from paper_2412_05781_amd import binding as B
     from paper_2412_05781_amd import synth
+    from paper_2412_05781_amd.gputime import graph_time
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    want = {"auto": B.WINO_AUTO, "f2": B.WINO_F2, "f4": B.WINO_F4, "fused_f2": B.WINO_FUSED_F2}[args.variant]
+    oracle = None
+    if not args.no_cpu_baseline:
+        import oracle                      # test infrastructure: only this leg of the bench touches it
+
+    def parity(layer, cpu_inputs, y_dev):
+        x, w, b = cpu_inputs
+        t0 = time.perf_counter()
+        ref = oracle.conv2d_direct(x.float().numpy(), w.float().numpy(), b.numpy())
+        dt_or = time.perf_counter() - t0
+        return oracle.rel_l2(y_dev.float().cpu().numpy(), ref), dt_or
+
+    # ---- headline: exactly --steps steps of the whole path, host clock, barrier = device synchronisation -----------
     layer = synth.LAYERS[args.layer]
-    N, C, K, H, W = layer.N, layer.C, layer.K, layer.H, layer.W
-    dt = B.DTYPE_OF[synth.TORCH_DTYPE[layer.dtype]]
-    esz = 2 if layer.dtype == "f16" else 4
-    want = {"auto": B.WINO_AUTO, "f2": B.WINO_F2, "f4": B.WINO_F4}[args.variant]
-    variant = B.wino_resolve_variant(N, C, H, W, K, dt, want)
-    assert variant in (B.WINO_F2, B.WINO_F4)
-    alpha, Cp, T = B.wino_transformed_dims(N, C, H, W, K, variant)
-    a2 = alpha * alpha
-
-    x, w, b = synth.make_layer_inputs(layer)
-    xd, wd, bd = x.to(dev), w.to(dev), b.to(dev)
-
-    # ---- filter transform: once per weight, timed on its own ----------------------------
-    w_t = B.wino_filter_transform(wd, variant)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(10):
-        B.wino_filter_transform(wd, variant)
-    e1.record(); torch.cuda.synchronize()
-    filter_ms = e0.elapsed_time(e1) / 10
-
-    # ---- buffer sets: rotate so that x, U, y stream from HBM -----------------------------
-    set_bytes = xd.numel() * esz + w_t.buf.numel() + N * K * H * W * esz
-    nsets = 1 if args.no_rotate else max(2, -(-(MALL_BYTES + (64 << 20)) // set_bytes))
-    sets = []
-    for i in range(nsets):
-        xi = xd if i == 0 else xd.clone()
-        wti = w_t if i == 0 else B.Filter(w_t.buf.clone(), B.wino_filter())
-        if i:
-            d = wti.desc
-            d.data, d.K, d.C, d.dtype, d.variant = wti.buf.data_ptr(), K, C, dt, variant
-        yi = torch.empty((N, K, H, W), dtype=xd.dtype, device=dev)
-        sets.append((xi, wti, yi))
-    ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, dt, variant), dtype=torch.uint8, device=dev)
-
-    def step(i):
-        xi, wti, yi = sets[i % nsets]
-        B.wino_conv2d_ex(xi, wti, bd, yi, ws)
-
-    # ---- the timed region ----------------------------------------------------------------------
+    cpu_in = synth.make_layer_inputs(layer)
+    run = LayerRun(layer, want, dev, rotate=not args.no_rotate, cpu_inputs=cpu_in)
+    filter_ms = run.filter_ms()
     for i in range(args.warmup):
-        step(i)
+        run.step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i)
+        run.step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tflops = layer.direct_flops / (ms_per_step * 1e-3) / 1e12
-
-    # ---- per-kernel durations: each kernel launched back to back between two HIP events
-    #      on the launch stream (torch's current stream is the one handed to the library) --
-    # V and M rotate like x, U and y do, so that no stage finds its input warm from its own previous launch
-    Vbufs = [torch.empty((a2, T, Cp), dtype=xd.dtype, device=dev) for _ in range(nsets)]
-    Mbufs = [torch.empty((a2, K, T), dtype=torch.float32, device=dev) for _ in range(nsets)]
-    for i in range(nsets):                          # valid contents for the stages that read them
-        B.wino_input_transform(sets[i][0], variant, out=Vbufs[i])
-        B.wino_batched_gemm(sets[i][1].buf.view(xd.dtype), Vbufs[i], K, C, T, variant, out=Mbufs[i])
-    torch.cuda.synchronize()
-    reps = 2 * nsets                                # every buffer set twice per replay
-
-    def time_kernel(fn):
-        """Average GPU duration of one launch: `reps` launches captured in a HIP graph on a side
-        stream (so the host's launch cost is out of the picture), replayed between two HIP events
-        recorded on that same stream."""
-        side = torch.cuda.Stream()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            for i in range(3):
-                fn(i)
-            side.synchronize()
-            with torch.cuda.graph(g, stream=side):
-                for i in range(reps):
-                    fn(i)
-            g.replay()
-            side.synchronize()
-            best = float("inf")
-            for _ in range(5):
-                a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(side)
-                g.replay()
-                z.record(side)
-                side.synchronize()
-                best = min(best, a.elapsed_time(z))
-        return best / reps * 1e-3                   # seconds per launch
-
-    t_in = time_kernel(lambda i: B.wino_input_transform(sets[i % nsets][0], variant, out=Vbufs[i % nsets]))
-    t_gemm = time_kernel(lambda i: B.wino_batched_gemm(sets[i % nsets][1].buf.view(xd.dtype), Vbufs[i % nsets], K, C, T, variant,
-                                                       out=Mbufs[i % nsets]))
-    t_out = time_kernel(lambda i: B.wino_output_transform(Mbufs[i % nsets], bd, N, K, H, W, xd.dtype, variant, out=sets[i % nsets][2]))
-
-    bytes_in = N * C * H * W * esz + a2 * T * Cp * esz
-    flops_gemm = 2 * a2 * K * C * T
-    bytes_gemm = a2 * K * Cp * esz + a2 * T * Cp * esz + a2 * K * T * 4
-    bytes_out = a2 * K * T * 4 + N * K * H * W * esz + K * 4
-    stages = {
-        "input_transform": {"us": t_in * 1e6, "bound": "hbm", "achieved": bytes_in / t_in / 1e9,
-                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": bytes_in / t_in / 1e9 / PEAK_HBM_GBS},
-        "batched_gemm": {"us": t_gemm * 1e6, "bound": "mfma", "achieved": flops_gemm / t_gemm / 1e12,
-                         "peak": PEAK_TFLOPS[layer.dtype], "unit": "TFLOP/s",
-                         "frac": flops_gemm / t_gemm / 1e12 / PEAK_TFLOPS[layer.dtype],
-                         "operand_GBs": bytes_gemm / t_gemm / 1e9},
-        "output_transform": {"us": t_out * 1e6, "bound": "hbm", "achieved": bytes_out / t_out / 1e9,
-                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": bytes_out / t_out / 1e9 / PEAK_HBM_GBS},
-    }
-    # The GEMM stage is the path's one dense contraction and the longest kernel.  Its binding roof
-    # is the smaller of the MFMA roof and the HBM roof at its algorithmic intensity.
-    g = stages["batched_gemm"]
-    g["hbm_frac"] = bytes_gemm / t_gemm / 1e9 / PEAK_HBM_GBS
-    t_mfma, t_hbm = flops_gemm / (PEAK_TFLOPS[layer.dtype] * 1e12), bytes_gemm / (PEAK_HBM_GBS * 1e9)
-    if t_hbm >= t_mfma:
-        roofline = {"bound": "hbm", "achieved": bytes_gemm / t_gemm / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": g["hbm_frac"]}
+    t_graph = graph_time(run.step, 2 * run.nsets)
+    stages, main_kernel = run.stage_times()
+    head, flops, kbytes = run.report(t_graph, stages, main_kernel)
+    t = stages[main_kernel]
+    if head["bound"] == "hbm":
+        roofline = {"bound": "hbm", "achieved": kbytes / t / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": kbytes / t / 1e9 / PEAK_HBM_GBS}
     else:
-        roofline = {"bound": "mfma", "achieved": g["achieved"], "peak": g["peak"], "unit": "TFLOP/s", "frac": g["frac"]}
-    roofline.update({"kernel": "wino_gemm_kernel", "avg_launch_us": g["us"], "mfma_frac": g["frac"],
-                     "algorithmic_bytes": bytes_gemm, "algorithmic_flops": flops_gemm,
-                     "traffic": MEASURED_TRAFFIC.get((layer.name, variant))})
+        roofline = {"bound": "mfma", "achieved": flops / t / 1e12, "peak": PEAK_TFLOPS[layer.dtype], "unit": "TFLOP/s",
+                    "frac": head["gemm_mfma_frac"]}
+    prof = PROFILED_TRAFFIC.get((layer.name, head["variant"]))
+    roofline.update({"kernel": main_kernel, "avg_launch_us": t * 1e6, "mfma_frac": head["gemm_mfma_frac"],
+                     "algorithmic_bytes": kbytes, "algorithmic_flops": flops,
+                     "traffic": prof[0] if prof else None, "traffic_source": prof[1] if prof else None})
 
-    # ---- CPU baseline leg: the oracle, timed on the host cores; its first run also gives the parity figure of
-    #      what was just timed (the oracle is test infrastructure: nothing outside this leg touches it) ------------
     cpu, rel = None, None
-    if not args.no_cpu_baseline:
-        import oracle
-        xn, wn, bn = x.float().numpy(), w.float().numpy(), b.numpy()
-        y_gpu = sets[0][2].float().cpu().numpy()
-        t_or = time.perf_counter()
-        ref = oracle.conv2d_direct(xn, wn, bn)
-        first = time.perf_counter() - t_or
-        rel = oracle.rel_l2(y_gpu, ref)
+    if oracle is not None:
+        # CPU baseline: the oracle as it stands on the host cores, on the headline layer; its first run also gives the
+        # parity figure of what was just timed
+        run.step(0)
+        torch.cuda.synchronize()
+        rel, first = parity(layer, cpu_in, run.sets[0][2])
+        xn, wn, bn = cpu_in[0].float().numpy(), cpu_in[1].float().numpy(), cpu_in[2].numpy()
         best, spent, runs = first, first, 1
         while spent < 10.0 and runs < 200:       # about ten seconds of CPU work
             t_or = time.perf_counter()
@@ -204,20 +230,48 @@ def main():
         cpu = {"value": layer.direct_flops / best / 1e12, "unit": "TFLOP/s (direct-equivalent)",
                "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"whole layer {layer.name}, fp64 direct correlation, best of {runs} runs ({best:.3f} s)"}
+    head["rel_l2_vs_oracle"] = rel
+    del run
+    torch.cuda.empty_cache()
 
+    # ---- every layer of the workload groups, graph-timed --------------------------------------------------------------
+    names = [] if args.layers == "none" else (WORKLOAD_LAYERS if args.layers == "all" else args.layers.split(","))
+    layers_out = []
+    for name in names:
+        if name == layer.name:
+            layers_out.append(head)
+            continue
+        L = synth.LAYERS[name]
+        cin = synth.make_layer_inputs(L) if oracle is not None else None
+        r = LayerRun(L, want, dev, rotate=not args.no_rotate, cpu_inputs=cin)
+        tl = graph_time(r.step, 2 * r.nsets)
+        st, mk = r.stage_times()
+        rec, _, _ = r.report(tl, st, mk)
+        if oracle is not None:
+            r.step(0)
+            torch.cuda.synchronize()
+            rec["rel_l2_vs_oracle"], _ = parity(L, cin, r.sets[0][2])
+        layers_out.append(rec)
+        print(f"bench: {name} {rec['variant']} {rec['us']:.1f} us {rec['tflops']:.0f} TFLOP/s", file=sys.stderr, flush=True)
+        del r, cin
+        torch.cuda.empty_cache()
+
+    N, C, K, H, W = layer.N, layer.C, layer.K, layer.H, layer.W
     out = {
         "metric": "direct-equivalent TFLOP/s per 3x3 conv layer; % of MFMA peak (GEMM stage)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": layer.dtype, "data": "synthetic",
         "config": {"workload": f"{layer.name}: 3x3 s1 p1 conv N={N} C={C} K={K} H=W={H} {layer.dtype} NCHW",
-                   "variant": f"F({variant}x{variant},3x3)", "rotating_buffer_sets": nsets,
+                   "variant": head["variant"], "rotating_buffer_sets": head["rotating_buffer_sets"],
                    "filter_transform_ms_once_per_weight": filter_ms},
-        "gemm_pct_of_mfma_peak": 100.0 * stages["batched_gemm"]["frac"],
+        "gemm_pct_of_mfma_peak": 100.0 * head["gemm_mfma_frac"],
         "rel_l2_vs_oracle": rel,
+        "graph_replay_us_per_step": t_graph * 1e6,
         "roofline": roofline,
-        "stages": stages,
+        "stages": head["kernel_us"],
         "cpu_baseline": cpu,
+        "layers": layers_out,
     }
     print(json.dumps(out))
 

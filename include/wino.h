@@ -70,8 +70,14 @@ typedef enum wino_dtype { WINO_F32 = 0, WINO_F16 = 1, WINO_BF16 = 2 } wino_dtype
  * rounding only; faster than the Winograd path where there are few channels and
  * many pixels, see wino_recommend_variant).  wino_direct_conv2d is a third thing:
  * a one-lane-per-output checking kernel.
+ * WINO_FUSED_F2: F(2x2,3x3) with steps (ii) and (iii) in ONE kernel (two launches per convolution
+ * instead of three).  Step (iii) is linear in the product, so a workgroup that owns a block of
+ * (output channels x tiles) walks the 16 positions in turn, keeps one product block in the MFMA
+ * accumulators and adds it at once, with its +-1 coefficients, into four output accumulators; the
+ * product M is never stored (the paper's locality argument: dependent steps stay on chip).  Same U and
+ * V as WINO_F2, same error (~5e-4 for fp16); workspace = V only.
  */
-typedef enum wino_variant { WINO_AUTO = 0, WINO_DIRECT = 1, WINO_F2 = 2, WINO_F4 = 4 } wino_variant;
+typedef enum wino_variant { WINO_AUTO = 0, WINO_DIRECT = 1, WINO_F2 = 2, WINO_F4 = 4, WINO_FUSED_F2 = 12 } wino_variant;
 
 /* Layout of x and y only (w is always [K][C][3][3]); NHWC = x[N][H][W][C], y[N][H][W][K]. */
 typedef enum wino_layout { WINO_NCHW = 0, WINO_NHWC = 1 } wino_layout;
@@ -82,7 +88,7 @@ typedef struct wino_filter {
     void *data;      /* device, U[alpha^2][K][Cp] in `dtype`, Cp = C rounded up to 8 */
     int K, C;
     int dtype;       /* wino_dtype   */
-    int variant;     /* wino_variant, resolved: WINO_F2 or WINO_F4 */
+    int variant;     /* wino_variant, resolved: WINO_F2, WINO_F4, WINO_FUSED_F2 or WINO_DIRECT */
 } wino_filter;
 
 int wino_version(void);                         /* major*10000 + minor*100 + patch */
@@ -158,6 +164,27 @@ int wino_output_transform(const float *M, const float *bias, void *y, int N, int
                           int dtype, int variant, int layout, void *stream);
 
 /*
+ * Steps (ii) and (iii) + bias in one kernel, the second launch of WINO_FUSED_F2 (F(2x2,3x3) only):
+ *   U[16][K][Cp], V[16][T][Cp] as above  ->  y[N][K][H][W] (WINO_NCHW) or y[N][H][W][K] (WINO_NHWC) in `dtype`.
+ * block_shape = -1 lets the library choose the workgroup's block; 0..3 name one (rows x columns of the
+ * block, rows = output channels for NCHW and tiles for NHWC): 0 = 64x64, 1 = 64x128, 2 = 128x64,
+ * 3 = 128x128.  Every shape gives the same sums in the same order; the argument exists so that tests and
+ * measurements can reach each kernel instantiation on small inputs.  WINO_ERR_VARIANT for other values.
+ */
+int wino_fused_gemm_output(const void *U, const void *V, const float *bias, void *y,
+                           int N, int C, int H, int W, int K, int dtype, int layout, int block_shape, void *stream);
+
+/*
+ * wino_batched_gemm with a named block shape instead of the library's choice, so that every instantiation
+ * of the step (ii) kernel can be reached on small, ragged inputs (tests, measurements):
+ *   0 = 128x128, 1 = 128x64, 2 = 64x128, 3 = 64x64 (4 waves, 2 ring slots), 4 = 256x256 (16 waves),
+ *   5 = 128x32, 6 = 32x128 (3 slots), 7 = 128x128 with 3 slots, 8 = 256x128 (8 waves, 3 slots);
+ * rows x columns = rows of the first operand x rows of the second.  WINO_ERR_VARIANT outside 0..8.
+ */
+int wino_batched_gemm_shape(const void *U, const void *V, float *M, int K, int C, int T,
+                            int dtype, int variant, int block_shape, void *stream);
+
+/*
  * The operators on either side of the convolution inside a residual block, fused into the
  * transforms so that the activation is not rewritten to memory in between (the paper's Section
  * "Techniques" argues for keeping dependent steps local; it names none of these operators, the
@@ -173,7 +200,8 @@ int wino_output_transform(const float *M, const float *bias, void *y, int N, int
  *                   instead of fp32, which halves the largest tensor of the path (1.2-1.4x on layers with
  *                   large images).  Accumulation stays fp32.  The relative L2 error of F(4x4) grows from
  *                   about 3.1e-3 to 3.8-4.2e-3 (F(2x2): 5e-4 to 6.4e-4), and |M| must stay below 65504.
- *                   Ignored where the reduction is split into partial products, and for fp32 storage.
+ *                   Ignored where the reduction is split into partial products, for fp32 storage, and by
+ *                   WINO_FUSED_F2 (which has no stored product).
  * A filter prepared with WINO_DIRECT is accepted too: the direct path reads x through the upsampling by address
  * arithmetic, adds in its epilogue, and applies GroupNorm + SiLU while it re-lays x into its workspace (the activated
  * tensor is rounded once to the storage type there; a channel-last x is then copied once instead of read in place).

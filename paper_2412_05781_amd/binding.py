@@ -20,7 +20,7 @@ WINO_OK = 0
 WINO_ERR_NULL, WINO_ERR_DIM, WINO_ERR_DTYPE, WINO_ERR_VARIANT = 1, 2, 3, 4
 WINO_ERR_ALIGN, WINO_ERR_WORKSPACE, WINO_ERR_ALIAS, WINO_ERR_HIP, WINO_ERR_LAYOUT = 5, 6, 7, 8, 9
 WINO_F32, WINO_F16, WINO_BF16 = 0, 1, 2
-WINO_AUTO, WINO_DIRECT, WINO_F2, WINO_F4 = 0, 1, 2, 4
+WINO_AUTO, WINO_DIRECT, WINO_F2, WINO_F4, WINO_FUSED_F2 = 0, 1, 2, 4, 12
 WINO_NCHW, WINO_NHWC = 0, 1
 
 DTYPE_OF = {torch.float32: WINO_F32, torch.float16: WINO_F16, torch.bfloat16: WINO_BF16}
@@ -34,6 +34,7 @@ EXPORTS = [
     "wino_igemm_filter_bytes", "wino_igemm_filter_repack", "wino_igemm_workspace_bytes", "wino_igemm_conv2d",
     "wino_recommend_variant",
     "wino_fp8_filter_bytes", "wino_fp8_filter_quantize", "wino_fp8_workspace_bytes", "wino_fp8_conv2d",
+    "wino_fused_gemm_output", "wino_batched_gemm_shape",
 ]
 
 
@@ -84,6 +85,10 @@ def lib() -> ctypes.CDLL:
         L.wino_input_transform.argtypes = [vp, vp, i, i, i, i, i, i, i, vp]
         L.wino_batched_gemm.restype = i
         L.wino_batched_gemm.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        L.wino_batched_gemm_shape.restype = i
+        L.wino_batched_gemm_shape.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp]
+        L.wino_fused_gemm_output.restype = i
+        L.wino_fused_gemm_output.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, vp]
         L.wino_output_transform.restype = i
         L.wino_output_transform.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.wino_direct_conv2d.restype = i
@@ -255,8 +260,10 @@ def wino_input_transform(x: torch.Tensor, variant: int, layout: int = WINO_NCHW,
     return V
 
 
-def wino_batched_gemm(U: torch.Tensor, V: torch.Tensor, K: int, C: int, T: int, variant: int, stream=None, out=None) -> torch.Tensor:
-    """U[alpha^2,K,Cp], V[alpha^2,T,Cp] -> M[alpha^2,K,T] fp32."""
+def wino_batched_gemm(U: torch.Tensor, V: torch.Tensor, K: int, C: int, T: int, variant: int, stream=None, out=None,
+                      block_shape: Optional[int] = None) -> torch.Tensor:
+    """U[alpha^2,K,Cp], V[alpha^2,T,Cp] -> M[alpha^2,K,T] fp32.  block_shape names one of the kernel's block shapes
+    (wino_batched_gemm_shape); None leaves the choice to the library (wino_batched_gemm)."""
     _dev(U, "U"); _dev(V, "V")
     a2 = (variant + 2) ** 2
     Cp = (C + 7) // 8 * 8
@@ -265,9 +272,36 @@ def wino_batched_gemm(U: torch.Tensor, V: torch.Tensor, K: int, C: int, T: int, 
     M = out if out is not None else torch.empty((a2, K, T), dtype=torch.float32, device=U.device)
     if M.numel() < a2 * K * T or M.dtype != torch.float32:
         raise ValueError("M buffer too small or not fp32")
-    _check(lib().wino_batched_gemm(_ptr(U), _ptr(V), _ptr(M), K, C, T, DTYPE_OF[U.dtype], variant, _stream(stream)),
-           "wino_batched_gemm")
+    if block_shape is None:
+        _check(lib().wino_batched_gemm(_ptr(U), _ptr(V), _ptr(M), K, C, T, DTYPE_OF[U.dtype], variant, _stream(stream)),
+               "wino_batched_gemm")
+    else:
+        _check(lib().wino_batched_gemm_shape(_ptr(U), _ptr(V), _ptr(M), K, C, T, DTYPE_OF[U.dtype], variant, int(block_shape),
+                                             _stream(stream)), "wino_batched_gemm_shape")
     return M
+
+
+wino_batched_gemm_shape = wino_batched_gemm
+
+
+def wino_fused_gemm_output(U: torch.Tensor, V: torch.Tensor, bias, N: int, C: int, H: int, W: int, K: int,
+                           layout: int = WINO_NCHW, block_shape: int = -1, stream=None, out=None) -> torch.Tensor:
+    """U[16,K,Cp], V[16,T,Cp] (F(2x2,3x3)) -> y: steps (ii) and (iii) + bias in one kernel."""
+    _dev(U, "U"); _dev(V, "V")
+    Cp = (C + 7) // 8 * 8
+    T = N * (-(-H // 2)) * (-(-W // 2))
+    if U.numel() < 16 * K * Cp or V.numel() < 16 * T * Cp or U.dtype != V.dtype:
+        raise ValueError("U or V buffer too small for these dimensions")
+    if layout not in (WINO_NCHW, WINO_NHWC):
+        raise WinoError(WINO_ERR_LAYOUT, "layout")
+    y = out if out is not None else torch.empty(_act_shape(N, K, H, W, layout), dtype=U.dtype, device=U.device)
+    if y.numel() < N * K * H * W or y.dtype != U.dtype:
+        raise ValueError("y buffer too small or of the wrong dtype")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != K or not bias.is_cuda):
+        raise ValueError("bias must be a GPU fp32 tensor of K elements")
+    _check(lib().wino_fused_gemm_output(_ptr(U), _ptr(V), _ptr(bias), _ptr(y), N, C, H, W, K, DTYPE_OF[U.dtype], layout,
+                                        int(block_shape), _stream(stream)), "wino_fused_gemm_output")
+    return y
 
 
 def wino_output_transform(M: torch.Tensor, bias, N: int, K: int, H: int, W: int, dtype: torch.dtype,
@@ -515,7 +549,7 @@ def conv2d_fused(x, w, bias=None, variant: int = WINO_AUTO, layout: int = WINO_N
     y = torch.empty(_act_shape(N, K, H, W, layout), dtype=x.dtype, device=x.device)
     v = (wino_recommend_variant(N, C, H, W, K, DTYPE_OF[x.dtype]) if variant == WINO_AUTO
          else wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant))
-    if v not in (WINO_F2, WINO_F4, WINO_DIRECT):
+    if v not in (WINO_F2, WINO_F4, WINO_FUSED_F2, WINO_DIRECT):
         raise WinoError(WINO_ERR_VARIANT, "conv2d_fused")
     stats = wino_groupnorm_stats(x, gn_groups, eps, layout) if gn_gamma is not None else None
     w_t = wino_filter_transform(w, v)

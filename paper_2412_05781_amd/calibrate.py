@@ -1,5 +1,6 @@
-"""Microbenchmarks that give the practical ceilings the kernels are compared with (HBM streaming, L2 -> CU
-bandwidth, register-only MFMA rates).  Plain HIP programs under ``calibration/``; nothing in the library uses them.
+"""The two microbenchmarks behind the roofline denominators: a plain copy kernel (HBM streaming; also the known-size
+reference the FETCH_SIZE / WRITE_SIZE counters are scaled by) and register-only MFMA rates.  Plain HIP programs under
+``calibration/``; nothing in the library uses them.
 
     python -m paper_2412_05781_amd.calibrate --build        # hipcc, works without a GPU
     python -m paper_2412_05781_amd.calibrate --run [name]   # on the GPU machine; prints each program's table

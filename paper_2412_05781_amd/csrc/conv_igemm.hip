@@ -19,7 +19,6 @@
 // even a channel-last input is copied once.  The optional 2x upsampling is pure address arithmetic.
 #include "wino_internal.h"
 #include "wino_mma.h"
-#include <stdlib.h>
 
 namespace wino {
 
@@ -403,12 +402,9 @@ static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, 
     constexpr int lds_bytes = (BM + BN) * 128 * NST;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
     auto kern = conv_igemm_kernel<E, EO, BM, BN, NST, PIX_A, WGM, WGN>;
-    static bool attr_set = false;                 // per instantiation; raising the limit is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per instantiation; a function-local static is initialised under the language's own lock
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (attr != hipSuccess) return attr;
     const E* zero_row = Wr + (size_t)g.R * g.R * g.K * g.Cp;
     hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(WGM * WGN * 64), lds_bytes, s,
                        xh, Wr, zero_row, bias, y, part, g, post, tiles_m, tiles_n, (int)total, per_xcd, nsplit);
@@ -428,9 +424,7 @@ static hipError_t launch_igemm_cfg(const E* xh, const E* Wr, const float* bias, 
 // then 128x128 while >= 256 blocks remain, else 64x64.
 struct IgemmShape { int tp, tk; };
 static IgemmShape igemm_shape(int T, int K) {
-    static const int forced = [] { const char* e = getenv("WINO_IGEMM_SHAPE"); return e ? atoi(e) : -1; }();   // tuning knob
     static const IgemmShape menu[5] = {{128, 128}, {64, 64}, {256, 256}, {256, 128}, {128, 256}};
-    if (forced >= 0 && forced < 5) return menu[forced];
     auto blocks = [&](int tp, int tk) { return (long long)((T + tp - 1) / tp) * ((K + tk - 1) / tk); };
     if (K % 256 == 0 && blocks(256, 256) >= 256) return menu[2];
     if (K % 128 == 0 && blocks(256, 128) >= 256) return menu[3];
@@ -445,12 +439,10 @@ int igemm_split(int T, int K, int Cp, int R, int dt) {
     // dt < 0: 8-bit operands, 128 reduction elements per stage
     const bool f16 = two_byte(dt);
     if (dt < 0) Cp = (Cp + 1) / 2;                        // same stage count as 64-element stages over half the channels
-    static const int forced = [] { const char* e = getenv("WINO_IGEMM_SPLIT"); return e ? atoi(e) : 0; }();       // tuning knob
     const int bke = f16 ? 64 : 32;
     const int nstage = R * R * ((Cp + bke - 1) / bke);
     int sp = 1;
-    if (forced > 0) sp = forced;
-    else {
+    {
         const IgemmShape sh = igemm_shape(T, K);
         const long long blocks = (long long)((T + sh.tp - 1) / sh.tp) * ((K + sh.tk - 1) / sh.tk);
         if (blocks < 256) sp = (int)((512 + blocks - 1) / blocks);

@@ -14,7 +14,6 @@
 // Bound by HBM/L2 traffic: reads x once (plus the 2-row/2-column halo), writes V.
 #include "wino_internal.h"
 #include "wino_transforms.h"
-#include <stdlib.h>
 
 namespace wino {
 
@@ -489,18 +488,17 @@ static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, const Pre
     // fast path: rows are whole 16-byte chunks and a 64-channel slab of x spans < 2 GB (32-bit lane offsets)
     const bool rows_are_chunks = ((size_t)g.W * sizeof(E)) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0 &&
                                  (size_t)CB * g.H * g.W * sizeof(E) < ((size_t)1 << 31);
-    static const int slide_cfg = [] { const char* e = getenv("WINO_IT_SLIDE"); return e ? atoi(e) : -1; }();   // tuning knob: 0 = off, n = steps per workgroup
     constexpr int STJ = 64 / (int)sizeof(E) / M;          // tiles per 64-byte body
-    if (rows_are_chunks && g.Cp % 64 == 0 && slide_cfg != 0) {
+    if (rows_are_chunks && g.Cp % 64 == 0) {
         const int steps = (g.tw + STJ / 2 + STJ - 1) / STJ;
         // Measured over the SD-shaped layers: with fp16 F(2x2) (16 tiles per body) the aligned fetch
         // alone pays from 16 tiles per row on; otherwise the strip kernel wins until a row has
         // eight steps.  Two steps per workgroup keep the grid large and the tail short.
         const bool wide_body = sizeof(E) == 2 && M == 2;
         const bool pays = wide_body ? g.tw >= STJ : steps >= 8;
-        const int spb = slide_cfg > 0 ? slide_cfg : (steps >= 8 ? 2 : 1);
+        const int spb = steps >= 8 ? 2 : 1;
         const long long total = (long long)g.N * g.th * (g.Cp / 64) * ((steps + spb - 1) / spb);
-        if ((slide_cfg > 0 || pays) && total <= 0x3fffffffLL) {
+        if (pays && total <= 0x3fffffffLL) {
             const int per_xcd = (int)((total + 7) / 8);
             if (gn) hipLaunchKernelGGL((input_transform_nchw_slide_kernel<M, E, STJ, true>), dim3((unsigned)(per_xcd * 8)), block, 0, s,
                                         (const E*)x, (E*)V, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, g.Cp, steps, spb, (int)total, per_xcd, po);
@@ -529,13 +527,7 @@ static hipError_t launch_it_cfg(const void* x, void* V, const Geom& g, const Pre
 template <int M, typename E>
 static hipError_t launch_it(const void* x, void* V, const Geom& g, const PreOp* pre, hipStream_t s) {
     constexpr int Q = 8 / M;      // TJ multiples that keep strips whole 16-byte chunks for fp16
-    static const int cfg = [] { const char* e = getenv("WINO_IT_CFG"); return e ? atoi(e) : 0; }();
-    switch (cfg) {                // tuning knob: tiles per strip (measured best: one tile per wave)
-        case 1: return launch_it_cfg<M, E, 64, 4 * Q>(x, V, g, pre, s);
-        case 2: return launch_it_cfg<M, E, 64, 1 * Q>(x, V, g, pre, s);
-        case 3: return launch_it_cfg<M, E, 64, 8 * Q>(x, V, g, pre, s);
-        default: return launch_it_cfg<M, E, 64, 2 * Q>(x, V, g, pre, s);
-    }
+    return launch_it_cfg<M, E, 64, 2 * Q>(x, V, g, pre, s);      // measured best of 1, 2, 4, 8 x Q tiles per strip
 }
 
 hipError_t launch_input_transform(const void* x, void* V, const Geom& g, int dt, bool nhwc, const PreOp* pre, hipStream_t s) {

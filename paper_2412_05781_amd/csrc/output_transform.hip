@@ -10,7 +10,6 @@
 #include "wino_internal.h"
 #include <type_traits>
 #include "wino_transforms.h"
-#include <stdlib.h>
 
 namespace wino {
 
@@ -157,12 +156,7 @@ static hipError_t launch_ot_cfg(const MT* Mt, const float* bias, void* y, const 
 
 template <int M, typename E>
 static hipError_t launch_ot(const float* Mt, const float* bias, void* y, const Geom& g, int nsplit, const PostOp& post, hipStream_t s) {
-    static const int cfg = [] { const char* e = getenv("WINO_OT_TPT"); return e ? atoi(e) : 0; }();   // tuning knob
-    // measured over the layer sweep: one tile per lane is never worse in the chained path
-    int tpt = cfg ? cfg : 1;
-    const bool aligned = (reinterpret_cast<uintptr_t>(Mt) & 15u) == 0;
-    if (tpt == 4 && g.T % 4 == 0 && aligned) return launch_ot_cfg<M, E, 4>(Mt, bias, y, g, nsplit, post, s);
-    if (tpt >= 2 && g.T % 2 == 0 && aligned) return launch_ot_cfg<M, E, 2>(Mt, bias, y, g, nsplit, post, s);
+    // measured over the layer sweep: one tile per lane is never worse than two or four in the chained path
     return launch_ot_cfg<M, E, 1>(Mt, bias, y, g, nsplit, post, s);
 }
 

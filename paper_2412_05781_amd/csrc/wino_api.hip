@@ -15,7 +15,9 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool dtype_ok(int d) { return d == WINO_F32 || d == WINO_F16 || d == WINO_BF16; }
 inline size_t esize(int d) { return d == WINO_F32 ? 4 : 2; }
-inline bool wino_variant_ok(int v) { return v == WINO_F2 || v == WINO_F4; }
+inline bool wino_variant_ok(int v) { return v == WINO_F2 || v == WINO_F4 || v == WINO_FUSED_F2; }
+// output tile edge m of a Winograd variant (the fused variant is F(2x2,3x3) with steps (ii) and (iii) in one kernel)
+inline int tile_edge(int v) { return v == WINO_F4 ? 4 : 2; }
 
 // products that must fit: element counts as size_t and tile counts as int
 bool dims_ok(int N, int C, int H, int W, int K, int m) {
@@ -62,10 +64,11 @@ size_t igemm_part_bytes(int N, int C, int H, int W, int K, int R, int stride, in
 }
 
 struct Workspace { size_t v_bytes, m_bytes, total; };
-Workspace workspace_layout(const Geom& g, int dtype) {
+Workspace workspace_layout(const Geom& g, int dtype, int variant) {
     Workspace ws;
     const size_t a2 = (size_t)g.alpha * g.alpha;
     ws.v_bytes = align_up(a2 * (size_t)g.T * g.Cp * esize(dtype));
+    if (variant == WINO_FUSED_F2) { ws.m_bytes = 0; ws.total = ws.v_bytes; return ws; }   // the product never leaves the registers
     // the product, times the number of partial copies the GEMM stage writes for this shape (the
     // policy depends on the operand order only through the block shape; take the larger of the two)
     const int sp_a = gemm_split(g.K, g.T, g.Cp, (int)a2, dtype), sp_b = gemm_split(g.T, g.K, g.Cp, (int)a2, dtype);
@@ -77,10 +80,12 @@ Workspace workspace_layout(const Geom& g, int dtype) {
 int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y, const Geom& g,
               void* workspace, bool nhwc, const PreOp* pre, const PostOp* post, hipStream_t s, bool half_product = false) {
     const int dt = w_t->dtype;
-    const Workspace ws = workspace_layout(g, w_t->dtype);
+    const Workspace ws = workspace_layout(g, w_t->dtype, w_t->variant);
     void* V = workspace;
     float* M = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + ws.v_bytes);
     if (launch_input_transform(x, V, g, dt, nhwc, pre, s) != hipSuccess) return WINO_ERR_HIP;
+    if (w_t->variant == WINO_FUSED_F2)
+        return launch_fused_gemm_output(w_t->data, V, bias, y, g, dt, nhwc, post, -1, s) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
     // channel-last: operands swapped, so the product comes out as M[alpha^2][T][K], k contiguous
     const int a2 = g.alpha * g.alpha;
     const int nsplit = nhwc ? gemm_split(g.T, g.K, g.Cp, a2, dt) : gemm_split(g.K, g.T, g.Cp, a2, dt);
@@ -101,7 +106,7 @@ int check_conv_args(const void* x, const wino_filter* w_t, const float* bias, co
         if (!igemm_dims_ok(N, C, H, W, K, 3, 1)) return WINO_ERR_DIM;
     } else {
         if (!wino_variant_ok(w_t->variant)) return WINO_ERR_VARIANT;
-        if (!dims_ok(N, C, H, W, K, w_t->variant)) return WINO_ERR_DIM;
+        if (!dims_ok(N, C, H, W, K, tile_edge(w_t->variant))) return WINO_ERR_DIM;
     }
     if (w_t->K != K || w_t->C != C) return WINO_ERR_DIM;
     if (!aligned16(x) || !aligned16(y) || !aligned16(w_t->data) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)))
@@ -137,8 +142,8 @@ const char* wino_status_string(int status) {
 
 int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int variant) {
     if (!dtype_ok(dtype)) return -1;
-    if (variant == WINO_DIRECT || variant == WINO_F2 || variant == WINO_F4) {
-        return dims_ok(N, C, H, W, K, variant == WINO_F2 ? 2 : 4) ? variant : -1;
+    if (variant == WINO_DIRECT || wino_variant_ok(variant)) {
+        return dims_ok(N, C, H, W, K, tile_edge(variant)) ? variant : -1;
     }
     if (variant != WINO_AUTO) return -1;
     if (!dims_ok(N, C, H, W, K, 2) || !dims_ok(N, C, H, W, K, 4)) return -1;
@@ -171,8 +176,8 @@ int wino_recommend_variant(int N, int C, int H, int W, int K, int dtype) {
 
 int wino_transformed_dims(int N, int C, int H, int W, int K, int variant, int* alpha, int* Cp, int* T) {
     if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
-    if (!dims_ok(N, C, H, W, K, variant)) return WINO_ERR_DIM;
-    const Geom g = make_geom(N, C, H, W, K, variant);
+    if (!dims_ok(N, C, H, W, K, tile_edge(variant))) return WINO_ERR_DIM;
+    const Geom g = make_geom(N, C, H, W, K, tile_edge(variant));
     if (alpha) *alpha = g.alpha;
     if (Cp) *Cp = g.Cp;
     if (T) *T = g.T;
@@ -181,16 +186,16 @@ int wino_transformed_dims(int N, int C, int H, int W, int K, int variant, int* a
 
 size_t wino_filter_bytes(int K, int C, int dtype, int variant) {
     if (variant == WINO_DIRECT) return wino_igemm_filter_bytes(K, C, 3, dtype);
-    if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !dims_ok(1, C, 1, 1, K, variant)) return 0;
-    const size_t a = variant + 2;
+    if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !dims_ok(1, C, 1, 1, K, tile_edge(variant))) return 0;
+    const size_t a = tile_edge(variant) + 2;
     return a * a * (size_t)K * (size_t)round_up(C, 8) * esize(dtype);
 }
 
 size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int dtype, int variant) {
     // the direct path: what the NCHW call needs (the channel-last call needs no more than that)
     if (variant == WINO_DIRECT) return wino_igemm_workspace_bytes(N, C, H, W, K, 3, 1, dtype, WINO_NCHW);
-    if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !dims_ok(N, C, H, W, K, variant)) return 0;
-    return workspace_layout(make_geom(N, C, H, W, K, variant), dtype).total;
+    if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !dims_ok(N, C, H, W, K, tile_edge(variant))) return 0;
+    return workspace_layout(make_geom(N, C, H, W, K, tile_edge(variant)), dtype, variant).total;
 }
 
 int wino_filter_transform(const void* w, void* w_t_data, int K, int C, int dtype, int variant,
@@ -204,9 +209,9 @@ int wino_filter_transform(const void* w, void* w_t_data, int K, int C, int dtype
         return WINO_OK;
     }
     if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
-    if (!dims_ok(1, C, 1, 1, K, variant) || K > 65535) return WINO_ERR_DIM;   // grid.y carries k
+    if (!dims_ok(1, C, 1, 1, K, tile_edge(variant)) || K > 65535) return WINO_ERR_DIM;   // grid.y carries k
     if (!aligned16(w) || !aligned16(w_t_data)) return WINO_ERR_ALIGN;
-    if (launch_filter_transform(w, w_t_data, K, C, round_up(C, 8), variant, dtype,
+    if (launch_filter_transform(w, w_t_data, K, C, round_up(C, 8), tile_edge(variant), dtype,
                                 static_cast<hipStream_t>(stream)) != hipSuccess)
         return WINO_ERR_HIP;
     out->data = w_t_data; out->K = K; out->C = C; out->dtype = dtype; out->variant = variant;
@@ -221,8 +226,8 @@ int wino_conv2d_ex(const void* x, const wino_filter* w_t, const float* bias, voi
     if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
     if (w_t->variant == WINO_DIRECT)
         return wino_igemm_conv2d(x, w_t->data, bias, y, N, C, H, W, K, 3, 1, w_t->dtype, layout, workspace, workspace_bytes, stream);
-    const Geom g = make_geom(N, C, H, W, K, w_t->variant);
-    const Workspace ws = workspace_layout(g, w_t->dtype);
+    const Geom g = make_geom(N, C, H, W, K, tile_edge(w_t->variant));
+    const Workspace ws = workspace_layout(g, w_t->dtype, w_t->variant);
     if (!workspace || workspace_bytes < ws.total) return WINO_ERR_WORKSPACE;
     if (!aligned16(workspace)) return WINO_ERR_ALIGN;
     return run_chain(x, w_t, bias, y, g, workspace, layout == WINO_NHWC, nullptr, nullptr, static_cast<hipStream_t>(stream));
@@ -241,8 +246,8 @@ int wino_conv2d(const void* x, const wino_filter* w_t, const float* bias, void* 
         if (hipFreeAsync(workspace, s) != hipSuccess) return WINO_ERR_HIP;
         return rc2;
     }
-    const Geom g = make_geom(N, C, H, W, K, w_t->variant);
-    const Workspace ws = workspace_layout(g, w_t->dtype);
+    const Geom g = make_geom(N, C, H, W, K, tile_edge(w_t->variant));
+    const Workspace ws = workspace_layout(g, w_t->dtype, w_t->variant);
     if (hipMallocAsync(&workspace, ws.total, s) != hipSuccess || !workspace) return WINO_ERR_HIP;
     const int rc2 = run_chain(x, w_t, bias, y, g, workspace, false, nullptr, nullptr, s);
     if (hipFreeAsync(workspace, s) != hipSuccess) return WINO_ERR_HIP;
@@ -325,8 +330,8 @@ int wino_conv2d_fused(const void* x, const wino_filter* w_t, const float* bias, 
         if (rb != yb && rb < ye && yb < re) return WINO_ERR_ALIAS;    // identical is fine (each element read, then written, by one lane)
     }
     post.addvec = f->addvec; post.residual = f->residual;
-    const Geom g = make_geom(N, C, H, W, K, w_t->variant);
-    const Workspace ws = workspace_layout(g, w_t->dtype);
+    const Geom g = make_geom(N, C, H, W, K, tile_edge(w_t->variant));
+    const Workspace ws = workspace_layout(g, w_t->dtype, w_t->variant);
     if (!workspace || workspace_bytes < ws.total) return WINO_ERR_WORKSPACE;
     if (!aligned16(workspace)) return WINO_ERR_ALIGN;
     if (f->product_fp16 != 0 && f->product_fp16 != 1) return WINO_ERR_DIM;
@@ -340,9 +345,9 @@ int wino_input_transform(const void* x, void* V, int N, int C, int H, int W,
     if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
     if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
     if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
-    if (!dims_ok(N, C, H, W, 1, variant)) return WINO_ERR_DIM;
+    if (!dims_ok(N, C, H, W, 1, tile_edge(variant))) return WINO_ERR_DIM;
     if (!aligned16(x) || !aligned16(V)) return WINO_ERR_ALIGN;
-    const Geom g = make_geom(N, C, H, W, 1, variant);
+    const Geom g = make_geom(N, C, H, W, 1, tile_edge(variant));
     return launch_input_transform(x, V, g, dtype, layout == WINO_NHWC, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
 }
@@ -351,9 +356,9 @@ int wino_batched_gemm(const void* U, const void* V, float* M, int K, int C, int 
                       int dtype, int variant, void* stream) {
     if (!U || !V || !M) return WINO_ERR_NULL;
     if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
-    if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
-    if (K < 1 || C < 1 || T < 1 || T > INT_MAX / 2 || !dims_ok(1, C, 1, 1, K, variant)) return WINO_ERR_DIM;
-    const unsigned long long a2 = (unsigned long long)(variant + 2) * (variant + 2);
+    if (variant != WINO_F2 && variant != WINO_F4) return WINO_ERR_VARIANT;      // the fused variant has no stored product
+    if (K < 1 || C < 1 || T < 1 || T > INT_MAX / 2 || !dims_ok(1, C, 1, 1, K, tile_edge(variant))) return WINO_ERR_DIM;
+    const unsigned long long a2 = (unsigned long long)(tile_edge(variant) + 2) * (tile_edge(variant) + 2);
     if (a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)round_up(C, 8) ||
         a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)K) return WINO_ERR_DIM;
     if (!aligned16(U) || !aligned16(V) || !aligned16(M)) return WINO_ERR_ALIGN;
@@ -361,17 +366,45 @@ int wino_batched_gemm(const void* U, const void* V, float* M, int K, int C, int 
                                static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
+int wino_batched_gemm_shape(const void* U, const void* V, float* M, int K, int C, int T,
+                            int dtype, int variant, int block_shape, void* stream) {
+    if (block_shape < 0 || block_shape > 8) return WINO_ERR_VARIANT;
+    if (!U || !V || !M) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (variant != WINO_F2 && variant != WINO_F4) return WINO_ERR_VARIANT;
+    if (K < 1 || C < 1 || T < 1 || T > INT_MAX / 2 || !dims_ok(1, C, 1, 1, K, tile_edge(variant))) return WINO_ERR_DIM;
+    const unsigned long long a2 = (unsigned long long)(variant + 2) * (variant + 2);
+    if (a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)round_up(C, 8) ||
+        a2 * (unsigned long long)T > (1ULL << 40) / (unsigned long long)K) return WINO_ERR_DIM;
+    if (!aligned16(U) || !aligned16(V) || !aligned16(M)) return WINO_ERR_ALIGN;
+    return launch_batched_gemm(U, V, M, K, round_up(C, 8), T, (int)a2, 1, dtype, false,
+                               static_cast<hipStream_t>(stream), block_shape) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+}
+
 int wino_output_transform(const float* M, const float* bias, void* y, int N, int K, int H, int W,
                           int dtype, int variant, int layout, void* stream) {
     if (!M || !y) return WINO_ERR_NULL;
     if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
-    if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
+    if (variant != WINO_F2 && variant != WINO_F4) return WINO_ERR_VARIANT;
     if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
-    if (!dims_ok(N, 1, H, W, K, variant)) return WINO_ERR_DIM;
+    if (!dims_ok(N, 1, H, W, K, tile_edge(variant))) return WINO_ERR_DIM;
     if (!aligned16(M) || !aligned16(y)) return WINO_ERR_ALIGN;
-    const Geom g = make_geom(N, 1, H, W, K, variant);
+    const Geom g = make_geom(N, 1, H, W, K, tile_edge(variant));
     return launch_output_transform(M, bias, y, g, 1, dtype, layout == WINO_NHWC, false, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
                ? WINO_OK : WINO_ERR_HIP;
+}
+
+int wino_fused_gemm_output(const void* U, const void* V, const float* bias, void* y, int N, int C, int H, int W, int K,
+                           int dtype, int layout, int block_shape, void* stream) {
+    if (!U || !V || !y) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    if (block_shape < -1 || block_shape > 3) return WINO_ERR_VARIANT;
+    if (!dims_ok(N, C, H, W, K, 2)) return WINO_ERR_DIM;
+    if (!aligned16(U) || !aligned16(V) || !aligned16(y) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u))) return WINO_ERR_ALIGN;
+    const Geom g = make_geom(N, C, H, W, K, 2);
+    return launch_fused_gemm_output(U, V, bias, y, g, dtype, layout == WINO_NHWC, nullptr, block_shape,
+                                    static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
 int wino_direct_conv2d(const void* x, const void* w, const float* bias, void* y,

@@ -18,7 +18,6 @@
 // through registers with zero fill instead.
 #include "wino_internal.h"
 #include "wino_mma.h"
-#include <stdlib.h>
 
 namespace wino {
 
@@ -181,12 +180,9 @@ static hipError_t launch_gemm_cfg(const void* U, const void* V, void* M, int K, 
     constexpr int lds_bytes = (BM + BN) * RB * NST;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
     auto kern = wino_gemm_kernel<E, MT, BM, BN, RB, NST, WGM, WGN>;
-    static bool attr_set = false;                 // per instantiation; raising the limit is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per instantiation; a function-local static is initialised under the language's own lock
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (attr != hipSuccess) return attr;
     dim3 block(WGM * WGN * 64), grid((unsigned)(per_xcd * 8));
     hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, (const E*)U, (const E*)V, (MT*)M,
                        K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd, nbatch, nsplit);
@@ -204,27 +200,19 @@ static const BlockShape kMenu[4] = {{128, 128, 1.00}, {128, 64, 0.85}, {64, 128,
 // 128x32 block with four waves stacked along K and a three-slot ring serves best.  Both rules
 // have a mirror image for the call with the operands swapped (rows of V x rows of U, which
 // leaves the product transposed for channel-last outputs).
-// WINO_GEMM_SHAPE=0..8 (read once) pins an entry, for tuning runs.
 static int pick_shape(int K, int T, int nbatch, bool f16) {
-    static const int forced = [] {
-        const char* e = getenv("WINO_GEMM_SHAPE");
-        return e ? atoi(e) : -1;
-    }();
-    if (forced >= 0) return forced;
     if ((K % 256 == 0 && T >= 4096) || (T % 256 == 0 && K >= 4096)) return 4;
     {   // one 256x256 workgroup (16 waves) per compute unit, nearly all units busy, little padding: measured
         // 18 % faster than any smaller block on 640 x 512 x 640 (SDXL's 64x64 layers)
-        static const bool off = getenv("WINO_GEMM_NO_BIG") != nullptr;     // tuning knob
         const long long tm = (K + 255) / 256, tn = (T + 255) / 256, blocks = tm * tn * nbatch;
-        if (!off && f16 && blocks >= 160 && blocks <= 256 && tm * tn * 256 * 256 * 4 <= (long long)K * T * 5) return 4;
+        if (f16 && blocks >= 160 && blocks <= 256 && tm * tn * 256 * 256 * 4 <= (long long)K * T * 5) return 4;
     }
     if (T <= 32) return 5;
     if (K <= 32) return 6;
     {   // 128x128 blocks would need a second, mostly empty round (257-384 of them) while 256x128 blocks fit in one:
         // SDXL's 1280-channel 32x32 layers, 360 -> 180 workgroups of 8 waves with three slots, measured 13 % faster
-        static const bool off = getenv("WINO_GEMM_NO_TALL") != nullptr;    // tuning knob
         const long long b128 = (long long)((K + 127) / 128) * ((T + 127) / 128) * nbatch;
-        if (!off && f16 && K % 256 == 0 && T % 128 == 0 && b128 > 256 && b128 <= 384) return 8;
+        if (f16 && K % 256 == 0 && T % 128 == 0 && b128 > 256 && b128 <= 384) return 8;
     }
     // fp16, at most one 128x128 workgroup per compute unit and next to no padding: nothing else
     // hides a workgroup's load latency, so it gets a third ring slot (measured 10-15 % over the
@@ -246,8 +234,8 @@ static int pick_shape(int K, int T, int nbatch, bool f16) {
 }
 
 template <typename E, typename MT>
-static hipError_t launch_gemm_t(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
-    switch (pick_shape(K, T, nbatch, sizeof(E) == 2)) {
+static hipError_t launch_gemm_t(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int shape, hipStream_t s) {
+    switch (shape < 0 ? pick_shape(K, T, nbatch, sizeof(E) == 2) : shape) {
         case 0: return launch_gemm_cfg<E, MT, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
         case 1: return launch_gemm_cfg<E, MT, 128, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
         case 2: return launch_gemm_cfg<E, MT, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
@@ -273,15 +261,13 @@ int gemm_max_split(int Cp, int dt) {
 // copies of the (small) product.
 int gemm_split(int rows, int cols, int Cp, int nbatch, int dt) {
     const bool f16 = two_byte(dt);
-    static const int forced = [] { const char* e = getenv("WINO_GEMM_SPLIT"); return e ? atoi(e) : 0; }();   // tuning knob
     const int shape = pick_shape(rows, cols, nbatch, f16);
     const int bm = (shape == 4 || shape == 8) ? 256 : (shape == 6 ? 32 : ((shape == 2 || shape == 3) ? 64 : 128));
     const int bn = shape == 4 ? 256 : (shape == 5 ? 32 : ((shape == 1 || shape == 3) ? 64 : 128));
     const long long blocks = (long long)((rows + bm - 1) / bm) * ((cols + bn - 1) / bn) * nbatch;
     const int max_split = gemm_max_split(Cp, dt);
     int sp = 1;
-    if (forced > 0) sp = forced;
-    else if (nbatch <= 16 && (bm < 128 || bn < 128) && blocks <= 320 && rows >= cols) {
+    if (nbatch <= 16 && (bm < 128 || bn < 128) && blocks <= 320 && rows >= cols) {
         // measured: pays 6-10 % for F(2x2) with narrow blocks (images of 8x8, and 16x16 at batch 1)
         // while there are about as many workgroups as compute units; with the 36 batches of
         // F(4x4) the extra copies of the product cost more than the GEMM stage gains, and so they do with the
@@ -294,13 +280,15 @@ int gemm_split(int rows, int cols, int Cp, int nbatch, int dt) {
     return sp < 1 ? 1 : sp;
 }
 
-hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int dt, bool half_product, hipStream_t s) {
+hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int dt, bool half_product,
+                               hipStream_t s, int shape) {
     if (nsplit < 1 || nsplit > gemm_max_split(Cp, dt)) return hipErrorInvalidValue;
+    if (shape < -1 || shape > 8) return hipErrorInvalidValue;
     if (half_product && (dt != DT_F16 || nsplit != 1)) return hipErrorInvalidValue;      // fp16 storage, unsplit reduction only
-    if (half_product) return launch_gemm_t<__half, __half>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+    if (half_product) return launch_gemm_t<__half, __half>(U, V, M, K, Cp, T, nbatch, nsplit, shape, s);
     return with_dtype(dt, [&](auto* tag) {
         using E = std::remove_pointer_t<decltype(tag)>;
-        return launch_gemm_t<E, float>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        return launch_gemm_t<E, float>(U, V, M, K, Cp, T, nbatch, nsplit, shape, s);
     });
 }
 

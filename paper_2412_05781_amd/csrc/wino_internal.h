@@ -109,11 +109,18 @@ hipError_t launch_input_transform(const void* x, void* V, const Geom& g, int dt,
 // [nsplit][nbatch][K][T], which launch_output_transform sums.  gemm_split() is the policy the
 // whole path uses for a shape (rows = rows of the first operand, cols = rows of the second).
 // half_product: M is stored as fp16 (fp16 storage and an unsplit reduction only)
-hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int dt, bool half_product, hipStream_t s);
+// shape: -1 = the library's choice for the problem size, 0..8 = a named block shape (see wino_gemm.hip)
+hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int dt, bool half_product,
+                               hipStream_t s, int shape = -1);
 int gemm_max_split(int Cp, int dt);
 int gemm_split(int rows, int cols, int Cp, int nbatch, int dt);
 hipError_t launch_output_transform(const void* M, const float* bias, void* y, const Geom& g, int nsplit, int dt, bool nhwc,
                                    bool half_product, const PostOp* post, hipStream_t s);
+// steps (ii) and (iii) in one kernel, F(2x2,3x3) only: U, V as for launch_batched_gemm, y written directly.
+// shape: -1 = chosen from the problem size, 0..3 = a named block shape (see wino_fused.hip)
+hipError_t launch_fused_gemm_output(const void* U, const void* V, const float* bias, void* y, const Geom& g, int dt, bool nhwc,
+                                    const PostOp* post, int shape, hipStream_t s);
+int fused_pick_shape(int rows, int cols);
 hipError_t launch_groupnorm_stats(const void* x, float* stats, int N, int C, int H, int W, int groups, float eps,
                                   int dt, bool nhwc, hipStream_t s);
 size_t groupnorm_stats_bytes(int N, int groups);

@@ -58,11 +58,17 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // track the transfer and does not drain every outstanding one before each barrier and LDS read;
 // the kernel waits with explicit vmcnt values instead (see the reduction loop).
 typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+// m0 is set and consumed inside the one asm statement and is named as clobbered, so the compiler
+// re-creates any m0 value of its own after it (the clobber reaches the machine code as an implicit
+// definition; clang's generic warning about clobbering a reserved register is switched off here).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma_load_1k(const void* src, unsigned char* lds_dst) {
     const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t*)lds_dst);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(m0v), "v"(src) : "memory");   // nothing else in these kernels reads m0
+                 :: "s"(m0v), "v"(src) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 }  // namespace wino
 #endif

@@ -7,7 +7,6 @@ the table that the file of the same topic under ``profiles/`` records:
     python -m paper_2412_05781_amd.timing flavours       1x1 and stride-2 convolutions through the implicit GEMM
     python -m paper_2412_05781_amd.timing direct         3x3 stride 1: Winograd vs direct vs 8-bit direct
     python -m paper_2412_05781_amd.timing half-product   the opt-in fp16 intermediate product
-    python -m paper_2412_05781_amd.timing vendor-gemm    the framework's batched GEMM on the GEMM stage's shapes
 
 "framework" columns call the stock deep-learning framework's own operators on the same tensors, as context.
 """
@@ -20,7 +19,7 @@ import torch
 
 from . import binding as B
 from . import synth
-from .sweep import graph_time
+from .gputime import graph_time
 
 DEV = "cuda:0"
 DT = torch.float16
@@ -162,32 +161,15 @@ def cmd_half_product(_):
                   f"{t1*1e6:8.2f} us ({L.direct_flops/t1/1e12:7.1f} TF)  x{t0/t1:.2f}", flush=True)
 
 
-def cmd_vendor_gemm(_):
-    for (K, T, C, b) in [(512, 4096, 512, 36), (320, 512, 320, 36), (1280, 512, 1280, 36), (640, 512, 640, 36), (1280, 128, 1280, 36)]:
-        n = _nsets(b * (K * C * 2 + T * C * 2 + K * T * 4))
-        Us = [torch.randn((b, K, C), device=DEV).to(DT) for _ in range(n)]
-        Vs = [torch.randn((b, T, C), device=DEV).to(DT) for _ in range(n)]
-        Ms = [torch.empty((b, K, T), device=DEV, dtype=torch.float32) for _ in range(n)]
-        Mh = [torch.empty((b, K, T), device=DEV, dtype=DT) for _ in range(n)]
-        variant = 4 if b == 36 else 2
-        t = graph_time(lambda i: B.wino_batched_gemm(Us[i % n], Vs[i % n], K, C, T, variant, out=Ms[i % n]), 2 * n)
-        for _ in range(2):
-            torch.bmm(Us[0], Vs[0].transpose(1, 2), out=Mh[0])
-        tv = graph_time(lambda i: torch.bmm(Us[i % n], Vs[i % n].transpose(1, 2), out=Mh[i % n]), 2 * n)
-        fl = 2 * b * K * T * C
-        print(f"K={K:5d} T={T:5d} C={C:5d} x{b}: this build (fp32 product) {t*1e6:8.2f} us ({fl/t/1e12:6.1f} TF) | framework bmm (fp16 product) "
-              f"{tv*1e6:8.2f} us ({fl/tv/1e12:6.1f} TF)", flush=True)
-
-
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["fused", "upsample", "flavours", "direct", "half-product", "vendor-gemm"])
+    ap.add_argument("what", choices=["fused", "upsample", "flavours", "direct", "half-product"])
     a = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("timing: no GPU visible", file=sys.stderr)
         return 2
     {"fused": cmd_fused, "upsample": cmd_upsample, "flavours": cmd_flavours, "direct": cmd_direct,
-     "half-product": cmd_half_product, "vendor-gemm": cmd_vendor_gemm}[a.what](a)
+     "half-product": cmd_half_product}[a.what](a)
     return 0
 
 

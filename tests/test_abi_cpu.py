@@ -147,8 +147,32 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
 
 
 def test_measurement_tools_import_without_a_gpu():
-    """The timing and calibration tools are part of the package: they import on a CPU-only box, and the calibration
-    sources they name exist."""
-    from paper_2412_05781_amd import calibrate, sweep, timing
-    assert calibrate.names() == ["hbm_stream_few_workgroups", "l2_to_cu", "mfma_rates", "mfma_vs_streaming_overlap", "stream"]
-    assert callable(timing.main) and callable(sweep.main)
+    """The timing tables and the two programs that measure the roofline denominators (a plain copy, register-only
+    MFMA rates) are part of the package: they import on a CPU-only box, and the sources they name exist."""
+    from paper_2412_05781_amd import calibrate, gputime, timing
+    assert calibrate.names() == ["mfma_rates", "stream"]
+    assert callable(timing.main) and callable(gputime.graph_time)
+
+
+def test_fused_variant_sizes_and_the_entry_points_added_for_it(L):
+    """WINO_FUSED_F2 keeps U and V of F(2x2) and has no stored product; the block-shape arguments
+    reject bad input on the host, before any HIP call (this test runs without a GPU)."""
+    assert B.WINO_FUSED_F2 == 12
+    assert B.wino_filter_bytes(320, 320, B.WINO_F16, B.WINO_FUSED_F2) == B.wino_filter_bytes(320, 320, B.WINO_F16, B.WINO_F2)
+    assert B.wino_transformed_dims(2, 320, 64, 64, 320, B.WINO_FUSED_F2) == (4, 320, 2048)
+    assert B.wino_workspace_bytes(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_FUSED_F2) == 16 * 2048 * 320 * 2      # V only
+    assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_FUSED_F2) == B.WINO_FUSED_F2
+    assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, 13) == -1
+    vp = ctypes.c_void_p
+    a = vp(0x1000)
+    # named block shapes out of range; null and misaligned pointers
+    assert L.wino_batched_gemm_shape(a, a, a, 8, 8, 8, B.WINO_F16, B.WINO_F2, 9, None) == B.WINO_ERR_VARIANT
+    assert L.wino_batched_gemm_shape(a, a, a, 8, 8, 8, B.WINO_F16, B.WINO_F2, -1, None) == B.WINO_ERR_VARIANT
+    assert L.wino_batched_gemm_shape(None, a, a, 8, 8, 8, B.WINO_F16, B.WINO_F2, 0, None) == B.WINO_ERR_NULL
+    assert L.wino_batched_gemm_shape(a, a, a, 8, 8, 8, B.WINO_F16, B.WINO_FUSED_F2, 0, None) == B.WINO_ERR_VARIANT
+    assert L.wino_batched_gemm(a, a, a, 8, 8, 8, B.WINO_F16, B.WINO_FUSED_F2, None) == B.WINO_ERR_VARIANT
+    assert L.wino_fused_gemm_output(a, a, None, a, 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 4, None) == B.WINO_ERR_VARIANT
+    assert L.wino_fused_gemm_output(a, None, None, a, 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_NULL
+    assert L.wino_fused_gemm_output(a, a, None, a, 1, 8, 4, 4, 8, B.WINO_F16, 5, 0, None) == B.WINO_ERR_LAYOUT
+    assert L.wino_fused_gemm_output(a, a, None, vp(0x1008), 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_ALIGN
+    assert L.wino_fused_gemm_output(a, a, None, a, 0, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_DIM

@@ -89,3 +89,39 @@ def test_model_without_rounding_is_exact():
     x = rng.standard_normal((1, 8, 9, 10)); w = rng.standard_normal((4, 8, 3, 3)); b = rng.standard_normal(4)
     y = wr.conv2d_winograd_storage_model(x, w, b, 4, store_dtype=np.float64)
     assert oracle.rel_l2(y, oracle.conv2d_direct(x, w, b)) < 1e-13
+
+
+# ---- the element-wise acceptance bound of the GPU parity tests (tests/parity_util.py) ------------------------------
+@pytest.mark.parametrize("shape", [(2, 320, 48, 32, 32), (1, 96, 64, 63, 66)])
+@pytest.mark.parametrize("m", [2, 4])
+def test_elementwise_bound_holds_for_a_correct_path_and_catches_one_wrong_element(m, shape):
+    """Per tile-position class the error of the storage model is close to Gaussian: no element further than 6 class-rms
+    from the exact result (beyond the half-ulp of the output rounding), so the GPU tests' bound of 8 passes a correct
+    path.  One element wrong by the size of a typical output (planted here, on the CPU, in a correct result) is
+    hundreds of class-rms away and fails it, although the relative L2 error of the tensor hardly moves."""
+    import sys, os
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    import parity_util as pu
+    N, C, K, H, W = shape
+    rng = np.random.default_rng(sum(shape) + m)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float16).astype(np.float64)
+    w = (rng.standard_normal((K, C, 3, 3)) / np.sqrt(9 * C)).astype(np.float16).astype(np.float64)
+    b = (0.01 * rng.standard_normal(K)).astype(np.float32).astype(np.float64)
+    ref = oracle.conv2d_direct(x, w, b)
+    y = wr.conv2d_winograd_storage_model(x, w, b, m)
+    ex = pu.elementwise_excess(y, ref, m, "f16")
+    assert ex <= 6.0, ex
+    assert pu.check(y, ref, 5e-3, m, "f16") <= 5e-3
+    # uniform grouping (m = 1) would NOT do for F(4x4): the tile positions differ in variance
+    if m == 4:
+        assert pu.elementwise_excess(y, ref, 1, "f16") > 8.0
+    bad = y.copy()
+    bad[N - 1, K // 2, H // 2, W // 3] += 1.0
+    assert oracle.rel_l2(bad, ref) <= 5e-3                      # the norm alone lets it through
+    assert pu.elementwise_excess(bad, ref, m, "f16") > 50.0
+    with pytest.raises(AssertionError):
+        pu.check(bad, ref, 5e-3, m, "f16")
+    # a path that only rounds its output (the direct variant) is covered by the half-ulp term alone
+    yd = ref.astype(np.float32).astype(np.float16).astype(np.float64)
+    assert pu.elementwise_excess(yd, ref, 1, "f16") == 0.0
+    # ... and a path that silently ran that variant where F(4x4) was asked for is still flagged by the error band

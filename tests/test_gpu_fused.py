@@ -47,7 +47,7 @@ CASES = [(1, 8, 8, 4, 4, 4), (2, 24, 40, 9, 13, 4), (1, 64, 130, 17, 30, 32), (2
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
-@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2])
 @pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
 @pytest.mark.parametrize("case", CASES)
 def test_fused_full_tensor(case, layout, variant, dtype):
@@ -110,7 +110,7 @@ UP_CASES = [(1, 8, 8, 3, 5, 4), (2, 24, 16, 8, 12, 8), (1, 64, 8, 4, 108, 32), (
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
-@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2])
 @pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
 @pytest.mark.parametrize("with_gn", [False, True])
 @pytest.mark.parametrize("case", UP_CASES)

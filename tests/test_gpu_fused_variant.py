@@ -1,0 +1,112 @@
+"""WINO_FUSED_F2: steps (ii) and (iii) of Section "Techniques" in one kernel (the product of step (ii) is scattered
+into the output accumulators position by position and never stored).  Parity against the CPU oracle, element by
+element, through the C ABI; every block shape of the kernel on small ragged inputs; both layouts; all storage types;
+agreement with the unfused F(2x2) path, whose sums it re-orders only in fp32."""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2412_05781_amd import binding as B
+from paper_2412_05781_amd import synth
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import parity_util as pu  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = {"f32": 1e-5, "f16": 5e-3, "bf16": 8e-3}
+
+# N, C, K, H, W: odd sizes, ragged tiles, channel counts off every block edge, more rows / columns than one block
+SHAPES = [(1, 1, 1, 1, 1), (1, 4, 3, 2, 3), (2, 5, 7, 5, 7), (1, 33, 65, 17, 30), (2, 64, 130, 33, 9), (1, 100, 40, 12, 40),
+          (2, 136, 200, 16, 16), (1, 72, 129, 70, 6), (1, 200, 150, 37, 41)]
+
+
+def _np(t):
+    return t.float().numpy().astype(np.float64)
+
+
+def _nchw(y, layout):
+    y = y.float().cpu()
+    return (y.permute(0, 3, 1, 2) if layout == B.WINO_NHWC else y).numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_whole_path_small_shapes(shape, layout, dtype):
+    N, C, K, H, W = shape
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=7000 + sum(shape))
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+    y = B.conv2d(xd, w.to(DEV), b.to(DEV), B.WINO_FUSED_F2, layout=layout)
+    torch.cuda.synchronize()
+    pu.check(_nchw(y, layout), ref, TOL[dtype], 2, dtype, what=(shape, layout, dtype))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("block_shape", [0, 1, 2, 3])
+@pytest.mark.parametrize("shape", [(2, 5, 7, 5, 7), (1, 33, 65, 17, 30), (2, 136, 200, 16, 16), (1, 200, 150, 37, 41), (1, 72, 300, 21, 39)])
+def test_every_block_shape(shape, block_shape, layout, dtype):
+    """The stage call with a named block shape: each instantiation on inputs with ragged rows and columns, a ragged
+    last reduction stage (C not a multiple of 64 / 32) and more than one block in both directions."""
+    N, C, K, H, W = shape
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=7100 + sum(shape))
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+    filt = B.wino_filter_transform(w.to(DEV), B.WINO_FUSED_F2)
+    assert filt.desc.variant == B.WINO_FUSED_F2
+    U = filt.buf.view(x.dtype)
+    V = B.wino_input_transform(xd, B.WINO_FUSED_F2, layout=layout)
+    y = B.wino_fused_gemm_output(U, V, b.to(DEV), N, C, H, W, K, layout=layout, block_shape=block_shape)
+    torch.cuda.synchronize()
+    pu.check(_nchw(y, layout), ref, TOL[dtype], 2, dtype, what=(shape, block_shape, layout, dtype))
+    # the library's own choice of block gives the same sums in the same order: bitwise equal
+    y_auto = B.wino_fused_gemm_output(U, V, b.to(DEV), N, C, H, W, K, layout=layout)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_auto)
+
+
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+def test_agrees_with_the_unfused_path(layout):
+    """Same U and V as WINO_F2; the product is added into the outputs in fp32 in another order, so the two results
+    differ by fp32 rounding before the one rounding to fp16: at most one unit in the last place, on few elements."""
+    N, C, K, H, W = 2, 96, 80, 20, 22
+    x, w, b = synth.make_inputs(N, C, K, H, W, "f16", seed=31)
+    xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+    y1 = B.conv2d(xd, w.to(DEV), b.to(DEV), B.WINO_F2, layout=layout)
+    y2 = B.conv2d(xd, w.to(DEV), b.to(DEV), B.WINO_FUSED_F2, layout=layout)
+    torch.cuda.synchronize()
+    d = (y1.float() - y2.float()).abs()
+    assert d.max().item() <= 2.0 ** -10 * y1.float().abs().max().item()
+    assert (d > 0).float().mean().item() < 0.05
+    # workspace: V only
+    assert B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, B.WINO_FUSED_F2) < B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, B.WINO_F2)
+
+
+def test_zero_input_no_bias_and_determinism():
+    x, w, b = synth.make_inputs(2, 40, 24, 10, 11, "f16", seed=5)
+    xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
+    y0 = B.conv2d(torch.zeros_like(xd), wd, bd, B.WINO_FUSED_F2)
+    torch.cuda.synchronize()
+    assert torch.equal(y0.float().cpu(), b.to(torch.float16).float().view(1, -1, 1, 1).expand(2, 24, 10, 11))
+    ref = oracle.conv2d_direct(_np(x), _np(w), None)
+    y = B.conv2d(xd, wd, None, B.WINO_FUSED_F2)
+    y_again = B.conv2d(xd, wd, None, B.WINO_FUSED_F2)
+    torch.cuda.synchronize()
+    pu.check(y.float().cpu().numpy().astype(np.float64), ref, 5e-3, 2, "f16")
+    assert torch.equal(y, y_again)
+
+
+def test_stage_calls_that_need_a_stored_product_reject_the_fused_variant():
+    U = torch.zeros(16 * 8 * 8, dtype=torch.float16, device=DEV)
+    with pytest.raises(B.WinoError) as e:
+        B.wino_batched_gemm(U, U, 8, 8, 8, B.WINO_FUSED_F2)
+    assert e.value.status == B.WINO_ERR_VARIANT
+    with pytest.raises(B.WinoError) as e:
+        B.wino_fused_gemm_output(U, U, None, 1, 8, 4, 4, 8, block_shape=9)
+    assert e.value.status == B.WINO_ERR_VARIANT
