@@ -11,11 +11,18 @@ last place of the storage type.  So, per position class (i mod m, j mod m):
 with C_SIGMA = 8: tests/test_error_model.py pins, on the CPU storage model, that a correct path stays below 6 (the
 expected maximum of 10^8 Gaussian samples is 5.9 sigma) and that one element that is wrong by the size of a typical
 output, planted in a correct result, breaks the bound.  The direct variant (m = 1 here) only rounds y, so for it the
-second term alone has to cover the error.
+second term alone has to cover the error.  With fewer than 32 input channels an output's error is a sum of only a few
+products of Gaussians, whose tails are heavier (the same pin shows up to 9 class-rms at C = 4): C_SIGMA_FEW = 16 there.
+With fp32 storage the error is that of the fp32 accumulation itself, whose size follows the running sums and not a
+fixed variance (an emulation of fp32 accumulation in the same pin file shows 7.4 class-rms on 2.6e5 outputs where
+rounded operands show 5): C_SIGMA_F32 = 12.
 """
 import numpy as np
 
 C_SIGMA = 8.0
+C_SIGMA_FEW = 16.0          # fewer than FEW_CHANNELS input channels
+C_SIGMA_F32 = 12.0          # fp32 storage
+FEW_CHANNELS = 32
 HALF_ULP = {"f16": 2.0 ** -11, "bf16": 2.0 ** -8, "f32": 2.0 ** -24}
 SUBNORMAL_HALF_ULP = {"f16": 2.0 ** -25, "bf16": 0.0, "f32": 0.0}      # fp16 spacing stops shrinking below 2^-14
 
@@ -46,12 +53,14 @@ def elementwise_excess(y, ref, m: int, dtype: str) -> float:
     return worst
 
 
-def check(y, ref, tol: float, m: int, dtype: str, what="") -> float:
-    """relL2 <= tol, every element finite, and the element-wise bound.  Returns relL2."""
+def check(y, ref, tol: float, m: int, dtype: str, what="", channels: int = FEW_CHANNELS) -> float:
+    """relL2 <= tol, every element finite, and the element-wise bound (`channels` = input channels of the layer).
+    Returns relL2."""
     assert y.shape == ref.shape, (what, y.shape, ref.shape)
     assert np.isfinite(y).all(), what
     err = rel_l2(y, ref)
     assert err <= tol, (what, "relL2", err)
     ex = elementwise_excess(y, ref, m, dtype)
-    assert ex <= C_SIGMA, (what, "an element is %.1f class-rms away from the oracle (relL2 %.2e)" % (ex, err))
+    lim = C_SIGMA_FEW if channels < FEW_CHANNELS else (C_SIGMA_F32 if dtype == "f32" else C_SIGMA)
+    assert ex <= lim, (what, "an element is %.1f class-rms away from the oracle (relL2 %.2e)" % (ex, err))
     return err

@@ -125,3 +125,52 @@ def test_elementwise_bound_holds_for_a_correct_path_and_catches_one_wrong_elemen
     yd = ref.astype(np.float32).astype(np.float16).astype(np.float64)
     assert pu.elementwise_excess(yd, ref, 1, "f16") == 0.0
     # ... and a path that silently ran that variant where F(4x4) was asked for is still flagged by the error band
+
+
+def test_elementwise_bound_with_few_channels():
+    """Four input channels (the conv_in layer): heavier tails, up to ~10 class-rms on a correct path (fp32 and fp16
+    storage models), hence the wider limit below 32 channels; a planted wrong element is still far outside it."""
+    import sys, os
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    import parity_util as pu
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((1, 4, 64, 64)).astype(np.float32).astype(np.float64)
+    w = (rng.standard_normal((64, 4, 3, 3)) / 6.0).astype(np.float32).astype(np.float64)
+    b = (0.01 * rng.standard_normal(64)).astype(np.float64)
+    ref = oracle.conv2d_direct(x, w, b)
+    for m in (2, 4):
+        for store, name, tol in ((np.float32, "f32", 1e-5), (np.float16, "f16", 5e-3)):
+            xs, ws = x.astype(store).astype(np.float64), w.astype(store).astype(np.float64)
+            r = oracle.conv2d_direct(xs, ws, b)
+            y = wr.conv2d_winograd_storage_model(xs, ws, b, m, store_dtype=store)
+            assert pu.elementwise_excess(y, r, m, name) <= 12.0
+            pu.check(y, r, tol, m, name, channels=4)
+            bad = y.copy(); bad[0, 7, 9, 11] += 0.5
+            with pytest.raises(AssertionError):
+                pu.check(bad, r, 1.0, m, name, channels=4)
+
+
+def test_elementwise_bound_with_fp32_accumulation():
+    """fp32 storage: what is left is the rounding of the fp32 accumulation, emulated here by adding the products of
+    two channels at a time into an fp32 array.  Its tails are heavier than those of rounded operands (about 7 class-rms
+    on 6.5e4 outputs against 4.5), which is why the GPU tests allow 12 for fp32 storage."""
+    import sys, os
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    import parity_util as pu
+    rng = np.random.default_rng(1)
+    N, C, K, H, W = 1, 160, 16, 64, 64
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w = (rng.standard_normal((K, C, 3, 3)) / np.sqrt(9 * C)).astype(np.float32)
+    b = np.zeros(K)
+    ref = oracle.conv2d_direct(x.astype(np.float64), w.astype(np.float64), b)
+    for m in (2, 4):
+        U = wr.filter_transform(w.astype(np.float64), m).astype(np.float32)
+        V = wr.input_transform(x.astype(np.float64), m).astype(np.float32)
+        M = np.zeros(U.shape[:3] + V.shape[3:], dtype=np.float32)
+        for c0 in range(0, C, 2):
+            M += np.einsum("xnkc,xnct->xnkt", U[..., c0:c0 + 2], V[:, :, c0:c0 + 2, :]).astype(np.float32)
+        y = wr.output_transform(M.astype(np.float64), b, N, H, W, m).astype(np.float32).astype(np.float64)
+        assert oracle.rel_l2(y, ref) <= 1e-5
+        ex = pu.elementwise_excess(y, ref, m, "f32")
+        assert 4.0 <= ex <= 10.0, ex
+        pu.check(y, ref, 1e-5, m, "f32", channels=C)

@@ -44,7 +44,7 @@ def test_whole_path_small_shapes(shape, layout, dtype):
     xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
     y = B.conv2d(xd, w.to(DEV), b.to(DEV), B.WINO_FUSED_F2, layout=layout)
     torch.cuda.synchronize()
-    pu.check(_nchw(y, layout), ref, TOL[dtype], 2, dtype, what=(shape, layout, dtype))
+    pu.check(_nchw(y, layout), ref, TOL[dtype], 2, dtype, what=(shape, layout, dtype), channels=C)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
@@ -64,7 +64,7 @@ def test_every_block_shape(shape, block_shape, layout, dtype):
     V = B.wino_input_transform(xd, B.WINO_FUSED_F2, layout=layout)
     y = B.wino_fused_gemm_output(U, V, b.to(DEV), N, C, H, W, K, layout=layout, block_shape=block_shape)
     torch.cuda.synchronize()
-    pu.check(_nchw(y, layout), ref, TOL[dtype], 2, dtype, what=(shape, block_shape, layout, dtype))
+    pu.check(_nchw(y, layout), ref, TOL[dtype], 2, dtype, what=(shape, block_shape, layout, dtype), channels=C)
     # the library's own choice of block gives the same sums in the same order: bitwise equal
     y_auto = B.wino_fused_gemm_output(U, V, b.to(DEV), N, C, H, W, K, layout=layout)
     torch.cuda.synchronize()
@@ -103,7 +103,7 @@ def test_zero_input_no_bias_and_determinism():
 
 
 def test_stage_calls_that_need_a_stored_product_reject_the_fused_variant():
-    U = torch.zeros(16 * 8 * 8, dtype=torch.float16, device=DEV)
+    U = torch.zeros(256 * 8 * 8, dtype=torch.float16, device=DEV)      # larger than any variant value could ask for
     with pytest.raises(B.WinoError) as e:
         B.wino_batched_gemm(U, U, 8, 8, 8, B.WINO_FUSED_F2)
     assert e.value.status == B.WINO_ERR_VARIANT

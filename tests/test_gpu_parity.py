@@ -193,7 +193,7 @@ def test_every_layer_whole_tensor(name):
     ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
     for variant in variants:
         y = _run(x, w, b, variant)
-        err = pu.check(y, ref, TOL[layer.dtype], TILE_EDGE[variant], layer.dtype, what=(name, variant))
+        err = pu.check(y, ref, TOL[layer.dtype], TILE_EDGE[variant], layer.dtype, what=(name, variant), channels=layer.C)
         print(f"{name} variant {variant}{' (auto)' if variant == auto else ''}: relL2 {err:.3e}", flush=True)
         if layer.dtype == "f16":
             lo, hi = FP16_BAND[variant]
