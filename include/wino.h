@@ -52,7 +52,8 @@ typedef enum wino_status {
     WINO_ERR_WORKSPACE = 6,  /* workspace NULL or smaller than wino_workspace_bytes*/
     WINO_ERR_ALIAS = 7,      /* x and y byte ranges overlap                        */
     WINO_ERR_HIP = 8,        /* a HIP call (launch, allocation) failed             */
-    WINO_ERR_LAYOUT = 9      /* layout enum out of range or unsupported here       */
+    WINO_ERR_LAYOUT = 9,     /* layout enum out of range or unsupported here       */
+    WINO_ERR_SCRATCH = 10    /* wino_conv2d_static: needs more than wino_static_scratch_bytes() */
 } wino_status;
 
 /* Storage type of x, w, y and of the transformed tensors U and V.  Accumulation is fp32 for all three.
@@ -141,6 +142,22 @@ int wino_conv2d(const void *x, const wino_filter *w_t, const float *bias, void *
 int wino_conv2d_ex(const void *x, const wino_filter *w_t, const float *bias, void *y,
                    int N, int C, int H, int W, int K, int layout,
                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * wino_conv2d_ex for callers that cannot allocate and have no workspace to hand over: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch (V and M; for a
+ * WINO_DIRECT filter the re-laid x and partial sums) lives in a device array inside the library,
+ * wino_static_scratch_bytes() = 64 MiB per GPU, held from the time the library is loaded until the
+ * process ends.  The call allocates nothing and frees nothing; its first call on a device looks up
+ * that device's copy of the array (no allocation either).  Same kernels, same results as
+ * wino_conv2d_ex, bit for bit.  Problems whose wino_workspace_bytes() exceed the array are refused
+ * with WINO_ERR_SCRATCH and nothing is launched (layer sizes up to about N=2, C=K=320, 64x64 in
+ * fp16 fit).  All calls on one GPU share the one array: calls that may overlap in time (different
+ * streams, different threads) race on it, so serialise them on one stream.
+ */
+size_t wino_static_scratch_bytes(void);
+int wino_conv2d_static(const void *x, const wino_filter *w_t, const float *bias, void *y,
+                       int N, int C, int H, int W, int K, int layout, void *stream);
 
 /*
  * The three stages on their own (the same kernels wino_conv2d_ex chains), for

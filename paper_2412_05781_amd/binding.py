@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libwino.so")
 
 WINO_OK = 0
 WINO_ERR_NULL, WINO_ERR_DIM, WINO_ERR_DTYPE, WINO_ERR_VARIANT = 1, 2, 3, 4
-WINO_ERR_ALIGN, WINO_ERR_WORKSPACE, WINO_ERR_ALIAS, WINO_ERR_HIP, WINO_ERR_LAYOUT = 5, 6, 7, 8, 9
+WINO_ERR_ALIGN, WINO_ERR_WORKSPACE, WINO_ERR_ALIAS, WINO_ERR_HIP, WINO_ERR_LAYOUT, WINO_ERR_SCRATCH = 5, 6, 7, 8, 9, 10
 WINO_F32, WINO_F16, WINO_BF16 = 0, 1, 2
 WINO_AUTO, WINO_DIRECT, WINO_F2, WINO_F4, WINO_FUSED_F2 = 0, 1, 2, 4, 12
 WINO_NCHW, WINO_NHWC = 0, 1
@@ -34,7 +34,7 @@ EXPORTS = [
     "wino_igemm_filter_bytes", "wino_igemm_filter_repack", "wino_igemm_workspace_bytes", "wino_igemm_conv2d",
     "wino_recommend_variant",
     "wino_fp8_filter_bytes", "wino_fp8_filter_quantize", "wino_fp8_workspace_bytes", "wino_fp8_conv2d",
-    "wino_fused_gemm_output", "wino_batched_gemm_shape",
+    "wino_fused_gemm_output", "wino_batched_gemm_shape", "wino_static_scratch_bytes", "wino_conv2d_static",
 ]
 
 
@@ -85,6 +85,9 @@ def lib() -> ctypes.CDLL:
         L.wino_input_transform.argtypes = [vp, vp, i, i, i, i, i, i, i, vp]
         L.wino_batched_gemm.restype = i
         L.wino_batched_gemm.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        L.wino_static_scratch_bytes.restype = sz; L.wino_static_scratch_bytes.argtypes = []
+        L.wino_conv2d_static.restype = i
+        L.wino_conv2d_static.argtypes = [vp, fp, vp, vp, i, i, i, i, i, i, vp]
         L.wino_batched_gemm_shape.restype = i
         L.wino_batched_gemm_shape.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp]
         L.wino_fused_gemm_output.restype = i
@@ -244,6 +247,19 @@ def wino_conv2d_ex(x, w_t: Filter, bias, y, workspace: torch.Tensor, layout: int
     _check(lib().wino_conv2d_ex(_ptr(x), ctypes.byref(w_t.desc), _ptr(bias), _ptr(y), N, C, H, W, K, layout,
                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "wino_conv2d_ex")
+    return y
+
+
+def wino_static_scratch_bytes() -> int:
+    return lib().wino_static_scratch_bytes()
+
+
+def wino_conv2d_static(x, w_t: Filter, bias, y, layout: int = WINO_NCHW, stream=None):
+    """wino_conv2d_ex with the scratch in the library's own device array: allocates nothing."""
+    _dev(x, "x"); _dev(y, "y")
+    N, C, H, W, K = _conv_shapes(x, w_t, bias, y, layout)
+    _check(lib().wino_conv2d_static(_ptr(x), ctypes.byref(w_t.desc), _ptr(bias), _ptr(y), N, C, H, W, K, layout,
+                                    _stream(stream)), "wino_conv2d_static")
     return y
 
 

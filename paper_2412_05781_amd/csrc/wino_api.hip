@@ -5,6 +5,7 @@
 #include "wino_internal.h"
 
 #include <limits.h>
+#include <mutex>
 
 using namespace wino;
 
@@ -136,6 +137,7 @@ const char* wino_status_string(int status) {
         case WINO_ERR_ALIAS: return "x and y overlap";
         case WINO_ERR_HIP: return "HIP call failed";
         case WINO_ERR_LAYOUT: return "unsupported layout";
+        case WINO_ERR_SCRATCH: return "problem needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }
@@ -252,6 +254,58 @@ int wino_conv2d(const void* x, const wino_filter* w_t, const float* bias, void* 
     const int rc2 = run_chain(x, w_t, bias, y, g, workspace, false, nullptr, nullptr, s);
     if (hipFreeAsync(workspace, s) != hipSuccess) return WINO_ERR_HIP;
     return rc2;
+}
+
+// ---- the entry point that allocates nothing -----------------------------------------------------------------
+// V and M (or the direct path's re-laid x and partial sums) live in a file-scope device array instead of a
+// caller's workspace or the stream-ordered allocator.  Each GPU holds its own copy of the array at its own
+// address; the address is looked up once per device and kept.
+}  // extern "C"
+
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (the array's name itself is only a host-side handle)
+int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return WINO_ERR_HIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return WINO_ERR_HIP;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return WINO_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t wino_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int wino_conv2d_static(const void* x, const wino_filter* w_t, const float* bias, void* y,
+                       int N, int C, int H, int W, int K, int layout, void* stream) {
+    const int rc = check_conv_args(x, w_t, bias, y, N, C, H, W, K);
+    if (rc != WINO_OK) return rc;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    const size_t need = w_t->variant == WINO_DIRECT
+                            ? wino_igemm_workspace_bytes(N, C, H, W, K, 3, 1, w_t->dtype, layout)
+                            : workspace_layout(make_geom(N, C, H, W, K, tile_edge(w_t->variant)), w_t->dtype, w_t->variant).total;
+    if (need > kStaticScratchBytes) return WINO_ERR_SCRATCH;
+    void* ws = nullptr;
+    const int rs = static_scratch(&ws);
+    if (rs != WINO_OK) return rs;
+    // every kernel of the chain writes the part of the scratch it later reads (V with its zero padding, M, partial
+    // sums), so nothing a previous call left there is ever read and nothing has to be cleared
+    if (w_t->variant == WINO_DIRECT)
+        return wino_igemm_conv2d(x, w_t->data, bias, y, N, C, H, W, K, 3, 1, w_t->dtype, layout, need ? ws : nullptr, need, stream);
+    const Geom g = make_geom(N, C, H, W, K, tile_edge(w_t->variant));
+    return run_chain(x, w_t, bias, y, g, ws, layout == WINO_NHWC, nullptr, nullptr, static_cast<hipStream_t>(stream));
 }
 
 size_t wino_groupnorm_stats_bytes(int N, int groups) {

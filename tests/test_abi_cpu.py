@@ -34,8 +34,8 @@ def test_header_and_library_agree(L):
 
 def test_version_and_status_strings(L):
     assert B.wino_version() >= 100
-    seen = {B.status_string(s) for s in range(0, 10)}
-    assert len(seen) == 10 and "ok" in seen
+    seen = {B.status_string(s) for s in range(0, 11)}
+    assert len(seen) == 11 and "ok" in seen
     assert B.status_string(12345) == "unknown status"
 
 
@@ -155,8 +155,8 @@ def test_measurement_tools_import_without_a_gpu():
 
 
 def test_fused_variant_sizes_and_the_entry_points_added_for_it(L):
-    """WINO_FUSED_F2 keeps U and V of F(2x2) and has no stored product; the block-shape arguments
-    reject bad input on the host, before any HIP call (this test runs without a GPU)."""
+    """WINO_FUSED_F2 keeps U and V of F(2x2) and has no stored product; the block-shape arguments and the scratch-free
+    entry point reject bad input on the host, before any HIP call (this test runs without a GPU)."""
     assert B.WINO_FUSED_F2 == 12
     assert B.wino_filter_bytes(320, 320, B.WINO_F16, B.WINO_FUSED_F2) == B.wino_filter_bytes(320, 320, B.WINO_F16, B.WINO_F2)
     assert B.wino_transformed_dims(2, 320, 64, 64, 320, B.WINO_FUSED_F2) == (4, 320, 2048)
@@ -176,3 +176,13 @@ def test_fused_variant_sizes_and_the_entry_points_added_for_it(L):
     assert L.wino_fused_gemm_output(a, a, None, a, 1, 8, 4, 4, 8, B.WINO_F16, 5, 0, None) == B.WINO_ERR_LAYOUT
     assert L.wino_fused_gemm_output(a, a, None, vp(0x1008), 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_ALIGN
     assert L.wino_fused_gemm_output(a, a, None, a, 0, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_DIM
+    # the scratch-free entry point: limit, and the same validation as wino_conv2d_ex
+    assert B.wino_static_scratch_bytes() == 64 << 20
+    f = B.wino_filter()
+    f.data, f.K, f.C, f.dtype, f.variant = 0x2000, 512, 512, B.WINO_F16, B.WINO_F4
+    x, y = vp(0x10000000), vp(0x20000000)
+    assert L.wino_conv2d_static(x, ctypes.byref(f), None, y, 1, 512, 128, 128, 512, B.WINO_NCHW, None) == B.WINO_ERR_SCRATCH
+    assert L.wino_conv2d_static(None, ctypes.byref(f), None, y, 1, 512, 128, 128, 512, B.WINO_NCHW, None) == B.WINO_ERR_NULL
+    assert L.wino_conv2d_static(x, ctypes.byref(f), None, y, 1, 512, 128, 128, 500, B.WINO_NCHW, None) == B.WINO_ERR_DIM
+    assert L.wino_conv2d_static(x, ctypes.byref(f), None, y, 1, 512, 8, 8, 512, 7, None) == B.WINO_ERR_LAYOUT
+    assert L.wino_conv2d_static(x, ctypes.byref(f), None, x, 1, 512, 8, 8, 512, B.WINO_NCHW, None) == B.WINO_ERR_ALIAS
