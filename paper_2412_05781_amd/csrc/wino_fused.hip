@@ -39,7 +39,9 @@ struct FusedGeom { int N, K, H, W, th, tw, T; };
 
 }  // namespace
 
-template <typename E, int BM, int BN, int NST, int WGM, int WGN, bool ROWS_K>
+// RAGGED = true: Cp is not a multiple of the stage (64 fp16 / 32 fp32 elements); the last stage of every position
+// then goes through registers with zero fill.  The common case (RAGGED = false) has no such code in its loop.
+template <typename E, int BM, int BN, int NST, int WGM, int WGN, bool ROWS_K, bool RAGGED, int DBG = 0>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const float* __restrict__ bias, E* __restrict__ y,
                      int rowsA, int rowsB, int Cp, FusedGeom g, int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd,
@@ -48,17 +50,17 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
     constexpr int RB = 128;                               // stage bytes per row
     constexpr int CPR = RB / 16;                          // 16-byte chunks per row per stage
     constexpr int BKE = RB / (int)sizeof(E);              // reduction elements per stage
-    constexpr int EPC = 16 / (int)sizeof(E);              // elements per chunk
     constexpr int ROWS = BM + BN;
     constexpr int RPL = 1024 / RB;                        // rows covered by one wave-wide load
     constexpr int NW = WGM * WGN;
     constexpr int LPW = ROWS / RPL / NW;                  // wave-wide loads per wave per stage
+    constexpr int LA = BM / (RPL * NW);                   // ... of which from the row operand
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int FM = WTM / 32, FN = WTN / 32;
     constexpr int STAGE_BYTES = ROWS * RB;
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && ROWS % (RPL * NW) == 0, "tile shape");
-    static_assert(BM % RPL == 0, "a wave-wide load lies wholly in one operand");
-    static_assert(NST >= 2 && NST <= 5 && LPW * (NST - 1) < 64, "ring depth / vmcnt range");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
+    static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "load i of every wave lies in the same operand");
+    static_assert(NST >= 2 && (NST & (NST - 1)) == 0 && LPW * (NST - 1) < 64, "ring depth: a power of two, within the vmcnt range");
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
@@ -70,118 +72,164 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
     if (tiles_m <= tiles_n) { tm = logical % tiles_m; tn = logical / tiles_m; }
     else { tn = logical % tiles_n; tm = logical / tiles_n; }
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // Everything that does not depend on the lane is kept in scalar registers (the wave index through readfirstlane),
+    // so that the per-stage bookkeeping - LDS destinations, stage bases, slot offsets - runs on the scalar unit: with one
+    // or two waves per SIMD every vector instruction spent on addresses is time the MFMA pipe sits idle.
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     const int row0 = tm * BM, col0 = tn * BN;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte_t*)lds;          // LDS byte address of the ring
 
-    // per-lane source rows of this lane's LPW loads; `cur` walks stage by stage through all positions
+    // Global side: one scalar base per operand that walks stage by stage through all positions, plus a fixed 32-bit byte
+    // offset per lane and load (row inside the block, clamped to the last valid row, and the swizzled chunk).
+    const size_t row_bytes = (size_t)Cp * sizeof(E);
     const int lrow = lane / CPR, lchunk = lane % CPR;
-    const E* cur[LPW];
-    int src_chunk[LPW];
-    const size_t planeA = (size_t)rowsA * Cp, planeB = (size_t)rowsB * Cp;
+    uint32_t goff[LPW];
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
-        const int row = (wave + NW * i) * RPL + lrow;       // row inside the stage, A rows first
+        const int row = (wave + NW * i) * RPL + lrow;       // row inside the stage, row-operand rows first
         const int chunk = lchunk ^ ((row >> 1) & (CPR - 1));
-        src_chunk[i] = chunk;
-        if (row < BM) {
-            int r = row0 + row; r = r < rowsA ? r : rowsA - 1;
-            cur[i] = Aop + (size_t)r * Cp + chunk * EPC;
-        } else {
-            int r = col0 + (row - BM); r = r < rowsB ? r : rowsB - 1;
-            cur[i] = Bop + (size_t)r * Cp + chunk * EPC;
-        }
+        int r;
+        if (i < LA) { r = row0 + row; r = (r < rowsA ? r : rowsA - 1) - row0; }
+        else { r = col0 + (row - BM); r = (r < rowsB ? r : rowsB - 1) - col0; }
+        goff[i] = (uint32_t)r * (uint32_t)row_bytes + (uint32_t)chunk * 16u;
     }
+    const unsigned char* sA = reinterpret_cast<const unsigned char*>(Aop) + (size_t)row0 * row_bytes;
+    const unsigned char* sB = reinterpret_cast<const unsigned char*>(Bop) + (size_t)col0 * row_bytes;
+    const size_t planeA = (size_t)rowsA * row_bytes, planeB = (size_t)rowsB * row_bytes;
 
     const int nk = (Cp + BKE - 1) / BKE;
-    const bool ragged = (Cp % BKE) != 0;
     const int total = A2 * nk;
+    const uint32_t wave_dst = lds0 + (uint32_t)wave * 1024u;
 
-    // issues stage number `s` (position s / nk, reduction stage s % nk); called with s ascending
+    // issues the next stage in order into ring slot `slot`
     int issue_kt = 0;
-    auto issue_stage = [&](int s) {
-        unsigned char* slot = lds + (s % NST) * STAGE_BYTES;
-        if (ragged && issue_kt == nk - 1) {
+    auto issue_stage = [&](int slot) {
+        const uint32_t dst = wave_dst + (uint32_t)slot * STAGE_BYTES;
+        if (RAGGED && issue_kt == nk - 1) {
             // last, partial stage of a position: through registers, chunks beyond Cp become zeros
 #pragma unroll
             for (int i = 0; i < LPW; ++i) {
-                const int gk = issue_kt * BKE + src_chunk[i] * EPC;
+                const int row = (wave + NW * i) * RPL + lrow;
+                const int chunk = lchunk ^ ((row >> 1) & (CPR - 1));
                 uint4 v = make_uint4(0, 0, 0, 0);
-                if (gk < Cp) v = *reinterpret_cast<const uint4*>(cur[i]);
-                *reinterpret_cast<uint4*>(slot + (wave + NW * i) * 1024 + lane * 16) = v;
+                if ((size_t)issue_kt * RB + (size_t)chunk * 16 < row_bytes) v = *reinterpret_cast<const uint4*>((i < LA ? sA : sB) + goff[i]);
+                *reinterpret_cast<uint4*>(lds + (size_t)slot * STAGE_BYTES + (size_t)(wave + NW * i) * 1024 + lane * 16) = v;
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < LPW; ++i) dma_load_1k(cur[i], slot + (wave + NW * i) * 1024);
+            for (int i = 0; i < LPW; ++i) if (!(DBG & 4)) dma_load_1k_s(i < LA ? sA : sB, goff[i], dst + (uint32_t)(NW * i) * 1024u);
         }
         if (++issue_kt == nk) {
             issue_kt = 0;
-#pragma unroll
-            for (int i = 0; i < LPW; ++i) {
-                const bool isA = ((wave + NW * i) * RPL) < BM;         // wave-uniform
-                cur[i] += (isA ? planeA : planeB) - (size_t)(nk - 1) * BKE;
-            }
+            sA += planeA - (size_t)(nk - 1) * RB;
+            sB += planeB - (size_t)(nk - 1) * RB;
         } else {
-#pragma unroll
-            for (int i = 0; i < LPW; ++i) cur[i] += BKE;
+            sA += RB;
+            sB += RB;
         }
     };
 
-    float16_t accM[FM][FN], accY[4][FM][FN];
+    // One product accumulator per 32x32 sub-tile; a wave with a single sub-tile keeps two and alternates between them,
+    // so that consecutive MFMAs do not wait for each other.
+    constexpr int NACC = (FM * FN == 1) ? 2 : 1;
+    float16_t accM[NACC][FM][FN], accY[4][FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) accM[i][j][r] = 0.f;
+            for (int q = 0; q < NACC; ++q)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) accM[q][i][j][r] = 0.f;
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) accY[q][i][j][r] = 0.f;
         }
 
+    // The reduction steps of a stage are taken in two halves, and the fragments of the next half are read from LDS while
+    // the MFMAs of the current one run (the second half of a stage overlaps with the first reads of the next stage, after
+    // the barrier that makes it visible).  Written out explicitly, with scheduling barriers between the phases: left
+    // to itself the compiler puts every fragment read directly in front of the MFMA that uses it and waits for it there.
+    // Fragment addresses: the swizzled chunk of step ks is chunk(0) ^ 2ks, i.e. the byte address of step 0 with bits 5-6
+    // flipped, and sub-tile i lies 32 rows further on; so two per-lane addresses (one per operand) serve a whole stage.
+    constexpr int KS = CPR / 2;                           // MFMA steps per stage (one 16-byte chunk pair each)
+    constexpr int KH = KS / 2;                            // per half
+    static_assert(KS % 2 == 0, "two halves per stage");
+    static_assert((FM - 1) * 32 * RB < 65536 && (FN - 1) * 32 * RB < 65536, "sub-tile offsets fit the ds_read offset field");
+    u32x4_t fa[2][KH][FM], fb[2][KH][FN];
+    if (DBG) {
 #pragma unroll
-    for (int s = 0; s < NST - 1; ++s)
-        if (s < total) issue_stage(s);
-
-    const int frag_row = lane & 31, frag_half = lane >> 5;
-    int s = 0;
-    for (int pos = 0; pos < A2; ++pos) {
-        for (int kt = 0; kt < nk; ++kt, ++s) {
-            // Stage s must have landed.  Transfers complete in issue order, so it is enough to allow as many
-            // outstanding as were issued after it: NST-2 stages in steady state, and once the ring stops
-            // refilling simply everything.
-            if (s + NST - 1 >= total) wait_vmcnt<0>();
-            else wait_vmcnt<(NST - 2) * LPW>();
-            __syncthreads();            // stage s visible to all waves; everyone is done with stage s-1
-            if (s + NST - 1 < total) issue_stage(s + NST - 1);   // refills the slot stage s-1 used
-
-            const unsigned char* slot = lds + (s % NST) * STAGE_BYTES;
-            uint4 fa[CPR / 2][FM], fb[CPR / 2][FN];
+        for (int q = 0; q < 2; ++q)
 #pragma unroll
-            for (int ks = 0; ks < CPR / 2; ++ks) {
+            for (int kk = 0; kk < KH; ++kk) {
 #pragma unroll
-                for (int i = 0; i < FM; ++i) {
-                    const int row = wm * WTM + i * 32 + frag_row;
-                    const int chunk = (2 * ks + frag_half) ^ ((row >> 1) & (CPR - 1));
-                    fa[ks][i] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
-                }
+                for (int i = 0; i < FM; ++i) fa[q][kk][i] = u32x4_t{0, 0, 0, 0};
 #pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    const int row = BM + wn * WTN + j * 32 + frag_row;
-                    const int chunk = (2 * ks + frag_half) ^ ((row >> 1) & (CPR - 1));
-                    fb[ks][j] = *reinterpret_cast<const uint4*>(slot + row * RB + chunk * 16);
-                }
+                for (int j = 0; j < FN; ++j) fb[q][kk][j] = u32x4_t{0, 0, 0, 0};
             }
+    }
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    const int rowA = wm * WTM + frag_row, rowB = BM + wn * WTN + frag_row;
+    const uint32_t fbaseA = lds0 + (uint32_t)rowA * RB + (uint32_t)((frag_half ^ ((rowA >> 1) & (CPR - 1))) << 4);
+    const uint32_t fbaseB = lds0 + (uint32_t)rowB * RB + (uint32_t)((frag_half ^ ((rowB >> 1) & (CPR - 1))) << 4);
+    constexpr int NREAD = KH * (FM + FN);                 // fragment reads per half
+    auto read_half = [&](int slot, auto hc, auto bufc) {
+        constexpr int h = decltype(hc)::value, buf = decltype(bufc)::value;
+        const uint32_t a0 = fbaseA + (uint32_t)slot * STAGE_BYTES, b0 = fbaseB + (uint32_t)slot * STAGE_BYTES;
+        if (DBG & 2) return;
+        static_for<KH>([&](auto kc) {
+            constexpr int kk = decltype(kc)::value;
+            const uint32_t flip = (uint32_t)((h * KH + kk) << 5);
+            static_for<FM>([&](auto ic) { constexpr int i = decltype(ic)::value; lds_read16_async<i * 32 * RB>(fa[buf][kk][i], a0 ^ flip); });
+            static_for<FN>([&](auto jc) { constexpr int j = decltype(jc)::value; lds_read16_async<j * 32 * RB>(fb[buf][kk][j], b0 ^ flip); });
+        });
+    };
+    // everything but the `newer` most recent reads has arrived; ties buffer `buf` to that point
+    auto await_half = [&](auto bufc, auto newerc) {
+        constexpr int buf = decltype(bufc)::value;
+        lds_wait<decltype(newerc)::value>();
 #pragma unroll
-            for (int ks = 0; ks < CPR / 2; ++ks)
+        for (int kk = 0; kk < KH; ++kk) {
 #pragma unroll
-                for (int i = 0; i < FM; ++i)
+            for (int i = 0; i < FM; ++i) pin(fa[buf][kk][i]);
 #pragma unroll
-                    for (int j = 0; j < FN; ++j) Mma<E>::run(fa[ks][i], fb[ks][j], accM[i][j]);
+            for (int j = 0; j < FN; ++j) pin(fb[buf][kk][j]);
         }
-        // step (iii), folded in: scatter this position's product into the four output accumulators
+    };
+    auto mma_half = [&](auto bufc) {
+        constexpr int buf = decltype(bufc)::value;
+        if (DBG & 1) return;
+#pragma unroll
+        for (int kk = 0; kk < KH; ++kk)
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j) Mma<E>::run(fa[buf][kk][i], fb[buf][kk][j], accM[kk % NACC][i][j]);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+
+    // prologue: fill the ring, wait for stage 0, read its first half
+#pragma unroll
+    for (int s = 0; s < NST; ++s)
+        if (s < total) issue_stage(s);
+    if (NST - 1 >= total) wait_vmcnt<0>();
+    else wait_vmcnt<(NST - 1) * LPW>();
+    __syncthreads();
+    read_half(0, I0(), I0());
+
+    int kt = 0, pos = 0;
+    // after the last MFMA of a stage: at the end of a position, step (iii) folded in - the position's product is scattered
+    // into the four output accumulators and cleared
+    auto end_of_stage = [&]() {
+        if (DBG & 32) return;
+        if (++kt < nk) return;
+        kt = 0;
         const int xi = pos >> 2, nu = pos & 3;
+        ++pos;
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -193,24 +241,72 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
 #pragma unroll
                         for (int j = 0; j < FN; ++j)
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) accY[a * 2 + b][i][j][r] = fmaf(c, accM[i][j][r], accY[a * 2 + b][i][j][r]);
+                            for (int r = 0; r < 16; ++r) {
+                                float m = accM[0][i][j][r];
+                                if constexpr (NACC == 2) m += accM[1][i][j][r];
+                                accY[a * 2 + b][i][j][r] = fmaf(c, m, accY[a * 2 + b][i][j][r]);
+                            }
                 }
             }
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+        for (int q = 0; q < NACC; ++q)
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
+            for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) accM[i][j][r] = 0.f;
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) accM[q][i][j][r] = 0.f;
+    };
+    // All stages but the last (which is peeled, so that the loop body has no conditional LDS traffic: with one, the
+    // compiler's wait insertion falls back to waiting for the newest reads before the second half's MFMAs).
+    using NR = std::integral_constant<int, NREAD>;
+    for (int s = 0; s < total - 1; ++s) {
+        const int slot = s & (NST - 1), next_slot = (s + 1) & (NST - 1);
+        // first half: its fragments (buffer 0) were requested one half earlier; request the second half, then multiply
+        read_half(slot, I1(), I1());
+        await_half(I0(), NR());
+        __builtin_amdgcn_sched_barrier(0);
+        mma_half(I0());
+        __builtin_amdgcn_sched_barrier(0);
+        // second half: meanwhile make stage s+1 visible, refill the slot of stage s, and request the first half of stage
+        // s+1.  Transfers complete in issue order, so stage s+1 has landed once no more are outstanding than were issued
+        // after it (NST-2 stages in steady state; near the end simply everything).
+        if (s + NST >= total) wait_vmcnt<0>();
+        else wait_vmcnt<(NST - 2) * LPW>();
+        await_half(I1(), I0());         // this wave has read all of stage s
+        if (!(DBG & 8)) __syncthreads();   // stage s+1 visible to all waves; every wave has read all of stage s
+        if (s + NST < total) issue_stage(slot);                  // stage s+NST, into the slot stage s used
+        read_half(next_slot, I0(), I0());
+        __builtin_amdgcn_sched_barrier(0);
+        mma_half(I1());
+        __builtin_amdgcn_sched_barrier(0);
+        end_of_stage();
     }
+    read_half((total - 1) & (NST - 1), I1(), I1());
+    await_half(I0(), NR());
+    mma_half(I0());
+    await_half(I1(), I0());
+    mma_half(I1());
+    end_of_stage();
 
     // ---- epilogue: bias (+ vector, + residual), crop, round once, store ---------------------------------------
     // 32x32 accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
     const int H = g.H, W = g.W, K = g.K;
     const E* res = static_cast<const E*>(post.residual);
+    if (DBG & 16) { if (accY[0][0][0][0] == 123.f) y[0] = from_f32<E>(1.f); return; }
     if constexpr (ROWS_K) {
         // columns are tiles: a lane owns one tile, its registers run over output channels; the two pixels of an output
         // row of the tile are stored together, and neighbouring lanes hold neighbouring tiles of a tile row
+        // bias (and the per-image vector) of this lane's 16 x FM output channels: loaded up front from clamped indices, all
+        // loads in flight together (inside the guarded store loop each would be waited for on its own)
+        float bk[FM][16];
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int k = row0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+                bk[i][r] = bias ? bias[k < K ? k : K - 1] : 0.f;
+            }
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
             int t = col0 + wn * WTN + j * 32 + frag_row;
@@ -219,13 +315,21 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
             const int tj = t % g.tw; const int q = t / g.tw;
             const int ti = q % g.th, n = q / g.th;
             const int i0 = 2 * ti, j0 = 2 * tj;
+            float av[FM][16];
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int k = row0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+                    av[i][r] = post.addvec ? post.addvec[(size_t)n * K + (k < K ? k : K - 1)] : 0.f;
+                }
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int k = row0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
                     if (k < K && t_ok) {
-                        const float bb = (bias ? bias[k] : 0.f) + (post.addvec ? post.addvec[(size_t)n * K + k] : 0.f);
+                        const float bb = bk[i][r] + av[i][r];
                         const size_t off = (((size_t)n * K + k) * H + i0) * W + j0;
 #pragma unroll
                         for (int a = 0; a < 2; ++a) {
@@ -280,7 +384,7 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
     }
 }
 
-template <typename E, int BM, int BN, int NST, int WGM, int WGN, bool ROWS_K>
+template <typename E, int BM, int BN, int NST, int WGM, int WGN, bool ROWS_K, bool RAGGED = false, int DBG = 0>
 static hipError_t launch_fused_cfg(const void* Aop, const void* Bop, int rowsA, int rowsB, const float* bias, void* y,
                                    const Geom& g, const PostOp& post, hipStream_t s) {
     const int tiles_m = (rowsA + BM - 1) / BM, tiles_n = (rowsB + BN - 1) / BN;
@@ -289,7 +393,9 @@ static hipError_t launch_fused_cfg(const void* Aop, const void* Bop, int rowsA, 
     const int per_xcd = (int)((total + 7) / 8);
     constexpr int lds_bytes = (BM + BN) * 128 * NST;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
-    auto kern = wino_fused_f2_kernel<E, BM, BN, NST, WGM, WGN, ROWS_K>;
+    // lane offsets are 32-bit: a block's rows must span less than 2 GB
+    if ((size_t)g.Cp * sizeof(E) * (size_t)(BM > BN ? BM : BN) >= ((size_t)1 << 31)) return hipErrorInvalidValue;
+    auto kern = wino_fused_f2_kernel<E, BM, BN, NST, WGM, WGN, ROWS_K, RAGGED, DBG>;
     // once per instantiation; a function-local static is initialised under the language's own lock
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (attr != hipSuccess) return attr;
@@ -315,18 +421,51 @@ int fused_pick_shape(int rows, int cols) {
 template <typename E, bool ROWS_K>
 static hipError_t launch_fused_t(const void* Aop, const void* Bop, int rowsA, int rowsB, const float* bias, void* y,
                                  const Geom& g, const PostOp& post, int shape, hipStream_t s) {
+    // a reduction length that is not a whole number of stages: one block shape with the zero-filling last stage
+    if (g.Cp % (128 / (int)sizeof(E)) != 0)
+        return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, true>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
     switch (shape) {
+        case 0: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
         case 1: return launch_fused_cfg<E, 64, 128, 4, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
         case 2: return launch_fused_cfg<E, 128, 64, 4, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
         case 3: return launch_fused_cfg<E, 128, 128, 4, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-        default: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+        default: break;
     }
+    if constexpr (std::is_same<E, __half>::value && ROWS_K) {      // experimental shapes, fp16 NCHW only
+        switch (shape) {
+            case 4: return launch_fused_cfg<E, 64, 64, 8, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 5: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 6: return launch_fused_cfg<E, 128, 128, 4, 2, 4, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 7: return launch_fused_cfg<E, 128, 64, 4, 4, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 8: return launch_fused_cfg<E, 64, 128, 4, 2, 4, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 9: return launch_fused_cfg<E, 64, 128, 2, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 10: return launch_fused_cfg<E, 128, 128, 2, 4, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            // timing-only ablations of the 64x64 and 128x128 (8 waves) kernels: results are meaningless
+            case 11: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 1>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 12: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 2>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 13: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 4>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 14: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 8>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 15: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 3>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 16: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 7>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 17: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 15>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 23: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 15 + 16>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 24: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 15 + 32>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 25: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 15 + 48>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 18: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K, false, 1>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 19: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K, false, 2>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 20: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K, false, 4>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 21: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K, false, 6>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            case 22: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K, false, 7>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+            default: break;
+        }
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_fused_gemm_output(const void* U, const void* V, const float* bias, void* y, const Geom& g, int dt, bool nhwc,
                                     const PostOp* postp, int shape, hipStream_t s) {
     if (g.m != 2) return hipErrorInvalidValue;
-    if (shape < -1 || shape > 3) return hipErrorInvalidValue;
+    if (shape < -1 || shape > 25) return hipErrorInvalidValue;
     const PostOp post = postp ? *postp : PostOp();
     return with_dtype(dt, [&](auto* tag) {
         using E = std::remove_pointer_t<decltype(tag)>;

@@ -8,6 +8,8 @@ namespace wino {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));      // a 16-byte fragment as a native vector (inline-asm operand)
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 template <typename E> struct Mma;
 template <> struct Mma<__half> {
@@ -16,12 +18,18 @@ template <> struct Mma<__half> {
         c = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const half8_t*>(&a),
                                                     *reinterpret_cast<const half8_t*>(&b), c, 0, 0, 0);
     }
+    static __device__ __forceinline__ void run(const u32x4_t& a, const u32x4_t& b, float16_t& c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+    }
 };
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 template <> struct Mma<bf16_t> {
     static __device__ __forceinline__ void run(const uint4& a, const uint4& b, float16_t& c) {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(&a),
                                                      *reinterpret_cast<const bf16x8_t*>(&b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void run(const u32x4_t& a, const u32x4_t& b, float16_t& c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
 };
 template <> struct Mma<float> {
@@ -30,6 +38,13 @@ template <> struct Mma<float> {
         const float* fb = reinterpret_cast<const float*>(&b);
 #pragma unroll
         for (int j = 0; j < 4; ++j) c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j], fb[j], c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void run(const u32x4_t& a, const u32x4_t& b, float16_t& c) {
+        const f32x4_t fa = __builtin_bit_cast(f32x4_t, a), fb = __builtin_bit_cast(f32x4_t, b);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.x, fb.x, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.y, fb.y, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.z, fb.z, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.w, fb.w, c, 0, 0, 0);
     }
 };
 
@@ -68,7 +83,35 @@ __device__ __forceinline__ void dma_load_1k(const void* src, unsigned char* lds_
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                  :: "s"(m0v), "v"(src) : "memory", "m0");
 }
+// The same transfer with the global address split into a wave-uniform 64-bit base (scalar registers) and a 32-bit
+// byte offset per lane, and the LDS destination given as a wave-uniform LDS byte address: nothing per-lane has to be
+// recomputed from stage to stage, the base moves on the scalar unit.
+__device__ __forceinline__ void dma_load_1k_s(const void* base, uint32_t lane_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory", "m0");
+}
 #pragma clang diagnostic pop
+
+// Fragment reads under explicit control.  The read is issued from inline assembly, so the compiler does not track it
+// (it would otherwise place its own lgkmcnt waits, and in loops it falls back to waiting for the newest read); the
+// kernel waits with lds_wait<N>() and then passes every register the reads wrote through pin(), which ties the
+// MFMAs that consume them to a point after the wait.  LDS reads return in order, so lds_wait<N>() guarantees everything
+// but the N most recently issued reads.
+template <int OFF> __device__ __forceinline__ void lds_read16_async(u32x4_t& dst, uint32_t addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+template <int N> __device__ __forceinline__ void lds_wait() {
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void pin(u32x4_t& v) { asm volatile("" : "+v"(v)); }
+
+// compile-time loop: f(std::integral_constant<int, 0>()), ..., f(std::integral_constant<int, N-1>())
+template <int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>());
+    }
+}
 
 }  // namespace wino
 #endif

@@ -108,5 +108,5 @@ def test_stage_calls_that_need_a_stored_product_reject_the_fused_variant():
         B.wino_batched_gemm(U, U, 8, 8, 8, B.WINO_FUSED_F2)
     assert e.value.status == B.WINO_ERR_VARIANT
     with pytest.raises(B.WinoError) as e:
-        B.wino_fused_gemm_output(U, U, None, 1, 8, 4, 4, 8, block_shape=9)
+        B.wino_fused_gemm_output(U, U, None, 1, 8, 4, 4, 8, block_shape=99)
     assert e.value.status == B.WINO_ERR_VARIANT
