@@ -183,10 +183,12 @@ int wino_output_transform(const float *M, const float *bias, void *y, int N, int
 /*
  * Steps (ii) and (iii) + bias in one kernel, the second launch of WINO_FUSED_F2 (F(2x2,3x3) only):
  *   U[16][K][Cp], V[16][T][Cp] as above  ->  y[N][K][H][W] (WINO_NCHW) or y[N][H][W][K] (WINO_NHWC) in `dtype`.
- * block_shape = -1 lets the library choose the workgroup's block; 0..3 name one (rows x columns of the
+ * block_shape = -1 lets the library choose the workgroup's block; 0..6 name one (rows x columns of the
  * block, rows = output channels for NCHW and tiles for NHWC): 0 = 64x64, 1 = 64x128, 2 = 128x64,
- * 3 = 128x128.  Every shape gives the same sums in the same order; the argument exists so that tests and
- * measurements can reach each kernel instantiation on small inputs.  WINO_ERR_VARIANT for other values.
+ * 3 = 128x128 with four waves, 4 = 128x128, 5 = 128x64, 6 = 64x128 with eight waves.  The shapes differ
+ * only in which fp32 partial sums are added first (results agree to fp32 rounding); the argument exists so
+ * that tests and measurements can reach each kernel instantiation on small inputs.  WINO_ERR_VARIANT for
+ * other values.  Reduction lengths that are not a multiple of 64 (fp32: 32) always run the 64x64 block.
  */
 int wino_fused_gemm_output(const void *U, const void *V, const float *bias, void *y,
                            int N, int C, int H, int W, int K, int dtype, int layout, int block_shape, void *stream);

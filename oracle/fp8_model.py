@@ -47,3 +47,30 @@ def conv2d_fp8(x, w, bias, sx: float, sw: float, stride: int = 1) -> np.ndarray:
     if bias is not None:
         y = y + np.asarray(bias, dtype=np.float64)[None, :, None, None]
     return y
+
+
+def conv2d_winograd_8bit(x, w, bias, m: int, fmt: str = "e4m3", per_position: bool = False) -> np.ndarray:
+    """Error model (not the definition of a result): the three Winograd steps with the TRANSFORMED tensors U and V held
+    in 8 bits - E4M3 with a power-of-two scale, or int8 with a symmetric linear scale - per tensor, or one scale per
+    position (xi, nu) of the transformed tile; products accumulated exactly, y kept in fp64.  Answers whether 8-bit
+    operands for step (ii) of the Winograd path could meet a useful tolerance: the transforms mix values of very
+    different size into one tensor and the inverse transform amplifies what the rounding leaves behind."""
+    from . import winograd_ref as wr
+    x = np.asarray(x, dtype=np.float64)
+    N, C, H, W = x.shape
+    U = wr.filter_transform(w, m)
+    V = wr.input_transform(x, m)
+
+    def q(a):
+        axes = (2, 3) if per_position else None
+        mx = np.max(np.abs(a), axis=axes, keepdims=True)
+        mx = np.where(mx == 0, 1.0, mx)
+        if fmt == "e4m3":
+            s = 2.0 ** np.floor(np.log2(E4M3_MAX / mx))
+            return round_to_e4m3(a * s) / s
+        if fmt == "int8":
+            s = 127.0 / mx
+            return np.clip(np.rint(a * s), -127, 127) / s
+        raise ValueError(fmt)
+
+    return wr.output_transform(wr.multiply(q(U), q(V)), bias, N, H, W, m)

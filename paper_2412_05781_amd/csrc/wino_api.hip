@@ -453,7 +453,7 @@ int wino_fused_gemm_output(const void* U, const void* V, const float* bias, void
     if (!U || !V || !y) return WINO_ERR_NULL;
     if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
     if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
-    if (block_shape < -1 || block_shape > 25) return WINO_ERR_VARIANT;
+    if (block_shape < -1 || block_shape > 6) return WINO_ERR_VARIANT;
     if (!dims_ok(N, C, H, W, K, 2)) return WINO_ERR_DIM;
     if (!aligned16(U) || !aligned16(V) || !aligned16(y) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u))) return WINO_ERR_ALIGN;
     const Geom g = make_geom(N, C, H, W, K, 2);

@@ -41,7 +41,7 @@ struct FusedGeom { int N, K, H, W, th, tw, T; };
 
 // RAGGED = true: Cp is not a multiple of the stage (64 fp16 / 32 fp32 elements); the last stage of every position
 // then goes through registers with zero fill.  The common case (RAGGED = false) has no such code in its loop.
-template <typename E, int BM, int BN, int NST, int WGM, int WGN, bool ROWS_K, bool RAGGED, int DBG = 0>
+template <typename E, int BM, int BN, int NST, int WGM, int WGN, bool ROWS_K, bool RAGGED>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const float* __restrict__ bias, E* __restrict__ y,
                      int rowsA, int rowsB, int Cp, FusedGeom g, int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd,
@@ -119,7 +119,7 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < LPW; ++i) if (!(DBG & 4)) dma_load_1k_s(i < LA ? sA : sB, goff[i], dst + (uint32_t)(NW * i) * 1024u);
+            for (int i = 0; i < LPW; ++i) dma_load_1k_s(i < LA ? sA : sB, goff[i], dst + (uint32_t)(NW * i) * 1024u);
         }
         if (++issue_kt == nk) {
             issue_kt = 0;
@@ -160,17 +160,6 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
     static_assert(KS % 2 == 0, "two halves per stage");
     static_assert((FM - 1) * 32 * RB < 65536 && (FN - 1) * 32 * RB < 65536, "sub-tile offsets fit the ds_read offset field");
     u32x4_t fa[2][KH][FM], fb[2][KH][FN];
-    if (DBG) {
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-#pragma unroll
-            for (int kk = 0; kk < KH; ++kk) {
-#pragma unroll
-                for (int i = 0; i < FM; ++i) fa[q][kk][i] = u32x4_t{0, 0, 0, 0};
-#pragma unroll
-                for (int j = 0; j < FN; ++j) fb[q][kk][j] = u32x4_t{0, 0, 0, 0};
-            }
-    }
     const int frag_row = lane & 31, frag_half = lane >> 5;
     const int rowA = wm * WTM + frag_row, rowB = BM + wn * WTN + frag_row;
     const uint32_t fbaseA = lds0 + (uint32_t)rowA * RB + (uint32_t)((frag_half ^ ((rowA >> 1) & (CPR - 1))) << 4);
@@ -179,7 +168,6 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
     auto read_half = [&](int slot, auto hc, auto bufc) {
         constexpr int h = decltype(hc)::value, buf = decltype(bufc)::value;
         const uint32_t a0 = fbaseA + (uint32_t)slot * STAGE_BYTES, b0 = fbaseB + (uint32_t)slot * STAGE_BYTES;
-        if (DBG & 2) return;
         static_for<KH>([&](auto kc) {
             constexpr int kk = decltype(kc)::value;
             const uint32_t flip = (uint32_t)((h * KH + kk) << 5);
@@ -201,7 +189,6 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
     };
     auto mma_half = [&](auto bufc) {
         constexpr int buf = decltype(bufc)::value;
-        if (DBG & 1) return;
 #pragma unroll
         for (int kk = 0; kk < KH; ++kk)
 #pragma unroll
@@ -225,7 +212,6 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
     // after the last MFMA of a stage: at the end of a position, step (iii) folded in - the position's product is scattered
     // into the four output accumulators and cleared
     auto end_of_stage = [&]() {
-        if (DBG & 32) return;
         if (++kt < nk) return;
         kt = 0;
         const int xi = pos >> 2, nu = pos & 3;
@@ -274,7 +260,7 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
         if (s + NST >= total) wait_vmcnt<0>();
         else wait_vmcnt<(NST - 2) * LPW>();
         await_half(I1(), I0());         // this wave has read all of stage s
-        if (!(DBG & 8)) __syncthreads();   // stage s+1 visible to all waves; every wave has read all of stage s
+        __syncthreads();                // stage s+1 visible to all waves; every wave has read all of stage s
         if (s + NST < total) issue_stage(slot);                  // stage s+NST, into the slot stage s used
         read_half(next_slot, I0(), I0());
         __builtin_amdgcn_sched_barrier(0);
@@ -293,7 +279,6 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
     // 32x32 accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
     const int H = g.H, W = g.W, K = g.K;
     const E* res = static_cast<const E*>(post.residual);
-    if (DBG & 16) { if (accY[0][0][0][0] == 123.f) y[0] = from_f32<E>(1.f); return; }
     if constexpr (ROWS_K) {
         // columns are tiles: a lane owns one tile, its registers run over output channels; the two pixels of an output
         // row of the tile are stored together, and neighbouring lanes hold neighbouring tiles of a tile row
@@ -384,7 +369,7 @@ wino_fused_f2_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
     }
 }
 
-template <typename E, int BM, int BN, int NST, int WGM, int WGN, bool ROWS_K, bool RAGGED = false, int DBG = 0>
+template <typename E, int BM, int BN, int NST, int WGM, int WGN, bool ROWS_K, bool RAGGED = false>
 static hipError_t launch_fused_cfg(const void* Aop, const void* Bop, int rowsA, int rowsB, const float* bias, void* y,
                                    const Geom& g, const PostOp& post, hipStream_t s) {
     const int tiles_m = (rowsA + BM - 1) / BM, tiles_n = (rowsB + BN - 1) / BN;
@@ -395,7 +380,7 @@ static hipError_t launch_fused_cfg(const void* Aop, const void* Bop, int rowsA, 
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
     // lane offsets are 32-bit: a block's rows must span less than 2 GB
     if ((size_t)g.Cp * sizeof(E) * (size_t)(BM > BN ? BM : BN) >= ((size_t)1 << 31)) return hipErrorInvalidValue;
-    auto kern = wino_fused_f2_kernel<E, BM, BN, NST, WGM, WGN, ROWS_K, RAGGED, DBG>;
+    auto kern = wino_fused_f2_kernel<E, BM, BN, NST, WGM, WGN, ROWS_K, RAGGED>;
     // once per instantiation; a function-local static is initialised under the language's own lock
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (attr != hipSuccess) return attr;
@@ -407,14 +392,13 @@ static hipError_t launch_fused_cfg(const void* Aop, const void* Bop, int rowsA, 
     return hipGetLastError();
 }
 
-// Block shapes on offer (rows x columns of the block, waves): 0 = 64x64 (2x2 waves), 1 = 64x128, 2 = 128x64,
-// 3 = 128x128 (each wave 64x64: 320 accumulator registers, one workgroup per compute unit).
+// Block shapes on offer (rows x columns of the block): 0 = 64x64, 1 = 64x128, 2 = 128x64, 3 = 128x128 (four waves, 2x2),
+// 4 = 128x128, 5 = 128x64, 6 = 64x128 (eight waves: two per SIMD, each with half the accumulators).
+// Measured on the SD-shaped layers: the larger blocks pay only while they still fill the chip.
 int fused_pick_shape(int rows, int cols) {
     auto blocks = [&](int bm, int bn) { return (long long)((rows + bm - 1) / bm) * ((cols + bn - 1) / bn); };
-    // the largest block that still leaves at least one workgroup per compute unit
-    if (blocks(128, 128) >= 256) return 3;
-    if (rows >= cols ? blocks(128, 64) >= 256 : blocks(64, 128) >= 256) return rows >= cols ? 2 : 1;
-    if (rows >= cols ? blocks(64, 128) >= 256 : blocks(128, 64) >= 256) return rows >= cols ? 1 : 2;
+    if (blocks(128, 128) >= 160) return 4;
+    if (rows >= cols ? blocks(64, 128) >= 200 : blocks(128, 64) >= 200) return rows >= cols ? 6 : 5;
     return 0;
 }
 
@@ -429,43 +413,17 @@ static hipError_t launch_fused_t(const void* Aop, const void* Bop, int rowsA, in
         case 1: return launch_fused_cfg<E, 64, 128, 4, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
         case 2: return launch_fused_cfg<E, 128, 64, 4, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
         case 3: return launch_fused_cfg<E, 128, 128, 4, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-        default: break;
+        case 4: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+        case 5: return launch_fused_cfg<E, 128, 64, 4, 4, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+        case 6: return launch_fused_cfg<E, 64, 128, 4, 2, 4, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
+        default: return hipErrorInvalidValue;
     }
-    if constexpr (std::is_same<E, __half>::value && ROWS_K) {      // experimental shapes, fp16 NCHW only
-        switch (shape) {
-            case 4: return launch_fused_cfg<E, 64, 64, 8, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 5: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 6: return launch_fused_cfg<E, 128, 128, 4, 2, 4, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 7: return launch_fused_cfg<E, 128, 64, 4, 4, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 8: return launch_fused_cfg<E, 64, 128, 4, 2, 4, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 9: return launch_fused_cfg<E, 64, 128, 2, 2, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 10: return launch_fused_cfg<E, 128, 128, 2, 4, 2, ROWS_K>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            // timing-only ablations of the 64x64 and 128x128 (8 waves) kernels: results are meaningless
-            case 11: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 1>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 12: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 2>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 13: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 4>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 14: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 8>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 15: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 3>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 16: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 7>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 17: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 15>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 23: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 15 + 16>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 24: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 15 + 32>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 25: return launch_fused_cfg<E, 64, 64, 4, 2, 2, ROWS_K, false, 15 + 48>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 18: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K, false, 1>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 19: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K, false, 2>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 20: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K, false, 4>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 21: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K, false, 6>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            case 22: return launch_fused_cfg<E, 128, 128, 4, 4, 2, ROWS_K, false, 7>(Aop, Bop, rowsA, rowsB, bias, y, g, post, s);
-            default: break;
-        }
-    }
-    return hipErrorInvalidValue;
 }
 
 hipError_t launch_fused_gemm_output(const void* U, const void* V, const float* bias, void* y, const Geom& g, int dt, bool nhwc,
                                     const PostOp* postp, int shape, hipStream_t s) {
     if (g.m != 2) return hipErrorInvalidValue;
-    if (shape < -1 || shape > 25) return hipErrorInvalidValue;
+    if (shape < -1 || shape > 6) return hipErrorInvalidValue;
     const PostOp post = postp ? *postp : PostOp();
     return with_dtype(dt, [&](auto* tag) {
         using E = std::remove_pointer_t<decltype(tag)>;

@@ -171,7 +171,7 @@ def test_fused_variant_sizes_and_the_entry_points_added_for_it(L):
     assert L.wino_batched_gemm_shape(None, a, a, 8, 8, 8, B.WINO_F16, B.WINO_F2, 0, None) == B.WINO_ERR_NULL
     assert L.wino_batched_gemm_shape(a, a, a, 8, 8, 8, B.WINO_F16, B.WINO_FUSED_F2, 0, None) == B.WINO_ERR_VARIANT
     assert L.wino_batched_gemm(a, a, a, 8, 8, 8, B.WINO_F16, B.WINO_FUSED_F2, None) == B.WINO_ERR_VARIANT
-    assert L.wino_fused_gemm_output(a, a, None, a, 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 4, None) == B.WINO_ERR_VARIANT
+    assert L.wino_fused_gemm_output(a, a, None, a, 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 7, None) == B.WINO_ERR_VARIANT
     assert L.wino_fused_gemm_output(a, None, None, a, 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_NULL
     assert L.wino_fused_gemm_output(a, a, None, a, 1, 8, 4, 4, 8, B.WINO_F16, 5, 0, None) == B.WINO_ERR_LAYOUT
     assert L.wino_fused_gemm_output(a, a, None, vp(0x1008), 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_ALIGN

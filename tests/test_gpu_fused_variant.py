@@ -49,8 +49,9 @@ def test_whole_path_small_shapes(shape, layout, dtype):
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 @pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
-@pytest.mark.parametrize("block_shape", [0, 1, 2, 3])
-@pytest.mark.parametrize("shape", [(2, 5, 7, 5, 7), (1, 33, 65, 17, 30), (2, 136, 200, 16, 16), (1, 200, 150, 37, 41), (1, 72, 300, 21, 39)])
+@pytest.mark.parametrize("block_shape", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("shape", [(2, 5, 7, 5, 7), (1, 33, 65, 17, 30), (2, 136, 200, 16, 16), (1, 200, 150, 37, 41), (1, 72, 300, 21, 39),
+                                   (1, 64, 200, 30, 34), (2, 128, 320, 16, 32), (1, 192, 130, 64, 64)])
 def test_every_block_shape(shape, block_shape, layout, dtype):
     """The stage call with a named block shape: each instantiation on inputs with ragged rows and columns, a ragged
     last reduction stage (C not a multiple of 64 / 32) and more than one block in both directions."""
@@ -65,10 +66,11 @@ def test_every_block_shape(shape, block_shape, layout, dtype):
     y = B.wino_fused_gemm_output(U, V, b.to(DEV), N, C, H, W, K, layout=layout, block_shape=block_shape)
     torch.cuda.synchronize()
     pu.check(_nchw(y, layout), ref, TOL[dtype], 2, dtype, what=(shape, block_shape, layout, dtype), channels=C)
-    # the library's own choice of block gives the same sums in the same order: bitwise equal
+    # the library's own choice of block differs at most in the order of fp32 additions
     y_auto = B.wino_fused_gemm_output(U, V, b.to(DEV), N, C, H, W, K, layout=layout)
     torch.cuda.synchronize()
-    assert torch.equal(y, y_auto)
+    d = (y.float() - y_auto.float()).abs().max().item()
+    assert d <= (2.0 ** -9 if dtype == "f16" else 1e-5) * max(1.0, y.float().abs().max().item())
 
 
 @pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
@@ -108,5 +110,5 @@ def test_stage_calls_that_need_a_stored_product_reject_the_fused_variant():
         B.wino_batched_gemm(U, U, 8, 8, 8, B.WINO_FUSED_F2)
     assert e.value.status == B.WINO_ERR_VARIANT
     with pytest.raises(B.WinoError) as e:
-        B.wino_fused_gemm_output(U, U, None, 1, 8, 4, 4, 8, block_shape=99)
+        B.wino_fused_gemm_output(U, U, None, 1, 8, 4, 4, 8, block_shape=7)
     assert e.value.status == B.WINO_ERR_VARIANT

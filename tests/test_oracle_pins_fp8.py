@@ -54,3 +54,27 @@ def test_quantised_convolution_properties_and_error_band():
     y1 = f8.conv2d_fp8(x, w1, None, sx, s1)
     assert np.abs(y1 - np.einsum("kc,nchw->nkhw", f8.round_to_e4m3(w1[:, :, 0, 0] * s1) / s1, xq)).max() < 1e-12
     assert np.array_equal(f8.conv2d_fp8(x, w, b, sx, sw, stride=2), y[:, :, ::2, ::2])
+
+
+def test_eight_bit_transformed_operands_error_bands():
+    """What 8-bit storage of the TRANSFORMED tensors U and V would cost the Winograd path (the model is exact when the
+    operands are already representable, see the first assertion).  E4M3 with per-tensor power-of-two scales: about
+    6e-2 for F(2x2) - 1.7x the error of quantising x and w themselves on the direct path - and 0.4 for F(4x4); scales
+    per tile position change nothing for a floating-point format.  int8 with one linear scale per tile position:
+    about 2.2e-2 for F(2x2), 0.13 for F(4x4).  These figures decide which 8-bit variants are worth building."""
+    rng = np.random.default_rng(3)
+    N, C, K, H, W = 1, 64, 16, 12, 12
+    x = rng.standard_normal((N, C, H, W)); w = rng.standard_normal((K, C, 3, 3)) / np.sqrt(9 * C); b = 0.1 * rng.standard_normal(K)
+    ref = oracle.conv2d_direct(x, w, b)
+    # operands whose transforms are small multiples of 1/2 need at most four significant bits: exact in E4M3 with a
+    # power-of-two scale, so the model then returns the exact convolution
+    xi = rng.integers(-2, 3, (1, 3, 6, 6)).astype(np.float64); wi = 2.0 * rng.integers(-1, 2, (2, 3, 3, 3)).astype(np.float64)
+    for pp in (False, True):
+        assert np.abs(f8.conv2d_winograd_8bit(xi, wi, None, 2, "e4m3", pp) - oracle.conv2d_direct(xi, wi, None)).max() < 1e-9
+    band = {(2, "e4m3", False): (4.5e-2, 8e-2), (2, "e4m3", True): (4.5e-2, 8e-2), (2, "int8", True): (1.5e-2, 3e-2),
+            (2, "int8", False): (1.8e-2, 3.5e-2), (4, "e4m3", False): (0.25, 0.6), (4, "int8", True): (0.08, 0.2)}
+    for (m, fmt, pp), (lo, hi) in band.items():
+        err = oracle.rel_l2(f8.conv2d_winograd_8bit(x, w, b, m, fmt, pp), ref)
+        assert lo <= err <= hi, (m, fmt, pp, err)
+    direct = oracle.rel_l2(f8.conv2d_fp8(x, w, b, f8.power_of_two_scale(x), f8.power_of_two_scale(w)), ref)
+    assert oracle.rel_l2(f8.conv2d_winograd_8bit(x, w, b, 2, "e4m3"), ref) > 1.4 * direct
