@@ -18,6 +18,7 @@
 // through registers with zero fill instead.
 #include "wino_internal.h"
 #include "wino_mma.h"
+#include <type_traits>
 
 namespace wino {
 
@@ -171,6 +172,224 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __restric
         }
 }
 
+// The same product for reduction lengths that are a whole number of stages (every Stable-Diffusion layer), written for
+// the way this chip behaves with one to four waves per SIMD: every instruction a wave spends on addresses, and every
+// wait placed by the compiler in front of an MFMA, is time the MFMA pipe idles.  So
+//  - everything that does not depend on the lane lives in scalar registers (the wave index through readfirstlane):
+//    LDS destinations, stage bases and slot offsets cost scalar instructions only; a transfer is one scalar base plus a
+//    fixed 32-bit offset per lane;
+//  - a stage's reduction steps are taken in two halves and the fragments of the next half (of the next stage, after the
+//    barrier) are requested while the MFMAs of the current half run; the reads are issued from inline assembly and waited
+//    for explicitly, because the compiler otherwise waits for the newest read in front of every MFMA;
+//  - a wave with a single 32x32 sub-tile alternates between two accumulators.
+// Block order, ring, swizzle and the meaning of every argument are those of wino_gemm_kernel.
+template <typename E, typename MT, int BM, int BN, int NST, int WGM, int WGN>
+__global__ void __launch_bounds__(WGM * WGN * 64)
+wino_gemm_lean_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __restrict__ Mo,
+                      int K, int Cp, int T, int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd,
+                      int nbatch, int nsplit) {
+    constexpr int RB = 128;
+    constexpr int CPR = RB / 16;
+    constexpr int BKE = RB / (int)sizeof(E);
+    constexpr int ROWS = BM + BN;
+    constexpr int RPL = 1024 / RB;
+    constexpr int NW = WGM * WGN;
+    constexpr int LPW = ROWS / RPL / NW;
+    constexpr int LA = BM / (RPL * NW);
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int FM = WTM / 32, FN = WTN / 32;
+    constexpr int STAGE_BYTES = ROWS * RB;
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
+    static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "load i of every wave lies in the same operand");
+    static_assert(NST >= 2 && NST <= 4 && LPW * (NST - 1) < 64, "ring depth");
+    static_assert((FM - 1) * 32 * RB < 65536 && (FN - 1) * 32 * RB < 65536, "sub-tile offsets fit the ds_read offset field");
+
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+
+    const int bid = blockIdx.x;
+    const int logical = (bid % 8) * blocks_per_xcd + bid / 8;
+    if (logical >= total_blocks) return;                  // uniform per workgroup, before any barrier
+    const int bs = logical / (tiles_n * tiles_m);
+    const int in_batch = logical - bs * (tiles_n * tiles_m);
+    const int batch = bs / nsplit, split = bs - batch * nsplit;
+    int tm, tn;
+    if (tiles_m <= tiles_n) { tm = in_batch % tiles_m; tn = in_batch / tiles_m; }
+    else { tn = in_batch % tiles_n; tm = in_batch / tiles_n; }
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int row0 = tm * BM, col0 = tn * BN;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte_t*)lds;
+
+    const size_t row_bytes = (size_t)Cp * sizeof(E);
+    const int nk_all = Cp / BKE;                          // Cp is a whole number of stages here
+    const int kt0 = (int)((long long)split * nk_all / nsplit), kt1 = (int)((long long)(split + 1) * nk_all / nsplit);
+    const int total = kt1 - kt0;                          // stages of this workgroup (>= 1: nsplit <= nk_all)
+
+    const int lrow = lane / CPR, lchunk = lane % CPR;
+    uint32_t goff[LPW];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        const int row = (wave + NW * i) * RPL + lrow;
+        const int chunk = lchunk ^ ((row >> 1) & (CPR - 1));
+        int r;
+        if (i < LA) { r = row0 + row; r = (r < K ? r : K - 1) - row0; }
+        else { r = col0 + (row - BM); r = (r < T ? r : T - 1) - col0; }
+        goff[i] = (uint32_t)r * (uint32_t)row_bytes + (uint32_t)chunk * 16u;
+    }
+    const unsigned char* sA = reinterpret_cast<const unsigned char*>(U) + ((size_t)batch * K + row0) * row_bytes + (size_t)kt0 * RB;
+    const unsigned char* sB = reinterpret_cast<const unsigned char*>(V) + ((size_t)batch * T + col0) * row_bytes + (size_t)kt0 * RB;
+    const uint32_t wave_dst = lds0 + (uint32_t)wave * 1024u;
+    auto issue_stage = [&](int slot) {                    // the next stage in order
+        const uint32_t dst = wave_dst + (uint32_t)slot * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) dma_load_1k_s(i < LA ? sA : sB, goff[i], dst + (uint32_t)(NW * i) * 1024u);
+        sA += RB;
+        sB += RB;
+    };
+
+    constexpr int NACC = (FM * FN == 1) ? 2 : 1;
+    float16_t acc[NACC][FM][FN];
+#pragma unroll
+    for (int q = 0; q < NACC; ++q)
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[q][i][j][r] = 0.f;
+
+    constexpr int KS = CPR / 2, KH = KS / 2;
+    constexpr int NREAD = KH * (FM + FN);
+    u32x4_t fa[2][KH][FM], fb[2][KH][FN];
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    const int rowA = wm * WTM + frag_row, rowB = BM + wn * WTN + frag_row;
+    const uint32_t fbaseA = lds0 + (uint32_t)rowA * RB + (uint32_t)((frag_half ^ ((rowA >> 1) & (CPR - 1))) << 4);
+    const uint32_t fbaseB = lds0 + (uint32_t)rowB * RB + (uint32_t)((frag_half ^ ((rowB >> 1) & (CPR - 1))) << 4);
+    auto read_half = [&](int slot, auto hc, auto bufc) {
+        constexpr int h = decltype(hc)::value, buf = decltype(bufc)::value;
+        const uint32_t a0 = fbaseA + (uint32_t)slot * STAGE_BYTES, b0 = fbaseB + (uint32_t)slot * STAGE_BYTES;
+        static_for<KH>([&](auto kc) {
+            constexpr int kk = decltype(kc)::value;
+            const uint32_t flip = (uint32_t)((h * KH + kk) << 5);
+            static_for<FM>([&](auto ic) { constexpr int i = decltype(ic)::value; lds_read16_async<i * 32 * RB>(fa[buf][kk][i], a0 ^ flip); });
+            static_for<FN>([&](auto jc) { constexpr int j = decltype(jc)::value; lds_read16_async<j * 32 * RB>(fb[buf][kk][j], b0 ^ flip); });
+        });
+    };
+    auto await_half = [&](auto bufc, auto newerc) {
+        constexpr int buf = decltype(bufc)::value;
+        lds_wait<decltype(newerc)::value>();
+#pragma unroll
+        for (int kk = 0; kk < KH; ++kk) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i) pin(fa[buf][kk][i]);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) pin(fb[buf][kk][j]);
+        }
+    };
+    auto mma_half = [&](auto bufc) {
+        constexpr int buf = decltype(bufc)::value;
+#pragma unroll
+        for (int kk = 0; kk < KH; ++kk)
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j) Mma<E>::run(fa[buf][kk][i], fb[buf][kk][j], acc[kk % NACC][i][j]);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using NR = std::integral_constant<int, NREAD>;
+
+    // prologue: fill the ring, wait for the first stage, request its first half
+#pragma unroll
+    for (int s = 0; s < NST; ++s)
+        if (s < total) issue_stage(s);
+    if (NST - 1 >= total) wait_vmcnt<0>();
+    else wait_vmcnt<(NST - 1) * LPW>();
+    __syncthreads();
+    read_half(0, I0(), I0());
+
+    int slot = 0;
+    for (int s = 0; s < total - 1; ++s) {
+        const int next_slot = slot + 1 == NST ? 0 : slot + 1;
+        read_half(slot, I1(), I1());
+        await_half(I0(), NR());
+        __builtin_amdgcn_sched_barrier(0);
+        mma_half(I0());
+        __builtin_amdgcn_sched_barrier(0);
+        // stage s+1 has landed once no more transfers are outstanding than were issued after it
+        if (s + NST >= total) wait_vmcnt<0>();
+        else wait_vmcnt<(NST - 2) * LPW>();
+        await_half(I1(), I0());         // this wave has read all of stage s
+        __syncthreads();                // stage s+1 visible to all waves; every wave has read all of stage s
+        if (s + NST < total) issue_stage(slot);                  // stage s+NST, into the slot stage s used
+        read_half(next_slot, I0(), I0());
+        __builtin_amdgcn_sched_barrier(0);
+        mma_half(I1());
+        __builtin_amdgcn_sched_barrier(0);
+        slot = next_slot;
+    }
+    read_half(slot, I1(), I1());
+    await_half(I0(), NR());
+    mma_half(I0());
+    await_half(I1(), I0());
+    mma_half(I1());
+
+    // 32x32 accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+    // The row part that depends on r is wave-uniform, so each store is a uniform row pointer plus one per-lane offset.
+    MT* Mb = Mo + ((size_t)split * nbatch + batch) * K * T;
+    if constexpr (NACC == 2) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[0][0][0][r] += acc[1][0][0][r];
+    }
+    const bool full = row0 + BM <= K && col0 + BN <= T && (size_t)K * T * sizeof(MT) < ((size_t)1 << 31);
+    if (full) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int kb = row0 + wm * WTM + i * 32;                     // uniform
+                const uint32_t loff = (uint32_t)(4 * frag_half) * (uint32_t)T + (uint32_t)(col0 + wn * WTN + j * 32 + frag_row);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    MT* rowp = Mb + (size_t)(kb + 8 * (r / 4) + (r % 4)) * T;     // uniform
+                    rowp[loff] = from_f32<MT>(acc[0][i][j][r]);
+                }
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int t = col0 + wn * WTN + j * 32 + frag_row;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int k = row0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+                    if (k < K && t < T) Mb[(size_t)k * T + t] = from_f32<MT>(acc[0][i][j][r]);
+                }
+            }
+    }
+}
+
+template <typename E, typename MT, int BM, int BN, int NST, int WGM, int WGN>
+static hipError_t launch_gemm_lean(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
+    const int tiles_m = (K + BM - 1) / BM, tiles_n = (T + BN - 1) / BN;
+    const long long total = (long long)tiles_m * tiles_n * nbatch * nsplit;
+    if (total > 0x3fffffffLL) return hipErrorInvalidValue;
+    // lane offsets are 32-bit: a block's rows must span less than 2 GB
+    if ((size_t)Cp * sizeof(E) * (size_t)(BM > BN ? BM : BN) >= ((size_t)1 << 31)) return hipErrorInvalidValue;
+    const int per_xcd = (int)((total + 7) / 8);
+    constexpr int lds_bytes = (BM + BN) * 128 * NST;
+    static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+    auto kern = wino_gemm_lean_kernel<E, MT, BM, BN, NST, WGM, WGN>;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(WGM * WGN * 64), lds_bytes, s, (const E*)U, (const E*)V, (MT*)M,
+                       K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd, nbatch, nsplit);
+    return hipGetLastError();
+}
+
 template <typename E, typename MT, int BM, int BN, int RB, int NST, int WGM = 2, int WGN = 2>
 static hipError_t launch_gemm_cfg(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
     const int tiles_m = (K + BM - 1) / BM, tiles_n = (T + BN - 1) / BN;
@@ -235,7 +454,21 @@ static int pick_shape(int K, int T, int nbatch, bool f16) {
 
 template <typename E, typename MT>
 static hipError_t launch_gemm_t(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int shape, hipStream_t s) {
-    switch (shape < 0 ? pick_shape(K, T, nbatch, sizeof(E) == 2) : shape) {
+    const int sh = shape < 0 ? pick_shape(K, T, nbatch, sizeof(E) == 2) : shape;
+    if (Cp % (128 / (int)sizeof(E)) == 0) {               // whole stages: the lean kernel, same block shapes
+        switch (sh) {
+            case 0: return launch_gemm_lean<E, MT, 128, 128, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+            case 1: return launch_gemm_lean<E, MT, 128, 64, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+            case 2: return launch_gemm_lean<E, MT, 64, 128, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+            case 3: return launch_gemm_lean<E, MT, 64, 64, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+            case 5: return launch_gemm_lean<E, MT, 128, 32, 3, 4, 1>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+            case 6: return launch_gemm_lean<E, MT, 32, 128, 3, 1, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+            case 7: return launch_gemm_lean<E, MT, 128, 128, 3, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+            case 8: return launch_gemm_lean<E, MT, 256, 128, 3, 4, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+            default: break;                                // 256x256 with 16 waves has no registers for two fragment sets
+        }
+    }
+    switch (sh) {
         case 0: return launch_gemm_cfg<E, MT, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
         case 1: return launch_gemm_cfg<E, MT, 128, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
         case 2: return launch_gemm_cfg<E, MT, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);

@@ -15,7 +15,8 @@ DEV = "cuda:0"
 @pytest.mark.parametrize("dtype", [torch.float16, torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4])
 @pytest.mark.parametrize("block_shape", list(range(9)))
-@pytest.mark.parametrize("dims", [(70, 40, 33), (300, 136, 290), (129, 72, 513)])
+# reduction lengths: ragged last stage (40, 136, 72) and whole stages (64, 192, 320), which take different kernels
+@pytest.mark.parametrize("dims", [(70, 40, 33), (300, 136, 290), (129, 72, 513), (70, 64, 33), (300, 192, 290), (129, 320, 513)])
 def test_named_block_shape_against_fp64_product(dims, block_shape, variant, dtype):
     K, C, T = dims
     a2 = (variant + 2) ** 2
@@ -31,11 +32,11 @@ def test_named_block_shape_against_fp64_product(dims, block_shape, variant, dtyp
     ref = np.einsum("bkc,btc->bkt", U.double().numpy(), V.double().numpy())
     got = M.cpu().numpy().astype(np.float64)
     assert got.shape == (a2, K, T)
-    # fp32 accumulation of <= 136 products of magnitude ~1: each element within a few fp32 ulps of sqrt(C)
-    tol = 2e-5 if dtype != torch.float32 else 2e-5
-    assert np.abs(got - ref).max() <= tol * np.sqrt(C) * 4, (dims, block_shape, np.abs(got - ref).max())
-    # every shape forms the same sums in the same order
-    assert torch.equal(M, M_auto)
+    # fp32 accumulation of <= 320 products of magnitude ~1: each element within a few fp32 ulps of sqrt(C)
+    tol = 2e-5 * np.sqrt(C) * 4
+    assert np.abs(got - ref).max() <= tol, (dims, block_shape, np.abs(got - ref).max())
+    # the shapes differ only in the order of the fp32 sums (one or two partial accumulators per sub-tile)
+    assert np.abs(got - M_auto.cpu().numpy().astype(np.float64)).max() <= tol
 
 
 def test_block_shape_out_of_range_is_rejected():
