@@ -79,14 +79,21 @@ output_transform_nchw_kernel(const MT* __restrict__ Mt, const float* __restrict_
     if constexpr (sizeof(MT) == 2) {
         static_assert(sizeof(MT) == 4 || TPT == 1, "half product: one tile per lane");
 #pragma unroll
-        for (int p = 0; p < A * A; ++p) v[p][0] = to_f32<MT>(Mt[(size_t)p * KT + f]);
+        for (int p = 0; p < A * A; ++p) {
+            const unsigned short h = load_stream(reinterpret_cast<const unsigned short*>(Mt + (size_t)p * KT + f));   // read once
+            v[p][0] = to_f32<MT>(*reinterpret_cast<const MT*>(&h));
+        }
     } else {
 #pragma unroll
         for (int p = 0; p < A * A; ++p) {
-            const typename FVec<TPT>::type q = *reinterpret_cast<const typename FVec<TPT>::type*>(Mt + (size_t)p * KT + f);
-            const float* qf = reinterpret_cast<const float*>(&q);
+            if constexpr (TPT == 1) {
+                v[p][0] = load_stream(Mt + (size_t)p * KT + f);          // the product is read once
+            } else {
+                const typename FVec<TPT>::type q = *reinterpret_cast<const typename FVec<TPT>::type*>(Mt + (size_t)p * KT + f);
+                const float* qf = reinterpret_cast<const float*>(&q);
 #pragma unroll
-            for (int u = 0; u < TPT; ++u) v[p][u] = qf[u];
+                for (int u = 0; u < TPT; ++u) v[p][u] = qf[u];
+            }
         }
         // partial products of a reduction cut into nsplit ranges: summed here, in a fixed order
         for (int sp = 1; sp < nsplit; ++sp) {
@@ -185,12 +192,22 @@ output_transform_nhwc_kernel(const MT* __restrict__ Mt, const float* __restrict_
 #pragma unroll
         for (int nu = 0; nu < A; ++nu) {
             const MT* p = src + (size_t)(xi * A + nu) * TK;
+            // the product is read once: streaming loads
             if constexpr (sizeof(MT) == 2) {
-                if constexpr (KPT == 2) { const float2 f = __half22float2(*reinterpret_cast<const __half2*>(p)); v[0][xi][nu] = f.x; v[1][xi][nu] = f.y; }
-                else v[0][xi][nu] = to_f32<MT>(p[0]);
+                if constexpr (KPT == 2) {
+                    const uint32_t w = load_stream(reinterpret_cast<const uint32_t*>(p));
+                    const float2 f = __half22float2(*reinterpret_cast<const __half2*>(&w));
+                    v[0][xi][nu] = f.x; v[1][xi][nu] = f.y;
+                } else {
+                    const unsigned short h = load_stream(reinterpret_cast<const unsigned short*>(p));
+                    v[0][xi][nu] = to_f32<MT>(*reinterpret_cast<const MT*>(&h));
+                }
             } else {
-                if constexpr (KPT == 2) { const float2 f = *reinterpret_cast<const float2*>(p); v[0][xi][nu] = f.x; v[1][xi][nu] = f.y; }
-                else v[0][xi][nu] = p[0];
+                if constexpr (KPT == 2) {
+                    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+                    const f32x2_t f = load_stream(reinterpret_cast<const f32x2_t*>(p));
+                    v[0][xi][nu] = f.x; v[1][xi][nu] = f.y;
+                } else v[0][xi][nu] = load_stream(reinterpret_cast<const float*>(p));
             }
         }
     if constexpr (sizeof(MT) == 4) {
