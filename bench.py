@@ -36,7 +36,9 @@ WORKLOAD_LAYERS = ["A_conv_in", "B_resblock", "C1_unet", "C2_unet", "C3_unet", "
 # HBM bytes per launch of the headline's dominant kernel, from two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE), scaled by
 # what the same counters read for a plain copy of known size; typed in from the profile named beside it (not measured in
 # this run).  Keyed by (layer, variant); absent -> null.
-PROFILED_TRAFFIC = {}
+PROFILED_TRAFFIC = {
+    ("B_resblock", "F4"): (int((10138.2 * 1.992 + 23040.0) * 1024), "profiles/B_resblock_f4_pmc_traffic.txt (rocprofv3 --pmc, not measured in this run)"),
+}
 
 
 def parse():

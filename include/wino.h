@@ -64,8 +64,8 @@ typedef enum wino_dtype { WINO_F32 = 0, WINO_F16 = 1, WINO_BF16 = 2 } wino_dtype
 
 /*
  * WINO_F2 / WINO_F4: Winograd F(2x2,3x3) / F(4x4,3x3), three kernels (activation
- * transform, batched MFMA GEMM, output transform).  WINO_AUTO: the library picks F2
- * or F4 per shape.  WINO_DIRECT: direct correlation; a filter prepared with it
+ * transform, batched MFMA GEMM, output transform).  WINO_AUTO: the library picks F2,
+ * F4 or the fused F2 variant per shape and storage type (wino_resolve_variant).  WINO_DIRECT: direct correlation; a filter prepared with it
  * (wino_filter_transform) makes wino_conv2d / wino_conv2d_ex run the implicit-GEMM
  * MFMA kernel described at the end of this header (no transformed tensors, output
  * rounding only; faster than the Winograd path where there are few channels and
@@ -95,14 +95,15 @@ typedef struct wino_filter {
 int wino_version(void);                         /* major*10000 + minor*100 + patch */
 const char *wino_status_string(int status);     /* static string, never NULL       */
 
-/* WINO_AUTO -> WINO_F2 or WINO_F4 for this shape; other values returned as they
- * are; -1 on bad arguments. */
+/* WINO_AUTO -> WINO_F2, WINO_F4 or WINO_FUSED_F2 for this shape and storage type, by measured speed within the
+ * type's error bound (F4 from 64 tiles on; fp32 with C > 640 and bf16 stay on F(2x2); the fused variant where it
+ * measured faster: 2-byte storage, K >= 32, and either F(2x2) with >= 4096 tiles or at most 128x128 channel pairs
+ * with >= 65536 F(2x2) tiles).  Other values are returned as they are; -1 on bad arguments. */
 int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int variant);
 
 /* WINO_F2, WINO_F4 or WINO_DIRECT, whichever was measured faster for 3x3 / stride 1 on shapes like this one
  * (the direct path where sqrt(C*K) is small and the image large, e.g. 128 channels at 1024x1024); -1 on bad
- * arguments.  wino_resolve_variant(WINO_AUTO) keeps to the two Winograd variants, which alone support
- * the fused operators of wino_conv2d_fused. */
+ * arguments.  wino_resolve_variant(WINO_AUTO) keeps to the Winograd variants. */
 int wino_recommend_variant(int N, int C, int H, int W, int K, int dtype);
 
 /* Sizes (elements, not bytes) of the transformed tensors for a resolved variant:

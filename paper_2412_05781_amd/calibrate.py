@@ -1,6 +1,8 @@
-"""The two microbenchmarks behind the roofline denominators: a plain copy kernel (HBM streaming; also the known-size
-reference the FETCH_SIZE / WRITE_SIZE counters are scaled by) and register-only MFMA rates.  Plain HIP programs under
-``calibration/``; nothing in the library uses them.
+"""The microbenchmarks behind the roofline denominators and the statements about what bounds the kernels: a plain copy
+kernel (HBM streaming; also the known-size reference the FETCH_SIZE / WRITE_SIZE counters are scaled by), register-only
+MFMA rates, the fill rate of a compute unit from L1 / L2 / beyond with ordinary loads and with direct-to-LDS transfers, and
+the step (ii) kernel's operand access pattern as a pure stream.  Plain HIP programs under ``calibration/``; nothing in the
+library uses them.
 
     python -m paper_2412_05781_amd.calibrate --build        # hipcc, works without a GPU
     python -m paper_2412_05781_amd.calibrate --run [name]   # on the GPU machine; prints each program's table

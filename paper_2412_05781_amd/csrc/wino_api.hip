@@ -158,6 +158,14 @@ int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int varia
     if (dtype == WINO_F32 && C > 640) pick = WINO_F2;
     // bfloat16 has 8 significant bits: F(4x4) would sit near 2.5e-2, F(2x2) near 4e-3
     if (dtype == WINO_BF16) pick = WINO_F2;
+    // The fused variant (steps (ii) and (iii) in one kernel, F(2x2)) where it measured faster with 2-byte storage:
+    // against the F(2x2) chain from 4096 tiles on (128x128 images at batch 2 and everything larger: 0.6-0.9x the time),
+    // against the F(4x4) chain only with at most 128 channels on 512x512 images and larger (0.9x).
+    const Geom g2 = make_geom(N, C, H, W, K, 2);
+    if (dtype != WINO_F32 && K >= 32) {
+        if (pick == WINO_F2 && g2.T >= 4096) pick = WINO_FUSED_F2;
+        if (pick == WINO_F4 && (long long)C * K <= 128LL * 128LL && g2.T >= 65536) pick = WINO_FUSED_F2;
+    }
     return pick;
 }
 

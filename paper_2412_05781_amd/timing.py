@@ -7,6 +7,7 @@ the table that the file of the same topic under ``profiles/`` records:
     python -m paper_2412_05781_amd.timing flavours       1x1 and stride-2 convolutions through the implicit GEMM
     python -m paper_2412_05781_amd.timing direct         3x3 stride 1: Winograd vs direct vs 8-bit direct
     python -m paper_2412_05781_amd.timing half-product   the opt-in fp16 intermediate product
+    python -m paper_2412_05781_amd.timing variants       every workload layer x {F(4x4), F(2x2), fused F(2x2)} x {NCHW, NHWC}
 
 "framework" columns call the stock deep-learning framework's own operators on the same tensors, as context.
 """
@@ -38,6 +39,10 @@ def _shape(N, C, H, W, layout):
     return (N, H, W, C) if layout == B.WINO_NHWC else (N, C, H, W)
 
 
+def _vname(v):
+    return {B.WINO_F2: "F2", B.WINO_F4: "F4", B.WINO_FUSED_F2: "fused-F2", B.WINO_DIRECT: "direct"}.get(v, str(v))
+
+
 def _lname(layout):
     return "NHWC" if layout == B.WINO_NHWC else "NCHW"
 
@@ -62,7 +67,7 @@ def cmd_fused(_):
             B.wino_groupnorm_stats(x, 32, out=st)
             B.wino_conv2d_fused(x, wt, bd, y, ws, gn_stats=st, gn_gamma=gamma, gn_beta=beta, gn_groups=32, addvec=add, residual=res)
         t_fused = graph_time(fused, 2 * n)
-        print(f"{name:12s} F{v}: plain call {t_plain*1e6:7.2f} us | groupnorm stats {t_stats*1e6:6.2f} us | stats + fused call "
+        print(f"{name:12s} {_vname(v)}: plain call {t_plain*1e6:7.2f} us | groupnorm stats {t_stats*1e6:6.2f} us | stats + fused call "
               f"{t_fused*1e6:7.2f} us | extra for GN+SiLU+adds {1e6*(t_fused-t_plain):+.1f} us", flush=True)
 
 
@@ -91,7 +96,7 @@ def cmd_upsample(_):
         yh = [torch.empty(N, H, W, K, device=DEV, dtype=DT) for _ in sets]
         t_dh = graph_time(lambda i: B.wino_conv2d_fused(xh[i % n], wtd, bd, yh[i % n], wsd, B.WINO_NHWC, upsample=True), 2 * n)
         rec = B.wino_recommend_variant(N, C, H, W, K, B.WINO_F16)
-        print(f"{name:22s} Winograd F{v} fused {t_f*1e6:8.2f} us | two-step: conv {t_c*1e6:8.2f} + framework upsample {t_u*1e6:6.2f} us "
+        print(f"{name:22s} Winograd {_vname(v)} fused {t_f*1e6:8.2f} us | two-step: conv {t_c*1e6:8.2f} + framework upsample {t_u*1e6:6.2f} us "
               f"(bitwise equal: {same}) | direct variant fused NCHW {t_d*1e6:8.2f} NHWC {t_dh*1e6:8.2f} us | recommended variant {rec}",
               flush=True)
 
@@ -119,7 +124,7 @@ def _igemm_case(name, N, C, K, H, W, R, st, framework=True, fp8=False, winograd=
             wt = B.wino_filter_transform(wd, v)
             wsw = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v), dtype=torch.uint8, device=DEV)
             tw = graph_time(lambda i: B.wino_conv2d_ex(sets[i % n][0], wt, bd, sets[i % n][3], wsw, layout), 2 * n)
-            out.append(f"Winograd F{v} {_lname(layout)} {tw*1e6:8.2f} us")
+            out.append(f"Winograd {_vname(v)} {_lname(layout)} {tw*1e6:8.2f} us")
         if framework and layout == B.WINO_NCHW:
             for _ in range(2):
                 torch.nn.functional.conv2d(sets[0][0], wd, bd.to(DT), stride=st, padding=pad)
@@ -157,19 +162,46 @@ def cmd_half_product(_):
             ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v), dtype=torch.uint8, device=DEV)
             t0 = graph_time(lambda i: B.wino_conv2d_fused(sets[i % n][0], sets[i % n][1], bd, sets[i % n][2], ws, layout), 2 * n)
             t1 = graph_time(lambda i: B.wino_conv2d_fused(sets[i % n][0], sets[i % n][1], bd, sets[i % n][2], ws, layout, product_fp16=True), 2 * n)
-            print(f"{name:12s} F{v} {_lname(layout)}: fp32 product {t0*1e6:8.2f} us ({L.direct_flops/t0/1e12:7.1f} TF) | fp16 product "
+            print(f"{name:12s} {_vname(v)} {_lname(layout)}: fp32 product {t0*1e6:8.2f} us ({L.direct_flops/t0/1e12:7.1f} TF) | fp16 product "
                   f"{t1*1e6:8.2f} us ({L.direct_flops/t1/1e12:7.1f} TF)  x{t0/t1:.2f}", flush=True)
+
+
+def cmd_variants(_):
+    """Whole-call time (wino_conv2d_ex) of every workload layer in each Winograd variant and both layouts; '*' marks
+    what WINO_AUTO resolves to."""
+    names = [n for n, L in synth.LAYERS.items() if L.dtype == "f16" and not n.startswith("T1")]
+    tags = {B.WINO_F4: "F4", B.WINO_F2: "F2", B.WINO_FUSED_F2: "fused F2"}
+    print(f"{'layer':12s} {'layout':5s} | " + " | ".join(f"{t + ' us':>11s}" for t in tags.values()) + " | fused/F2  fused/F4  workspace MB (F4 / F2 / fused)")
+    for name in names:
+        L = synth.LAYERS[name]
+        N, C, K, H, W = L.N, L.C, L.K, L.H, L.W
+        auto = B.wino_resolve_variant(N, C, H, W, K, B.WINO_F16, B.WINO_AUTO)
+        wd, bd = _w(K, C), torch.randn(K, device=DEV) * 0.01
+        for layout in (B.WINO_NCHW, B.WINO_NHWC):
+            t = {}
+            for v in tags:
+                n = _nsets((N * C * H * W + N * K * H * W) * 2 + B.wino_filter_bytes(K, C, B.WINO_F16, v), hi=24)
+                sets = [(torch.randn(_shape(N, C, H, W, layout), device=DEV).to(DT), B.wino_filter_transform(wd, v),
+                         torch.empty(_shape(N, K, H, W, layout), device=DEV, dtype=DT)) for _ in range(n)]
+                ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v), dtype=torch.uint8, device=DEV)
+                t[v] = graph_time(lambda i: B.wino_conv2d_ex(sets[i % n][0], sets[i % n][1], bd, sets[i % n][2], ws, layout), 2 * n) * 1e6
+                del sets, ws
+                torch.cuda.empty_cache()
+            wsb = [B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v) / 1e6 for v in tags]
+            print(f"{name:12s} {_lname(layout):5s} | " + " | ".join(f"{t[v]:10.1f}{'*' if v == auto else ' '}" for v in tags) +
+                  f" |   {t[B.WINO_FUSED_F2] / t[B.WINO_F2]:5.2f}     {t[B.WINO_FUSED_F2] / t[B.WINO_F4]:5.2f}    {wsb[0]:7.1f} / {wsb[1]:7.1f} / {wsb[2]:7.1f}",
+                  flush=True)
 
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["fused", "upsample", "flavours", "direct", "half-product"])
+    ap.add_argument("what", choices=["fused", "upsample", "flavours", "direct", "half-product", "variants"])
     a = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("timing: no GPU visible", file=sys.stderr)
         return 2
     {"fused": cmd_fused, "upsample": cmd_upsample, "flavours": cmd_flavours, "direct": cmd_direct,
-     "half-product": cmd_half_product}[a.what](a)
+     "half-product": cmd_half_product, "variants": cmd_variants}[a.what](a)
     return 0
 
 

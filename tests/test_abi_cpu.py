@@ -69,6 +69,12 @@ def test_resolve_variant(L):
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
     # 8x8 images with wide channels: the transformed filter dominates the traffic, F2's is 2.25x smaller
     assert B.wino_resolve_variant(2, 1280, 8, 8, 1280, B.WINO_F16, B.WINO_AUTO) == B.WINO_F2
+    # the fused variant where it measured faster: <= 128 channels on >= 512x512 images (fp16), many-tile layers in bf16
+    assert B.wino_resolve_variant(1, 128, 1024, 1024, 128, B.WINO_F16, B.WINO_AUTO) == B.WINO_FUSED_F2
+    assert B.wino_resolve_variant(1, 128, 1024, 1024, 3, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
+    assert B.wino_resolve_variant(1, 256, 512, 512, 256, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
+    assert B.wino_resolve_variant(2, 320, 128, 128, 320, B.WINO_BF16, B.WINO_AUTO) == B.WINO_FUSED_F2
+    assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_BF16, B.WINO_AUTO) == B.WINO_F2
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, 3) == -1
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, 9, B.WINO_AUTO) == -1
     assert B.wino_resolve_variant(0, 320, 64, 64, 320, B.WINO_F16, B.WINO_AUTO) == -1

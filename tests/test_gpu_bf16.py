@@ -72,7 +72,8 @@ def test_bf16_channel_last_and_stages(variant):
 
 def test_bf16_auto_never_picks_f4():
     for (N, C, K, H, W) in [(2, 320, 320, 64, 64), (1, 512, 512, 256, 256), (2, 1280, 1280, 8, 8)]:
-        assert B.wino_resolve_variant(N, C, H, W, K, B.WINO_BF16, B.WINO_AUTO) == B.WINO_F2
+        assert B.wino_resolve_variant(N, C, H, W, K, B.WINO_BF16, B.WINO_AUTO) in (B.WINO_F2, B.WINO_FUSED_F2)
+    assert B.wino_resolve_variant(1, 512, 256, 256, 512, B.WINO_BF16, B.WINO_AUTO) == B.WINO_FUSED_F2      # 16384 tiles
 
 
 @pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
