@@ -60,6 +60,28 @@ void run(const unsigned char* buf, uint4* out, int blocks, int pitch, int ppw) {
            best * 1e3, bytes / (best * 1e-3) / 1e12, bytes / 1e6);
     fflush(stdout);
 }
+// One launch over `bytes` of a 1 GB buffer, the region advancing with every launch so that each launch reads from HBM:
+// what a single short kernel (the weight-streaming layers read 52-105 MB per launch) can reach, start-up and drain included.
+template <int SW, int NST>
+void run_cold(const unsigned char* buf, uint4* out, int blocks, int pitch) {
+    hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
+    const int lds = 128 * SW * NST;
+    hipFuncSetAttribute(reinterpret_cast<const void*>(k<SW, NST, false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    const size_t region = (size_t)blocks * 128 * pitch;
+    const int nreg = (int)(((size_t)1 << 30) / region);
+    const int launches = 2 * nreg;
+    hipLaunchKernelGGL((k<SW, NST, false, true>), dim3(blocks), dim3(256), lds, 0, buf, pitch, 1, out);
+    hipDeviceSynchronize();
+    hipEventRecord(e0);
+    for (int i = 0; i < launches; ++i)
+        hipLaunchKernelGGL((k<SW, NST, false, true>), dim3(blocks), dim3(256), lds, 0, buf + (size_t)(i % nreg) * region, pitch, 1, out);
+    hipEventRecord(e1); hipEventSynchronize(e1);
+    float ms; hipEventElapsedTime(&ms, e0, e1);
+    const double us = ms * 1e3 / launches;
+    printf("cold single launch, row-walk swizzled stage %3d B/row ring %d blocks %4d pitch %5d: %7.1f us per launch %6.2f TB/s (%.0f MB per launch, %d regions)\n",
+           SW, NST, blocks, pitch, us, region / (us * 1e-6) / 1e12, region / 1e6, nreg);
+    fflush(stdout);
+}
 int main() {
     unsigned char* buf; uint4* out; const size_t SZ = (size_t)1 << 30;
     hipMalloc(&buf, SZ); hipMalloc(&out, 64); hipMemset(buf, 1, SZ);
@@ -73,5 +95,10 @@ int main() {
             if (ppw > 1) { run<128, 3, false>(buf, out, blocks, pitch, 1); run<128, 3, false, true>(buf, out, blocks, pitch, 1); }
         }
     }
+    for (int pitch : {2560, 5120})
+        for (int blocks : {160, 320, 480}) {
+            run_cold<128, 3>(buf, out, blocks, pitch);
+            run_cold<256, 3>(buf, out, blocks, pitch);
+        }
     return 0;
 }
