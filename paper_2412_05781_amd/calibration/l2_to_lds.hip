@@ -11,7 +11,7 @@ __device__ __forceinline__ void dma16(const void* src, unsigned char* lds_dst) {
     const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_byte_t*)lds_dst);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(m0v), "v"(src) : "memory", "m0");
 }
-// MODE 0: plain 16B/lane to registers; 1: LDS-DMA 16B/lane
+// MODE 0: plain 16B/lane to registers; 1: LDS-DMA 16B/lane; 3: both, alternating (half of the bytes each way)
 // PAT 0: wave reads 1 KB contiguous; 1: 8 rows of 128 B at 640 B pitch
 template <int MODE, int PAT>
 __global__ void __launch_bounds__(256) k(const unsigned char* __restrict__ buf, unsigned win_mask, int iters, size_t wg_stride, uint4* out) {
@@ -28,12 +28,14 @@ __global__ void __launch_bounds__(256) k(const unsigned char* __restrict__ buf, 
         for (int u = 0; u < 8; ++u) {
             const unsigned char* p = base + (off & win_mask);
             if (MODE == 0) { uint4 v = *reinterpret_cast<const uint4*>(p); acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w; }
+            else if (MODE == 3 && (u & 1)) { uint4 v = *reinterpret_cast<const uint4*>(p); acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w; }
             else dma16(p, lds + (wave * 8 + u) * 1024);
             off += step;
         }
         if (MODE == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        if (MODE == 3) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     }
-    if (MODE == 1) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); __syncthreads(); acc = *reinterpret_cast<uint4*>(lds + tid * 16); }
+    if (MODE == 1 || MODE == 3) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); __syncthreads(); uint4 t = *reinterpret_cast<uint4*>(lds + tid * 16); acc.x ^= t.x; acc.y ^= t.y; }
     if (acc.x == 0x12345678u && acc.y == 77u) out[0] = acc;
 }
 template <int MODE, int PAT>
@@ -66,6 +68,7 @@ int main() {
             snprintf(nm, sizeof nm, "plain16 contiguous  %s", tag); run<0, 0>(nm, buf, out, blocks, win, stride);
             snprintf(nm, sizeof nm, "dma16   contiguous  %s", tag); run<1, 0>(nm, buf, out, blocks, win, stride);
             snprintf(nm, sizeof nm, "dma16   128B rows   %s", tag); run<1, 1>(nm, buf, out, blocks, win, stride);
+            snprintf(nm, sizeof nm, "both    contiguous  %s", tag); run<3, 0>(nm, buf, out, blocks, win, stride);
         }
     }
     return 0;
