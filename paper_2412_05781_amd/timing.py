@@ -167,30 +167,31 @@ def cmd_half_product(_):
 
 
 def cmd_variants(_):
-    """Whole-call time (wino_conv2d_ex) of every workload layer in each Winograd variant and both layouts; '*' marks
-    what WINO_AUTO resolves to."""
-    names = [n for n, L in synth.LAYERS.items() if L.dtype == "f16" and not n.startswith("T1")]
+    """Whole-call time (wino_conv2d_ex) of every synthetic layer (the workload groups and the paper's Table-1 shapes, in the
+    layer's own storage type) in each Winograd variant and both layouts; '*' marks what WINO_AUTO resolves to."""
     tags = {B.WINO_F4: "F4", B.WINO_F2: "F2", B.WINO_FUSED_F2: "fused F2"}
-    print(f"{'layer':12s} {'layout':5s} | " + " | ".join(f"{t + ' us':>11s}" for t in tags.values()) + " | fused/F2  fused/F4  workspace MB (F4 / F2 / fused)")
-    for name in names:
-        L = synth.LAYERS[name]
+    print(f"{'layer':18s} {'layout':5s} | " + " | ".join(f"{t + ' us':>11s}" for t in tags.values()) +
+          " |  AUTO TF/s | fused/F2  fused/F4  workspace MB (F4 / F2 / fused)")
+    for name, L in synth.LAYERS.items():
         N, C, K, H, W = L.N, L.C, L.K, L.H, L.W
-        auto = B.wino_resolve_variant(N, C, H, W, K, B.WINO_F16, B.WINO_AUTO)
-        wd, bd = _w(K, C), torch.randn(K, device=DEV) * 0.01
+        tdt = synth.TORCH_DTYPE[L.dtype]
+        dt, e = B.DTYPE_OF[tdt], (4 if L.dtype == "f32" else 2)
+        auto = B.wino_resolve_variant(N, C, H, W, K, dt, B.WINO_AUTO)
+        wd, bd = _w(K, C).to(tdt), torch.randn(K, device=DEV) * 0.01
         for layout in (B.WINO_NCHW, B.WINO_NHWC):
             t = {}
             for v in tags:
-                n = _nsets((N * C * H * W + N * K * H * W) * 2 + B.wino_filter_bytes(K, C, B.WINO_F16, v), hi=24)
-                sets = [(torch.randn(_shape(N, C, H, W, layout), device=DEV).to(DT), B.wino_filter_transform(wd, v),
-                         torch.empty(_shape(N, K, H, W, layout), device=DEV, dtype=DT)) for _ in range(n)]
-                ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v), dtype=torch.uint8, device=DEV)
+                n = _nsets((N * C * H * W + N * K * H * W) * e + B.wino_filter_bytes(K, C, dt, v), hi=24)
+                sets = [(torch.randn(_shape(N, C, H, W, layout), device=DEV).to(tdt), B.wino_filter_transform(wd, v),
+                         torch.empty(_shape(N, K, H, W, layout), device=DEV, dtype=tdt)) for _ in range(n)]
+                ws = torch.empty(B.wino_workspace_bytes(N, C, H, W, K, dt, v), dtype=torch.uint8, device=DEV)
                 t[v] = graph_time(lambda i: B.wino_conv2d_ex(sets[i % n][0], sets[i % n][1], bd, sets[i % n][2], ws, layout), 2 * n) * 1e6
                 del sets, ws
                 torch.cuda.empty_cache()
-            wsb = [B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v) / 1e6 for v in tags]
-            print(f"{name:12s} {_lname(layout):5s} | " + " | ".join(f"{t[v]:10.1f}{'*' if v == auto else ' '}" for v in tags) +
-                  f" |   {t[B.WINO_FUSED_F2] / t[B.WINO_F2]:5.2f}     {t[B.WINO_FUSED_F2] / t[B.WINO_F4]:5.2f}    {wsb[0]:7.1f} / {wsb[1]:7.1f} / {wsb[2]:7.1f}",
-                  flush=True)
+            wsb = [B.wino_workspace_bytes(N, C, H, W, K, dt, v) / 1e6 for v in tags]
+            print(f"{name:18s} {_lname(layout):5s} | " + " | ".join(f"{t[v]:10.1f}{'*' if v == auto else ' '}" for v in tags) +
+                  f" | {L.direct_flops / t[auto] / 1e6:10.1f} |   {t[B.WINO_FUSED_F2] / t[B.WINO_F2]:5.2f}     {t[B.WINO_FUSED_F2] / t[B.WINO_F4]:5.2f}"
+                  f"    {wsb[0]:7.1f} / {wsb[1]:7.1f} / {wsb[2]:7.1f}", flush=True)
 
 
 def main(argv=None):
