@@ -153,10 +153,11 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
 
 
 def test_measurement_tools_import_without_a_gpu():
-    """The timing tables and the two programs that measure the roofline denominators (a plain copy, register-only
-    MFMA rates) are part of the package: they import on a CPU-only box, and the sources they name exist."""
+    """The timing tables and the programs that measure the roofline denominators (a plain copy, register-only MFMA
+    rates, the fill rate of a compute unit, the operand access pattern as a pure stream) are part of the package: they
+    import on a CPU-only box, and the sources they name exist."""
     from paper_2412_05781_amd import calibrate, gputime, timing
-    assert calibrate.names() == ["mfma_rates", "stream"]
+    assert calibrate.names() == ["l2_to_lds", "mfma_rates", "operand_stream", "stream"]
     assert callable(timing.main) and callable(gputime.graph_time)
 
 
