@@ -67,9 +67,10 @@ class LayerRun:
         self.dt = B.DTYPE_OF[self.tdt]
         self.esz = 2 if layer.dtype == "f16" else 4
         self.variant = B.wino_resolve_variant(N, C, H, W, K, self.dt, want)
-        assert self.variant in (B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2), self.variant
-        self.alpha, self.Cp, self.T = B.wino_transformed_dims(N, C, H, W, K, self.variant)
-        self.a2 = self.alpha * self.alpha
+        assert self.variant in (B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2, B.WINO_DIRECT), self.variant
+        if self.variant != B.WINO_DIRECT:            # the direct variant is only timed as a whole call (step)
+            self.alpha, self.Cp, self.T = B.wino_transformed_dims(N, C, H, W, K, self.variant)
+            self.a2 = self.alpha * self.alpha
         if cpu_inputs is not None:                   # the seeded CPU recipe (needed where the oracle checks the result)
             x, w, b = cpu_inputs
             xd, wd, self.bd = x.to(dev), w.to(dev), b.to(dev)
@@ -253,6 +254,18 @@ def main():
             r.step(0)
             torch.cuda.synchronize()
             rec["rel_l2_vs_oracle"], _ = parity(L, cin, r.sets[0][2])
+        # where the library recommends its direct path over the Winograd variants (few channels on large images, or a
+        # handful of output channels), that call is timed too, same inputs, same rotation
+        if B.wino_recommend_variant(L.N, L.C, L.H, L.W, L.K, r.dt) == B.WINO_DIRECT:
+            del r
+            torch.cuda.empty_cache()
+            r = LayerRun(L, B.WINO_DIRECT, dev, rotate=not args.no_rotate, cpu_inputs=cin)
+            td = graph_time(r.step, 2 * r.nsets)
+            rec["recommended"] = {"variant": "DIRECT", "us": td * 1e6, "tflops": L.direct_flops / td / 1e12}
+            if oracle is not None:
+                r.step(0)
+                torch.cuda.synchronize()
+                rec["recommended"]["rel_l2_vs_oracle"], _ = parity(L, cin, r.sets[0][2])
         layers_out.append(rec)
         print(f"bench: {name} {rec['variant']} {rec['us']:.1f} us {rec['tflops']:.0f} TFLOP/s", file=sys.stderr, flush=True)
         del r, cin

@@ -101,8 +101,9 @@ const char *wino_status_string(int status);     /* static string, never NULL    
  * with >= 65536 F(2x2) tiles).  Other values are returned as they are; -1 on bad arguments. */
 int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int variant);
 
-/* WINO_F2, WINO_F4 or WINO_DIRECT, whichever was measured faster for 3x3 / stride 1 on shapes like this one
- * (the direct path where sqrt(C*K) is small and the image large, e.g. 128 channels at 1024x1024); -1 on bad
+/* A Winograd variant or WINO_DIRECT, whichever was measured faster for 3x3 / stride 1 on shapes like this one
+ * (the direct path where sqrt(C*K) is small and the image large, e.g. 128 channels at 1024x1024, and for at most
+ * four output channels on images of 512x512 pixels and more, which have a kernel of their own there); -1 on bad
  * arguments.  wino_resolve_variant(WINO_AUTO) keeps to the Winograd variants. */
 int wino_recommend_variant(int N, int C, int H, int W, int K, int dtype);
 

@@ -515,6 +515,9 @@ hipError_t launch_igemm_conv2d(const void* x, const void* Wr, const float* bias,
                                int N, int C, int H, int W, int K, int R, int st, int dt, bool nhwc,
                                void* workspace, size_t xh_bytes, int up, const PreOp* prep, const float* addvec, const void* residual,
                                hipStream_t s) {
+    // a handful of output channels: one pass over x on the vector ALU instead of a re-layout and a padded MFMA tile
+    if (fewk_conv_ok(x, N, C, H, W, K, R, st, dt, nhwc, up, prep && prep->stats, addvec || residual))
+        return launch_fewk_conv3x3(x, Wr, bias, y, N, C, H, W, K, nhwc, s);
     IgemmPost post; post.addvec = addvec; post.residual = residual;
     const PreOp pre = prep ? *prep : PreOp();
     ConvGeom g;

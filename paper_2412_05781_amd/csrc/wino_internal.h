@@ -109,6 +109,11 @@ __device__ __forceinline__ float pre_apply(float x, const PreLane& l, bool in_im
     return __fdividef(v, 1.f + __expf(-v));
 }
 
+// Direct 3x3 / stride 1 kernel for K <= 4 output channels on large images (fp16, conv_fewk.hip): whether it applies, and the launch.
+// Wr is the tap-major filter of the implicit-GEMM path.
+bool fewk_conv_ok(const void* x, int N, int C, int H, int W, int K, int R, int st, int dt, bool nhwc, int up, bool pre, bool post);
+hipError_t launch_fewk_conv3x3(const void* x, const void* Wr, const float* bias, void* y, int N, int C, int H, int W, int K, bool nhwc, hipStream_t s);
+
 // launchers (each enqueues on `s`, returns the launch status)
 hipError_t launch_filter_transform(const void* w, void* U, int K, int C, int Cp, int m, int dt, hipStream_t s);
 hipError_t launch_input_transform(const void* x, void* V, const Geom& g, int dt, bool nhwc, const PreOp* pre, hipStream_t s);

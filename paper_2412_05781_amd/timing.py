@@ -142,7 +142,7 @@ def cmd_flavours(_):
 
 
 def cmd_direct(_):
-    for c in [("E4 128@1024", 1, 128, 128, 1024, 1024, 3, 1), ("E3 256@512", 1, 256, 256, 512, 512, 3, 1),
+    for c in [("E5 128->3@1024", 1, 128, 3, 1024, 1024, 3, 1), ("E4 128@1024", 1, 128, 128, 1024, 1024, 3, 1), ("E3 256@512", 1, 256, 256, 512, 512, 3, 1),
               ("E2 512@256", 1, 512, 512, 256, 256, 3, 1), ("E1 512@128", 1, 512, 512, 128, 128, 3, 1),
               ("D2 2x640@64", 2, 640, 640, 64, 64, 3, 1), ("B 2x320@64", 2, 320, 320, 64, 64, 3, 1),
               ("C4 2x1280@16", 2, 1280, 1280, 16, 16, 3, 1)]:

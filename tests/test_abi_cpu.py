@@ -75,6 +75,8 @@ def test_resolve_variant(L):
     assert B.wino_resolve_variant(1, 256, 512, 512, 256, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
     assert B.wino_resolve_variant(2, 320, 128, 128, 320, B.WINO_BF16, B.WINO_AUTO) == B.WINO_FUSED_F2
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_BF16, B.WINO_AUTO) == B.WINO_F2
+    assert B.wino_recommend_variant(1, 128, 1024, 1024, 3, B.WINO_F16) == B.WINO_DIRECT      # few output channels, large image
+    assert B.wino_recommend_variant(2, 320, 64, 64, 4, B.WINO_F16) == B.WINO_F4               # ... but not on a 64x64 latent
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, 3) == -1
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, 9, B.WINO_AUTO) == -1
     assert B.wino_resolve_variant(0, 320, 64, 64, 320, B.WINO_F16, B.WINO_AUTO) == -1

@@ -14,8 +14,8 @@ from paper_2412_05781_amd import synth
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-TOL = {B.WINO_F2: 8e-3, B.WINO_F4: 4e-2, B.WINO_DIRECT: 3e-3}
-BAND = {B.WINO_F2: (3.0e-3, 6.0e-3), B.WINO_F4: (1.8e-2, 3.3e-2), B.WINO_DIRECT: (1.2e-3, 2.2e-3)}
+TOL = {B.WINO_F2: 8e-3, B.WINO_FUSED_F2: 8e-3, B.WINO_F4: 4e-2, B.WINO_DIRECT: 3e-3}
+BAND = {B.WINO_F2: (3.0e-3, 6.0e-3), B.WINO_FUSED_F2: (3.0e-3, 6.0e-3), B.WINO_F4: (1.8e-2, 3.3e-2), B.WINO_DIRECT: (1.2e-3, 2.2e-3)}
 
 
 def _np(t):
@@ -25,7 +25,7 @@ def _np(t):
 SHAPES = [(2, 5, 7, 5, 7), (1, 33, 65, 17, 30), (2, 64, 130, 33, 16), (1, 136, 40, 12, 216), (1, 1024, 64, 8, 8)]
 
 
-@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4, B.WINO_DIRECT])
+@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_FUSED_F2, B.WINO_F4, B.WINO_DIRECT])
 @pytest.mark.parametrize("shape", SHAPES)
 def test_bf16_full_tensor(shape, variant):
     N, C, K, H, W = shape
@@ -68,6 +68,21 @@ def test_bf16_channel_last_and_stages(variant):
     # the GEMM stage is exact up to fp32 accumulation on the stored operands
     M = B.wino_batched_gemm(U, V, K, C, T, variant)
     assert oracle.rel_l2(_np(M.cpu()), np.einsum("bkc,btc->bkt", Uh, Vh)) <= 1e-6
+
+
+def test_bf16_auto_on_a_many_tile_layer_runs_the_fused_variant():
+    """4096 F(2x2) tiles: WINO_AUTO resolves to the fused variant for bf16; whole tensor and element-wise against the oracle."""
+    import os, sys
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    import parity_util as pu
+    N, C, K, H, W = 1, 64, 64, 128, 128
+    assert B.wino_resolve_variant(N, C, H, W, K, B.WINO_BF16, B.WINO_AUTO) == B.WINO_FUSED_F2
+    x, w, b = synth.make_inputs(N, C, K, H, W, "bf16", seed=10777)
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    y = B.conv2d(x.to(DEV), w.to(DEV), b.to(DEV), B.WINO_AUTO)
+    torch.cuda.synchronize()
+    err = pu.check(_np(y.cpu()), ref, TOL[B.WINO_FUSED_F2], 2, "bf16", what="bf16 auto", channels=C)
+    assert BAND[B.WINO_FUSED_F2][0] <= err <= BAND[B.WINO_FUSED_F2][1], err
 
 
 def test_bf16_auto_never_picks_f4():

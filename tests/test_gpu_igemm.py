@@ -118,3 +118,57 @@ def test_igemm_argument_checks():
     assert L.wino_igemm_conv2d(*args(x=None)) == B.WINO_ERR_NULL
     assert B.wino_igemm_workspace_bytes(1, 8, 8, 8, 8, 1, 1, B.WINO_F16, B.WINO_NHWC) == 0   # read in place, one stage: nothing to hold
     torch.cuda.synchronize()
+
+
+# ---- very few output channels (K <= 4) on large images, fp16: the one-pass vector-ALU kernel behind the same entry points ----
+# (N, C, K, H, W), each with at least 512 tiles of 8 x 64 pixels (below that the implicit-GEMM kernels take the call): one and
+# several channel steps, heights that are not multiples of 8, widths that are multiples of 8 but not of 64 (and, channel-last,
+# not even of 8), every K
+FEWK_SHAPES = [(1, 16, 3, 517, 512), (2, 32, 4, 261, 520), (1, 48, 1, 1024, 256), (3, 16, 2, 200, 456)]
+
+
+def _fewk_run(x, w, b, layout):
+    xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+    y = B.conv2d_igemm(xd, w.to(DEV), None if b is None else b.to(DEV), 1, layout)
+    torch.cuda.synchronize()
+    y = y.cpu()
+    return y.permute(0, 3, 1, 2) if layout == B.WINO_NHWC else y
+
+
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("shape", FEWK_SHAPES)
+def test_few_output_channels_full_tensor(shape, layout):
+    """Whole tensor, element by element, against the fp64 oracle; every output is one rounding of an fp32 sum, so each
+    element must be within fp16 rounding of the oracle plus the fp32 accumulation error."""
+    N, C, K, H, W = shape
+    if layout == B.WINO_NHWC:
+        W += 3                                      # channel-last has no 8-column requirement
+    x, w, b = _inputs(N, C, K, H, W, 3, "f16", seed=7700 + sum(shape))
+    ref = oracle.conv2d_general(_np(x), _np(w), _np(b), 1)
+    for use_bias in (True, False):
+        r = ref if use_bias else ref - _np(b)[None, :, None, None]
+        got = _np(_fewk_run(x, w, b if use_bias else None, layout))
+        assert got.shape == r.shape
+        err = oracle.rel_l2(got, r)
+        assert err <= 6e-4, (shape, use_bias, err)
+        # element-wise: half an fp16 ulp of the result plus a few fp32 ulps of the largest partial sum
+        bound = 2.0 ** -11 * 1.001 * np.abs(r) + 2.0 ** -25 + 1e-5
+        assert np.all(np.abs(got - r) <= bound), (shape, use_bias, float(np.abs(got - r).max()))
+    if layout == B.WINO_NCHW:      # the same call through the direct variant of the Winograd entry points
+        w_t = B.wino_filter_transform(w.to(DEV), B.WINO_DIRECT)
+        ws = torch.empty(max(16, B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, B.WINO_DIRECT)), dtype=torch.uint8, device=DEV)
+        y2 = B.wino_conv2d_ex(x.to(DEV), w_t, b.to(DEV), torch.empty((N, K, H, W), dtype=torch.float16, device=DEV), ws)
+        y1 = B.conv2d_igemm(x.to(DEV), w.to(DEV), b.to(DEV), 1, B.WINO_NCHW)
+        torch.cuda.synchronize()
+        assert torch.equal(y1, y2)
+
+
+def test_few_output_channels_falls_back_where_the_kernel_does_not_apply():
+    """Small images, a width that is not a multiple of 8, 24 channels, fp32: the implicit-GEMM kernels take the call; same
+    tolerance."""
+    for (N, C, K, H, W, dtype, layout) in [(1, 16, 3, 9, 16, "f16", B.WINO_NCHW), (1, 16, 3, 517, 509, "f16", B.WINO_NCHW),
+                                           (1, 24, 3, 517, 512, "f16", B.WINO_NHWC), (1, 16, 3, 517, 512, "f32", B.WINO_NCHW)]:
+        x, w, b = _inputs(N, C, K, H, W, 3, dtype, seed=7800 + C + W)
+        ref = oracle.conv2d_general(_np(x), _np(w), _np(b), 1)
+        y = _fewk_run(x, w, b, layout).float()
+        assert oracle.rel_l2(y.numpy(), ref) <= TOL[dtype]
