@@ -276,6 +276,9 @@ int wino_direct_conv2d(const void *x, const void *w, const float *bias, void *y,
  * in place) holds x re-laid with the channel index contiguous and, for shapes with few output pixels and
  * a long reduction, fp32 partial sums of a reduction that is cut into ranges.  Same conventions as above: device
  * pointers 16-byte aligned, arguments validated on the host, work enqueued on `stream`, deterministic.
+ * One shape class takes a kernel of its own behind the same call, with the same result up to summation order: 3x3 / stride 1
+ * with K <= 4 output channels in fp16 on images of at least 512 tiles of 8 x 64 pixels (one pass over x on the vector ALU, no
+ * re-layout, no workspace use; C a multiple of 16, and W a multiple of 8 for WINO_NCHW - otherwise the general kernels run).
  */
 size_t wino_igemm_filter_bytes(int K, int C, int R, int dtype);
 int wino_igemm_filter_repack(const void *w, void *w_r, int K, int C, int R, int dtype, void *stream);
