@@ -310,6 +310,40 @@ int wino_fp8_conv2d(const void *x, const void *w_q, const float *bias, void *y,
                     float scale_x, float scale_w, const wino_fusion *f,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The Winograd path with 8-bit integer transformed tensors: F(2x2,3x3), U and V held as symmetric integer codes with one
+ * quantisation step per row of each of the 16 matrix products of step (ii), exact int32 accumulation on the chip's 8-bit
+ * integer MFMA path.  The paper's Section "Techniques" only remarks that its stack supports quantised operators; the scheme
+ * is this library's, chosen by a CPU error model first (F(4x4) and 8-bit floating point amplify the rounding too much):
+ *
+ *     U = G g G^T,  V = (B^T d) B                            b = xi*4 + nu, the position inside the transformed tile
+ *     mU[b][k] = max_c |U[b][k][c]|,  Uq = rint(U * (127 / mU)),  dU = mU / 127      (codes -127..127, ties to even;
+ *     mV[b][t] = max_c |V[b][t][c]|,  Vq = rint(V * (127 / mV)),  dV = mV / 127       a zero row has codes 0 and step 0)
+ *     M[b][k][t] = float(sum_c Uq[b][k][c] * Vq[b][t][c]) * dU[b][k] * dV[b][t],     y = A^T M A + bias
+ *
+ * The filter side is decided in fp64 (U is exact there) once per weight tensor; the activation side in fp32 on every call,
+ * row combination B^T d first, so that every entry is one IEEE operation and the codes are reproducible bit for bit.  The
+ * steps follow the data (no calibration, no scale arguments).  Halves the bytes of U and V: meant for the layers whose
+ * step (ii) streams a large U against few tiles (8x8 and 16x16 images with 640-2560 channels).  Relative L2 error against
+ * the exact convolution on unit-variance data: 1.4e-2 ... 2.0e-2 (tolerance of this path: 3e-2) - an opt-in, never chosen
+ * by WINO_AUTO.  x and y are in `dtype` (any storage type), NCHW or NHWC; C <= 65536.
+ *   u_q        device, wino_i8_filter_bytes(K, C): Uq[16][K][Cq] int8 (Cq = C rounded up to 16, padding zero), then,
+ *              256-byte aligned, dU[16][K] fp32
+ *   workspace  device, wino_i8_workspace_bytes(): Vq[16][T][Cq], dV[16][T], M (each 256-byte aligned), T = N*ceil(H/2)*ceil(W/2)
+ * wino_i8_input_transform and wino_i8_batched_gemm are the first two stages on their own (the third is
+ * wino_output_transform with WINO_F2); block_shape as for wino_batched_gemm_shape, -1 = the library's choice.
+ */
+size_t wino_i8_filter_bytes(int K, int C);
+int wino_i8_filter_transform(const void *w, void *u_q, int K, int C, int dtype, void *stream);
+size_t wino_i8_workspace_bytes(int N, int C, int H, int W, int K);
+int wino_i8_conv2d(const void *x, const void *u_q, const float *bias, void *y,
+                   int N, int C, int H, int W, int K, int dtype, int layout,
+                   void *workspace, size_t workspace_bytes, void *stream);
+int wino_i8_input_transform(const void *x, void *Vq, float *dV, int N, int C, int H, int W,
+                            int dtype, int layout, void *stream);
+int wino_i8_batched_gemm(const void *Uq, const float *dU, const void *Vq, const float *dV, float *M,
+                         int K, int C, int T, int block_shape, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

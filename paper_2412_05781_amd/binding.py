@@ -35,6 +35,8 @@ EXPORTS = [
     "wino_recommend_variant",
     "wino_fp8_filter_bytes", "wino_fp8_filter_quantize", "wino_fp8_workspace_bytes", "wino_fp8_conv2d",
     "wino_fused_gemm_output", "wino_batched_gemm_shape", "wino_static_scratch_bytes", "wino_conv2d_static",
+    "wino_i8_filter_bytes", "wino_i8_filter_transform", "wino_i8_workspace_bytes", "wino_i8_conv2d",
+    "wino_i8_input_transform", "wino_i8_batched_gemm",
 ]
 
 
@@ -108,6 +110,12 @@ def lib() -> ctypes.CDLL:
         L.wino_fp8_conv2d.restype = i
         L.wino_fp8_conv2d.argtypes = [vp, vp, vp, vp] + [i] * 9 + [ctypes.c_float, ctypes.c_float, ctypes.POINTER(wino_fusion), vp, sz, vp]
         L.wino_recommend_variant.restype = i; L.wino_recommend_variant.argtypes = [i] * 6
+        L.wino_i8_filter_bytes.restype = sz; L.wino_i8_filter_bytes.argtypes = [i, i]
+        L.wino_i8_filter_transform.restype = i; L.wino_i8_filter_transform.argtypes = [vp, vp, i, i, i, vp]
+        L.wino_i8_workspace_bytes.restype = sz; L.wino_i8_workspace_bytes.argtypes = [i] * 5
+        L.wino_i8_conv2d.restype = i; L.wino_i8_conv2d.argtypes = [vp, vp, vp, vp] + [i] * 7 + [vp, sz, vp]
+        L.wino_i8_input_transform.restype = i; L.wino_i8_input_transform.argtypes = [vp, vp, vp] + [i] * 6 + [vp]
+        L.wino_i8_batched_gemm.restype = i; L.wino_i8_batched_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
         L.wino_igemm_filter_bytes.restype = sz; L.wino_igemm_filter_bytes.argtypes = [i] * 4
         L.wino_igemm_filter_repack.restype = i
         L.wino_igemm_filter_repack.argtypes = [vp, vp, i, i, i, i, vp]
@@ -507,7 +515,93 @@ def wino_fp8_conv2d(x: torch.Tensor, w_q: torch.Tensor, bias, y: torch.Tensor, K
     return y
 
 
+def _align256(v: int) -> int:
+    return (v + 255) // 256 * 256
+
+
+def wino_i8_filter_bytes(K, C) -> int:
+    return lib().wino_i8_filter_bytes(K, C)
+
+
+def wino_i8_filter_transform(w: torch.Tensor, stream=None) -> torch.Tensor:
+    """w[K,C,3,3] -> raw byte buffer: codes Uq[16][K][Cq] int8, then (256-byte aligned) steps dU[16][K] fp32."""
+    _dev(w, "w")
+    if w.dim() != 4 or tuple(w.shape[2:]) != (3, 3) or w.dtype not in DTYPE_OF:
+        raise ValueError("w must be [K,C,3,3] in one of the storage types")
+    K, C = int(w.shape[0]), int(w.shape[1])
+    nbytes = wino_i8_filter_bytes(K, C)
+    if nbytes == 0:
+        raise WinoError(WINO_ERR_DIM, "wino_i8_filter_bytes")
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    _check(lib().wino_i8_filter_transform(_ptr(w), _ptr(buf), K, C, DTYPE_OF[w.dtype], _stream(stream)), "wino_i8_filter_transform")
+    return buf
+
+
+def i8_filter_views(u_q: torch.Tensor, K: int, C: int):
+    """(Uq[16][K][Cq] int8, dU[16][K] fp32) as views of the buffer wino_i8_filter_transform wrote."""
+    Cq = (C + 15) // 16 * 16
+    n = 16 * K * Cq
+    return u_q[:n].view(torch.int8).view(16, K, Cq), u_q[_align256(n):_align256(n) + 64 * K].view(torch.float32).view(16, K)
+
+
+def wino_i8_workspace_bytes(N, C, H, W, K) -> int:
+    return lib().wino_i8_workspace_bytes(N, C, H, W, K)
+
+
+def wino_i8_conv2d(x: torch.Tensor, u_q: torch.Tensor, bias, y: torch.Tensor, K: int, workspace: torch.Tensor,
+                   layout: int = WINO_NCHW, stream=None) -> torch.Tensor:
+    _dev(x, "x"); _dev(u_q, "u_q"); _dev(y, "y"); _dev(workspace, "workspace")
+    N, C, H, W = _unpack(x, layout)
+    if tuple(y.shape) != _act_shape(N, K, H, W, layout) or y.dtype != x.dtype or x.dtype not in DTYPE_OF:
+        raise ValueError(f"expected y{_act_shape(N, K, H, W, layout)} of dtype {x.dtype}")
+    if u_q.numel() * u_q.element_size() < wino_i8_filter_bytes(K, C):
+        raise ValueError("quantised filter buffer too small")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != K or not bias.is_cuda):
+        raise ValueError("bias must be a GPU fp32 tensor of K elements")
+    _check(lib().wino_i8_conv2d(_ptr(x), _ptr(u_q), _ptr(bias), _ptr(y), N, C, H, W, K, DTYPE_OF[x.dtype], layout, _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)), "wino_i8_conv2d")
+    return y
+
+
+def wino_i8_input_transform(x: torch.Tensor, layout: int = WINO_NCHW, stream=None):
+    """x -> (Vq[16][T][Cq] int8, dV[16][T] fp32)."""
+    _dev(x, "x")
+    N, C, H, W = _unpack(x, layout)
+    T, Cq = N * ((H + 1) // 2) * ((W + 1) // 2), (C + 15) // 16 * 16
+    Vq = torch.empty((16, T, Cq), dtype=torch.int8, device=x.device)
+    dV = torch.empty((16, T), dtype=torch.float32, device=x.device)
+    _check(lib().wino_i8_input_transform(_ptr(x), _ptr(Vq), _ptr(dV), N, C, H, W, DTYPE_OF[x.dtype], layout, _stream(stream)),
+           "wino_i8_input_transform")
+    return Vq, dV
+
+
+def wino_i8_batched_gemm(Uq: torch.Tensor, dU: torch.Tensor, Vq: torch.Tensor, dV: torch.Tensor, K: int, C: int, T: int,
+                         block_shape: int = -1, stream=None) -> torch.Tensor:
+    """M[16][K][T] fp32 = float(sum_c Uq * Vq) * dU[b][k] * dV[b][t]; called as (Vq, dV, Uq, dU, T, C, K) it writes M[16][T][K]."""
+    for t, name in ((Uq, "Uq"), (dU, "dU"), (Vq, "Vq"), (dV, "dV")):
+        _dev(t, name)
+    Cq = (C + 15) // 16 * 16
+    if Uq.dtype != torch.int8 or Vq.dtype != torch.int8 or Uq.numel() != 16 * K * Cq or Vq.numel() != 16 * T * Cq:
+        raise ValueError("Uq / Vq must be int8 tensors of 16*K*Cq and 16*T*Cq elements")
+    if dU.dtype != torch.float32 or dV.dtype != torch.float32 or dU.numel() != 16 * K or dV.numel() != 16 * T:
+        raise ValueError("dU / dV must be fp32 tensors of 16*K and 16*T elements")
+    M = torch.empty((16, K, T), dtype=torch.float32, device=Uq.device)
+    _check(lib().wino_i8_batched_gemm(_ptr(Uq), _ptr(dU), _ptr(Vq), _ptr(dV), _ptr(M), K, C, T, block_shape, _stream(stream)),
+           "wino_i8_batched_gemm")
+    return M
+
+
 # ---- convenience (allocation only) ------------------------------------------------------------
+def conv2d_i8(x: torch.Tensor, w: torch.Tensor, bias=None, layout: int = WINO_NCHW) -> torch.Tensor:
+    """Quantise the transformed filter, allocate workspace and output, run the Winograd path with 8-bit integer U and V."""
+    N, C, H, W = _unpack(x, layout)
+    K = int(w.shape[0])
+    y = torch.empty(_act_shape(N, K, H, W, layout), dtype=x.dtype, device=x.device)
+    u_q = wino_i8_filter_transform(w)
+    ws = torch.empty(max(16, wino_i8_workspace_bytes(N, C, H, W, K)), dtype=torch.uint8, device=x.device)
+    return wino_i8_conv2d(x, u_q, bias, y, K, ws, layout)
+
+
 def conv2d_fp8(x: torch.Tensor, w: torch.Tensor, bias, scale_x: float, scale_w: float, stride: int = 1, layout: int = WINO_NCHW,
                **fused) -> torch.Tensor:
     """Quantise the filter, allocate workspace and output, run the 8-bit direct path (fused operators by keyword)."""

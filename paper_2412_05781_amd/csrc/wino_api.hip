@@ -614,4 +614,93 @@ int wino_fp8_conv2d(const void* x, const void* w_q, const float* bias, void* y,
                                    static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
+// ---- Winograd F(2x2,3x3) with 8-bit integer U and V -------------------------------------------------------------
+namespace {
+constexpr int kI8MaxC = 65536;                    // 65536 * 127^2 < 2^31: the int32 sums cannot overflow
+inline int i8_cq(int C) { return round_up(C, 16); }
+bool i8_dims_ok(int N, int C, int H, int W, int K) { return dims_ok(N, C, H, W, K, 2) && C <= kI8MaxC; }
+size_t i8_codes_bytes(int rows, int Cq) { return align_up((size_t)16 * (size_t)rows * (size_t)Cq); }
+size_t i8_steps_bytes(int rows) { return align_up((size_t)16 * (size_t)rows * sizeof(float)); }
+int i8_split(const Geom& g, bool nhwc) {
+    return nhwc ? gemm_split(g.T, g.K, i8_cq(g.C), 16, DT_I8) : gemm_split(g.K, g.T, i8_cq(g.C), 16, DT_I8);
+}
+}  // namespace
+
+size_t wino_i8_filter_bytes(int K, int C) {
+    if (!i8_dims_ok(1, C, 1, 1, K)) return 0;
+    return i8_codes_bytes(K, i8_cq(C)) + i8_steps_bytes(K);
+}
+
+int wino_i8_filter_transform(const void* w, void* u_q, int K, int C, int dtype, void* stream) {
+    if (!w || !u_q) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (!i8_dims_ok(1, C, 1, 1, K)) return WINO_ERR_DIM;
+    if (!aligned16(w) || !aligned16(u_q)) return WINO_ERR_ALIGN;
+    float* dU = reinterpret_cast<float*>(static_cast<unsigned char*>(u_q) + i8_codes_bytes(K, i8_cq(C)));
+    return launch_filter_quant_i8(w, u_q, dU, K, C, i8_cq(C), dtype, static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+}
+
+size_t wino_i8_workspace_bytes(int N, int C, int H, int W, int K) {
+    if (!i8_dims_ok(N, C, H, W, K)) return 0;
+    const Geom g = make_geom(N, C, H, W, K, 2);
+    const int sp_a = i8_split(g, false), sp_b = i8_split(g, true);
+    return i8_codes_bytes(g.T, i8_cq(C)) + i8_steps_bytes(g.T) +
+           align_up((size_t)16 * (size_t)K * (size_t)g.T * sizeof(float) * (size_t)(sp_a > sp_b ? sp_a : sp_b));
+}
+
+int wino_i8_input_transform(const void* x, void* Vq, float* dV, int N, int C, int H, int W, int dtype, int layout, void* stream) {
+    if (!x || !Vq || !dV) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    if (!i8_dims_ok(N, C, H, W, 1)) return WINO_ERR_DIM;
+    if (!aligned16(x) || !aligned16(Vq) || (reinterpret_cast<uintptr_t>(dV) & 3u)) return WINO_ERR_ALIGN;
+    const Geom g = make_geom(N, C, H, W, 1, 2);
+    return launch_input_transform_i8(x, Vq, dV, g, i8_cq(C), dtype, layout == WINO_NHWC, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? WINO_OK : WINO_ERR_HIP;
+}
+
+int wino_i8_batched_gemm(const void* Uq, const float* dU, const void* Vq, const float* dV, float* M, int K, int C, int T,
+                         int block_shape, void* stream) {
+    if (block_shape < -1 || block_shape > 8) return WINO_ERR_VARIANT;
+    if (!Uq || !dU || !Vq || !dV || !M) return WINO_ERR_NULL;
+    if (K < 1 || C < 1 || T < 1 || T > INT_MAX / 2 || !i8_dims_ok(1, C, 1, 1, K)) return WINO_ERR_DIM;
+    if (16ULL * (unsigned long long)T > (1ULL << 40) / (unsigned long long)i8_cq(C) ||
+        16ULL * (unsigned long long)T > (1ULL << 40) / (unsigned long long)K) return WINO_ERR_DIM;
+    if (!aligned16(Uq) || !aligned16(Vq) || !aligned16(M) ||
+        ((reinterpret_cast<uintptr_t>(dU) | reinterpret_cast<uintptr_t>(dV)) & 3u)) return WINO_ERR_ALIGN;
+    return launch_batched_gemm_i8(Uq, dU, Vq, dV, M, K, i8_cq(C), T, 16, 1, static_cast<hipStream_t>(stream), block_shape) == hipSuccess
+               ? WINO_OK : WINO_ERR_HIP;
+}
+
+int wino_i8_conv2d(const void* x, const void* u_q, const float* bias, void* y, int N, int C, int H, int W, int K,
+                   int dtype, int layout, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!x || !u_q || !y) return WINO_ERR_NULL;
+    if (!dtype_ok(dtype)) return WINO_ERR_DTYPE;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    if (!i8_dims_ok(N, C, H, W, K)) return WINO_ERR_DIM;
+    if (!aligned16(x) || !aligned16(u_q) || !aligned16(y) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u))) return WINO_ERR_ALIGN;
+    const size_t es = esize(dtype);
+    const uintptr_t xb = reinterpret_cast<uintptr_t>(x), xe = xb + (size_t)N * C * H * W * es;
+    const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + (size_t)N * K * H * W * es;
+    if (xb < ye && yb < xe) return WINO_ERR_ALIAS;
+    if (!workspace || workspace_bytes < wino_i8_workspace_bytes(N, C, H, W, K)) return WINO_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return WINO_ERR_ALIGN;
+    const bool nhwc = layout == WINO_NHWC;
+    const Geom g = make_geom(N, C, H, W, K, 2);
+    const int Cq = i8_cq(C);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    void* Vq = ws;
+    float* dV = reinterpret_cast<float*>(ws + i8_codes_bytes(g.T, Cq));
+    float* M = reinterpret_cast<float*>(ws + i8_codes_bytes(g.T, Cq) + i8_steps_bytes(g.T));
+    const float* dU = reinterpret_cast<const float*>(static_cast<const unsigned char*>(u_q) + i8_codes_bytes(K, Cq));
+    if (launch_input_transform_i8(x, Vq, dV, g, Cq, dtype, nhwc, s) != hipSuccess) return WINO_ERR_HIP;
+    const int nsplit = i8_split(g, nhwc);
+    // channel-last: operands swapped, so the product comes out as M[16][T][K], k contiguous
+    const hipError_t ge = nhwc ? launch_batched_gemm_i8(Vq, dV, u_q, dU, M, g.T, Cq, g.K, 16, nsplit, s)
+                               : launch_batched_gemm_i8(u_q, dU, Vq, dV, M, g.K, Cq, g.T, 16, nsplit, s);
+    if (ge != hipSuccess) return WINO_ERR_HIP;
+    return launch_output_transform(M, bias, y, g, nsplit, dtype, nhwc, false, nullptr, s) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+}
+
 }  // extern "C"

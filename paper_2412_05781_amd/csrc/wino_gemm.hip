@@ -22,12 +22,24 @@
 
 namespace wino {
 
+// 8-bit integer operands carry one quantisation step per row of each operand (rs[nbatch][K] for the first, cs[nbatch][T]
+// for the second); the integer sum becomes the product by  float(sum) * rs[batch][k] * cs[batch][t].  For the floating-point
+// storage types the accumulator is the product and both pointers are unused.
+template <typename E> __device__ __forceinline__ float column_step(const float* cs, int batch, int T, int t) {
+    if constexpr (std::is_same_v<E, i8_t>) return t < T ? cs[(size_t)batch * T + t] : 0.f;
+    else return 1.f;
+}
+template <typename E, typename A> __device__ __forceinline__ float product_value(A a, const float* rs, int batch, int K, int k, float cstep) {
+    if constexpr (std::is_same_v<E, i8_t>) return (float)a * rs[(size_t)batch * K + k] * cstep;
+    else return a;
+}
+
 // MT = type the product is stored in: float, or __half for the opt-in half-product mode.
 template <typename E, typename MT, int BM, int BN, int RB, int NST, int WGM, int WGN>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __restrict__ Mo,
                  int K, int Cp, int T, int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd,
-                 int nbatch, int nsplit) {
+                 int nbatch, int nsplit, const float* __restrict__ rs, const float* __restrict__ cs) {
     constexpr int CPR = RB / 16;                          // 16-byte chunks per row per stage
     constexpr int BKE = RB / (int)sizeof(E);              // reduction elements per stage
     constexpr int EPC = 16 / (int)sizeof(E);              // elements per chunk
@@ -109,13 +121,13 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __restric
         }
     };
 
-    float16_t acc[FM][FN];
+    typename Mma<E>::acc_t acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
@@ -164,10 +176,11 @@ wino_gemm_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __restric
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
             const int t = row_t0 + wn * WTN + j * 32 + frag_row;
+            const float cstep = column_step<E>(cs, batch, T, t);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int k = row_k0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
-                if (k < K && t < T) Mb[(size_t)k * T + t] = from_f32<MT>(acc[i][j][r]);
+                if (k < K && t < T) Mb[(size_t)k * T + t] = from_f32<MT>(product_value<E>(acc[i][j][r], rs, batch, K, k, cstep));
             }
         }
 }
@@ -187,7 +200,7 @@ template <typename E, typename MT, int BM, int BN, int NST, int WGM, int WGN>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 wino_gemm_lean_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __restrict__ Mo,
                       int K, int Cp, int T, int tiles_m, int tiles_n, int total_blocks, int blocks_per_xcd,
-                      int nbatch, int nsplit) {
+                      int nbatch, int nsplit, const float* __restrict__ rs, const float* __restrict__ cs) {
     constexpr int RB = 128;
     constexpr int CPR = RB / 16;
     constexpr int BKE = RB / (int)sizeof(E);
@@ -250,7 +263,7 @@ wino_gemm_lean_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __re
     };
 
     constexpr int NACC = (FM * FN == 1) ? 2 : 1;
-    float16_t acc[NACC][FM][FN];
+    typename Mma<E>::acc_t acc[NACC][FM][FN];
 #pragma unroll
     for (int q = 0; q < NACC; ++q)
 #pragma unroll
@@ -258,7 +271,7 @@ wino_gemm_lean_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __re
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[q][i][j][r] = 0.f;
+                for (int r = 0; r < 16; ++r) acc[q][i][j][r] = 0;
 
     constexpr int KS = CPR / 2, KH = KS / 2;
     constexpr int NREAD = KH * (FM + FN);
@@ -351,10 +364,11 @@ wino_gemm_lean_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __re
             for (int j = 0; j < FN; ++j) {
                 const int kb = row0 + wm * WTM + i * 32;                     // uniform
                 const uint32_t loff = (uint32_t)(4 * frag_half) * (uint32_t)T + (uint32_t)(col0 + wn * WTN + j * 32 + frag_row);
+                const float cstep = column_step<E>(cs, batch, T, col0 + wn * WTN + j * 32 + frag_row);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     MT* rowp = Mb + (size_t)(kb + 8 * (r / 4) + (r % 4)) * T;     // uniform
-                    rowp[loff] = from_f32<MT>(acc[0][i][j][r]);
+                    rowp[loff] = from_f32<MT>(product_value<E>(acc[0][i][j][r], rs, batch, K, kb + 8 * (r / 4) + 4 * frag_half + (r % 4), cstep));
                 }
             }
     } else {
@@ -363,17 +377,19 @@ wino_gemm_lean_kernel(const E* __restrict__ U, const E* __restrict__ V, MT* __re
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
                 const int t = col0 + wn * WTN + j * 32 + frag_row;
+                const float cstep = column_step<E>(cs, batch, T, t);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int k = row0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
-                    if (k < K && t < T) Mb[(size_t)k * T + t] = from_f32<MT>(acc[0][i][j][r]);
+                    if (k < K && t < T) Mb[(size_t)k * T + t] = from_f32<MT>(product_value<E>(acc[0][i][j][r], rs, batch, K, k, cstep));
                 }
             }
     }
 }
 
 template <typename E, typename MT, int BM, int BN, int NST, int WGM, int WGN>
-static hipError_t launch_gemm_lean(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
+static hipError_t launch_gemm_lean(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s,
+                                   const float* rs, const float* cs) {
     const int tiles_m = (K + BM - 1) / BM, tiles_n = (T + BN - 1) / BN;
     const long long total = (long long)tiles_m * tiles_n * nbatch * nsplit;
     if (total > 0x3fffffffLL) return hipErrorInvalidValue;
@@ -386,12 +402,13 @@ static hipError_t launch_gemm_lean(const void* U, const void* V, void* M, int K,
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(WGM * WGN * 64), lds_bytes, s, (const E*)U, (const E*)V, (MT*)M,
-                       K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd, nbatch, nsplit);
+                       K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd, nbatch, nsplit, rs, cs);
     return hipGetLastError();
 }
 
 template <typename E, typename MT, int BM, int BN, int RB, int NST, int WGM = 2, int WGN = 2>
-static hipError_t launch_gemm_cfg(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s) {
+static hipError_t launch_gemm_cfg(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, hipStream_t s,
+                                  const float* rs, const float* cs) {
     const int tiles_m = (K + BM - 1) / BM, tiles_n = (T + BN - 1) / BN;
     const long long total = (long long)tiles_m * tiles_n * nbatch * nsplit;
     if (total > 0x3fffffffLL) return hipErrorInvalidValue;
@@ -404,7 +421,7 @@ static hipError_t launch_gemm_cfg(const void* U, const void* V, void* M, int K, 
     if (attr != hipSuccess) return attr;
     dim3 block(WGM * WGN * 64), grid((unsigned)(per_xcd * 8));
     hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, (const E*)U, (const E*)V, (MT*)M,
-                       K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd, nbatch, nsplit);
+                       K, Cp, T, tiles_m, tiles_n, (int)total, per_xcd, nbatch, nsplit, rs, cs);
     return hipGetLastError();
 }
 
@@ -453,37 +470,38 @@ static int pick_shape(int K, int T, int nbatch, bool f16) {
 }
 
 template <typename E, typename MT>
-static hipError_t launch_gemm_t(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int shape, hipStream_t s) {
+static hipError_t launch_gemm_t(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int shape, hipStream_t s,
+                                const float* rs = nullptr, const float* cs = nullptr) {
     const int sh = shape < 0 ? pick_shape(K, T, nbatch, sizeof(E) == 2) : shape;
     if (Cp % (128 / (int)sizeof(E)) == 0) {               // whole stages: the lean kernel, same block shapes
         switch (sh) {
-            case 0: return launch_gemm_lean<E, MT, 128, 128, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-            case 1: return launch_gemm_lean<E, MT, 128, 64, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-            case 2: return launch_gemm_lean<E, MT, 64, 128, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-            case 3: return launch_gemm_lean<E, MT, 64, 64, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-            case 5: return launch_gemm_lean<E, MT, 128, 32, 3, 4, 1>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-            case 6: return launch_gemm_lean<E, MT, 32, 128, 3, 1, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-            case 7: return launch_gemm_lean<E, MT, 128, 128, 3, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-            case 8: return launch_gemm_lean<E, MT, 256, 128, 3, 4, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+            case 0: return launch_gemm_lean<E, MT, 128, 128, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+            case 1: return launch_gemm_lean<E, MT, 128, 64, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+            case 2: return launch_gemm_lean<E, MT, 64, 128, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+            case 3: return launch_gemm_lean<E, MT, 64, 64, 2, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+            case 5: return launch_gemm_lean<E, MT, 128, 32, 3, 4, 1>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+            case 6: return launch_gemm_lean<E, MT, 32, 128, 3, 1, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+            case 7: return launch_gemm_lean<E, MT, 128, 128, 3, 2, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+            case 8: return launch_gemm_lean<E, MT, 256, 128, 3, 4, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
             default: break;                                // 256x256 with 16 waves has no registers for two fragment sets
         }
     }
     switch (sh) {
-        case 0: return launch_gemm_cfg<E, MT, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 1: return launch_gemm_cfg<E, MT, 128, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 2: return launch_gemm_cfg<E, MT, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 3: return launch_gemm_cfg<E, MT, 64, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 5: return launch_gemm_cfg<E, MT, 128, 32, 128, 3, 4, 1>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 6: return launch_gemm_cfg<E, MT, 32, 128, 128, 3, 1, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 7: return launch_gemm_cfg<E, MT, 128, 128, 128, 3>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        case 8: return launch_gemm_cfg<E, MT, 256, 128, 128, 3, 4, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s);
-        default: return launch_gemm_cfg<E, MT, 256, 256, 128, 2, 4, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s);
+        case 0: return launch_gemm_cfg<E, MT, 128, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+        case 1: return launch_gemm_cfg<E, MT, 128, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+        case 2: return launch_gemm_cfg<E, MT, 64, 128, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+        case 3: return launch_gemm_cfg<E, MT, 64, 64, 128, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+        case 5: return launch_gemm_cfg<E, MT, 128, 32, 128, 3, 4, 1>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+        case 6: return launch_gemm_cfg<E, MT, 32, 128, 128, 3, 1, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+        case 7: return launch_gemm_cfg<E, MT, 128, 128, 128, 3>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+        case 8: return launch_gemm_cfg<E, MT, 256, 128, 128, 3, 4, 2>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
+        default: return launch_gemm_cfg<E, MT, 256, 256, 128, 2, 4, 4>(U, V, M, K, Cp, T, nbatch, nsplit, s, rs, cs);
     }
 }
 
 // Stages are 128 bytes of reduction per row in every block shape.
 int gemm_max_split(int Cp, int dt) {
-    const int bke = two_byte(dt) ? 64 : 32;
+    const int bke = dt == DT_I8 ? 128 : (two_byte(dt) ? 64 : 32);
     const int stages = (Cp + bke - 1) / bke;
     return stages < 1 ? 1 : stages;
 }
@@ -523,6 +541,13 @@ hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int
         using E = std::remove_pointer_t<decltype(tag)>;
         return launch_gemm_t<E, float>(U, V, M, K, Cp, T, nbatch, nsplit, shape, s);
     });
+}
+
+hipError_t launch_batched_gemm_i8(const void* Uq, const float* dU, const void* Vq, const float* dV, float* M, int K, int Cq, int T,
+                                  int nbatch, int nsplit, hipStream_t s, int shape) {
+    if (nsplit < 1 || nsplit > gemm_max_split(Cq, DT_I8)) return hipErrorInvalidValue;
+    if (shape < -1 || shape > 8 || !dU || !dV || Cq % 16 != 0) return hipErrorInvalidValue;
+    return launch_gemm_t<i8_t, float>(Uq, Vq, M, K, Cq, T, nbatch, nsplit, shape, s, dU, dV);
 }
 
 }  // namespace wino

@@ -34,7 +34,7 @@ inline Geom make_geom(int N, int C, int H, int W, int K, int m) {
 // Storage types (values of wino_dtype).  `with_dtype` calls f with a null pointer of the element
 // type, so that a generic lambda can name it:  using E = std::remove_pointer_t<decltype(tag)>.
 typedef __hip_bfloat16 bf16_t;
-enum { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
+enum { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2, DT_I8 = 3 };     // DT_I8: internal only (operands of the quantised Winograd path)
 inline bool two_byte(int dt) { return dt != DT_F32; }
 template <typename F> inline hipError_t with_dtype(int dt, F&& f) {
     if (dt == DT_F16) return f(static_cast<__half*>(nullptr));
@@ -44,6 +44,8 @@ template <typename F> inline hipError_t with_dtype(int dt, F&& f) {
 
 // 8-bit floating-point operand (OCP E4M3) of the quantised direct path: storage only.
 struct fp8_t { uint8_t v; };
+// 8-bit integer code of the quantised Winograd path (symmetric, -127..127): storage only.
+struct i8_t { int8_t v; };
 // nearest E4M3 value of v after clamping to the format's range (+-448), ties to even
 __device__ __forceinline__ uint32_t quant_e4m3(float v) {
     v = fminf(fmaxf(v, -448.f), 448.f);
@@ -124,6 +126,14 @@ hipError_t launch_input_transform(const void* x, void* V, const Geom& g, int dt,
 // shape: -1 = the library's choice for the problem size, 0..8 = a named block shape (see wino_gemm.hip)
 hipError_t launch_batched_gemm(const void* U, const void* V, void* M, int K, int Cp, int T, int nbatch, int nsplit, int dt, bool half_product,
                                hipStream_t s, int shape = -1);
+// the same product on 8-bit integer codes (rows of 16-byte multiples, Cq % 16 == 0) with one quantisation step per row of each
+// operand: M[b][k][t] = float(sum_c Uq[b][k][c] * Vq[b][t][c]) * dU[b][k] * dV[b][t]; int32 accumulation, exact
+hipError_t launch_batched_gemm_i8(const void* Uq, const float* dU, const void* Vq, const float* dV, float* M, int K, int Cq, int T,
+                                  int nbatch, int nsplit, hipStream_t s, int shape = -1);
+// step (i) of the quantised F(2x2) path (wino_int8.hip): codes and steps of the filter (once per weight tensor, fp64 decisions)
+// and of the activation (fp32 decisions); Uq[16][K][Cq], dU[16][K], Vq[16][T][Cq], dV[16][T], Cq % 16 == 0, padded channels zero
+hipError_t launch_filter_quant_i8(const void* w, void* Uq, float* dU, int K, int C, int Cq, int dt, hipStream_t s);
+hipError_t launch_input_transform_i8(const void* x, void* Vq, float* dV, const Geom& g, int Cq, int dt, bool nhwc, hipStream_t s);
 int gemm_max_split(int Cp, int dt);
 int gemm_split(int rows, int cols, int Cp, int nbatch, int dt);
 hipError_t launch_output_transform(const void* M, const float* bias, void* y, const Geom& g, int nsplit, int dt, bool nhwc,

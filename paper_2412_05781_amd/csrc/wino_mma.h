@@ -11,8 +11,13 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));      // a 16-byte fragment as a native vector (inline-asm operand)
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
+typedef int int16v_t __attribute__((ext_vector_type(16)));
+typedef int int4v_t __attribute__((ext_vector_type(4)));
+
+// acc_t: the sixteen accumulator registers of one 32x32 tile (fp32; int32 for 8-bit integer operands)
 template <typename E> struct Mma;
 template <> struct Mma<__half> {
+    using acc_t = float16_t;
     // one 16-byte chunk = 8 reduction elements; lanes 0-31 and 32-63 hold different chunks
     static __device__ __forceinline__ void run(const uint4& a, const uint4& b, float16_t& c) {
         c = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const half8_t*>(&a),
@@ -24,6 +29,7 @@ template <> struct Mma<__half> {
 };
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 template <> struct Mma<bf16_t> {
+    using acc_t = float16_t;
     static __device__ __forceinline__ void run(const uint4& a, const uint4& b, float16_t& c) {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(&a),
                                                      *reinterpret_cast<const bf16x8_t*>(&b), c, 0, 0, 0);
@@ -33,6 +39,7 @@ template <> struct Mma<bf16_t> {
     }
 };
 template <> struct Mma<float> {
+    using acc_t = float16_t;
     static __device__ __forceinline__ void run(const uint4& a, const uint4& b, float16_t& c) {
         const float* fa = reinterpret_cast<const float*>(&a);
         const float* fb = reinterpret_cast<const float*>(&b);
@@ -48,7 +55,18 @@ template <> struct Mma<float> {
     }
 };
 
-// 8-bit operands: one 32x32x64 step takes 32 bytes per lane and operand, i.e. two 16-byte chunks (lanes 0-31
+// 8-bit integer operands, exact int32 accumulation: one 16-byte chunk = 16 reduction elements per lane (32 per step)
+template <> struct Mma<i8_t> {
+    using acc_t = int16v_t;
+    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, int16v_t& c) {
+        c = __builtin_amdgcn_mfma_i32_32x32x32_i8(*reinterpret_cast<const int4v_t*>(&a), *reinterpret_cast<const int4v_t*>(&b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void run(const u32x4_t& a, const u32x4_t& b, int16v_t& c) {
+        c = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(int4v_t, a), __builtin_bit_cast(int4v_t, b), c, 0, 0, 0);
+    }
+};
+
+// 8-bit floating-point operands: one 32x32x64 step takes 32 bytes per lane and operand, i.e. two 16-byte chunks (lanes 0-31
 // and 32-63 hold different chunk pairs).  Which byte lands on which k inside the instruction does not matter as
 // long as both operands are loaded the same way.  Format selectors 0 = E4M3; scale bytes 0x7f = 2^0.
 typedef int int8v_t __attribute__((ext_vector_type(8)));

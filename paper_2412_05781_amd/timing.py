@@ -8,6 +8,7 @@ the table that the file of the same topic under ``profiles/`` records:
     python -m paper_2412_05781_amd.timing direct         3x3 stride 1: Winograd vs direct vs 8-bit direct
     python -m paper_2412_05781_amd.timing half-product   the opt-in fp16 intermediate product
     python -m paper_2412_05781_amd.timing variants       every workload layer x {F(4x4), F(2x2), fused F(2x2)} x {NCHW, NHWC}
+    python -m paper_2412_05781_amd.timing int8           F(2x2) with 8-bit integer U and V against the fp16 call, stage by stage
 
 "framework" columns call the stock deep-learning framework's own operators on the same tensors, as context.
 """
@@ -194,15 +195,61 @@ def cmd_variants(_):
                   f"    {wsb[0]:7.1f} / {wsb[1]:7.1f} / {wsb[2]:7.1f}", flush=True)
 
 
+def cmd_int8(_):
+    """The layers whose step (ii) streams U (8x8 and 16x16 images) and two larger ones: whole call and the first two stages alone,
+    fp16 (what WINO_AUTO runs) against the 8-bit integer path; every stage reads cold input (rotating sets)."""
+    print(f"{'layer':10s} {'layout':5s} | fp16: {'call':>7s} {'K2':>6s} {'K3':>6s} | int8: {'call':>7s} {'K2':>6s} {'K3':>6s} | call x    K3 x   (us)")
+    for name in ("C3_unet", "C4_unet", "C5_unet", "C6_unet", "D3_sdxl", "C7_unet", "B_resblock"):
+        L = synth.LAYERS[name]
+        N, C, K, H, W = L.N, L.C, L.K, L.H, L.W
+        wd, bd = _w(K, C), torch.randn(K, device=DEV) * 0.01
+        v = B.wino_resolve_variant(N, C, H, W, K, B.WINO_F16, B.WINO_AUTO)
+        _, Cp, T = B.wino_transformed_dims(N, C, H, W, K, B.WINO_F2)
+        for layout in (B.WINO_NCHW, B.WINO_NHWC):
+            n = _nsets((N * C * H * W + N * K * H * W) * 2 + B.wino_i8_filter_bytes(K, C), hi=24)
+            xs = [torch.randn(_shape(N, C, H, W, layout), device=DEV).to(DT) for _ in range(n)]
+            ys = [torch.empty(_shape(N, K, H, W, layout), device=DEV, dtype=DT) for _ in range(n)]
+            fs = [B.wino_filter_transform(wd, v) for _ in range(n)]
+            qs = [B.wino_i8_filter_transform(wd) for _ in range(n)]
+            ws = torch.empty(max(B.wino_workspace_bytes(N, C, H, W, K, B.WINO_F16, v), B.wino_i8_workspace_bytes(N, C, H, W, K)),
+                             dtype=torch.uint8, device=DEV)
+            t16 = graph_time(lambda i: B.wino_conv2d_ex(xs[i % n], fs[i % n], bd, ys[i % n], ws, layout), 2 * n) * 1e6
+            t8 = graph_time(lambda i: B.wino_i8_conv2d(xs[i % n], qs[i % n], bd, ys[i % n], K, ws, layout), 2 * n) * 1e6
+            # stages alone (F(2x2) geometry for both so that the columns compare like with like)
+            f2 = [B.wino_filter_transform(wd, B.WINO_F2) for _ in range(n)]
+            V16 = B.wino_input_transform(xs[0], B.WINO_F2, layout)
+            k2_16 = graph_time(lambda i: B.wino_input_transform(xs[i % n], B.WINO_F2, layout, out=V16), 2 * n) * 1e6
+            M = torch.empty((16, K, T), dtype=torch.float32, device=DEV)
+            if layout == B.WINO_NHWC:
+                k3_16 = graph_time(lambda i: B.wino_batched_gemm(V16, f2[i % n].buf.view(DT).view(16, K, Cp), T, C, K, B.WINO_F2, out=M.view(16, T, K)), 2 * n) * 1e6
+            else:
+                k3_16 = graph_time(lambda i: B.wino_batched_gemm(f2[i % n].buf.view(DT).view(16, K, Cp), V16, K, C, T, B.WINO_F2, out=M), 2 * n) * 1e6
+            Vq, dV = B.wino_i8_input_transform(xs[0], layout)
+            L_ = B.lib()
+            k2_8 = graph_time(lambda i: B._check(L_.wino_i8_input_transform(B._ptr(xs[i % n]), B._ptr(Vq), B._ptr(dV), N, C, H, W, B.WINO_F16, layout,
+                                                                             B._stream(None)), "k2"), 2 * n) * 1e6
+            views = [B.i8_filter_views(q, K, C) for q in qs]
+            if layout == B.WINO_NHWC:
+                k3_8 = graph_time(lambda i: B._check(L_.wino_i8_batched_gemm(B._ptr(Vq), B._ptr(dV), B._ptr(views[i % n][0]), B._ptr(views[i % n][1]),
+                                                                              B._ptr(M), T, C, K, -1, B._stream(None)), "k3"), 2 * n) * 1e6
+            else:
+                k3_8 = graph_time(lambda i: B._check(L_.wino_i8_batched_gemm(B._ptr(views[i % n][0]), B._ptr(views[i % n][1]), B._ptr(Vq), B._ptr(dV),
+                                                                              B._ptr(M), K, C, T, -1, B._stream(None)), "k3"), 2 * n) * 1e6
+            print(f"{name:10s} {_lname(layout):5s} | {_vname(v):>5s} {t16:7.1f} {k2_16:6.1f} {k3_16:6.1f} |       {t8:7.1f} {k2_8:6.1f} {k3_8:6.1f} |"
+                  f"  {t16 / t8:5.2f}   {k3_16 / k3_8:5.2f}", flush=True)
+            del xs, ys, fs, qs, f2, views, ws
+            torch.cuda.empty_cache()
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["fused", "upsample", "flavours", "direct", "half-product", "variants"])
+    ap.add_argument("what", choices=["fused", "upsample", "flavours", "direct", "half-product", "variants", "int8"])
     a = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("timing: no GPU visible", file=sys.stderr)
         return 2
     {"fused": cmd_fused, "upsample": cmd_upsample, "flavours": cmd_flavours, "direct": cmd_direct,
-     "half-product": cmd_half_product, "variants": cmd_variants}[a.what](a)
+     "half-product": cmd_half_product, "variants": cmd_variants, "int8": cmd_int8}[a.what](a)
     return 0
 
 
