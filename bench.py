@@ -187,6 +187,19 @@ def main():
         dt_or = time.perf_counter() - t0
         return oracle.rel_l2(y_dev.float().cpu().numpy(), ref), dt_or
 
+    def int8_record(L, r, cpu_inputs):
+        n = r.nsets
+        qs = [B.wino_i8_filter_transform(r.wd) for _ in range(n)]
+        ws8 = torch.empty(B.wino_i8_workspace_bytes(L.N, L.C, L.H, L.W, L.K), dtype=torch.uint8, device=dev)
+        call = lambda i: B.wino_i8_conv2d(r.sets[i % n][0], qs[i % n], r.bd, r.sets[i % n][2], L.K, ws8)
+        t8 = graph_time(call, 2 * n)
+        out8 = {"us": t8 * 1e6, "tflops": L.direct_flops / t8 / 1e12}
+        if oracle is not None:
+            call(0)
+            torch.cuda.synchronize()
+            out8["rel_l2_vs_oracle"], _ = parity(L, cpu_inputs, r.sets[0][2])
+        return out8
+
     # ---- headline: exactly --steps steps of the whole path, host clock, barrier = device synchronisation -----------
     layer = synth.LAYERS[args.layer]
     cpu_in = synth.make_layer_inputs(layer)
@@ -266,6 +279,10 @@ def main():
                 r.step(0)
                 torch.cuda.synchronize()
                 rec["recommended"]["rel_l2_vs_oracle"], _ = parity(L, cin, r.sets[0][2])
+        # the layers whose step (ii) streams a large U against few tiles: the opt-in path with 8-bit integer U and V beside it
+        # (lower precision: about 1.7e-2 against 5e-4; never what the headline or the `us` column runs)
+        if L.dtype == "f16" and L.C >= 640 and L.N * ((L.H + 1) // 2) * ((L.W + 1) // 2) <= 128:
+            rec["int8_uv"] = int8_record(L, r, cin)
         layers_out.append(rec)
         print(f"bench: {name} {rec['variant']} {rec['us']:.1f} us {rec['tflops']:.0f} TFLOP/s", file=sys.stderr, flush=True)
         del r, cin

@@ -10,8 +10,8 @@
 //
 // A row's maximum needs the whole row, so a workgroup owns whole rows: the filter kernel one output channel k (all 16
 // positions), the activation kernel one tile t and one row xi of the transformed tile (4 positions, which need only two
-// rows of the 4x4 window).  Both make two passes over their inputs (maximum, then codes); the second pass of the
-// activation kernel re-reads at most a few KB that the first pass has just brought into the cache.
+// rows of the 4x4 window).  The filter kernel makes two passes over its input (maximum, then codes); the activation kernel
+// keeps a row's entries in registers between the two and recomputes only what exceeds them (more than 3072 channels).
 #include "wino_internal.h"
 
 namespace wino {
@@ -110,38 +110,28 @@ __device__ __forceinline__ void bt_row(int xi, int& ia, int& ib, bool& add) {
     add = xi == 1;
 }
 
-// the four entries V[xi][0..3] of channel c of one tile: (B^T d) first - one addition or subtraction of two window rows
-// per column - then the column combination, again one operation per entry.  Pixels outside the image and channels
-// c >= C read as zero.
+// x[n][c][h][w] (or [n][h][w][c]) as fp32, zero outside the image and for c >= C.  The load itself is unconditional (a
+// clamped, always valid address), so that a thread's loads can all be in flight together.
 template <typename E, bool NHWC>
-__device__ __forceinline__ void activation_row(const E* __restrict__ x, int n, int c, int C, int H, int W, int h0, int w0,
-                                               int ia, int ib, bool add, float (&v)[4]) {
-    float ra[4], rb[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int wj = w0 + j, ha = h0 + ia, hb = h0 + ib;
-        const bool okw = c < C && wj >= 0 && wj < W;
-        const bool oka = okw && ha >= 0 && ha < H, okb = okw && hb >= 0 && hb < H;
-        const size_t offa = NHWC ? (((size_t)n * H + ha) * W + wj) * C + c : (((size_t)n * C + c) * H + ha) * W + wj;
-        const size_t offb = NHWC ? (((size_t)n * H + hb) * W + wj) * C + c : (((size_t)n * C + c) * H + hb) * W + wj;
-        ra[j] = oka ? to_f32<E>(x[offa]) : 0.f;
-        rb[j] = okb ? to_f32<E>(x[offb]) : 0.f;
-    }
-    float t[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) t[j] = add ? __fadd_rn(ra[j], rb[j]) : __fsub_rn(ra[j], rb[j]);
-    v[0] = __fsub_rn(t[0], t[2]);
-    v[1] = __fadd_rn(t[1], t[2]);
-    v[2] = __fsub_rn(t[2], t[1]);
-    v[3] = __fsub_rn(t[1], t[3]);
+__device__ __forceinline__ float load_x(const E* __restrict__ x, int n, int c, int h, int w, int C, int H, int W) {
+    const bool ok = c < C && h >= 0 && h < H && w >= 0 && w < W;
+    const size_t off = NHWC ? (((size_t)n * H + h) * W + w) * C + c : (((size_t)n * C + c) * H + h) * W + w;
+    const float v = to_f32<E>(x[ok ? off : 0]);
+    return ok ? v : 0.f;
 }
 
-// grid.x = 4 * T: workgroup = (tile t, row xi of the transformed tile); threads stride over the channels.
-// KEEP channel rounds are held in registers between the two passes; longer rows are recomputed in the second pass.
-template <typename E, bool NHWC, int KEEP>
+__device__ __forceinline__ int8_t code_of(float v, float scale) { return (int8_t)(int)rintf(__fmul_rn(v, scale)); }
+
+// The activation transform defined in the header of this file.  grid.x = 4 * T: a workgroup owns tile t and row xi of the
+// transformed tile, i.e. the four rows V[xi*4 + nu][t][:] of the products' second operand, over all channels.  (B^T d)
+// first - one addition or subtraction of two window rows per column - then the column combination, again one operation per entry.
+//
+// Channel-last: a lane owns a channel (a wave's loads are 128 contiguous bytes), computes all four nu and keeps them in
+// registers for KEEP rounds of blockDim.x channels; rows longer than that are recomputed in the second pass.
+template <typename E, int KEEP>
 __global__ void __launch_bounds__(1024)
-input_transform_i8_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq, float* __restrict__ dV,
-                          int N, int C, int H, int W, int th, int tw, int T, int Cq) {
+input_transform_i8_nhwc_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq, float* __restrict__ dV,
+                               int N, int C, int H, int W, int th, int tw, int T, int Cq) {
     __shared__ float red[4 * kMaxWaves];
     const int t = blockIdx.x >> 2, xi = blockIdx.x & 3;
     const int n = t / (th * tw), rem = t - n * th * tw, ti = rem / tw, tj = rem - ti * tw;
@@ -149,27 +139,52 @@ input_transform_i8_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq, floa
     int ia, ib; bool add;
     bt_row(xi, ia, ib, add);
     const int nt = blockDim.x;
+    auto row = [&](int c, float (&v)[4]) {
+        float tt[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float a = load_x<E, true>(x, n, c, h0 + ia, w0 + j, C, H, W), b = load_x<E, true>(x, n, c, h0 + ib, w0 + j, C, H, W);
+            tt[j] = add ? __fadd_rn(a, b) : __fsub_rn(a, b);
+        }
+        v[0] = __fsub_rn(tt[0], tt[2]);
+        v[1] = __fadd_rn(tt[1], tt[2]);
+        v[2] = __fsub_rn(tt[2], tt[1]);
+        v[3] = __fsub_rn(tt[1], tt[3]);
+    };
     float kept[KEEP][4];
     float mx[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int r = 0; r < KEEP; ++r) {
-        const int c = threadIdx.x + r * nt;
-        if (c < Cq) {
-            activation_row<E, NHWC>(x, n, c, C, H, W, h0, w0, ia, ib, add, kept[r]);
+    for (int r = 0; r < KEEP; ++r) row(threadIdx.x + r * nt, kept[r]);      // channels >= C give zeros
 #pragma unroll
-            for (int nu = 0; nu < 4; ++nu) mx[nu] = fmaxf(mx[nu], fabsf(kept[r][nu]));
-        }
-    }
+    for (int r = 0; r < KEEP; ++r)
+#pragma unroll
+        for (int nu = 0; nu < 4; ++nu) mx[nu] = fmaxf(mx[nu], fabsf(kept[r][nu]));
     for (int c = threadIdx.x + KEEP * nt; c < Cq; c += nt) {
         float v[4];
-        activation_row<E, NHWC>(x, n, c, C, H, W, h0, w0, ia, ib, add, v);
+        row(c, v);
 #pragma unroll
         for (int nu = 0; nu < 4; ++nu) mx[nu] = fmaxf(mx[nu], fabsf(v[nu]));
     }
-    block_max<4>(mx, red);
+    // maximum over the workgroup: lanes of a wave, then the waves through LDS (unused wave slots hold 0, a neutral value)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x < 4 * kMaxWaves) red[threadIdx.x] = 0.f;
+    __syncthreads();
+#pragma unroll
+    for (int nu = 0; nu < 4; ++nu) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) mx[nu] = fmaxf(mx[nu], __shfl_xor(mx[nu], off, 64));
+        if (lane == 0) red[nu * kMaxWaves + wave] = mx[nu];
+    }
+    __syncthreads();
     float sc[4];
 #pragma unroll
-    for (int nu = 0; nu < 4; ++nu) sc[nu] = mx[nu] > 0.f ? __fdiv_rn(127.f, mx[nu]) : 0.f;
+    for (int nu = 0; nu < 4; ++nu) {
+        float m = 0.f;
+#pragma unroll
+        for (int w = 0; w < kMaxWaves; ++w) m = fmaxf(m, red[nu * kMaxWaves + w]);
+        mx[nu] = m;
+        sc[nu] = m > 0.f ? __fdiv_rn(127.f, m) : 0.f;
+    }
     int8_t* dst = Vq + ((size_t)(xi * 4) * T + t) * Cq;
     const size_t plane = (size_t)T * Cq;
 #pragma unroll
@@ -177,14 +192,14 @@ input_transform_i8_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq, floa
         const int c = threadIdx.x + r * nt;
         if (c < Cq) {
 #pragma unroll
-            for (int nu = 0; nu < 4; ++nu) dst[nu * plane + c] = (int8_t)(int)rintf(__fmul_rn(kept[r][nu], sc[nu]));
+            for (int nu = 0; nu < 4; ++nu) dst[nu * plane + c] = code_of(kept[r][nu], sc[nu]);
         }
     }
     for (int c = threadIdx.x + KEEP * nt; c < Cq; c += nt) {
         float v[4];
-        activation_row<E, NHWC>(x, n, c, C, H, W, h0, w0, ia, ib, add, v);
+        row(c, v);
 #pragma unroll
-        for (int nu = 0; nu < 4; ++nu) dst[nu * plane + c] = (int8_t)(int)rintf(__fmul_rn(v[nu], sc[nu]));
+        for (int nu = 0; nu < 4; ++nu) dst[nu * plane + c] = code_of(v[nu], sc[nu]);
     }
     if (threadIdx.x < 4) {
         float m = 0.f;
@@ -192,6 +207,62 @@ input_transform_i8_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq, floa
         for (int nu = 0; nu < 4; ++nu) m = threadIdx.x == nu ? mx[nu] : m;
         dV[(size_t)(xi * 4 + threadIdx.x) * T + t] = __fdiv_rn(m, 127.f);
     }
+}
+
+// NCHW: the only contiguity is along the image row, so four adjacent lanes own the four window columns of one channel (a
+// wave's load touches 16 channel planes instead of 64) and exchange their entries of B^T d for the column combination;
+// lane 4q + nu ends up with V[xi*4 + nu] of its channel.  A round covers blockDim.x / 4 channels.
+template <typename E, int KEEP>
+__global__ void __launch_bounds__(1024)
+input_transform_i8_nchw_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq, float* __restrict__ dV,
+                               int N, int C, int H, int W, int th, int tw, int T, int Cq) {
+    __shared__ float red[4 * kMaxWaves];
+    const int t = blockIdx.x >> 2, xi = blockIdx.x & 3;
+    const int n = t / (th * tw), rem = t - n * th * tw, ti = rem / tw, tj = rem - ti * tw;
+    const int h0 = 2 * ti - 1, w0 = 2 * tj - 1;
+    int ia, ib; bool add;
+    bt_row(xi, ia, ib, add);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nu = threadIdx.x & 3, cl = threadIdx.x >> 2, cpr = blockDim.x >> 2;       // channels per round
+    // sources of this lane's column combination inside its quad: nu 0: t0 - t2, 1: t1 + t2, 2: t2 - t1, 3: t1 - t3
+    const int qa = (lane & ~3) + (nu == 0 ? 0 : (nu == 2 ? 2 : 1));
+    const int qb = (lane & ~3) + (nu == 0 ? 2 : (nu == 1 ? 2 : (nu == 2 ? 1 : 3)));
+    auto entry = [&](int c) -> float {
+        const float a = load_x<E, false>(x, n, c, h0 + ia, w0 + nu, C, H, W), b = load_x<E, false>(x, n, c, h0 + ib, w0 + nu, C, H, W);
+        const float tt = add ? __fadd_rn(a, b) : __fsub_rn(a, b);
+        const float ta = __shfl(tt, qa, 64), tb = __shfl(tt, qb, 64);
+        return nu == 1 ? __fadd_rn(ta, tb) : __fsub_rn(ta, tb);
+    };
+    float kept[KEEP];
+    float mx = 0.f;
+#pragma unroll
+    for (int r = 0; r < KEEP; ++r) kept[r] = entry(cl + r * cpr);
+#pragma unroll
+    for (int r = 0; r < KEEP; ++r) mx = fmaxf(mx, fabsf(kept[r]));
+    const int rounds = (Cq + cpr - 1) / cpr;                 // the same for every thread: the exchange inside entry() needs whole quads
+    for (int r = KEEP; r < rounds; ++r) mx = fmaxf(mx, fabsf(entry(cl + r * cpr)));
+    if (threadIdx.x < 4 * kMaxWaves) red[threadIdx.x] = 0.f;
+    __syncthreads();
+#pragma unroll
+    for (int off = 32; off >= 4; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));       // lanes with the same nu
+    if (lane < 4) red[lane * kMaxWaves + wave] = mx;
+    __syncthreads();
+    float m = 0.f;
+#pragma unroll
+    for (int w = 0; w < kMaxWaves; ++w) m = fmaxf(m, red[nu * kMaxWaves + w]);
+    const float sc = m > 0.f ? __fdiv_rn(127.f, m) : 0.f;
+    int8_t* dst = Vq + ((size_t)(xi * 4 + nu) * T + t) * Cq;
+#pragma unroll
+    for (int r = 0; r < KEEP; ++r) {
+        const int c = cl + r * cpr;
+        if (c < Cq) dst[c] = code_of(kept[r], sc);
+    }
+    for (int r = KEEP; r < rounds; ++r) {
+        const int c = cl + r * cpr;
+        const float v = entry(c);
+        if (c < Cq) dst[c] = code_of(v, sc);
+    }
+    if (threadIdx.x < 4) dV[(size_t)(xi * 4 + nu) * T + t] = __fdiv_rn(m, 127.f);
 }
 
 }  // namespace
@@ -205,17 +276,36 @@ hipError_t launch_filter_quant_i8(const void* w, void* Uq, float* dU, int K, int
     });
 }
 
+template <typename E, int KEEP>
+static void launch_i8_nhwc(const void* x, void* Vq, float* dV, const Geom& g, int Cq, int threads, hipStream_t s) {
+    hipLaunchKernelGGL((input_transform_i8_nhwc_kernel<E, KEEP>), dim3((unsigned)(4 * g.T)), dim3((unsigned)threads), 0, s,
+                       (const E*)x, (int8_t*)Vq, dV, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, Cq);
+}
+template <typename E, int KEEP>
+static void launch_i8_nchw(const void* x, void* Vq, float* dV, const Geom& g, int Cq, int threads, hipStream_t s) {
+    hipLaunchKernelGGL((input_transform_i8_nchw_kernel<E, KEEP>), dim3((unsigned)(4 * g.T)), dim3((unsigned)threads), 0, s,
+                       (const E*)x, (int8_t*)Vq, dV, g.N, g.C, g.H, g.W, g.th, g.tw, g.T, Cq);
+}
+
 hipError_t launch_input_transform_i8(const void* x, void* Vq, float* dV, const Geom& g, int Cq, int dt, bool nhwc, hipStream_t s) {
     if (g.m != 2 || Cq < g.C || Cq % 16 != 0 || (long long)g.T * 4 > 0x7fffffffLL) return hipErrorInvalidValue;
-    int threads = round_up(Cq, 64);
-    if (threads > 1024) threads = 1024;
-    const dim3 grid((unsigned)(4 * g.T)), block((unsigned)threads);
+    // a round = the channels one pass of the workgroup covers (a lane per channel, or per channel and window column); the
+    // workgroup is sized so that its rounds are full, and rows of up to 3 (12) rounds stay in registers between the passes
+    const int per_round_max = nhwc ? 1024 : 256;
+    const int rounds = (Cq + per_round_max - 1) / per_round_max;
+    const int per_round = round_up((Cq + rounds - 1) / rounds, nhwc ? 64 : 16);
+    const int threads = nhwc ? per_round : 4 * per_round;
     return with_dtype(dt, [&](auto* tag) {
         using E = std::remove_pointer_t<decltype(tag)>;
-        if (nhwc) hipLaunchKernelGGL((input_transform_i8_kernel<E, true, 3>), grid, block, 0, s, (const E*)x, (int8_t*)Vq, dV,
-                                     g.N, g.C, g.H, g.W, g.th, g.tw, g.T, Cq);
-        else      hipLaunchKernelGGL((input_transform_i8_kernel<E, false, 3>), grid, block, 0, s, (const E*)x, (int8_t*)Vq, dV,
-                                     g.N, g.C, g.H, g.W, g.th, g.tw, g.T, Cq);
+        if (nhwc) {
+            if (rounds <= 1) launch_i8_nhwc<E, 1>(x, Vq, dV, g, Cq, threads, s);
+            else if (rounds == 2) launch_i8_nhwc<E, 2>(x, Vq, dV, g, Cq, threads, s);
+            else launch_i8_nhwc<E, 3>(x, Vq, dV, g, Cq, threads, s);
+        } else {
+            if (rounds <= 3) launch_i8_nchw<E, 3>(x, Vq, dV, g, Cq, threads, s);
+            else if (rounds <= 6) launch_i8_nchw<E, 6>(x, Vq, dV, g, Cq, threads, s);
+            else launch_i8_nchw<E, 12>(x, Vq, dV, g, Cq, threads, s);
+        }
         return hipGetLastError();
     });
 }
