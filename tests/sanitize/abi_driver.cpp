@@ -31,6 +31,10 @@ int main() {
     CHECK(wino_igemm_workspace_bytes(1, 40, 9, 9, 64, 5, 2, WINO_F16, WINO_NCHW), 0);
     CHECK(wino_fp8_filter_bytes(64, 40, 3), 9LL * 64 * 48 + 48);
     CHECK(wino_fp8_workspace_bytes(1, 40, 9, 9, 64, 3, 1) > 0, 1);
+    CHECK(wino_i8_filter_bytes(64, 40), 16LL * 64 * 48 + 16LL * 64 * 4);
+    CHECK(wino_i8_filter_bytes(64, 70000), 0);
+    CHECK(wino_i8_workspace_bytes(1, 40, 8, 8, 64), 16LL * 16 * 48 + 16LL * 16 * 4 + 16LL * 64 * 16 * 4);
+    CHECK(wino_i8_workspace_bytes(1, 40, 0, 8, 64), 0);
     CHECK(wino_groupnorm_stats_bytes(2, 32) > 0, 1);
     CHECK(wino_groupnorm_stats_bytes(0, 32), 0);
     CHECK(wino_static_scratch_bytes(), 64LL << 20);
@@ -75,6 +79,13 @@ int main() {
     CHECK(wino_igemm_conv2d(a, a, nullptr, b, 1, 8, 8, 8, 8, 3, 1, WINO_F16, WINO_NCHW, nullptr, 0, nullptr), WINO_ERR_WORKSPACE);
     CHECK(wino_fp8_filter_quantize(a, b, 8, 8, 3, WINO_F16, -1.f, nullptr), WINO_ERR_DIM);
     CHECK(wino_fp8_conv2d(a, a, nullptr, b, 1, 8, 8, 8, 8, 3, 1, WINO_F16, WINO_NCHW, 0.f, 1.f, nullptr, a, 1 << 20, nullptr), WINO_ERR_DIM);
+    CHECK(wino_i8_filter_transform(a, nullptr, 8, 8, WINO_F16, nullptr), WINO_ERR_NULL);
+    CHECK(wino_i8_filter_transform(a, b, 8, 70000, WINO_F16, nullptr), WINO_ERR_DIM);
+    CHECK(wino_i8_input_transform(a, b, reinterpret_cast<float*>(b), 1, 8, 8, 8, 7, WINO_NCHW, nullptr), WINO_ERR_DTYPE);
+    CHECK(wino_i8_batched_gemm(a, reinterpret_cast<const float*>(a), a, reinterpret_cast<const float*>(a), reinterpret_cast<float*>(b), 8, 8, 8, 9, nullptr), WINO_ERR_VARIANT);
+    CHECK(wino_i8_conv2d(a, a, nullptr, b, 1, 8, 8, 8, 8, WINO_F16, WINO_NCHW, nullptr, 0, nullptr), WINO_ERR_WORKSPACE);
+    CHECK(wino_i8_conv2d(a, a, nullptr, a, 1, 8, 8, 8, 8, WINO_F16, WINO_NCHW, b, 1 << 20, nullptr), WINO_ERR_ALIAS);
+    CHECK(wino_i8_conv2d(a, a, nullptr, b, 1, 8, 8, 8, 8, WINO_F16, 5, b, 1 << 20, nullptr), WINO_ERR_LAYOUT);
     std::printf("abi sanitizer run ok\n");
     return 0;
 }
