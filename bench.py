@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--layer", default=HEADLINE, help="headline layer, a name from paper_2412_05781_amd.synth.LAYERS")
     ap.add_argument("--layers", default="all", help="'all' (the 18 layers of the workload groups), 'none', or a comma-separated list")
-    ap.add_argument("--variant", default="auto", choices=["auto", "f2", "f4", "fused_f2"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "f2", "f4", "fused_f2", "fused_f4"])
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip every oracle run (baseline timing and parity figures)")
     ap.add_argument("--no-rotate", action="store_true", help="reuse one buffer set (cache-warm x, U, y)")
     return ap.parse_args()
@@ -67,7 +67,7 @@ class LayerRun:
         self.dt = B.DTYPE_OF[self.tdt]
         self.esz = 2 if layer.dtype == "f16" else 4
         self.variant = B.wino_resolve_variant(N, C, H, W, K, self.dt, want)
-        assert self.variant in (B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2, B.WINO_DIRECT), self.variant
+        assert self.variant in (B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2, B.WINO_FUSED_F4, B.WINO_DIRECT), self.variant
         if self.variant != B.WINO_DIRECT:            # the direct variant is only timed as a whole call (step)
             self.alpha, self.Cp, self.T = B.wino_transformed_dims(N, C, H, W, K, self.variant)
             self.a2 = self.alpha * self.alpha
@@ -116,16 +116,18 @@ class LayerRun:
         torch, B, L = self.torch, self.B, self.layer
         N, C, K, H, W = L.N, L.C, L.K, L.H, L.W
         n, v = self.nsets, self.variant
-        per_set = self.a2 * self.T * self.Cp * self.esz + (0 if v == B.WINO_FUSED_F2 else self.a2 * K * self.T * 4)
+        fused = v in (B.WINO_FUSED_F2, B.WINO_FUSED_F4)
+        per_set = self.a2 * self.T * self.Cp * self.esz + (0 if fused else self.a2 * K * self.T * 4)
         nv = max(2, min(n, (8 << 30) // max(1, per_set)))          # V / M sets: rotate, within 8 GB
         Vb = [torch.empty((self.a2, self.T, self.Cp), dtype=self.tdt, device=self.dev) for _ in range(nv)]
         for i in range(nv):
             B.wino_input_transform(self.sets[i % n][0], v, out=Vb[i])
         out = {"input_transform": graph_time(lambda i: B.wino_input_transform(self.sets[i % n][0], v, out=Vb[i % nv]), 2 * n)}
         U = lambda i: self.sets[i % n][1].buf.view(self.tdt)
-        if v == B.WINO_FUSED_F2:
+        if fused:
             out["fused_gemm_output"] = graph_time(
-                lambda i: B.wino_fused_gemm_output(U(i), Vb[i % nv], self.bd, N, C, H, W, K, out=self.sets[i % n][2]), 2 * n)
+                lambda i: B.wino_fused_gemm_output(U(i), Vb[i % nv], self.bd, N, C, H, W, K, out=self.sets[i % n][2],
+                                                   m=2 if v == B.WINO_FUSED_F2 else 4), 2 * n)
             return out, "fused_gemm_output"
         Mb = [torch.empty((self.a2, K, self.T), dtype=torch.float32, device=self.dev) for _ in range(nv)]
         for i in range(nv):
@@ -147,7 +149,7 @@ class LayerRun:
         t = stages[main_kernel]
         t_mfma, t_hbm = flops / (PEAK_TFLOPS[L.dtype] * 1e12), kbytes[main_kernel] / (PEAK_HBM_GBS * 1e9)
         mfma_frac, hbm_frac = t_mfma / t, t_hbm / t
-        rec = {"name": L.name, "variant": {B.WINO_F2: "F2", B.WINO_F4: "F4", B.WINO_FUSED_F2: "FUSED_F2"}[self.variant],
+        rec = {"name": L.name, "variant": {B.WINO_F2: "F2", B.WINO_F4: "F4", B.WINO_FUSED_F2: "FUSED_F2", B.WINO_FUSED_F4: "FUSED_F4"}[self.variant],
                "us": t_layer * 1e6, "tflops": L.direct_flops / t_layer / 1e12,
                "kernel_us": {k: v * 1e6 for k, v in stages.items()},
                "kernel_GBs": {k: kbytes[k] / v / 1e9 for k, v in stages.items()},
@@ -175,7 +177,7 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    want = {"auto": B.WINO_AUTO, "f2": B.WINO_F2, "f4": B.WINO_F4, "fused_f2": B.WINO_FUSED_F2}[args.variant]
+    want = {"auto": B.WINO_AUTO, "f2": B.WINO_F2, "f4": B.WINO_F4, "fused_f2": B.WINO_FUSED_F2, "fused_f4": B.WINO_FUSED_F4}[args.variant]
     oracle = None
     if not args.no_cpu_baseline:
         import oracle                      # test infrastructure: only this leg of the bench touches it

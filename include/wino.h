@@ -65,7 +65,7 @@ typedef enum wino_dtype { WINO_F32 = 0, WINO_F16 = 1, WINO_BF16 = 2 } wino_dtype
 /*
  * WINO_F2 / WINO_F4: Winograd F(2x2,3x3) / F(4x4,3x3), three kernels (activation
  * transform, batched MFMA GEMM, output transform).  WINO_AUTO: the library picks F2,
- * F4 or the fused F2 variant per shape and storage type (wino_resolve_variant).  WINO_DIRECT: direct correlation; a filter prepared with it
+ * F4 or one of the fused variants per shape and storage type (wino_resolve_variant).  WINO_DIRECT: direct correlation; a filter prepared with it
  * (wino_filter_transform) makes wino_conv2d / wino_conv2d_ex run the implicit-GEMM
  * MFMA kernel described at the end of this header (no transformed tensors, output
  * rounding only; faster than the Winograd path where there are few channels and
@@ -77,8 +77,12 @@ typedef enum wino_dtype { WINO_F32 = 0, WINO_F16 = 1, WINO_BF16 = 2 } wino_dtype
  * accumulators and adds it at once, with its +-1 coefficients, into four output accumulators; the
  * product M is never stored (the paper's locality argument: dependent steps stay on chip).  Same U and
  * V as WINO_F2, same error (~5e-4 for fp16); workspace = V only.
+ * WINO_FUSED_F4: the same for F(4x4,3x3), two-byte storage types only (WINO_ERR_DTYPE for fp32).  An output tile has 16 values,
+ * so step (iii) is folded in one dimension at a time: four row sums per row of the transformed tile, added into the 16 output
+ * accumulators when the row is complete.  Same U and V as WINO_F4, same error (~3e-3 for fp16); workspace = V only.  Meant for
+ * large images, where the unfused path is bound by writing and re-reading the product.
  */
-typedef enum wino_variant { WINO_AUTO = 0, WINO_DIRECT = 1, WINO_F2 = 2, WINO_F4 = 4, WINO_FUSED_F2 = 12 } wino_variant;
+typedef enum wino_variant { WINO_AUTO = 0, WINO_DIRECT = 1, WINO_F2 = 2, WINO_F4 = 4, WINO_FUSED_F2 = 12, WINO_FUSED_F4 = 14 } wino_variant;
 
 /* Layout of x and y only (w is always [K][C][3][3]); NHWC = x[N][H][W][C], y[N][H][W][K]. */
 typedef enum wino_layout { WINO_NCHW = 0, WINO_NHWC = 1 } wino_layout;
@@ -89,16 +93,17 @@ typedef struct wino_filter {
     void *data;      /* device, U[alpha^2][K][Cp] in `dtype`, Cp = C rounded up to 8 */
     int K, C;
     int dtype;       /* wino_dtype   */
-    int variant;     /* wino_variant, resolved: WINO_F2, WINO_F4, WINO_FUSED_F2 or WINO_DIRECT */
+    int variant;     /* wino_variant, resolved: WINO_F2, WINO_F4, WINO_FUSED_F2, WINO_FUSED_F4 or WINO_DIRECT */
 } wino_filter;
 
 int wino_version(void);                         /* major*10000 + minor*100 + patch */
 const char *wino_status_string(int status);     /* static string, never NULL       */
 
-/* WINO_AUTO -> WINO_F2, WINO_F4 or WINO_FUSED_F2 for this shape and storage type, by measured speed within the
- * type's error bound (F4 from 64 tiles on; fp32 with C > 640 and bf16 stay on F(2x2); the fused variant where it
- * measured faster: 2-byte storage, K >= 32, and either F(2x2) with >= 4096 tiles or at most 128x128 channel pairs
- * with >= 65536 F(2x2) tiles).  Other values are returned as they are; -1 on bad arguments. */
+/* WINO_AUTO -> WINO_F2, WINO_F4, WINO_FUSED_F2 or WINO_FUSED_F4 for this shape and storage type, by measured speed within
+ * the type's error bound (F4 from 64 tiles on; fp32 with C > 640 and bf16 stay on F(2x2); the fused variants where they
+ * measured faster: 2-byte storage, K >= 32, and F(2x2) with >= 4096 tiles, or F(4x4) with >= 16384 tiles and at most 256
+ * input and output channels).  Other values are returned as they are; -1 on bad arguments (a variant that does not exist
+ * for the storage type included). */
 int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int variant);
 
 /* A Winograd variant or WINO_DIRECT, whichever was measured faster for 3x3 / stride 1 on shapes like this one
@@ -194,6 +199,12 @@ int wino_output_transform(const float *M, const float *bias, void *y, int N, int
  */
 int wino_fused_gemm_output(const void *U, const void *V, const float *bias, void *y,
                            int N, int C, int H, int W, int K, int dtype, int layout, int block_shape, void *stream);
+
+/* The same for F(4x4,3x3), the second launch of WINO_FUSED_F4: U[36][K][Cp], V[36][T][Cp] -> y, two-byte `dtype` only.
+ * block_shape: -1 = the library's choice, 0 = 64x64 (eight waves), 1 = 32x64 (four waves); reduction lengths that are
+ * not a multiple of 64 always run the 32x64 block. */
+int wino_fused_f4_gemm_output(const void *U, const void *V, const float *bias, void *y,
+                              int N, int C, int H, int W, int K, int dtype, int layout, int block_shape, void *stream);
 
 /*
  * wino_batched_gemm with a named block shape instead of the library's choice, so that every instantiation

@@ -20,7 +20,7 @@ WINO_OK = 0
 WINO_ERR_NULL, WINO_ERR_DIM, WINO_ERR_DTYPE, WINO_ERR_VARIANT = 1, 2, 3, 4
 WINO_ERR_ALIGN, WINO_ERR_WORKSPACE, WINO_ERR_ALIAS, WINO_ERR_HIP, WINO_ERR_LAYOUT, WINO_ERR_SCRATCH = 5, 6, 7, 8, 9, 10
 WINO_F32, WINO_F16, WINO_BF16 = 0, 1, 2
-WINO_AUTO, WINO_DIRECT, WINO_F2, WINO_F4, WINO_FUSED_F2 = 0, 1, 2, 4, 12
+WINO_AUTO, WINO_DIRECT, WINO_F2, WINO_F4, WINO_FUSED_F2, WINO_FUSED_F4 = 0, 1, 2, 4, 12, 14
 WINO_NCHW, WINO_NHWC = 0, 1
 
 DTYPE_OF = {torch.float32: WINO_F32, torch.float16: WINO_F16, torch.bfloat16: WINO_BF16}
@@ -36,7 +36,7 @@ EXPORTS = [
     "wino_fp8_filter_bytes", "wino_fp8_filter_quantize", "wino_fp8_workspace_bytes", "wino_fp8_conv2d",
     "wino_fused_gemm_output", "wino_batched_gemm_shape", "wino_static_scratch_bytes", "wino_conv2d_static",
     "wino_i8_filter_bytes", "wino_i8_filter_transform", "wino_i8_workspace_bytes", "wino_i8_conv2d",
-    "wino_i8_input_transform", "wino_i8_batched_gemm",
+    "wino_i8_input_transform", "wino_i8_batched_gemm", "wino_fused_f4_gemm_output",
 ]
 
 
@@ -94,6 +94,8 @@ def lib() -> ctypes.CDLL:
         L.wino_batched_gemm_shape.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp]
         L.wino_fused_gemm_output.restype = i
         L.wino_fused_gemm_output.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, vp]
+        L.wino_fused_f4_gemm_output.restype = i
+        L.wino_fused_f4_gemm_output.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, vp]
         L.wino_output_transform.restype = i
         L.wino_output_transform.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.wino_direct_conv2d.restype = i
@@ -309,12 +311,16 @@ wino_batched_gemm_shape = wino_batched_gemm
 
 
 def wino_fused_gemm_output(U: torch.Tensor, V: torch.Tensor, bias, N: int, C: int, H: int, W: int, K: int,
-                           layout: int = WINO_NCHW, block_shape: int = -1, stream=None, out=None) -> torch.Tensor:
-    """U[16,K,Cp], V[16,T,Cp] (F(2x2,3x3)) -> y: steps (ii) and (iii) + bias in one kernel."""
+                           layout: int = WINO_NCHW, block_shape: int = -1, stream=None, out=None, m: int = 2) -> torch.Tensor:
+    """U[a2,K,Cp], V[a2,T,Cp] -> y: steps (ii) and (iii) + bias in one kernel; m = 2: F(2x2,3x3), a2 = 16 (wino_fused_gemm_output),
+    m = 4: F(4x4,3x3), a2 = 36 (wino_fused_f4_gemm_output)."""
     _dev(U, "U"); _dev(V, "V")
+    if m not in (2, 4):
+        raise WinoError(WINO_ERR_VARIANT, "m")
+    a2 = (m + 2) ** 2
     Cp = (C + 7) // 8 * 8
-    T = N * (-(-H // 2)) * (-(-W // 2))
-    if U.numel() < 16 * K * Cp or V.numel() < 16 * T * Cp or U.dtype != V.dtype:
+    T = N * (-(-H // m)) * (-(-W // m))
+    if U.numel() < a2 * K * Cp or V.numel() < a2 * T * Cp or U.dtype != V.dtype:
         raise ValueError("U or V buffer too small for these dimensions")
     if layout not in (WINO_NCHW, WINO_NHWC):
         raise WinoError(WINO_ERR_LAYOUT, "layout")
@@ -323,8 +329,9 @@ def wino_fused_gemm_output(U: torch.Tensor, V: torch.Tensor, bias, N: int, C: in
         raise ValueError("y buffer too small or of the wrong dtype")
     if bias is not None and (bias.dtype != torch.float32 or bias.numel() != K or not bias.is_cuda):
         raise ValueError("bias must be a GPU fp32 tensor of K elements")
-    _check(lib().wino_fused_gemm_output(_ptr(U), _ptr(V), _ptr(bias), _ptr(y), N, C, H, W, K, DTYPE_OF[U.dtype], layout,
-                                        int(block_shape), _stream(stream)), "wino_fused_gemm_output")
+    fn = lib().wino_fused_gemm_output if m == 2 else lib().wino_fused_f4_gemm_output
+    _check(fn(_ptr(U), _ptr(V), _ptr(bias), _ptr(y), N, C, H, W, K, DTYPE_OF[U.dtype], layout, int(block_shape), _stream(stream)),
+           "wino_fused_gemm_output" if m == 2 else "wino_fused_f4_gemm_output")
     return y
 
 
@@ -659,7 +666,7 @@ def conv2d_fused(x, w, bias=None, variant: int = WINO_AUTO, layout: int = WINO_N
     y = torch.empty(_act_shape(N, K, H, W, layout), dtype=x.dtype, device=x.device)
     v = (wino_recommend_variant(N, C, H, W, K, DTYPE_OF[x.dtype]) if variant == WINO_AUTO
          else wino_resolve_variant(N, C, H, W, K, DTYPE_OF[x.dtype], variant))
-    if v not in (WINO_F2, WINO_F4, WINO_FUSED_F2, WINO_DIRECT):
+    if v not in (WINO_F2, WINO_F4, WINO_FUSED_F2, WINO_FUSED_F4, WINO_DIRECT):
         raise WinoError(WINO_ERR_VARIANT, "conv2d_fused")
     stats = wino_groupnorm_stats(x, gn_groups, eps, layout) if gn_gamma is not None else None
     w_t = wino_filter_transform(w, v)

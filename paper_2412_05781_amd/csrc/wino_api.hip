@@ -16,9 +16,12 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool dtype_ok(int d) { return d == WINO_F32 || d == WINO_F16 || d == WINO_BF16; }
 inline size_t esize(int d) { return d == WINO_F32 ? 4 : 2; }
-inline bool wino_variant_ok(int v) { return v == WINO_F2 || v == WINO_F4 || v == WINO_FUSED_F2; }
-// output tile edge m of a Winograd variant (the fused variant is F(2x2,3x3) with steps (ii) and (iii) in one kernel)
-inline int tile_edge(int v) { return v == WINO_F4 ? 4 : 2; }
+inline bool wino_variant_ok(int v) { return v == WINO_F2 || v == WINO_F4 || v == WINO_FUSED_F2 || v == WINO_FUSED_F4; }
+inline bool fused_variant(int v) { return v == WINO_FUSED_F2 || v == WINO_FUSED_F4; }
+// output tile edge m of a Winograd variant (the fused variants are F(2x2,3x3) / F(4x4,3x3) with steps (ii) and (iii) in one kernel)
+inline int tile_edge(int v) { return (v == WINO_F4 || v == WINO_FUSED_F4) ? 4 : 2; }
+// the fused F(4x4) kernel exists for the two-byte storage types only
+inline bool variant_dtype_ok(int v, int d) { return !(v == WINO_FUSED_F4 && d == WINO_F32); }
 
 // products that must fit: element counts as size_t and tile counts as int
 bool dims_ok(int N, int C, int H, int W, int K, int m) {
@@ -69,7 +72,7 @@ Workspace workspace_layout(const Geom& g, int dtype, int variant) {
     Workspace ws;
     const size_t a2 = (size_t)g.alpha * g.alpha;
     ws.v_bytes = align_up(a2 * (size_t)g.T * g.Cp * esize(dtype));
-    if (variant == WINO_FUSED_F2) { ws.m_bytes = 0; ws.total = ws.v_bytes; return ws; }   // the product never leaves the registers
+    if (fused_variant(variant)) { ws.m_bytes = 0; ws.total = ws.v_bytes; return ws; }   // the product never leaves the registers
     // the product, times the number of partial copies the GEMM stage writes for this shape (the
     // policy depends on the operand order only through the block shape; take the larger of the two)
     const int sp_a = gemm_split(g.K, g.T, g.Cp, (int)a2, dtype), sp_b = gemm_split(g.T, g.K, g.Cp, (int)a2, dtype);
@@ -87,6 +90,8 @@ int run_chain(const void* x, const wino_filter* w_t, const float* bias, void* y,
     if (launch_input_transform(x, V, g, dt, nhwc, pre, s) != hipSuccess) return WINO_ERR_HIP;
     if (w_t->variant == WINO_FUSED_F2)
         return launch_fused_gemm_output(w_t->data, V, bias, y, g, dt, nhwc, post, -1, s) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+    if (w_t->variant == WINO_FUSED_F4)
+        return launch_fused4_gemm_output(w_t->data, V, bias, y, g, dt, nhwc, post, -1, s) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
     // channel-last: operands swapped, so the product comes out as M[alpha^2][T][K], k contiguous
     const int a2 = g.alpha * g.alpha;
     const int nsplit = nhwc ? gemm_split(g.T, g.K, g.Cp, a2, dt) : gemm_split(g.K, g.T, g.Cp, a2, dt);
@@ -107,6 +112,7 @@ int check_conv_args(const void* x, const wino_filter* w_t, const float* bias, co
         if (!igemm_dims_ok(N, C, H, W, K, 3, 1)) return WINO_ERR_DIM;
     } else {
         if (!wino_variant_ok(w_t->variant)) return WINO_ERR_VARIANT;
+        if (!variant_dtype_ok(w_t->variant, w_t->dtype)) return WINO_ERR_DTYPE;
         if (!dims_ok(N, C, H, W, K, tile_edge(w_t->variant))) return WINO_ERR_DIM;
     }
     if (w_t->K != K || w_t->C != C) return WINO_ERR_DIM;
@@ -145,7 +151,7 @@ const char* wino_status_string(int status) {
 int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int variant) {
     if (!dtype_ok(dtype)) return -1;
     if (variant == WINO_DIRECT || wino_variant_ok(variant)) {
-        return dims_ok(N, C, H, W, K, tile_edge(variant)) ? variant : -1;
+        return (dims_ok(N, C, H, W, K, tile_edge(variant)) && variant_dtype_ok(variant, dtype)) ? variant : -1;
     }
     if (variant != WINO_AUTO) return -1;
     if (!dims_ok(N, C, H, W, K, 2) || !dims_ok(N, C, H, W, K, 4)) return -1;
@@ -158,13 +164,14 @@ int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int varia
     if (dtype == WINO_F32 && C > 640) pick = WINO_F2;
     // bfloat16 has 8 significant bits: F(4x4) would sit near 2.5e-2, F(2x2) near 4e-3
     if (dtype == WINO_BF16) pick = WINO_F2;
-    // The fused variant (steps (ii) and (iii) in one kernel, F(2x2)) where it measured faster with 2-byte storage:
-    // against the F(2x2) chain from 4096 tiles on (128x128 images at batch 2 and everything larger: 0.6-0.9x the time),
-    // against the F(4x4) chain only with at most 128 channels on 512x512 images and larger (0.9x).
+    // The fused variants (steps (ii) and (iii) in one kernel) where they measured faster with 2-byte storage.  F(2x2): against
+    // the F(2x2) chain from 4096 tiles on (128x128 images at batch 2 and everything larger: 0.6-0.9x the time).  F(4x4): against
+    // the F(4x4) chain from 16384 tiles on with at most 256 channels (256 channels at 512x512: 0.83x, 128 at 1024x1024: 0.66x;
+    // with 512 channels at 256x256 it is level, below that slower).
     const Geom g2 = make_geom(N, C, H, W, K, 2);
     if (dtype != WINO_F32 && K >= 32) {
         if (pick == WINO_F2 && g2.T >= 4096) pick = WINO_FUSED_F2;
-        if (pick == WINO_F4 && (long long)C * K <= 128LL * 128LL && g2.T >= 65536) pick = WINO_FUSED_F2;
+        if (pick == WINO_F4 && g4.T >= 16384 && C <= 256 && K <= 256) pick = WINO_FUSED_F4;
     }
     return pick;
 }
@@ -202,7 +209,7 @@ int wino_transformed_dims(int N, int C, int H, int W, int K, int variant, int* a
 
 size_t wino_filter_bytes(int K, int C, int dtype, int variant) {
     if (variant == WINO_DIRECT) return wino_igemm_filter_bytes(K, C, 3, dtype);
-    if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !dims_ok(1, C, 1, 1, K, tile_edge(variant))) return 0;
+    if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !variant_dtype_ok(variant, dtype) || !dims_ok(1, C, 1, 1, K, tile_edge(variant))) return 0;
     const size_t a = tile_edge(variant) + 2;
     return a * a * (size_t)K * (size_t)round_up(C, 8) * esize(dtype);
 }
@@ -210,7 +217,7 @@ size_t wino_filter_bytes(int K, int C, int dtype, int variant) {
 size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int dtype, int variant) {
     // the direct path: what the NCHW call needs (the channel-last call needs no more than that)
     if (variant == WINO_DIRECT) return wino_igemm_workspace_bytes(N, C, H, W, K, 3, 1, dtype, WINO_NCHW);
-    if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !dims_ok(N, C, H, W, K, tile_edge(variant))) return 0;
+    if (!dtype_ok(dtype) || !wino_variant_ok(variant) || !variant_dtype_ok(variant, dtype) || !dims_ok(N, C, H, W, K, tile_edge(variant))) return 0;
     return workspace_layout(make_geom(N, C, H, W, K, tile_edge(variant)), dtype, variant).total;
 }
 
@@ -225,6 +232,7 @@ int wino_filter_transform(const void* w, void* w_t_data, int K, int C, int dtype
         return WINO_OK;
     }
     if (!wino_variant_ok(variant)) return WINO_ERR_VARIANT;
+    if (!variant_dtype_ok(variant, dtype)) return WINO_ERR_DTYPE;
     if (!dims_ok(1, C, 1, 1, K, tile_edge(variant)) || K > 65535) return WINO_ERR_DIM;   // grid.y carries k
     if (!aligned16(w) || !aligned16(w_t_data)) return WINO_ERR_ALIGN;
     if (launch_filter_transform(w, w_t_data, K, C, round_up(C, 8), tile_edge(variant), dtype,
@@ -473,6 +481,19 @@ int wino_fused_gemm_output(const void* U, const void* V, const float* bias, void
     const Geom g = make_geom(N, C, H, W, K, 2);
     return launch_fused_gemm_output(U, V, bias, y, g, dtype, layout == WINO_NHWC, nullptr, block_shape,
                                     static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
+}
+
+int wino_fused_f4_gemm_output(const void* U, const void* V, const float* bias, void* y, int N, int C, int H, int W, int K,
+                              int dtype, int layout, int block_shape, void* stream) {
+    if (!U || !V || !y) return WINO_ERR_NULL;
+    if (dtype != WINO_F16 && dtype != WINO_BF16) return WINO_ERR_DTYPE;
+    if (layout != WINO_NCHW && layout != WINO_NHWC) return WINO_ERR_LAYOUT;
+    if (block_shape < -1 || block_shape > 1) return WINO_ERR_VARIANT;
+    if (!dims_ok(N, C, H, W, K, 4)) return WINO_ERR_DIM;
+    if (!aligned16(U) || !aligned16(V) || !aligned16(y) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u))) return WINO_ERR_ALIGN;
+    const Geom g = make_geom(N, C, H, W, K, 4);
+    return launch_fused4_gemm_output(U, V, bias, y, g, dtype, layout == WINO_NHWC, nullptr, block_shape,
+                                     static_cast<hipStream_t>(stream)) == hipSuccess ? WINO_OK : WINO_ERR_HIP;
 }
 
 int wino_direct_conv2d(const void* x, const void* w, const float* bias, void* y,

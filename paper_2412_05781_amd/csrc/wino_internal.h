@@ -143,6 +143,9 @@ hipError_t launch_output_transform(const void* M, const float* bias, void* y, co
 hipError_t launch_fused_gemm_output(const void* U, const void* V, const float* bias, void* y, const Geom& g, int dt, bool nhwc,
                                     const PostOp* post, int shape, hipStream_t s);
 int fused_pick_shape(int rows, int cols);
+// the same for F(4x4,3x3) (wino_fused_f4.hip), two-byte storage types; shape: -1 = chosen from the problem size, 0..1 = a named block shape
+hipError_t launch_fused4_gemm_output(const void* U, const void* V, const float* bias, void* y, const Geom& g, int dt, bool nhwc,
+                                     const PostOp* post, int shape, hipStream_t s);
 hipError_t launch_groupnorm_stats(const void* x, float* stats, int N, int C, int H, int W, int groups, float eps,
                                   int dt, bool nhwc, hipStream_t s);
 size_t groupnorm_stats_bytes(int N, int groups);

@@ -7,7 +7,7 @@ the table that the file of the same topic under ``profiles/`` records:
     python -m paper_2412_05781_amd.timing flavours       1x1 and stride-2 convolutions through the implicit GEMM
     python -m paper_2412_05781_amd.timing direct         3x3 stride 1: Winograd vs direct vs 8-bit direct
     python -m paper_2412_05781_amd.timing half-product   the opt-in fp16 intermediate product
-    python -m paper_2412_05781_amd.timing variants       every workload layer x {F(4x4), F(2x2), fused F(2x2)} x {NCHW, NHWC}
+    python -m paper_2412_05781_amd.timing variants       every workload layer x {F(4x4), F(2x2), fused F(2x2), fused F(4x4)} x {NCHW, NHWC}
     python -m paper_2412_05781_amd.timing int8           F(2x2) with 8-bit integer U and V against the fp16 call, stage by stage
 
 "framework" columns call the stock deep-learning framework's own operators on the same tensors, as context.
@@ -41,7 +41,7 @@ def _shape(N, C, H, W, layout):
 
 
 def _vname(v):
-    return {B.WINO_F2: "F2", B.WINO_F4: "F4", B.WINO_FUSED_F2: "fused-F2", B.WINO_DIRECT: "direct"}.get(v, str(v))
+    return {B.WINO_F2: "F2", B.WINO_F4: "F4", B.WINO_FUSED_F2: "fused-F2", B.WINO_FUSED_F4: "fused-F4", B.WINO_DIRECT: "direct"}.get(v, str(v))
 
 
 def _lname(layout):
@@ -169,10 +169,11 @@ def cmd_half_product(_):
 
 def cmd_variants(_):
     """Whole-call time (wino_conv2d_ex) of every synthetic layer (the workload groups and the paper's Table-1 shapes, in the
-    layer's own storage type) in each Winograd variant and both layouts; '*' marks what WINO_AUTO resolves to."""
-    tags = {B.WINO_F4: "F4", B.WINO_F2: "F2", B.WINO_FUSED_F2: "fused F2"}
+    layer's own storage type) in each Winograd variant and both layouts; '*' marks what WINO_AUTO resolves to.  The fused
+    F(4x4) variant exists for the two-byte storage types only ('-' for the fp32 layers)."""
+    tags = {B.WINO_F4: "F4", B.WINO_F2: "F2", B.WINO_FUSED_F2: "fused F2", B.WINO_FUSED_F4: "fused F4"}
     print(f"{'layer':18s} {'layout':5s} | " + " | ".join(f"{t + ' us':>11s}" for t in tags.values()) +
-          " |  AUTO TF/s | fused/F2  fused/F4  workspace MB (F4 / F2 / fused)")
+          " |  AUTO TF/s | fusedF2/F2 fusedF4/F4  workspace MB (F4 / F2 / fused F2 / fused F4)")
     for name, L in synth.LAYERS.items():
         N, C, K, H, W = L.N, L.C, L.K, L.H, L.W
         tdt = synth.TORCH_DTYPE[L.dtype]
@@ -182,6 +183,8 @@ def cmd_variants(_):
         for layout in (B.WINO_NCHW, B.WINO_NHWC):
             t = {}
             for v in tags:
+                if B.wino_resolve_variant(N, C, H, W, K, dt, v) != v:
+                    continue
                 n = _nsets((N * C * H * W + N * K * H * W) * e + B.wino_filter_bytes(K, C, dt, v), hi=24)
                 sets = [(torch.randn(_shape(N, C, H, W, layout), device=DEV).to(tdt), B.wino_filter_transform(wd, v),
                          torch.empty(_shape(N, K, H, W, layout), device=DEV, dtype=tdt)) for _ in range(n)]
@@ -190,9 +193,11 @@ def cmd_variants(_):
                 del sets, ws
                 torch.cuda.empty_cache()
             wsb = [B.wino_workspace_bytes(N, C, H, W, K, dt, v) / 1e6 for v in tags]
-            print(f"{name:18s} {_lname(layout):5s} | " + " | ".join(f"{t[v]:10.1f}{'*' if v == auto else ' '}" for v in tags) +
-                  f" | {L.direct_flops / t[auto] / 1e6:10.1f} |   {t[B.WINO_FUSED_F2] / t[B.WINO_F2]:5.2f}     {t[B.WINO_FUSED_F2] / t[B.WINO_F4]:5.2f}"
-                  f"    {wsb[0]:7.1f} / {wsb[1]:7.1f} / {wsb[2]:7.1f}", flush=True)
+            cell = lambda v: (f"{t[v]:10.1f}{'*' if v == auto else ' '}" if v in t else f"{'-':>10s} ")
+            r4 = f"{t[B.WINO_FUSED_F4] / t[B.WINO_F4]:5.2f}" if B.WINO_FUSED_F4 in t else "    -"
+            print(f"{name:18s} {_lname(layout):5s} | " + " | ".join(cell(v) for v in tags) +
+                  f" | {L.direct_flops / t[auto] / 1e6:10.1f} |    {t[B.WINO_FUSED_F2] / t[B.WINO_F2]:5.2f}      {r4}"
+                  f"    {wsb[0]:7.1f} / {wsb[1]:7.1f} / {wsb[2]:7.1f} / {wsb[3]:7.1f}", flush=True)
 
 
 def cmd_int8(_):

@@ -69,10 +69,12 @@ def test_resolve_variant(L):
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
     # 8x8 images with wide channels: the transformed filter dominates the traffic, F2's is 2.25x smaller
     assert B.wino_resolve_variant(2, 1280, 8, 8, 1280, B.WINO_F16, B.WINO_AUTO) == B.WINO_F2
-    # the fused variant where it measured faster: <= 128 channels on >= 512x512 images (fp16), many-tile layers in bf16
-    assert B.wino_resolve_variant(1, 128, 1024, 1024, 128, B.WINO_F16, B.WINO_AUTO) == B.WINO_FUSED_F2
+    # the fused variants where they measured faster: F(4x4) from 16384 tiles on with <= 256 channels (fp16), many-tile layers in bf16
+    assert B.wino_resolve_variant(1, 128, 1024, 1024, 128, B.WINO_F16, B.WINO_AUTO) == B.WINO_FUSED_F4
     assert B.wino_resolve_variant(1, 128, 1024, 1024, 3, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
-    assert B.wino_resolve_variant(1, 256, 512, 512, 256, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
+    assert B.wino_resolve_variant(1, 256, 512, 512, 256, B.WINO_F16, B.WINO_AUTO) == B.WINO_FUSED_F4
+    assert B.wino_resolve_variant(1, 512, 256, 256, 512, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
+    assert B.wino_resolve_variant(1, 512, 512, 512, 512, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
     assert B.wino_resolve_variant(2, 320, 128, 128, 320, B.WINO_BF16, B.WINO_AUTO) == B.WINO_FUSED_F2
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_BF16, B.WINO_AUTO) == B.WINO_F2
     assert B.wino_recommend_variant(1, 128, 1024, 1024, 3, B.WINO_F16) == B.WINO_DIRECT      # few output channels, large image
@@ -172,6 +174,15 @@ def test_fused_variant_sizes_and_the_entry_points_added_for_it(L):
     assert B.wino_workspace_bytes(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_FUSED_F2) == 16 * 2048 * 320 * 2      # V only
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_FUSED_F2) == B.WINO_FUSED_F2
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, 13) == -1
+    # WINO_FUSED_F4: U and V of F(4x4), no stored product, two-byte storage types only
+    assert B.WINO_FUSED_F4 == 14
+    assert B.wino_filter_bytes(320, 320, B.WINO_F16, B.WINO_FUSED_F4) == B.wino_filter_bytes(320, 320, B.WINO_F16, B.WINO_F4)
+    assert B.wino_transformed_dims(2, 320, 64, 64, 320, B.WINO_FUSED_F4) == (6, 320, 512)
+    assert B.wino_workspace_bytes(2, 320, 64, 64, 320, B.WINO_BF16, B.WINO_FUSED_F4) == 36 * 512 * 320 * 2      # V only
+    assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_FUSED_F4) == B.WINO_FUSED_F4
+    assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F32, B.WINO_FUSED_F4) == -1
+    assert B.wino_filter_bytes(320, 320, B.WINO_F32, B.WINO_FUSED_F4) == 0
+    assert B.wino_workspace_bytes(2, 320, 64, 64, 320, B.WINO_F32, B.WINO_FUSED_F4) == 0
     vp = ctypes.c_void_p
     a = vp(0x1000)
     # named block shapes out of range; null and misaligned pointers
@@ -184,6 +195,10 @@ def test_fused_variant_sizes_and_the_entry_points_added_for_it(L):
     assert L.wino_fused_gemm_output(a, None, None, a, 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_NULL
     assert L.wino_fused_gemm_output(a, a, None, a, 1, 8, 4, 4, 8, B.WINO_F16, 5, 0, None) == B.WINO_ERR_LAYOUT
     assert L.wino_fused_gemm_output(a, a, None, vp(0x1008), 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_ALIGN
+    assert L.wino_fused_f4_gemm_output(a, a, None, a, 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 2, None) == B.WINO_ERR_VARIANT
+    assert L.wino_fused_f4_gemm_output(a, a, None, a, 1, 8, 4, 4, 8, B.WINO_F32, B.WINO_NCHW, 0, None) == B.WINO_ERR_DTYPE
+    assert L.wino_fused_f4_gemm_output(a, None, None, a, 1, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_NULL
+    assert L.wino_fused_f4_gemm_output(a, a, None, a, 1, 8, 4, 4, 8, B.WINO_BF16, 5, 0, None) == B.WINO_ERR_LAYOUT
     assert L.wino_fused_gemm_output(a, a, None, a, 0, 8, 4, 4, 8, B.WINO_F16, B.WINO_NCHW, 0, None) == B.WINO_ERR_DIM
     # the scratch-free entry point: limit, and the same validation as wino_conv2d_ex
     assert B.wino_static_scratch_bytes() == 64 << 20

@@ -112,3 +112,79 @@ def test_stage_calls_that_need_a_stored_product_reject_the_fused_variant():
     with pytest.raises(B.WinoError) as e:
         B.wino_fused_gemm_output(U, U, None, 1, 8, 4, 4, 8, block_shape=7)
     assert e.value.status == B.WINO_ERR_VARIANT
+
+
+# ---- WINO_FUSED_F4: the same for F(4x4,3x3), two-byte storage types ---------------------------------------------------
+TOL4 = {"f16": 5e-3, "bf16": 4e-2}
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("shape", SHAPES + [(1, 64, 96, 40, 44), (2, 128, 70, 9, 64)])
+def test_f4_whole_path_small_shapes(shape, layout, dtype):
+    N, C, K, H, W = shape
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=7300 + sum(shape))
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+    y = B.conv2d(xd, w.to(DEV), b.to(DEV), B.WINO_FUSED_F4, layout=layout)
+    torch.cuda.synchronize()
+    pu.check(_nchw(y, layout), ref, TOL4[dtype], 4, dtype, what=(shape, layout, dtype), channels=C)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
+@pytest.mark.parametrize("block_shape", [0, 1])
+@pytest.mark.parametrize("shape", [(2, 5, 7, 5, 7), (1, 33, 65, 17, 30), (2, 136, 200, 16, 16), (1, 200, 150, 37, 41), (1, 72, 300, 21, 39),
+                                   (1, 64, 200, 30, 36), (2, 128, 320, 16, 32), (1, 192, 130, 64, 64)])
+def test_f4_every_block_shape(shape, block_shape, layout, dtype):
+    """The stage call with a named block shape on inputs with ragged rows and columns, a ragged last reduction stage (C not a
+    multiple of 64) and more than one block in both directions; against the oracle and against the unfused F(4x4) stages."""
+    N, C, K, H, W = shape
+    x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=7400 + sum(shape))
+    ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
+    xd = (x.permute(0, 2, 3, 1).contiguous() if layout == B.WINO_NHWC else x).to(DEV)
+    filt = B.wino_filter_transform(w.to(DEV), B.WINO_FUSED_F4)
+    assert filt.desc.variant == B.WINO_FUSED_F4
+    U = filt.buf.view(x.dtype)
+    V = B.wino_input_transform(xd, B.WINO_FUSED_F4, layout=layout)
+    y = B.wino_fused_gemm_output(U, V, b.to(DEV), N, C, H, W, K, layout=layout, block_shape=block_shape, m=4)
+    torch.cuda.synchronize()
+    pu.check(_nchw(y, layout), ref, TOL4[dtype], 4, dtype, what=(shape, block_shape, layout, dtype), channels=C)
+    # the unfused F(4x4) path on the same U and V adds the same products in fp32 in another order
+    y_chain = B.conv2d(xd, w.to(DEV), b.to(DEV), B.WINO_F4, layout=layout)
+    torch.cuda.synchronize()
+    d = (y.float() - y_chain.float()).abs().max().item()
+    assert d <= (2.0 ** -9 if dtype == "f16" else 2.0 ** -6) * max(1.0, y.float().abs().max().item())
+
+
+def test_f4_zero_input_no_bias_determinism_and_workspace():
+    x, w, b = synth.make_inputs(2, 40, 24, 10, 11, "f16", seed=5)
+    xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
+    y0 = B.conv2d(torch.zeros_like(xd), wd, bd, B.WINO_FUSED_F4)
+    torch.cuda.synchronize()
+    assert torch.equal(y0.float().cpu(), b.to(torch.float16).float().view(1, -1, 1, 1).expand(2, 24, 10, 11))
+    ref = oracle.conv2d_direct(_np(x), _np(w), None)
+    y = B.conv2d(xd, wd, None, B.WINO_FUSED_F4)
+    y_again = B.conv2d(xd, wd, None, B.WINO_FUSED_F4)
+    torch.cuda.synchronize()
+    pu.check(y.float().cpu().numpy().astype(np.float64), ref, 5e-3, 4, "f16")
+    assert torch.equal(y, y_again)
+    assert B.wino_workspace_bytes(2, 40, 10, 11, 24, B.WINO_F16, B.WINO_FUSED_F4) < B.wino_workspace_bytes(2, 40, 10, 11, 24, B.WINO_F16, B.WINO_F4)
+
+
+def test_f4_fused_is_for_two_byte_storage_only():
+    assert B.wino_resolve_variant(1, 8, 8, 8, 8, B.WINO_F32, B.WINO_FUSED_F4) == -1
+    assert B.wino_filter_bytes(8, 8, B.WINO_F32, B.WINO_FUSED_F4) == 0
+    assert B.wino_workspace_bytes(1, 8, 8, 8, 8, B.WINO_F32, B.WINO_FUSED_F4) == 0
+    w = torch.zeros(8, 8, 3, 3, device=DEV)
+    with pytest.raises(B.WinoError) as e:
+        B.wino_filter_transform(w, B.WINO_FUSED_F4)
+    assert e.value.status == B.WINO_ERR_VARIANT          # raised by the binding: wino_filter_bytes is 0 for this pair
+    U = torch.zeros(36 * 8 * 8, dtype=torch.float32, device=DEV)
+    with pytest.raises(B.WinoError) as e:
+        B.wino_fused_gemm_output(U, U, None, 1, 8, 4, 4, 8, m=4)
+    assert e.value.status == B.WINO_ERR_DTYPE
+    Uh = U.half()
+    with pytest.raises(B.WinoError) as e:
+        B.wino_fused_gemm_output(Uh, Uh, None, 1, 8, 4, 4, 8, block_shape=2, m=4)
+    assert e.value.status == B.WINO_ERR_VARIANT

@@ -164,7 +164,8 @@ FP16_BAND = {B.WINO_F2: (2.5e-4, 1.0e-3), B.WINO_F4: (1.5e-3, 4.5e-3), B.WINO_DI
 
 # ---- every full-size layer, whole tensor, element by element -------------------------------------------------------
 # Beside the variant the library picks for the layer (what bench.py times), the variants listed here are run on the
-# same oracle result: the fused variant everywhere (its block shapes differ from layer to layer), the other tile size
+# same oracle result: the fused variants everywhere (their block shapes differ from layer to layer; F(4x4) fused exists for the
+# two-byte types), the other tile size
 # on the largest workspaces (E4/F2: M alone is 2.1 GB, byte offsets pass 2^31) and the smallest images, the direct
 # variant on VAE- and UNet-sized layers.
 EXTRA_VARIANTS = {
@@ -172,8 +173,9 @@ EXTRA_VARIANTS = {
     "E2_vae": [B.WINO_DIRECT], "C6_unet": [B.WINO_DIRECT], "B_resblock": [B.WINO_F2, B.WINO_F4, B.WINO_DIRECT],
     "A_conv_in": [B.WINO_F2, B.WINO_F4, B.WINO_DIRECT], "D3_sdxl": [B.WINO_F2, B.WINO_F4], "C8_unet": [B.WINO_F4],
 }
-TILE_EDGE = {B.WINO_F2: 2, B.WINO_F4: 4, B.WINO_FUSED_F2: 2, B.WINO_DIRECT: 1}
+TILE_EDGE = {B.WINO_F2: 2, B.WINO_F4: 4, B.WINO_FUSED_F2: 2, B.WINO_FUSED_F4: 4, B.WINO_DIRECT: 1}
 FP16_BAND[B.WINO_FUSED_F2] = FP16_BAND[B.WINO_F2]
+FP16_BAND[B.WINO_FUSED_F4] = FP16_BAND[B.WINO_F4]
 
 
 @pytest.mark.parametrize("name", [l.name for l in synth.ALL_LAYERS])
@@ -188,8 +190,9 @@ def test_every_layer_whole_tensor(name):
     x, w, b = synth.make_layer_inputs(layer)
     dt = B.DTYPE_OF[synth.TORCH_DTYPE[layer.dtype]]
     auto = B.wino_resolve_variant(layer.N, layer.C, layer.H, layer.W, layer.K, dt, B.WINO_AUTO)
-    assert auto in (B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2)
-    variants = [auto] + [v for v in [B.WINO_FUSED_F2] + EXTRA_VARIANTS.get(name, []) if v != auto]
+    assert auto in (B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2, B.WINO_FUSED_F4)
+    fused = [B.WINO_FUSED_F2] + ([B.WINO_FUSED_F4] if layer.dtype != "f32" else [])
+    variants = [auto] + [v for v in fused + EXTRA_VARIANTS.get(name, []) if v != auto]
     ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
     for variant in variants:
         y = _run(x, w, b, variant)
