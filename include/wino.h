@@ -107,9 +107,10 @@ const char *wino_status_string(int status);     /* static string, never NULL    
 int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int variant);
 
 /* A Winograd variant or WINO_DIRECT, whichever was measured faster for 3x3 / stride 1 on shapes like this one
- * (the direct path where sqrt(C*K) is small and the image large, e.g. 128 channels at 1024x1024, and for at most
- * four output channels on images of 512x512 pixels and more, which have a kernel of their own there); -1 on bad
- * arguments.  wino_resolve_variant(WINO_AUTO) keeps to the Winograd variants. */
+ * (the direct path where sqrt(C*K) is small and the image large but WINO_AUTO does not resolve to the fused F(4x4)
+ * variant - e.g. 64 channels at 256x256, or bf16 with 256 channels at 512x512 - and for at most four output channels
+ * on images of 512x512 pixels and more, which have a kernel of their own there); -1 on bad arguments.
+ * wino_resolve_variant(WINO_AUTO) keeps to the Winograd variants. */
 int wino_recommend_variant(int N, int C, int H, int W, int K, int dtype);
 
 /* Sizes (elements, not bytes) of the transformed tensors for a resolved variant:

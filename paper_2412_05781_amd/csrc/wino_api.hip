@@ -190,6 +190,9 @@ int wino_recommend_variant(int N, int C, int H, int W, int K, int dtype) {
     if (dtype == WINO_F16 && K <= 4 && C >= 16 && C % 16 == 0 && W % 8 == 0 &&
         (long long)N * ((H + 7) / 8) * ((W + 63) / 64) >= 512)
         return WINO_DIRECT;
+    // where WINO_AUTO takes the fused F(4x4) variant it is also ahead of the direct path in NCHW (256 channels at 512x512: 346-384
+    // against 403-445 us; 128 at 1024x1024: 535-562 against 719-729) and level with it channel-last (384 / 562 against 352 / 551)
+    if (v == WINO_FUSED_F4) return v;
     const long long pixels = (long long)N * H * W;
     const long long ck = (long long)C * K;
     const long long cross = v == WINO_F4 ? 320LL * 320LL : 448LL * 448LL;

@@ -56,7 +56,8 @@ def test_sizes(L):
     assert B.wino_filter_bytes(320, 320, B.WINO_F16, B.WINO_DIRECT) == (9 * 320 * 320 + 320) * 2
     # what the library recommends: Winograd for the UNet layers, the direct path for few channels on huge images
     assert B.wino_recommend_variant(2, 320, 64, 64, 320, B.WINO_F16) == B.WINO_F4
-    assert B.wino_recommend_variant(1, 128, 1024, 1024, 128, B.WINO_F16) == B.WINO_DIRECT
+    assert B.wino_recommend_variant(1, 128, 1024, 1024, 128, B.WINO_F16) == B.WINO_FUSED_F4      # the fused variant beats the direct path there
+    assert B.wino_recommend_variant(1, 128, 256, 256, 128, B.WINO_F16) == B.WINO_DIRECT
     assert B.wino_recommend_variant(1, 512, 256, 256, 512, B.WINO_F16) == B.WINO_F4
     assert B.wino_recommend_variant(1, 256, 512, 512, 256, B.WINO_BF16) == B.WINO_DIRECT
     assert B.wino_recommend_variant(2, 1280, 8, 8, 1280, B.WINO_F16) == B.WINO_F2
