@@ -46,13 +46,15 @@ CASES = [(1, 8, 8, 4, 4, 4), (2, 24, 40, 9, 13, 4), (1, 64, 130, 17, 30, 32), (2
          (2, 60, 8, 7, 216, 4), (1, 128, 6, 5, 108, 32)]
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16"])
-@pytest.mark.parametrize("variant", [B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2, B.WINO_FUSED_F4])
+# every variant in fp32 and fp16; the fused F(4x4) kernel exists for the two-byte storage types only
+VARIANT_DTYPE = [(v, d) for d in ("f32", "f16") for v in (B.WINO_F2, B.WINO_F4, B.WINO_FUSED_F2, B.WINO_FUSED_F4)
+                 if not (v == B.WINO_FUSED_F4 and d == "f32")]
+
+
+@pytest.mark.parametrize("variant,dtype", VARIANT_DTYPE)
 @pytest.mark.parametrize("layout", [B.WINO_NCHW, B.WINO_NHWC])
 @pytest.mark.parametrize("case", CASES)
 def test_fused_full_tensor(case, layout, variant, dtype):
-    if variant == B.WINO_FUSED_F4 and dtype == "f32":
-        pytest.skip("the fused F(4x4) kernel exists for the two-byte storage types only")
     N, C, K, H, W, G = case
     x, w, b = synth.make_inputs(N, C, K, H, W, dtype, seed=3000 + sum(case))
     gamma, beta, addvec, residual = _extras(N, C, K, H, W, dtype, 77 + sum(case))
