@@ -45,7 +45,11 @@ int main() {
     CHECK(wino_transformed_dims(1, 5, 7, 9, 3, WINO_AUTO, &alpha, &Cp, &T), WINO_ERR_VARIANT);
     CHECK(wino_resolve_variant(2, 320, 64, 64, 320, WINO_F16, WINO_AUTO) > 0, 1);
     CHECK(wino_resolve_variant(2, 320, 64, 64, 320, WINO_F16, 13), -1);
-    CHECK(wino_recommend_variant(1, 128, 1024, 1024, 128, WINO_F16), WINO_DIRECT);
+    CHECK(wino_recommend_variant(1, 128, 1024, 1024, 128, WINO_F16), WINO_FUSED_F4);
+    CHECK(wino_recommend_variant(1, 128, 256, 256, 128, WINO_F16), WINO_DIRECT);
+    CHECK(wino_resolve_variant(1, 128, 1024, 1024, 128, WINO_F32, WINO_FUSED_F4), -1);
+    CHECK(wino_workspace_bytes(1, 128, 64, 64, 128, WINO_F16, WINO_FUSED_F4), 36LL * 256 * 128 * 2);
+    CHECK(wino_fused_f4_gemm_output(a, a, nullptr, b, 1, 8, 4, 4, 8, WINO_F32, WINO_NCHW, 0, nullptr), WINO_ERR_DTYPE);
     // pre-launch error paths of every entry point
     wino_filter f{a, 320, 320, WINO_F16, WINO_F4};
     CHECK(wino_filter_transform(nullptr, a, 8, 8, WINO_F16, WINO_F2, &f, nullptr), WINO_ERR_NULL);
