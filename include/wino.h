@@ -130,7 +130,8 @@ size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int dtype, int va
  * rounded once to `dtype`.  Done once per weight tensor.
  *   w         device, [K][C][3][3] in `dtype`
  *   w_t_data  device, at least wino_filter_bytes(K,C,dtype,variant) bytes
- *   variant   WINO_F2, WINO_F4 or WINO_DIRECT (AUTO is rejected: the shape is not known here)
+ *   variant   WINO_F2, WINO_F4, WINO_FUSED_F2, WINO_FUSED_F4 (the fused variants share U with their tile size; WINO_FUSED_F4 with
+ *             fp32 is WINO_ERR_DTYPE) or WINO_DIRECT; WINO_AUTO is rejected: the shape is not known here
  *   out       host, filled on success
  */
 int wino_filter_transform(const void *w, void *w_t_data, int K, int C, int dtype, int variant,
@@ -234,7 +235,7 @@ int wino_batched_gemm_shape(const void *U, const void *V, float *M, int K, int C
  *                   large images).  Accumulation stays fp32.  The relative L2 error of F(4x4) grows from
  *                   about 3.1e-3 to 3.8-4.2e-3 (F(2x2): 5e-4 to 6.4e-4), and |M| must stay below 65504.
  *                   Ignored where the reduction is split into partial products, for fp32 storage, and by
- *                   WINO_FUSED_F2 (which has no stored product).
+ *                   the fused variants (which have no stored product).
  * A filter prepared with WINO_DIRECT is accepted too: the direct path reads x through the upsampling by address
  * arithmetic, adds in its epilogue, and applies GroupNorm + SiLU while it re-lays x into its workspace (the activated
  * tensor is rounded once to the storage type there; a channel-last x is then copied once instead of read in place).
