@@ -209,9 +209,11 @@ input_transform_i8_nhwc_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq,
     }
 }
 
-// NCHW: the only contiguity is along the image row, so four adjacent lanes own the four window columns of one channel (a
-// wave's load touches 16 channel planes instead of 64) and exchange their entries of B^T d for the column combination;
-// lane 4q + nu ends up with V[xi*4 + nu] of its channel.  A round covers blockDim.x / 4 channels.
+// NCHW: the only contiguity is along the image row, so eight adjacent lanes own the 2 x 4 entries of the window that row xi
+// needs of one channel (one load per lane; a wave's load touches 8 channel planes - on 8x8 images a plane is a single
+// 128-byte line, and how many lines a compute unit has to fetch is what this kernel's time follows).  The two rows are
+// exchanged between the halves of the octet, the entries of B^T d between the lanes of a quad; both quads of an octet hold
+// the same values, lane 8q + nu stores V[xi*4 + nu] of its channel.  A round covers blockDim.x / 8 channels.
 template <typename E, int KEEP>
 __global__ void __launch_bounds__(1024)
 input_transform_i8_nchw_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq, float* __restrict__ dV,
@@ -223,12 +225,15 @@ input_transform_i8_nchw_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq,
     int ia, ib; bool add;
     bt_row(xi, ia, ib, add);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int nu = threadIdx.x & 3, cl = threadIdx.x >> 2, cpr = blockDim.x >> 2;       // channels per round
+    const int nu = threadIdx.x & 3, second = (threadIdx.x >> 2) & 1, cl = threadIdx.x >> 3, cpr = blockDim.x >> 3;   // channels per round
+    const int hrow = h0 + (second ? ib : ia);
     // sources of this lane's column combination inside its quad: nu 0: t0 - t2, 1: t1 + t2, 2: t2 - t1, 3: t1 - t3
     const int qa = (lane & ~3) + (nu == 0 ? 0 : (nu == 2 ? 2 : 1));
     const int qb = (lane & ~3) + (nu == 0 ? 2 : (nu == 1 ? 2 : (nu == 2 ? 1 : 3)));
     auto entry = [&](int c) -> float {
-        const float a = load_x<E, false>(x, n, c, h0 + ia, w0 + nu, C, H, W), b = load_x<E, false>(x, n, c, h0 + ib, w0 + nu, C, H, W);
+        const float mine = load_x<E, false>(x, n, c, hrow, w0 + nu, C, H, W);
+        const float other = __shfl_xor(mine, 4, 64);                   // the same column of the other window row
+        const float a = second ? other : mine, b = second ? mine : other;
         const float tt = add ? __fadd_rn(a, b) : __fsub_rn(a, b);
         const float ta = __shfl(tt, qa, 64), tb = __shfl(tt, qb, 64);
         return nu == 1 ? __fadd_rn(ta, tb) : __fsub_rn(ta, tb);
@@ -239,12 +244,12 @@ input_transform_i8_nchw_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq,
     for (int r = 0; r < KEEP; ++r) kept[r] = entry(cl + r * cpr);
 #pragma unroll
     for (int r = 0; r < KEEP; ++r) mx = fmaxf(mx, fabsf(kept[r]));
-    const int rounds = (Cq + cpr - 1) / cpr;                 // the same for every thread: the exchange inside entry() needs whole quads
+    const int rounds = (Cq + cpr - 1) / cpr;                 // the same for every thread: the exchanges inside entry() need whole octets
     for (int r = KEEP; r < rounds; ++r) mx = fmaxf(mx, fabsf(entry(cl + r * cpr)));
     if (threadIdx.x < 4 * kMaxWaves) red[threadIdx.x] = 0.f;
     __syncthreads();
 #pragma unroll
-    for (int off = 32; off >= 4; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));       // lanes with the same nu
+    for (int off = 32; off >= 8; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));       // lanes with the same nu
     if (lane < 4) red[lane * kMaxWaves + wave] = mx;
     __syncthreads();
     float m = 0.f;
@@ -255,12 +260,12 @@ input_transform_i8_nchw_kernel(const E* __restrict__ x, int8_t* __restrict__ Vq,
 #pragma unroll
     for (int r = 0; r < KEEP; ++r) {
         const int c = cl + r * cpr;
-        if (c < Cq) dst[c] = code_of(kept[r], sc);
+        if (c < Cq && !second) dst[c] = code_of(kept[r], sc);
     }
     for (int r = KEEP; r < rounds; ++r) {
         const int c = cl + r * cpr;
         const float v = entry(c);
-        if (c < Cq) dst[c] = code_of(v, sc);
+        if (c < Cq && !second) dst[c] = code_of(v, sc);
     }
     if (threadIdx.x < 4) dV[(size_t)(xi * 4 + nu) * T + t] = __fdiv_rn(m, 127.f);
 }
@@ -289,12 +294,12 @@ static void launch_i8_nchw(const void* x, void* Vq, float* dV, const Geom& g, in
 
 hipError_t launch_input_transform_i8(const void* x, void* Vq, float* dV, const Geom& g, int Cq, int dt, bool nhwc, hipStream_t s) {
     if (g.m != 2 || Cq < g.C || Cq % 16 != 0 || (long long)g.T * 4 > 0x7fffffffLL) return hipErrorInvalidValue;
-    // a round = the channels one pass of the workgroup covers (a lane per channel, or per channel and window column); the
-    // workgroup is sized so that its rounds are full, and rows of up to 3 (12) rounds stay in registers between the passes
-    const int per_round_max = nhwc ? 1024 : 256;
+    // a round = the channels one pass of the workgroup covers (a lane per channel, or eight lanes per channel); the
+    // workgroup is sized so that its rounds are full, and rows of up to 3 (24) rounds stay in registers between the passes
+    const int per_round_max = nhwc ? 1024 : 128;
     const int rounds = (Cq + per_round_max - 1) / per_round_max;
-    const int per_round = round_up((Cq + rounds - 1) / rounds, nhwc ? 64 : 16);
-    const int threads = nhwc ? per_round : 4 * per_round;
+    const int per_round = round_up((Cq + rounds - 1) / rounds, nhwc ? 64 : 8);
+    const int threads = nhwc ? per_round : 8 * per_round;
     return with_dtype(dt, [&](auto* tag) {
         using E = std::remove_pointer_t<decltype(tag)>;
         if (nhwc) {
@@ -304,7 +309,8 @@ hipError_t launch_input_transform_i8(const void* x, void* Vq, float* dV, const G
         } else {
             if (rounds <= 3) launch_i8_nchw<E, 3>(x, Vq, dV, g, Cq, threads, s);
             else if (rounds <= 6) launch_i8_nchw<E, 6>(x, Vq, dV, g, Cq, threads, s);
-            else launch_i8_nchw<E, 12>(x, Vq, dV, g, Cq, threads, s);
+            else if (rounds <= 12) launch_i8_nchw<E, 12>(x, Vq, dV, g, Cq, threads, s);
+            else launch_i8_nchw<E, 24>(x, Vq, dV, g, Cq, threads, s);
         }
         return hipGetLastError();
     });
