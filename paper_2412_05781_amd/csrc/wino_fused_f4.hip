@@ -6,10 +6,11 @@
 //   - a wave owns a 16 x 32 piece (two 16x16 MFMA tiles, v_mfma_f32_16x16x32: four accumulator registers per tile), and
 //   - step (iii) is taken one dimension at a time.  Positions run xi-major; while nu runs over a row of the
 //     transformed tile the product is folded into four row sums  Z[b] += A^T[b][nu] * M[xi,nu]; at the end of the row
-//     Y[a][b] += A^T[a][xi] * Z[b].  That is 21 accumulator sets (16 + 4 + 1) of 8 registers, all in vector registers,
-//     and 180 multiply-adds per accumulator register instead of 324.
+//     Y[a][b] += A^T[a][xi] * Z[b].  That is 22 accumulator sets of 8 registers (16 outputs, 4 row sums, and the product twice:
+//     the two MFMA steps of a stage alternate between two accumulators), all in vector registers, and 180 multiply-adds per
+//     accumulator register instead of 324.
 // The price of the small wave tile is traffic: 3 KB of LDS fragments per 32 reduction elements and wave, and a block of
-// at most 64 x 64 per compute unit (the register file holds no more 21-fold accumulators), so every byte of U and V is
+// at most 64 x 64 per compute unit (the register file holds no more accumulators of this kind), so every byte of U and V is
 // fetched into LDS by T/64 and K/64 workgroups.  That fill traffic bounds the kernel; it pays on large images with at
 // most 256 channels, where the unfused path is bound by writing and re-reading M.  Two-byte storage types only.
 //
