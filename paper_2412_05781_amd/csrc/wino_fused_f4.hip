@@ -310,29 +310,57 @@ wino_fused_f4_kernel(const E* __restrict__ Aop, const E* __restrict__ Bop, const
             }
         }
     } else {
-        // columns are output channels: lanes run along k, which is contiguous in a channel-last y
+        // Columns are output channels, which are contiguous in a channel-last y - but a lane holds one channel and a 16x16
+        // tile only 16 of them, so stores straight from the accumulators would be 32-byte pieces.  The block goes through LDS
+        // instead (the ring is free by now): for each output row a of the tile, every wave parks its values for the four
+        // pixels (a, b) as storage-type elements at [b][tile][channel], and the workgroup then writes them out as 16-byte
+        // pieces, eight lanes to a 128-byte line.  Bias, vector and residual are added before the one rounding, as everywhere.
+        constexpr int PSTRIDE = BN * 2 + 16;              // bytes per (pixel, tile) row in LDS; the pad spreads the rows over the banks
+        constexpr int PIECES = BN / 8;                    // 16-byte pieces per row
+        static_assert(4 * BM * PSTRIDE <= NST * STAGE_BYTES, "the parked rows fit the ring's LDS");
+        const bool rows16 = (K % 8 == 0);                 // a pixel's channel vector starts on a 16-byte boundary
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int k = col0 + wn * 32 + j * 16 + frag_row;
-            const bool k_ok = k < K;
-            const float bk = (bias && k_ok) ? bias[k] : 0.f;
+        for (int a = 0; a < 4; ++a) {                     // unrolled: the accumulators are registers, a must be a constant
+            __syncthreads();                              // nobody reads the ring (or the previous rows) any more
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int t = row0 + wm * 16 + 4 * frag_q + r;
-                if (!(t < g.T && k_ok)) continue;
-                const int tj = t % g.tw; const int q = t / g.tw;
-                const int ti = q % g.th, n = q / g.th;
-                const float bb = bk + (post.addvec ? post.addvec[(size_t)n * K + k] : 0.f);
+            for (int j = 0; j < 2; ++j) {
+                const int kl = wn * 32 + j * 16 + frag_row, k = col0 + kl;
+                const bool k_ok = k < K;
+                const float bk = (bias && k_ok) ? bias[k] : 0.f;
 #pragma unroll
-                for (int a = 0; a < 4; ++a)
+                for (int r = 0; r < 4; ++r) {
+                    const int tl = wm * 16 + 4 * frag_q + r, t = row0 + tl;
+                    const bool ok = t < g.T && k_ok;
+                    const int tc = t < g.T ? t : g.T - 1;
+                    const int tj = tc % g.tw; const int q = tc / g.tw;
+                    const int ti = q % g.th, n = q / g.th;
+                    const float bb = bk + ((post.addvec && ok) ? post.addvec[(size_t)n * K + k] : 0.f);
+                    const int ii = 4 * ti + a;
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
-                        const int ii = 4 * ti + a, jj = 4 * tj + b;
-                        if (ii < H && jj < W) {
-                            const size_t o = (((size_t)n * H + ii) * W + jj) * K + k;
-                            y[o] = from_f32<E>(accY[a][b][j][r] + bb + (res ? to_f32<E>(res[o]) : 0.f));
-                        }
+                        const int jj = 4 * tj + b;
+                        float v = accY[a][b][j][r] + bb;
+                        if (res && ok && ii < H && jj < W) v += to_f32<E>(res[(((size_t)n * H + ii) * W + jj) * K + k]);
+                        *reinterpret_cast<E*>(lds + (size_t)(b * BM + tl) * PSTRIDE + (size_t)kl * 2) = from_f32<E>(v);
                     }
+                }
+            }
+            __syncthreads();
+            for (int idx = tid; idx < 4 * BM * PIECES; idx += NW * 64) {
+                const int piece = idx % PIECES, tl = (idx / PIECES) % BM, b = idx / (PIECES * BM);
+                const int t = row0 + tl, k0 = col0 + piece * 8;
+                if (t >= g.T || k0 >= K) continue;
+                const int tj = t % g.tw; const int q = t / g.tw;
+                const int ti = q % g.th, n = q / g.th;
+                const int ii = 4 * ti + a, jj = 4 * tj + b;
+                if (ii >= H || jj >= W) continue;
+                const unsigned char* src = lds + (size_t)(b * BM + tl) * PSTRIDE + (size_t)piece * 16;
+                E* dst = y + (((size_t)n * H + ii) * W + jj) * K + k0;
+                if (rows16 && k0 + 8 <= K) {
+                    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+                } else {
+                    for (int e = 0; e < 8 && k0 + e < K; ++e) dst[e] = reinterpret_cast<const E*>(src)[e];
+                }
             }
         }
     }
