@@ -101,8 +101,8 @@ const char *wino_status_string(int status);     /* static string, never NULL    
 
 /* WINO_AUTO -> WINO_F2, WINO_F4, WINO_FUSED_F2 or WINO_FUSED_F4 for this shape and storage type, by measured speed within
  * the type's error bound (F4 from 64 tiles on; fp32 with C > 640 and bf16 stay on F(2x2); the fused variants where they
- * measured faster: 2-byte storage, K >= 32, and F(2x2) with >= 4096 tiles, or F(4x4) with >= 16384 tiles and at most 256
- * input and output channels).  Other values are returned as they are; -1 on bad arguments (a variant that does not exist
+ * measured faster: 2-byte storage, K >= 32, and F(2x2) with >= 4096 tiles, or F(4x4) with >= 4096 tiles, at most 512
+ * input and output channels and at least 512 blocks of 64 output channels x 64 tiles).  Other values are returned as they are; -1 on bad arguments (a variant that does not exist
  * for the storage type included). */
 int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int variant);
 

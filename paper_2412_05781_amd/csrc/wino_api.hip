@@ -166,12 +166,13 @@ int wino_resolve_variant(int N, int C, int H, int W, int K, int dtype, int varia
     if (dtype == WINO_BF16) pick = WINO_F2;
     // The fused variants (steps (ii) and (iii) in one kernel) where they measured faster with 2-byte storage.  F(2x2): against
     // the F(2x2) chain from 4096 tiles on (128x128 images at batch 2 and everything larger: 0.6-0.9x the time).  F(4x4): against
-    // the F(4x4) chain from 16384 tiles on with at most 256 channels (256 channels at 512x512: 0.83x, 128 at 1024x1024: 0.66x;
-    // with 512 channels at 256x256 it is level, below that slower).
+    // the F(4x4) chain from 4096 tiles on, with at most 512 channels and enough 64x64 blocks for two rounds of workgroups
+    // (512 channels at 256x256: 0.96x, 256 at 512x512: 0.85x, 128 at 1024x1024: 0.67x; with fewer tiles 1.2-2.2x slower).
     const Geom g2 = make_geom(N, C, H, W, K, 2);
     if (dtype != WINO_F32 && K >= 32) {
         if (pick == WINO_F2 && g2.T >= 4096) pick = WINO_FUSED_F2;
-        if (pick == WINO_F4 && g4.T >= 16384 && C <= 256 && K <= 256) pick = WINO_FUSED_F4;
+        const long long blocks4 = (long long)((K + 63) / 64) * ((g4.T + 63) / 64);
+        if (pick == WINO_F4 && g4.T >= 4096 && C <= 512 && K <= 512 && blocks4 >= 512) pick = WINO_FUSED_F4;
     }
     return pick;
 }
@@ -190,8 +191,8 @@ int wino_recommend_variant(int N, int C, int H, int W, int K, int dtype) {
     if (dtype == WINO_F16 && K <= 4 && C >= 16 && C % 16 == 0 && W % 8 == 0 &&
         (long long)N * ((H + 7) / 8) * ((W + 63) / 64) >= 512)
         return WINO_DIRECT;
-    // where WINO_AUTO takes the fused F(4x4) variant it is also ahead of the direct path in NCHW (256 channels at 512x512: 346-384
-    // against 403-445 us; 128 at 1024x1024: 535-562 against 719-729) and level with it channel-last (384 / 562 against 352 / 551)
+    // where WINO_AUTO takes the fused F(4x4) variant it is also ahead of the direct path (256 channels at 512x512: 342-350 us in
+    // either layout against 417 / 356 NCHW / NHWC; 128 at 1024x1024: 530 / 498 against 702 / 541; 512 at 256x256: 254 / 252 against 351 / 326)
     if (v == WINO_FUSED_F4) return v;
     const long long pixels = (long long)N * H * W;
     const long long ck = (long long)C * K;

@@ -58,7 +58,7 @@ def test_sizes(L):
     assert B.wino_recommend_variant(2, 320, 64, 64, 320, B.WINO_F16) == B.WINO_F4
     assert B.wino_recommend_variant(1, 128, 1024, 1024, 128, B.WINO_F16) == B.WINO_FUSED_F4      # the fused variant beats the direct path there
     assert B.wino_recommend_variant(1, 128, 256, 256, 128, B.WINO_F16) == B.WINO_DIRECT
-    assert B.wino_recommend_variant(1, 512, 256, 256, 512, B.WINO_F16) == B.WINO_F4
+    assert B.wino_recommend_variant(1, 512, 256, 256, 512, B.WINO_F16) == B.WINO_FUSED_F4
     assert B.wino_recommend_variant(1, 256, 512, 512, 256, B.WINO_BF16) == B.WINO_DIRECT
     assert B.wino_recommend_variant(2, 1280, 8, 8, 1280, B.WINO_F16) == B.WINO_F2
     assert B.wino_recommend_variant(0, 1, 1, 1, 1, B.WINO_F16) == -1
@@ -70,12 +70,14 @@ def test_resolve_variant(L):
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
     # 8x8 images with wide channels: the transformed filter dominates the traffic, F2's is 2.25x smaller
     assert B.wino_resolve_variant(2, 1280, 8, 8, 1280, B.WINO_F16, B.WINO_AUTO) == B.WINO_F2
-    # the fused variants where they measured faster: F(4x4) from 16384 tiles on with <= 256 channels (fp16), many-tile layers in bf16
+    # the fused variants where they measured faster: F(4x4) from 4096 tiles on with <= 512 channels and >= 512 blocks (fp16), many-tile layers in bf16
     assert B.wino_resolve_variant(1, 128, 1024, 1024, 128, B.WINO_F16, B.WINO_AUTO) == B.WINO_FUSED_F4
     assert B.wino_resolve_variant(1, 128, 1024, 1024, 3, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
     assert B.wino_resolve_variant(1, 256, 512, 512, 256, B.WINO_F16, B.WINO_AUTO) == B.WINO_FUSED_F4
-    assert B.wino_resolve_variant(1, 512, 256, 256, 512, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
-    assert B.wino_resolve_variant(1, 512, 512, 512, 512, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
+    assert B.wino_resolve_variant(1, 512, 256, 256, 512, B.WINO_F16, B.WINO_AUTO) == B.WINO_FUSED_F4
+    assert B.wino_resolve_variant(1, 512, 128, 128, 512, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4          # 1024 tiles
+    assert B.wino_resolve_variant(1, 64, 256, 256, 64, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4            # 64 blocks
+    assert B.wino_resolve_variant(1, 1024, 256, 256, 1024, B.WINO_F16, B.WINO_AUTO) == B.WINO_F4
     assert B.wino_resolve_variant(2, 320, 128, 128, 320, B.WINO_BF16, B.WINO_AUTO) == B.WINO_FUSED_F2
     assert B.wino_resolve_variant(2, 320, 64, 64, 320, B.WINO_BF16, B.WINO_AUTO) == B.WINO_F2
     assert B.wino_recommend_variant(1, 128, 1024, 1024, 3, B.WINO_F16) == B.WINO_DIRECT      # few output channels, large image
