@@ -23,7 +23,7 @@ def _np(t):
     return t.float().numpy().astype(np.float64)
 
 
-@pytest.mark.parametrize("variant", [B.WINO_F4, B.WINO_F2, B.WINO_FUSED_F2, B.WINO_DIRECT])
+@pytest.mark.parametrize("variant", [B.WINO_F4, B.WINO_F2, B.WINO_FUSED_F2, B.WINO_FUSED_F4, B.WINO_DIRECT])
 def test_two_calls_in_a_row_second_smaller(variant):
     for (N, C, K, H, W) in [(2, 96, 80, 40, 44), (1, 40, 24, 9, 14)]:
         x, w, b = synth.make_inputs(N, C, K, H, W, "f16", seed=8000 + H)
@@ -35,7 +35,7 @@ def test_two_calls_in_a_row_second_smaller(variant):
         torch.cuda.synchronize()
         assert torch.equal(y_ex, y_st), (variant, (N, C, K, H, W))
         ref = oracle.conv2d_direct(_np(x), _np(w), _np(b))
-        pu.check(y_st.float().cpu().numpy().astype(np.float64), ref, 5e-3, {B.WINO_F4: 4, B.WINO_DIRECT: 1}.get(variant, 2), "f16")
+        pu.check(y_st.float().cpu().numpy().astype(np.float64), ref, 5e-3, {B.WINO_F4: 4, B.WINO_FUSED_F4: 4, B.WINO_DIRECT: 1}.get(variant, 2), "f16")
 
 
 def test_channel_last_and_fp32():
