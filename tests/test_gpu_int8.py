@@ -178,6 +178,29 @@ def test_i8_full_size_weight_streaming_layers(name, layout):
     assert 1.3e-2 <= err <= 2.3e-2, (name, err)
 
 
+def test_i8_zero_input_no_bias_determinism_and_scaling():
+    N, C, K, H, W = 2, 40, 24, 10, 11
+    x, w, b = synth.make_inputs(N, C, K, H, W, "f16", seed=5)
+    xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
+    # an all-zero image: every row of V has step 0 and codes 0, so y is the bias, rounded once
+    y0 = B.conv2d_i8(torch.zeros_like(xd), wd, bd)
+    torch.cuda.synchronize()
+    assert torch.equal(y0.float().cpu(), b.to(torch.float16).float().view(1, -1, 1, 1).expand(N, K, H, W))
+    # no bias; the same call twice gives the same bits
+    y1, y2 = B.conv2d_i8(xd, wd, None), B.conv2d_i8(xd, wd, None)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+    model = i8.conv2d_winograd_int8(_np(x), _np(w), None)
+    assert oracle.rel_l2(y1.float().cpu().numpy().astype(np.float64), model) <= OUT_TOL["f16"]
+    # the steps follow the data: an image 16 times larger (exact in fp16 here) gives 16 times the result, the codes unchanged
+    xs = (x * 16.0).to(torch.float16)
+    assert torch.equal(xs.float(), x.float() * 16.0)
+    Vq1, dV1 = B.wino_i8_input_transform(xd)
+    Vq2, dV2 = B.wino_i8_input_transform(xs.to(DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(Vq1, Vq2) and torch.equal(dV2, dV1 * 16.0)
+
+
 def test_i8_rejects_bad_arguments():
     x = torch.zeros(1, 16, 8, 8, dtype=torch.float16, device=DEV)
     w = torch.zeros(8, 16, 3, 3, dtype=torch.float16, device=DEV)
